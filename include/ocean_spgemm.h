@@ -1,0 +1,198 @@
+/*
+ * Ocean SpGEMM for AMD MI355X (gfx950): C = A*B on CSR matrices held in
+ * device memory, computed by the estimation-based workflow of the Ocean paper:
+ * an analysis step, a per-row size prediction (HyperLogLog estimate, exact
+ * symbolic count, or the product-count upper bound), binned Gustavson
+ * accumulation in LDS / global hash tables with an overflow-and-retry path,
+ * then per-row sort and compaction to canonical CSR.
+ *
+ * Plain C ABI.  Unless a parameter says "host", every pointer inside an
+ * ocean_csr and every array argument is a DEVICE pointer on the current HIP
+ * device.  Functions return OCEAN_OK (0) or an error code; they never throw
+ * or abort.  ocean_last_error() returns a description of the last failure on
+ * the calling thread.
+ */
+#ifndef OCEAN_SPGEMM_H
+#define OCEAN_SPGEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* A hipStream_t (0 = the null stream).  Kept opaque so that C callers need no HIP headers. */
+typedef void *ocean_stream_t;
+
+enum { OCEAN_F64 = 0, OCEAN_F32 = 1 };
+
+enum {
+    OCEAN_OK = 0,
+    OCEAN_EINVAL = 1, /* null / inconsistent arguments, A.cols != B.rows, dtype mismatch, invalid CSR content */
+    OCEAN_EALLOC = 2, /* the allocator could not provide memory */
+    OCEAN_EHIP = 3    /* a HIP runtime call failed */
+};
+
+/* Workflows of Table 1 of the paper.  AUTO applies the table's rule. */
+enum { OCEAN_WF_AUTO = 0, OCEAN_WF_UPPER_BOUND = 1, OCEAN_WF_HLL = 2, OCEAN_WF_SYMBOLIC = 3 };
+
+/*
+ * CSR matrix (Section 2.1): row_ptr has rows+1 ascending 0-based offsets,
+ * col_idx / val hold the entries of each row contiguously.  Column ids are
+ * 32-bit as in the paper; row offsets are 64-bit because nnz(C) can exceed
+ * 2^31.  Inputs may hold unsorted rows, repeated columns and explicit zeros
+ * (repeated columns add up).  Outputs are canonical: strictly ascending
+ * columns inside each row and one entry per structurally reachable (i, j);
+ * numerical cancellation does not remove entries.
+ */
+typedef struct ocean_csr {
+    int64_t rows, cols, nnz;
+    int64_t *row_ptr; /* device, rows+1 */
+    int32_t *col_idx; /* device, nnz */
+    void *val;        /* device, nnz elements of dtype */
+    int32_t dtype;    /* OCEAN_F64 or OCEAN_F32 */
+    int32_t reserved;
+} ocean_csr;
+
+/*
+ * Device-memory provider.  alloc returns 0 and a pointer aligned to at least
+ * 256 bytes, usable on the stream passed to the library call; release gives
+ * it back.  Both are called on the calling host thread only.  With a NULL
+ * allocator the library uses hipMalloc / hipFree.
+ */
+typedef struct ocean_allocator {
+    void *ctx;
+    int (*alloc)(void *ctx, size_t bytes, void **ptr);
+    void (*release)(void *ctx, void *ptr);
+} ocean_allocator;
+
+/* Parameters; ocean_default_options fills in the paper's values (Section 4.3, Table 1). */
+typedef struct ocean_options {
+    int32_t workflow;                /* OCEAN_WF_*; AUTO = Table 1 */
+    int32_t hll_registers;           /* 0 = 32 if ER < 48 else 64 (Section 4.3); or 32 / 64 / 128 */
+    double upper_bound_avg_products; /* 64: below this average products/row, bin by the product count */
+    double er_threshold;             /* 8 */
+    double cr_threshold;             /* 8 */
+    double expand_coef;              /* 0 = 1.5, or 2.0 with 32 registers (Section 5.3); else the factor itself */
+    double exact_load_coef;          /* table slots per exact output entry on the two-pass path (1.5, Section 2.2) */
+    double sample_ratio;             /* 0.03 */
+    int32_t sample_min, sample_max;  /* 600, 10000 */
+    uint32_t sample_seed;
+    double estimate_scale;           /* test hook: every estimate is multiplied by this before binning (1.0) */
+    int32_t validate_inputs;         /* 1: check column ids and row offsets on the device first */
+    int32_t reserved;
+    const ocean_allocator *allocator; /* host pointer, may be NULL */
+} ocean_options;
+
+#define OCEAN_MAX_BINS 12
+/* stage indices of ocean_stats.stage_ms */
+enum {
+    OCEAN_ST_ANALYSIS = 0,  /* input check, products per row, ER */
+    OCEAN_ST_SKETCH = 1,    /* one HLL sketch per row of B */
+    OCEAN_ST_SAMPLE = 2,    /* merged sketches of the sampled rows, sampled CR */
+    OCEAN_ST_PREDICT = 3,   /* HLL merge+estimate of all rows, or the exact symbolic pass */
+    OCEAN_ST_BINNING = 4,   /* row classification, scans, output allocation */
+    OCEAN_ST_NUMERIC = 5,   /* accumulation + per-row sort, all bins */
+    OCEAN_ST_RETRY = 6,     /* overflow rows recomputed with bound-sized accumulators */
+    OCEAN_ST_COMPACT = 7,   /* row sizes -> row_ptr, rows moved to contiguous CSR */
+    OCEAN_NUM_STAGES = 8
+};
+
+typedef struct ocean_stats {
+    int64_t products;          /* P: intermediate products */
+    int64_t max_row_products;
+    int64_t nnz_c;
+    double er;                 /* P / nnz(A) */
+    double avg_products;       /* P / rows(A) */
+    double sampled_cr;         /* 0 when not computed */
+    int32_t workflow;          /* the one that ran */
+    int32_t hll_registers;     /* 0 when no sketch was built */
+    int32_t sampled_rows;
+    int32_t fell_back;         /* 1: estimation workflow abandoned for the two-pass one (out of memory) */
+    int64_t rows_per_bin[OCEAN_MAX_BINS];          /* numeric bins */
+    int64_t symbolic_rows_per_bin[OCEAN_MAX_BINS]; /* symbolic bins (two-pass workflow) */
+    int64_t overflow_rows;
+    int64_t temp_slots;        /* output slots reserved before compaction (estimation workflows) */
+    int64_t peak_bytes;        /* largest total obtained from the allocator at one time */
+    float stage_ms[OCEAN_NUM_STAGES];
+    float total_ms;            /* host wall clock of the call */
+} ocean_stats;
+
+void ocean_default_options(ocean_options *opt /* host */);
+
+/*
+ * C = A*B (paper, Section 2.1 problem statement; workflow of Figure 4).
+ * A is m x k, B is k x n, both borrowed and never modified; dtype(A) ==
+ * dtype(B) == dtype(C).  C is a host struct the call fills in: its three
+ * arrays come from opt->allocator (or hipMalloc) and belong to the caller,
+ * who returns them with ocean_csr_release.  col_idx / val may be larger than
+ * nnz entries.  opt and stats are host pointers and may be NULL.  Work is
+ * enqueued on `stream`; the call blocks the host wherever a total has to be
+ * read back to size an allocation and returns after the stream has drained,
+ * so C is complete on return.  On failure *C is zeroed and everything the
+ * call obtained from the allocator has been released.  The result is exact
+ * whatever the estimates were (Section 3.2, overflow handling).
+ */
+int ocean_spgemm(const ocean_csr *A, const ocean_csr *B, ocean_csr *C, const ocean_options *opt,
+                 ocean_stats *stats, ocean_stream_t stream);
+
+/* Return C's arrays to the allocator that produced them (NULL = hipFree) and zero the struct. */
+int ocean_csr_release(ocean_csr *C, const ocean_allocator *allocator);
+
+/*
+ * Analysis (Section 3.2): prod[i] = sum over stored A_ik of nnz(B_k), the
+ * number of intermediate products and an upper bound of nnz(C_i).  prod:
+ * device int64[A->rows].  total / max_row: host outputs, may be NULL.
+ * Blocks until done.  Column ids of A outside [0, B->rows) give OCEAN_EINVAL.
+ */
+int ocean_row_products(const ocean_csr *A, const ocean_csr *B, int64_t *prod, int64_t *total, int64_t *max_row,
+                       ocean_stream_t stream);
+
+/*
+ * HLL construct (Sections 2.4, 3.1): one sketch of m one-byte registers per
+ * row of B, sketches: device uint8[B->rows * m], m in {32, 64, 128}.
+ * Register index = low log2(m) bits of the 32-bit hash, register value =
+ * 1 + leading zeros of the remaining bits (0 = empty).  Asynchronous on stream.
+ */
+int ocean_hll_sketch_rows(const ocean_csr *B, int32_t m, uint8_t *sketches, ocean_stream_t stream);
+
+/*
+ * HLL merge + estimate (Section 3.1): for each selected row i of A the
+ * element-wise maximum of the sketches of the rows of B it references, and
+ * the cardinality estimate of that merged sketch.  rows: device int64[n_rows]
+ * row ids, or NULL for rows 0..n_rows-1 (then n_rows must be A->rows).
+ * prod / b_cols: when prod is non-NULL (device int64[A->rows]) the estimate
+ * is limited to [longest referenced row of B, min(prod[i], b_cols)].
+ * est: device double[n_rows].  merged: device uint8[n_rows*m] or NULL.
+ * b_row_ptr: device, B's row offsets (needed for the lower limit; may be NULL
+ * when prod is NULL).  Asynchronous on stream.
+ */
+int ocean_hll_merge_estimate(const ocean_csr *A, const uint8_t *sketches, int32_t m, const int64_t *rows,
+                             int64_t n_rows, const int64_t *prod, const int64_t *b_row_ptr, int64_t b_cols,
+                             double *est, uint8_t *merged, ocean_stream_t stream);
+
+/*
+ * Exact symbolic pass (Section 2.3): nnz_per_row[i] = number of distinct
+ * output columns of row i; device int32[A->rows].  Blocks until done.
+ */
+int ocean_symbolic(const ocean_csr *A, const ocean_csr *B, int32_t *nnz_per_row, const ocean_options *opt,
+                   ocean_stats *stats, ocean_stream_t stream);
+
+/* Host-only helpers of the analysis step (Section 4.3, Table 1). */
+int32_t ocean_select_workflow(double avg_products, double er, double cr, const ocean_options *opt);
+int32_t ocean_hll_register_count(double er, const ocean_options *opt);
+int64_t ocean_sample_size(int64_t rows, const ocean_options *opt);
+/* rows_out: host int64[ocean_sample_size(rows)], ascending row ids of the stratified sample. */
+int ocean_sample_rows(int64_t rows, const ocean_options *opt, int64_t *rows_out);
+
+/* Number of numeric / symbolic bins and the table slots of each (host arrays of OCEAN_MAX_BINS). */
+int ocean_bin_layout(int32_t *numeric_slots, int32_t *n_numeric, int32_t *symbolic_slots, int32_t *n_symbolic);
+
+const char *ocean_last_error(void);
+int ocean_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OCEAN_SPGEMM_H */

@@ -1,0 +1,314 @@
+// Analysis step and HyperLogLog size prediction (paper Sections 2.4, 3.1, 3.2).
+//
+//   k_validate        input check (row offsets ascending, column ids in range)
+//   k_row_products    prod[i] = sum_{k in A_i} nnz(B_k); P and the largest row; longest B row per A row
+//   k_hll_sketch      construct: one m-register sketch per row of B, registers live in LDS per lane group
+//   k_hll_merge       merge along each row of A (byte-wise max of 8 registers per lane) + estimate
+//   k_sample_reduce   sums over the sampled rows for the sampled compression ratio
+//
+// All kernels are HBM/L2-bound gathers; rows are mapped to groups of G lanes
+// (G a power of two <= 64 chosen from the average row length) so that short
+// rows do not leave most of a 64-wide wave idle.
+#include "ocean_internal.hpp"
+
+namespace ocean {
+
+constexpr int TPB = 256;
+
+static inline int ilog2_ceil(double x, int lo, int hi)
+{
+    int l = lo;
+    while (l < hi && (double)(1 << l) < x) ++l;
+    return l;
+}
+
+// ---------------------------------------------------------------- validate
+__global__ void k_validate(const int64_t *rp, const int32_t *col, int64_t rows, int64_t cols, int64_t nnz,
+                           int32_t *flags, int bit)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    bool bad = false;
+    for (int64_t i = t0; i < rows; i += stride) {
+        int64_t a = rp[i], b = rp[i + 1];
+        bad |= (b < a) | (a < 0) | (b > nnz);
+    }
+    if (t0 == 0) bad |= (rp[0] != 0) | (rp[rows] != nnz);
+    for (int64_t e = t0; e < nnz; e += stride) {
+        int32_t c = col[e];
+        bad |= ((uint32_t)c >= (uint64_t)cols);
+    }
+    if (__ballot(bad) != 0 && lane_id() == 0) atomicOr(flags, bit);
+}
+
+hipError_t launch_validate(const Csr &A, const Csr &B, int32_t *flags, hipStream_t s)
+{
+    auto go = [&](const Csr &M, int bit) {
+        int64_t work = M.nnz > M.rows ? M.nnz : M.rows;
+        int blocks = (int)((work + TPB * 4 - 1) / (TPB * 4));
+        if (blocks < 1) blocks = 1;
+        if (blocks > 65536) blocks = 65536;
+        hipLaunchKernelGGL(k_validate, dim3(blocks), dim3(TPB), 0, s, M.rp, M.col, M.rows, M.cols, M.nnz, flags, bit);
+    };
+    go(A, 1);
+    if (B.rp != A.rp || B.col != A.col || B.rows != A.rows || B.cols != A.cols) go(B, 2);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------ row products
+__global__ void __launch_bounds__(TPB)
+k_row_products(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col, int64_t m,
+               const int64_t *__restrict__ b_rp, int64_t b_rows, int g_log2, int64_t *__restrict__ prod,
+               int32_t *__restrict__ maxb, unsigned long long *totals, int32_t *flags)
+{
+    __shared__ long long s_sum[TPB / WAVE];
+    __shared__ long long s_max[TPB / WAVE];
+    const int G = 1 << g_log2;
+    const int64_t gt = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t row = gt >> g_log2;
+    const int sub = (int)(gt & (G - 1));
+    long long p = 0;
+    long long mx = 0;
+    bool bad = false;
+    if (row < m) {
+        const int64_t e1 = a_rp[row + 1];
+        for (int64_t e = a_rp[row] + sub; e < e1; e += G) {
+            const int32_t k = a_col[e];
+            if ((uint32_t)k >= (uint64_t)b_rows) { bad = true; continue; }
+            const long long len = b_rp[k + 1] - b_rp[k];
+            p += len;
+            mx = len > mx ? len : mx;
+        }
+    }
+    p = group_reduce_sum(p, G);
+    mx = group_reduce_max(mx, G);
+    long long contrib = 0;
+    if (row < m && sub == 0) {
+        prod[row] = p;
+        maxb[row] = (int32_t)(mx > 0x7fffffffLL ? 0x7fffffffLL : mx);
+        contrib = p;
+    }
+    long long wsum = group_reduce_sum(contrib, WAVE);
+    long long wmax = group_reduce_max(contrib, WAVE);
+    const int w = threadIdx.x / WAVE;
+    if (lane_id() == 0) { s_sum[w] = wsum; s_max[w] = wmax; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        long long bs = 0, bm = 0;
+        for (int i = 0; i < TPB / WAVE; ++i) { bs += s_sum[i]; bm = s_max[i] > bm ? s_max[i] : bm; }
+        if (bs) atomicAdd(&totals[0], (unsigned long long)bs);
+        if (bm) atomicMax(&totals[1], (unsigned long long)bm);
+    }
+    if (__ballot(bad) != 0 && lane_id() == 0) atomicOr(flags, 4);
+}
+
+hipError_t launch_row_products(const Csr &A, const int64_t *b_rp, int64_t b_rows, int64_t *prod, int32_t *maxb,
+                               unsigned long long *totals, int32_t *flags, hipStream_t s)
+{
+    if (A.rows == 0) return hipSuccess;
+    const double avg = A.rows ? (double)A.nnz / (double)A.rows : 0.0;
+    const int g_log2 = ilog2_ceil(avg, 1, 6);
+    const int64_t threads = A.rows << g_log2;
+    const int64_t blocks = (threads + TPB - 1) / TPB;
+    hipLaunchKernelGGL(k_row_products, dim3((unsigned)blocks), dim3(TPB), 0, s, A.rp, A.col, A.rows, b_rp, b_rows,
+                       g_log2, prod, maxb, totals, flags);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------- HLL sketch
+// Registers of the rows in flight sit in LDS as 32-bit words (LDS has a
+// 32-bit atomic max, Section 3.1 "parallel updates ... atomicMax"); they are
+// packed to one byte per register (Section 4.3) when the sketch is stored.
+template <int M>
+__global__ void __launch_bounds__(TPB)
+k_hll_sketch(const int64_t *__restrict__ rp, const int32_t *__restrict__ col, int64_t rows, int g_log2,
+             uint8_t *__restrict__ out)
+{
+    extern __shared__ uint32_t s_regs[];  // [TPB >> g_log2][M]
+    constexpr int P = (M == 32) ? 5 : (M == 64) ? 6 : 7;
+    const int G = 1 << g_log2;
+    const int sub = threadIdx.x & (G - 1);
+    const int rl = threadIdx.x >> g_log2;
+    const int R = TPB >> g_log2;
+    uint32_t *my = s_regs + rl * M;
+    for (int64_t base = (int64_t)blockIdx.x * R; base < rows; base += (int64_t)gridDim.x * R) {
+        const int64_t row = base + rl;
+        for (int j = sub; j < M; j += G) my[j] = 0;
+        wave_sync();
+        if (row < rows) {
+            const int64_t p1 = rp[row + 1];
+            for (int64_t p = rp[row] + sub; p < p1; p += G) {
+                const uint32_t h = hll_hash(col[p]);
+                const uint32_t w = h >> P;
+                const uint32_t rank = w ? (uint32_t)(__clz((int)w) - P + 1) : (uint32_t)(32 - P + 1);
+                atomicMax(&my[h & (M - 1)], rank);
+            }
+        }
+        wave_sync();
+        if (row < rows) {
+            uint32_t *dst = reinterpret_cast<uint32_t *>(out + row * M);
+            for (int j = sub; j < M / 4; j += G)
+                dst[j] = my[4 * j] | (my[4 * j + 1] << 8) | (my[4 * j + 2] << 16) | (my[4 * j + 3] << 24);
+        }
+        wave_sync();
+    }
+}
+
+hipError_t launch_hll_sketch(const Csr &B, int m, uint8_t *sketches, hipStream_t s)
+{
+    if (B.rows == 0) return hipSuccess;
+    const double avg = (double)B.nnz / (double)B.rows;
+    const int g_log2 = ilog2_ceil(avg, 3, 6);
+    const int R = TPB >> g_log2;
+    int64_t blocks = (B.rows + R - 1) / R;
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    const size_t lds = (size_t)R * m * sizeof(uint32_t);
+    switch (m) {
+    case 32: hipLaunchKernelGGL(k_hll_sketch<32>, dim3((unsigned)blocks), dim3(TPB), lds, s, B.rp, B.col, B.rows, g_log2, sketches); break;
+    case 64: hipLaunchKernelGGL(k_hll_sketch<64>, dim3((unsigned)blocks), dim3(TPB), lds, s, B.rp, B.col, B.rows, g_log2, sketches); break;
+    case 128: hipLaunchKernelGGL(k_hll_sketch<128>, dim3((unsigned)blocks), dim3(TPB), lds, s, B.rp, B.col, B.rows, g_log2, sketches); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// -------------------------------------------------------------- HLL merge
+// Registers are below 128, so a byte-wise maximum of eight registers is a few
+// 64-bit integer operations: (a|0x80)-b keeps bit 7 of a byte set exactly
+// when a >= b, and no borrow crosses a byte.
+__device__ __forceinline__ uint64_t bytemax8(uint64_t a, uint64_t b)
+{
+    const uint64_t H = 0x8080808080808080ull;
+    const uint64_t ge = (((a | H) - b) & H) >> 7;
+    const uint64_t mask = ge * 0xFFull;
+    return (a & mask) | (b & ~mask);
+}
+
+__device__ __forceinline__ double hll_alpha(int m)
+{
+    return m == 32 ? 0.697 : m == 64 ? 0.709 : 0.7213 / (1.0 + 1.079 / (double)m);
+}
+
+// One group of G lanes per selected row of A; L = M/8 lanes cover one sketch
+// (8 registers per lane in a 64-bit word) so G/L entries of the row are
+// merged at once.  Each 64-byte sketch of B is read as one coalesced line.
+template <int M>
+__global__ void __launch_bounds__(TPB)
+k_hll_merge(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col,
+            const uint64_t *__restrict__ sk, const int64_t *__restrict__ rows, int64_t n_rows, int g_log2,
+            const int64_t *__restrict__ prod, const int32_t *__restrict__ maxb, const int64_t *__restrict__ b_rp,
+            int64_t b_cols, double *__restrict__ est, uint64_t *__restrict__ merged)
+{
+    constexpr int L = M / 8;
+    const int G = 1 << g_log2;  // >= L
+    const int64_t gt = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t t = gt >> g_log2;
+    const int sub = (int)(gt & (G - 1));
+    const int slice = sub & (L - 1);
+    const int part = sub / L;
+    const int parts = G / L;
+    uint64_t acc = 0;
+    long long blen_max = 0;
+    int64_t row = -1;
+    if (t < n_rows) {
+        row = rows ? rows[t] : t;
+        const int64_t e1 = a_rp[row + 1];
+        for (int64_t e = a_rp[row] + part; e < e1; e += parts) {
+            const int64_t k = a_col[e];
+            acc = bytemax8(acc, sk[k * L + slice]);
+            if (b_rp != nullptr && slice == 0) {
+                const long long len = b_rp[k + 1] - b_rp[k];
+                blen_max = len > blen_max ? len : blen_max;
+            }
+        }
+    }
+    for (int off = L; off < G; off <<= 1) acc = bytemax8(acc, __shfl_xor((unsigned long long)acc, off, WAVE));
+    if (b_rp != nullptr) blen_max = group_reduce_max(blen_max, G);
+    // harmonic sum and empty-register count of this lane's 8 registers
+    double ssum = 0.0;
+    int zeros = 0;
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+        const unsigned r = (unsigned)(acc >> (8 * b)) & 0xFFu;
+        ssum += __longlong_as_double((long long)(1023 - (int)r) << 52);  // 2^-r, exact
+        zeros += (r == 0);
+    }
+    for (int off = L >> 1; off > 0; off >>= 1) {
+        ssum += __shfl_xor(ssum, off, WAVE);
+        zeros += __shfl_xor(zeros, off, WAVE);
+    }
+    if (t < n_rows) {
+        if (merged != nullptr && part == 0) merged[t * L + slice] = acc;
+        if (sub == 0) {
+            const double dm = (double)M;
+            double e = hll_alpha(M) * dm * dm / ssum;
+            if (e <= 2.5 * dm && zeros > 0) e = dm * log(dm / (double)zeros);
+            if (prod != nullptr) {
+                const long long pr = prod[row];
+                const double hi = (double)(pr < b_cols ? pr : b_cols);
+                const double lo = (double)(maxb != nullptr ? (long long)maxb[row] : blen_max);
+                e = e < lo ? lo : e;
+                e = e > hi ? hi : e;
+            }
+            est[t] = e;
+        }
+    }
+}
+
+hipError_t launch_hll_merge(const Csr &A, const uint8_t *sketches, int m, const int64_t *rows, int64_t n_rows,
+                            const int64_t *prod, const int32_t *maxb, const int64_t *b_rp, int64_t b_cols,
+                            double *est, uint8_t *merged, hipStream_t s)
+{
+    if (n_rows == 0) return hipSuccess;
+    const int L = m / 8;
+    const double avg = A.rows ? (double)A.nnz / (double)A.rows : 1.0;
+    int g_log2 = ilog2_ceil(avg * L, 0, 6);
+    while ((1 << g_log2) < L) ++g_log2;
+    const int64_t threads = n_rows << g_log2;
+    const int64_t blocks = (threads + TPB - 1) / TPB;
+    const uint64_t *sk = reinterpret_cast<const uint64_t *>(sketches);
+    uint64_t *mg = reinterpret_cast<uint64_t *>(merged);
+    switch (m) {
+    case 32: hipLaunchKernelGGL(k_hll_merge<32>, dim3((unsigned)blocks), dim3(TPB), 0, s, A.rp, A.col, sk, rows, n_rows, g_log2, prod, maxb, b_rp, b_cols, est, mg); break;
+    case 64: hipLaunchKernelGGL(k_hll_merge<64>, dim3((unsigned)blocks), dim3(TPB), 0, s, A.rp, A.col, sk, rows, n_rows, g_log2, prod, maxb, b_rp, b_cols, est, mg); break;
+    case 128: hipLaunchKernelGGL(k_hll_merge<128>, dim3((unsigned)blocks), dim3(TPB), 0, s, A.rp, A.col, sk, rows, n_rows, g_log2, prod, maxb, b_rp, b_cols, est, mg); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------- sample reduce
+// Sums over the sampled rows in a fixed order (one workgroup, strided partial
+// sums, tree reduction), so the sampled CR is the same on every run.
+__global__ void __launch_bounds__(TPB)
+k_sample_reduce(const int64_t *__restrict__ rows, int64_t n_rows, const int64_t *__restrict__ prod,
+                const double *__restrict__ est, double *out)
+{
+    __shared__ double s_p[TPB];
+    __shared__ double s_e[TPB];
+    double sp = 0.0, se = 0.0;
+    for (int64_t t = threadIdx.x; t < n_rows; t += TPB) {
+        const double e = est[t];
+        if (e > 0.0) { se += e; sp += (double)prod[rows[t]]; }
+    }
+    s_p[threadIdx.x] = sp;
+    s_e[threadIdx.x] = se;
+    __syncthreads();
+    for (int off = TPB / 2; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) {
+            s_p[threadIdx.x] += s_p[threadIdx.x + off];
+            s_e[threadIdx.x] += s_e[threadIdx.x + off];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) { out[0] = s_p[0]; out[1] = s_e[0]; }
+}
+
+hipError_t launch_sample_reduce(const int64_t *rows, int64_t n_rows, const int64_t *prod, const double *est,
+                                double *out, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_sample_reduce, dim3(1), dim3(TPB), 0, s, rows, n_rows, prod, est, out);
+    return hipGetLastError();
+}
+
+}  // namespace ocean

@@ -1,0 +1,581 @@
+// Numeric pass: Gustavson's row-wise product (paper Section 2.1) with
+// open-addressing hash accumulators (Section 2.2) sized per bin, followed by
+// the per-row sort that makes the output CSR-compliant (Section 4.2).
+//
+//   k_numeric_group   several short rows per wave (16 or 64 lanes per row), table in LDS
+//   k_numeric_wg      one workgroup per row, keys + values + sort buffer in LDS (512..8192 slots)
+//   k_numeric_hybrid  32768 keys in LDS, values accumulated in a global slab (Section 3.3,
+//                     enhanced hash accumulator); rows leave sorted through an LDS bitmap rank
+//   k_numeric_global  whole table in global memory for rows beyond any LDS table
+//
+// A row reports overflow (row_nnz = -1) when its table fills up or when it
+// produced more entries than the space reserved for it; such rows are redone
+// by the caller with bound-sized tables (Section 3.2, overflow handling).
+#include "ocean_internal.hpp"
+
+namespace ocean {
+
+template <typename V>
+__device__ __forceinline__ void lds_add(V *p, V v)
+{
+    __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+template <typename V>
+__device__ __forceinline__ void l2_add(V *p, V v)
+{
+    __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Find the slot of `key` in an LDS table of 2^BITS slots, inserting it when
+// absent.  Linear probing; -1 when the table is full.
+template <int BITS>
+__device__ __forceinline__ int lds_find_or_insert(int32_t *keys, int32_t key)
+{
+    constexpr uint32_t MASK = (1u << BITS) - 1u;
+    uint32_t h = table_hash(key, BITS);
+    for (uint32_t probe = 0; probe <= MASK; ++probe) {
+        const int32_t cur = __hip_atomic_load(&keys[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (cur == key) return (int)h;
+        if (cur == EMPTY_KEY) {
+            const int32_t old = atomicCAS(&keys[h], EMPTY_KEY, key);
+            if (old == EMPTY_KEY || old == key) return (int)h;
+        }
+        h = (h + 1u) & MASK;
+    }
+    return -1;
+}
+
+// Slot of a key known to be present.
+template <int BITS>
+__device__ __forceinline__ int lds_find(const int32_t *keys, int32_t key)
+{
+    constexpr uint32_t MASK = (1u << BITS) - 1u;
+    uint32_t h = table_hash(key, BITS);
+    for (uint32_t probe = 0; probe <= MASK; ++probe) {
+        if (keys[h] == key) return (int)h;
+        h = (h + 1u) & MASK;
+    }
+    return 0;
+}
+
+__device__ __forceinline__ int pow2_ceil_i32(int x)
+{
+    return x <= 1 ? 1 : 1 << (32 - __clz(x - 1));
+}
+
+// ======================================================== group kernel ====
+// G lanes per row, 256/G rows per workgroup, no workgroup barrier anywhere:
+// the lanes of a row are part of one wave.
+template <typename V, int G, int BITS>
+__global__ void __launch_bounds__(256)
+k_numeric_group(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col, const V *__restrict__ a_val,
+                const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_col, const V *__restrict__ b_val,
+                const int32_t *__restrict__ rows, int64_t count, int gb_log2,
+                const int64_t *__restrict__ out_ptr, int32_t *__restrict__ out_col, V *__restrict__ out_val,
+                int32_t *__restrict__ row_nnz)
+{
+    constexpr int SLOTS = 1 << BITS;
+    constexpr int R = 256 / G;
+    __shared__ int32_t s_keys[R * SLOTS];
+    __shared__ int32_t s_sort[R * SLOTS];
+    __shared__ V s_vals[R * SLOTS];
+    const int rl = threadIdx.x / G;
+    const int sub = threadIdx.x % G;
+    int32_t *keys = s_keys + rl * SLOTS;
+    int32_t *sbuf = s_sort + rl * SLOTS;
+    V *vals = s_vals + rl * SLOTS;
+    const int gb = 1 << gb_log2;  // lanes that share one row of B (<= G)
+    const int sub_b = sub & (gb - 1);
+    const int part = sub >> gb_log2;
+    const int parts = G >> gb_log2;
+    const int group_shift = (lane_id() / G) * G;
+    const unsigned long long group_mask = (G == 64) ? ~0ull : ((1ull << G) - 1ull);
+
+    const int64_t r = (int64_t)blockIdx.x * R + rl;
+    const bool live = r < count;
+    const int64_t row = live ? rows[r] : 0;
+
+    for (int s = sub; s < SLOTS; s += G) { keys[s] = EMPTY_KEY; vals[s] = (V)0; }
+    wave_sync();
+
+    bool ovf = false;
+    if (live) {
+        const int64_t e1 = a_rp[row + 1];
+        for (int64_t e = a_rp[row] + part; e < e1; e += parts) {
+            const int64_t k = a_col[e];
+            const V a = a_val[e];
+            const int64_t p1 = b_rp[k + 1];
+            for (int64_t p = b_rp[k] + sub_b; p < p1; p += gb) {
+                const int32_t j = b_col[p];
+                const V v = a * b_val[p];
+                const int slot = lds_find_or_insert<BITS>(keys, j);
+                if (slot >= 0) lds_add(&vals[slot], v);
+                else ovf = true;
+            }
+        }
+    }
+    wave_sync();
+
+    // gather the occupied keys of this row's table
+    int c = 0;
+#pragma unroll
+    for (int it = 0; it < SLOTS / G; ++it) {
+        const int32_t key = keys[it * G + sub];
+        const bool occ = key != EMPTY_KEY;
+        const unsigned long long m = (__ballot(occ) >> group_shift) & group_mask;
+        if (occ) sbuf[c + __popcll(m & ((1ull << sub) - 1ull))] = key;
+        c += __popcll(m);
+    }
+    const bool ovf_any = ((__ballot(ovf) >> group_shift) & group_mask) != 0;
+    const int N = pow2_ceil_i32(c);
+    for (int s = c + sub; s < N; s += G) sbuf[s] = SORT_PAD;
+    wave_sync();
+
+    // bitonic sort of N keys by the G lanes of the row
+    for (int k = 2; k <= N; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = sub; i < (N >> 1); i += G) {
+                const int lo = ((i & ~(j - 1)) << 1) | (i & (j - 1));
+                const int hi = lo | j;
+                const int32_t x = sbuf[lo], y = sbuf[hi];
+                if ((x > y) == ((lo & k) == 0)) { sbuf[lo] = y; sbuf[hi] = x; }
+            }
+            wave_sync();
+        }
+    }
+
+    if (live) {
+        const int64_t o = out_ptr[row];
+        const int64_t cap = out_ptr[row + 1] - o;
+        if (ovf_any || (int64_t)c > cap) {
+            if (sub == 0) row_nnz[row] = -1;
+        } else {
+            for (int t = sub; t < c; t += G) {
+                const int32_t key = sbuf[t];
+                out_col[o + t] = key;
+                out_val[o + t] = vals[lds_find<BITS>(keys, key)];
+            }
+            if (sub == 0) row_nnz[row] = c;
+        }
+    }
+}
+
+// =================================================== workgroup helpers ====
+template <int THREADS>
+__device__ __forceinline__ int block_exclusive_scan_i32(int v, int *s_wave, int &total)
+{
+    int inc = v;
+    for (int off = 1; off < WAVE; off <<= 1) {
+        const int o = __shfl_up(inc, off, WAVE);
+        if (lane_id() >= off) inc += o;
+    }
+    const int w = threadIdx.x / WAVE;
+    if (lane_id() == WAVE - 1) s_wave[w] = inc;
+    __syncthreads();
+    int wave_off = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < THREADS / WAVE; ++i) {
+        const int x = s_wave[i];
+        if (i < w) wave_off += x;
+        tot += x;
+    }
+    __syncthreads();
+    total = tot;
+    return wave_off + inc - v;
+}
+
+// Lanes that cooperate on one entry of the row of A: at least 2^gb_log2 (the
+// typical length of a row of B), widened until the whole workgroup has work.
+template <int THREADS>
+__device__ __forceinline__ int entry_group_log2(int64_t n_entries, int gb_log2)
+{
+    int g = gb_log2;
+    while ((1 << g) < THREADS && (n_entries << g) < THREADS) ++g;
+    return g;
+}
+
+// ==================================================== workgroup kernel ====
+template <typename V, int BITS, int THREADS>
+__global__ void __launch_bounds__(THREADS)
+k_numeric_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col, const V *__restrict__ a_val,
+             const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_col, const V *__restrict__ b_val,
+             const int32_t *__restrict__ rows, int64_t count, int gb_log2,
+             const int64_t *__restrict__ out_ptr, int32_t *__restrict__ out_col, V *__restrict__ out_val,
+             int32_t *__restrict__ row_nnz)
+{
+    constexpr int SLOTS = 1 << BITS;
+    constexpr int PER = SLOTS / THREADS;
+    __shared__ int32_t s_keys[SLOTS];
+    __shared__ int32_t s_sort[SLOTS];
+    __shared__ V s_vals[SLOTS];
+    __shared__ int s_wave[THREADS / WAVE];
+    __shared__ int s_ovf;
+    const int tid = threadIdx.x;
+    const int64_t r = blockIdx.x;
+    if (r >= count) return;
+    const int64_t row = rows[r];
+
+    for (int s = tid; s < SLOTS; s += THREADS) { s_keys[s] = EMPTY_KEY; s_vals[s] = (V)0; }
+    if (tid == 0) s_ovf = 0;
+    __syncthreads();
+
+    const int64_t e0 = a_rp[row], e1 = a_rp[row + 1];
+    const int ge_log2 = entry_group_log2<THREADS>(e1 - e0, gb_log2);
+    const int ge = 1 << ge_log2;
+    const int sub_b = tid & (ge - 1);
+    const int part = tid >> ge_log2;
+    const int parts = THREADS >> ge_log2;
+    for (int64_t e = e0 + part; e < e1; e += parts) {
+        const int64_t k = a_col[e];
+        const V a = a_val[e];
+        const int64_t p1 = b_rp[k + 1];
+        for (int64_t p = b_rp[k] + sub_b; p < p1; p += ge) {
+            const int32_t j = b_col[p];
+            const V v = a * b_val[p];
+            const int slot = lds_find_or_insert<BITS>(s_keys, j);
+            if (slot >= 0) lds_add(&s_vals[slot], v);
+            else s_ovf = 1;
+        }
+    }
+    __syncthreads();
+
+    // compaction of the keys: each thread owns PER consecutive slots
+    int mine = 0;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) mine += (s_keys[tid * PER + q] != EMPTY_KEY);
+    int c;
+    int pos = block_exclusive_scan_i32<THREADS>(mine, s_wave, c);
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+        const int32_t key = s_keys[tid * PER + q];
+        if (key != EMPTY_KEY) s_sort[pos++] = key;
+    }
+    const int N = pow2_ceil_i32(c);
+    for (int s = c + tid; s < N; s += THREADS) s_sort[s] = SORT_PAD;
+    __syncthreads();
+
+    for (int k = 2; k <= N; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = tid; i < (N >> 1); i += THREADS) {
+                const int lo = ((i & ~(j - 1)) << 1) | (i & (j - 1));
+                const int hi = lo | j;
+                const int32_t x = s_sort[lo], y = s_sort[hi];
+                if ((x > y) == ((lo & k) == 0)) { s_sort[lo] = y; s_sort[hi] = x; }
+            }
+            __syncthreads();
+        }
+    }
+
+    const int64_t o = out_ptr[row];
+    const int64_t cap = out_ptr[row + 1] - o;
+    if (s_ovf || (int64_t)c > cap) {
+        if (tid == 0) row_nnz[row] = -1;
+    } else {
+        for (int t = tid; t < c; t += THREADS) {
+            const int32_t key = s_sort[t];
+            out_col[o + t] = key;
+            out_val[o + t] = s_vals[lds_find<BITS>(s_keys, key)];
+        }
+        if (tid == 0) row_nnz[row] = c;
+    }
+}
+
+// ======================================================= hybrid kernel ====
+// Keys of a 32768-slot table stay in LDS; values are accumulated with
+// fire-and-forget atomics into this workgroup's slab in global memory (it is
+// 256 KB, so it lives in the L2 of the XCD the workgroup runs on).  The row is
+// emitted in ascending order without a sort: per window of WIN columns an LDS
+// bitmap of the present keys and its prefix popcount give every key its rank.
+constexpr int HY_BITS = 15;
+constexpr int HY_SLOTS = 1 << HY_BITS;
+constexpr int HY_THREADS = 1024;
+constexpr int HY_WIN = 131072;          // columns per ranking window
+constexpr int HY_WORDS = HY_WIN / 32;   // 4096
+
+template <typename V>
+__global__ void __launch_bounds__(HY_THREADS)
+k_numeric_hybrid(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col, const V *__restrict__ a_val,
+                 const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_col, const V *__restrict__ b_val,
+                 const int32_t *__restrict__ rows, int64_t count, int gb_log2, unsigned long long *queue,
+                 V *__restrict__ slab_all, const int64_t *__restrict__ out_ptr, int32_t *__restrict__ out_col,
+                 V *__restrict__ out_val, int32_t *__restrict__ row_nnz)
+{
+    constexpr int PER = HY_SLOTS / HY_THREADS;   // 32 slots per thread
+    constexpr int WPT = HY_WORDS / HY_THREADS;   // 4 bitmap words per thread
+    __shared__ int32_t s_keys[HY_SLOTS];
+    __shared__ uint32_t s_bm[HY_WORDS];
+    __shared__ uint16_t s_pre[HY_WORDS];
+    __shared__ int s_wave[HY_THREADS / WAVE];
+    __shared__ int s_ovf;
+    __shared__ int s_min, s_max;
+    __shared__ long long s_row;
+    const int tid = threadIdx.x;
+    V *slab = slab_all + (size_t)blockIdx.x * HY_SLOTS;
+
+    for (;;) {
+        if (tid == 0) s_row = (long long)atomicAdd(queue, 1ull);
+        __syncthreads();
+        const int64_t r = s_row;
+        if (r >= count) break;   // uniform: every wave of the workgroup leaves here
+        const int64_t row = rows[r];
+        for (int s = tid; s < HY_SLOTS; s += HY_THREADS) s_keys[s] = EMPTY_KEY;
+        if (tid == 0) { s_ovf = 0; s_min = 0x7fffffff; s_max = -1; }
+        __syncthreads();
+
+        const int64_t e0 = a_rp[row], e1 = a_rp[row + 1];
+        const int ge_log2 = entry_group_log2<HY_THREADS>(e1 - e0, gb_log2);
+        const int ge = 1 << ge_log2;
+        const int sub_b = tid & (ge - 1);
+        const int part = tid >> ge_log2;
+        const int parts = HY_THREADS >> ge_log2;
+        int kmin = 0x7fffffff, kmax = -1;
+        for (int64_t e = e0 + part; e < e1; e += parts) {
+            const int64_t k = a_col[e];
+            const V a = a_val[e];
+            const int64_t p1 = b_rp[k + 1];
+            for (int64_t p = b_rp[k] + sub_b; p < p1; p += ge) {
+                const int32_t j = b_col[p];
+                const V v = a * b_val[p];
+                const int slot = lds_find_or_insert<HY_BITS>(s_keys, j);
+                if (slot >= 0) {
+                    l2_add(&slab[slot], v);
+                    kmin = j < kmin ? j : kmin;
+                    kmax = j > kmax ? j : kmax;
+                } else {
+                    s_ovf = 1;
+                }
+            }
+        }
+        kmin = -group_reduce_max(-kmin, WAVE);
+        kmax = group_reduce_max(kmax, WAVE);
+        if (lane_id() == 0) { atomicMin(&s_min, kmin); atomicMax(&s_max, kmax); }
+        __threadfence();   // the slab additions are in L2 before anyone exchanges them out
+        __syncthreads();
+
+        const int64_t o = out_ptr[row];
+        const int64_t cap = out_ptr[row + 1] - o;
+        const int lo_key = s_min, hi_key = s_max;
+        int done = 0;
+        for (int64_t w0 = (int64_t)(lo_key >= 0 ? lo_key : 0) & ~(int64_t)(HY_WIN - 1); w0 <= (int64_t)hi_key; w0 += HY_WIN) {
+#pragma unroll
+            for (int q = 0; q < WPT; ++q) s_bm[tid * WPT + q] = 0u;
+            __syncthreads();
+            for (int q = 0; q < PER; ++q) {
+                const int32_t key = s_keys[q * HY_THREADS + tid];
+                const int64_t d = (int64_t)key - w0;
+                if (key != EMPTY_KEY && d >= 0 && d < HY_WIN) atomicOr(&s_bm[d >> 5], 1u << (d & 31));
+            }
+            __syncthreads();
+            int cnt[WPT];
+            int mine = 0;
+#pragma unroll
+            for (int q = 0; q < WPT; ++q) { cnt[q] = __popc(s_bm[tid * WPT + q]); mine += cnt[q]; }
+            int wtotal;
+            int run = block_exclusive_scan_i32<HY_THREADS>(mine, s_wave, wtotal);
+#pragma unroll
+            for (int q = 0; q < WPT; ++q) { s_pre[tid * WPT + q] = (uint16_t)run; run += cnt[q]; }
+            __syncthreads();
+            for (int q = 0; q < PER; ++q) {
+                const int slot = q * HY_THREADS + tid;
+                const int32_t key = s_keys[slot];
+                const int64_t d = (int64_t)key - w0;
+                if (key != EMPTY_KEY && d >= 0 && d < HY_WIN) {
+                    const int rank = done + (int)s_pre[d >> 5] + __popc(s_bm[d >> 5] & ((1u << (d & 31)) - 1u));
+                    const V val = __hip_atomic_exchange(&slab[slot], (V)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if ((int64_t)rank < cap) { out_col[o + rank] = key; out_val[o + rank] = val; }
+                }
+            }
+            done += wtotal;
+            __syncthreads();
+        }
+        if (tid == 0) row_nnz[row] = (s_ovf || (int64_t)done > cap) ? -1 : done;
+        __threadfence();
+        __syncthreads();
+    }
+}
+
+// ======================================================= global kernel ====
+// The table of a row lives in this workgroup's region of global memory
+// (tables are EMPTY / zero between rows).  Rows are emitted in order through
+// an LDS bitmap over windows of 512 K columns, which also restores the table.
+constexpr int GL_THREADS = 1024;
+constexpr int GL_WIN = 524288;
+constexpr int GL_WORDS = GL_WIN / 32;   // 16384
+
+__device__ __forceinline__ int64_t gl_find_or_insert(int32_t *keys, int bits, int32_t key)
+{
+    const uint32_t mask = (1u << bits) - 1u;
+    uint32_t h = table_hash(key, bits);
+    for (uint32_t probe = 0; probe <= mask; ++probe) {
+        const int32_t cur = __hip_atomic_load(&keys[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (cur == key) return h;
+        if (cur == EMPTY_KEY) {
+            const int32_t old = atomicCAS(&keys[h], EMPTY_KEY, key);
+            if (old == EMPTY_KEY || old == key) return h;
+        }
+        h = (h + 1u) & mask;
+    }
+    return -1;
+}
+
+template <typename V>
+__global__ void __launch_bounds__(GL_THREADS)
+k_numeric_global(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col, const V *__restrict__ a_val,
+                 const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_col, const V *__restrict__ b_val,
+                 const int32_t *__restrict__ rows, int64_t count, int gb_log2, unsigned long long *queue,
+                 int32_t *__restrict__ gkeys_all, V *__restrict__ gvals_all, int gbits_max, double coef,
+                 const int64_t *__restrict__ out_ptr, int32_t *__restrict__ out_col, V *__restrict__ out_val,
+                 int32_t *__restrict__ row_nnz)
+{
+    constexpr int WPT = GL_WORDS / GL_THREADS;   // 16 words per thread
+    __shared__ uint32_t s_bm[GL_WORDS];
+    __shared__ uint32_t s_pre[GL_WORDS];
+    __shared__ int s_wave[GL_THREADS / WAVE];
+    __shared__ int s_ovf;
+    __shared__ int s_min, s_max;
+    __shared__ long long s_row;
+    const int tid = threadIdx.x;
+    int32_t *gk = gkeys_all + ((size_t)blockIdx.x << gbits_max);
+    V *gv = gvals_all + ((size_t)blockIdx.x << gbits_max);
+
+    for (;;) {
+        if (tid == 0) s_row = (long long)atomicAdd(queue, 1ull);
+        __syncthreads();
+        const int64_t r = s_row;
+        if (r >= count) break;
+        const int64_t row = rows[r];
+        const int64_t o = out_ptr[row];
+        const int64_t cap = out_ptr[row + 1] - o;
+        // table size of this row: a power of two holding coef * capacity, at most the region
+        int bits = 10;
+        {
+            const double want = coef * (double)cap;
+            while (bits < gbits_max && (double)(1ll << bits) < want) ++bits;
+        }
+        const int64_t slots = 1ll << bits;
+        if (tid == 0) { s_ovf = 0; s_min = 0x7fffffff; s_max = -1; }
+        __syncthreads();
+
+        const int64_t e0 = a_rp[row], e1 = a_rp[row + 1];
+        const int ge_log2 = entry_group_log2<GL_THREADS>(e1 - e0, gb_log2);
+        const int ge = 1 << ge_log2;
+        const int sub_b = tid & (ge - 1);
+        const int part = tid >> ge_log2;
+        const int parts = GL_THREADS >> ge_log2;
+        int kmin = 0x7fffffff, kmax = -1;
+        for (int64_t e = e0 + part; e < e1; e += parts) {
+            const int64_t k = a_col[e];
+            const V a = a_val[e];
+            const int64_t p1 = b_rp[k + 1];
+            for (int64_t p = b_rp[k] + sub_b; p < p1; p += ge) {
+                const int32_t j = b_col[p];
+                const V v = a * b_val[p];
+                const int64_t slot = gl_find_or_insert(gk, bits, j);
+                if (slot >= 0) {
+                    l2_add(&gv[slot], v);
+                    kmin = j < kmin ? j : kmin;
+                    kmax = j > kmax ? j : kmax;
+                } else {
+                    s_ovf = 1;
+                }
+            }
+        }
+        kmin = -group_reduce_max(-kmin, WAVE);
+        kmax = group_reduce_max(kmax, WAVE);
+        if (lane_id() == 0) { atomicMin(&s_min, kmin); atomicMax(&s_max, kmax); }
+        __threadfence();
+        __syncthreads();
+
+        const int lo_key = s_min, hi_key = s_max;
+        long long done = 0;
+        for (int64_t w0 = (int64_t)(lo_key >= 0 ? lo_key : 0) & ~(int64_t)(GL_WIN - 1); w0 <= (int64_t)hi_key; w0 += GL_WIN) {
+#pragma unroll
+            for (int q = 0; q < WPT; ++q) s_bm[tid * WPT + q] = 0u;
+            __syncthreads();
+            for (int64_t s = tid; s < slots; s += GL_THREADS) {
+                const int32_t key = __hip_atomic_load(&gk[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const int64_t d = (int64_t)key - w0;
+                if (key != EMPTY_KEY && d >= 0 && d < GL_WIN) atomicOr(&s_bm[d >> 5], 1u << (d & 31));
+            }
+            __syncthreads();
+            int cnt[WPT];
+            int mine = 0;
+#pragma unroll
+            for (int q = 0; q < WPT; ++q) { cnt[q] = __popc(s_bm[tid * WPT + q]); mine += cnt[q]; }
+            int wtotal;
+            int run = block_exclusive_scan_i32<GL_THREADS>(mine, s_wave, wtotal);
+#pragma unroll
+            for (int q = 0; q < WPT; ++q) { s_pre[tid * WPT + q] = (uint32_t)run; run += cnt[q]; }
+            __syncthreads();
+            for (int64_t s = tid; s < slots; s += GL_THREADS) {
+                const int32_t key = __hip_atomic_load(&gk[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const int64_t d = (int64_t)key - w0;
+                if (key != EMPTY_KEY && d >= 0 && d < GL_WIN) {
+                    const long long rank = done + (long long)s_pre[d >> 5] + __popc(s_bm[d >> 5] & ((1u << (d & 31)) - 1u));
+                    const V val = __hip_atomic_exchange(&gv[s], (V)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(&gk[s], EMPTY_KEY, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (rank < cap) { out_col[o + rank] = key; out_val[o + rank] = val; }
+                }
+            }
+            done += wtotal;
+            __syncthreads();
+        }
+        if (tid == 0) row_nnz[row] = (s_ovf || done > cap) ? -1 : (int32_t)done;
+        __threadfence();
+        __syncthreads();
+    }
+}
+
+// ============================================================ dispatch ====
+template <typename V>
+static hipError_t dispatch(const Csr &A, const Csr &B, const NumLaunch &l, int gb_log2, hipStream_t s)
+{
+    if (l.count <= 0) return hipSuccess;
+    const V *av = static_cast<const V *>(A.val);
+    const V *bv = static_cast<const V *>(B.val);
+    V *ov = static_cast<V *>(l.out_val);
+    const int gbl = gb_log2;
+#define OCEAN_WG(BITS, THREADS)                                                                                   \
+    hipLaunchKernelGGL((k_numeric_wg<V, BITS, THREADS>), dim3((unsigned)l.count), dim3(THREADS), 0, s, A.rp, A.col, \
+                       av, B.rp, B.col, bv, l.rows, l.count, gbl, l.out_ptr, l.out_col, ov, l.row_nnz)
+    switch (l.bin) {
+    case NB_G16: {
+        const int64_t blocks = (l.count + 15) / 16;
+        hipLaunchKernelGGL((k_numeric_group<V, 16, 6>), dim3((unsigned)blocks), dim3(256), 0, s, A.rp, A.col, av, B.rp,
+                           B.col, bv, l.rows, l.count, gbl < 4 ? gbl : 4, l.out_ptr, l.out_col, ov, l.row_nnz);
+        break;
+    }
+    case NB_W64: {
+        const int64_t blocks = (l.count + 3) / 4;
+        hipLaunchKernelGGL((k_numeric_group<V, 64, 8>), dim3((unsigned)blocks), dim3(256), 0, s, A.rp, A.col, av, B.rp,
+                           B.col, bv, l.rows, l.count, gbl, l.out_ptr, l.out_col, ov, l.row_nnz);
+        break;
+    }
+    case NB_S512: OCEAN_WG(9, 128); break;
+    case NB_S1K: OCEAN_WG(10, 256); break;
+    case NB_S2K: OCEAN_WG(11, 512); break;
+    case NB_S4K: OCEAN_WG(12, 1024); break;
+    case NB_S8K: OCEAN_WG(13, 1024); break;
+    case NB_HYBRID:
+        hipLaunchKernelGGL((k_numeric_hybrid<V>), dim3((unsigned)l.n_wg), dim3(HY_THREADS), 0, s, A.rp, A.col, av, B.rp,
+                           B.col, bv, l.rows, l.count, gbl, l.queue, static_cast<V *>(l.slab), l.out_ptr, l.out_col, ov,
+                           l.row_nnz);
+        break;
+    case NB_GLOBAL:
+        hipLaunchKernelGGL((k_numeric_global<V>), dim3((unsigned)l.n_wg), dim3(GL_THREADS), 0, s, A.rp, A.col, av, B.rp,
+                           B.col, bv, l.rows, l.count, gbl, l.queue, l.gkeys, static_cast<V *>(l.gvals), l.gbits, l.coef,
+                           l.out_ptr, l.out_col, ov, l.row_nnz);
+        break;
+    default: return hipErrorInvalidValue;
+    }
+#undef OCEAN_WG
+    return hipGetLastError();
+}
+
+hipError_t launch_numeric_bin(const Csr &A, const Csr &B, int dtype, const NumLaunch &l, int gb_log2, hipStream_t s)
+{
+    return dtype == OCEAN_F64 ? dispatch<double>(A, B, l, gb_log2, s) : dispatch<float>(A, B, l, gb_log2, s);
+}
+
+}  // namespace ocean

@@ -1,0 +1,842 @@
+// C-ABI entry points and host orchestration of the Ocean SpGEMM pipeline
+// (workflow of the paper's Figure 4: analysis -> size prediction -> binning ->
+// numeric accumulation -> overflow retry -> sort/compaction).
+#include <chrono>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <utility>
+#include <vector>
+
+#include "ocean_internal.hpp"
+
+using namespace ocean;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const std::string &msg)
+{
+    g_err = msg;
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                                   \
+    do {                                                                                                \
+        hipError_t e__ = (expr);                                                                        \
+        if (e__ != hipSuccess)                                                                          \
+            return fail(OCEAN_EHIP, std::string(#expr) + ": " + hipGetErrorString(e__));                \
+    } while (0)
+
+#define OC_TRY(expr)                   \
+    do {                               \
+        int rc__ = (expr);             \
+        if (rc__ != OCEAN_OK) return rc__; \
+    } while (0)
+
+// Device scalars of one call; zeroed at the start.
+struct Scalars {
+    unsigned long long totals[2];                 // P, largest row
+    unsigned long long bin_count[OCEAN_MAX_BINS];
+    unsigned long long bin_cursor[OCEAN_MAX_BINS];
+    unsigned long long max_cap;
+    unsigned long long ovf_count;
+    unsigned long long queue[4];
+    double sample_sums[2];
+    int32_t flags;
+    int32_t pad;
+};
+
+constexpr size_t ALIGN = 256;
+inline size_t up(size_t b) { return (b + ALIGN - 1) / ALIGN * ALIGN; }
+
+struct Ctx {
+    hipStream_t s = nullptr;
+    const ocean_allocator *al = nullptr;
+    std::vector<std::pair<void *, size_t>> live;
+    size_t cur = 0, peak = 0;
+    int n_cu = 256;
+    Scalars *h = nullptr;   // pinned host mirror
+    // stage timing
+    std::vector<hipEvent_t> ev;
+    std::vector<int> ev_stage;
+
+    void *alloc(size_t bytes)
+    {
+        if (bytes == 0) bytes = ALIGN;
+        void *p = nullptr;
+        if (al && al->alloc) {
+            if (al->alloc(al->ctx, bytes, &p) != 0) p = nullptr;
+        } else {
+            if (hipMalloc(&p, bytes) != hipSuccess) { (void)hipGetLastError(); p = nullptr; }
+        }
+        if (p) {
+            live.emplace_back(p, bytes);
+            cur += bytes;
+            peak = cur > peak ? cur : peak;
+        }
+        return p;
+    }
+    void release(void *p)
+    {
+        if (!p) return;
+        for (size_t i = 0; i < live.size(); ++i)
+            if (live[i].first == p) {
+                cur -= live[i].second;
+                live.erase(live.begin() + i);
+                break;
+            }
+        if (al && al->release) al->release(al->ctx, p);
+        else (void)hipFree(p);
+    }
+    // hand ownership to the caller
+    void detach(void *p)
+    {
+        for (size_t i = 0; i < live.size(); ++i)
+            if (live[i].first == p) { live.erase(live.begin() + i); return; }
+    }
+    void release_all()
+    {
+        while (!live.empty()) release(live.back().first);
+    }
+};
+
+struct PinnedHost {
+    Scalars *p = nullptr;
+    std::vector<hipEvent_t> events;
+};
+thread_local PinnedHost g_pinned;
+
+int device_cu_count()
+{
+    static thread_local int cached = 0;
+    if (cached == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            cached = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+        else
+            cached = 256;
+    }
+    return cached;
+}
+
+int ctx_init(Ctx &c, const ocean_options *opt, ocean_stream_t stream)
+{
+    c.s = static_cast<hipStream_t>(stream);
+    c.al = opt ? opt->allocator : nullptr;
+    c.n_cu = device_cu_count();
+    if (!g_pinned.p) {
+        void *p = nullptr;
+        HIP_TRY(hipHostMalloc(&p, sizeof(Scalars) + 4096, hipHostMallocPortable));
+        g_pinned.p = static_cast<Scalars *>(p);
+    }
+    c.h = g_pinned.p;
+    return OCEAN_OK;
+}
+
+int mark(Ctx &c, int stage)
+{
+    const size_t i = c.ev.size();
+    if (g_pinned.events.size() <= i) {
+        hipEvent_t e;
+        HIP_TRY(hipEventCreate(&e));
+        g_pinned.events.push_back(e);
+    }
+    HIP_TRY(hipEventRecord(g_pinned.events[i], c.s));
+    c.ev.push_back(g_pinned.events[i]);
+    c.ev_stage.push_back(stage);
+    return OCEAN_OK;
+}
+
+void collect_times(Ctx &c, ocean_stats *st)
+{
+    if (!st) return;
+    for (int i = 0; i < OCEAN_NUM_STAGES; ++i) st->stage_ms[i] = 0.f;
+    for (size_t i = 0; i + 1 < c.ev.size(); ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, c.ev[i], c.ev[i + 1]) == hipSuccess && c.ev_stage[i] >= 0) st->stage_ms[c.ev_stage[i]] += ms;
+    }
+}
+
+int fetch_scalars(Ctx &c, const Scalars *dev)
+{
+    HIP_TRY(hipMemcpyAsync(c.h, dev, sizeof(Scalars), hipMemcpyDeviceToHost, c.s));
+    HIP_TRY(hipStreamSynchronize(c.s));
+    return OCEAN_OK;
+}
+
+Csr view(const ocean_csr *M) { return Csr{M->row_ptr, M->col_idx, M->val, M->rows, M->cols, M->nnz}; }
+
+int check_csr(const ocean_csr *M, const char *name)
+{
+    if (!M) return fail(OCEAN_EINVAL, std::string(name) + " is null");
+    if (M->rows < 0 || M->cols < 0 || M->nnz < 0) return fail(OCEAN_EINVAL, std::string(name) + ": negative size");
+    if (M->cols > 0x7fffffffLL || M->rows > 0x7fffffffLL) return fail(OCEAN_EINVAL, std::string(name) + ": more than 2^31-1 rows or columns");
+    if (!M->row_ptr) return fail(OCEAN_EINVAL, std::string(name) + ": row_ptr is null");
+    if (M->nnz > 0 && (!M->col_idx)) return fail(OCEAN_EINVAL, std::string(name) + ": col_idx is null");
+    if (M->dtype != OCEAN_F64 && M->dtype != OCEAN_F32) return fail(OCEAN_EINVAL, std::string(name) + ": unknown dtype");
+    return OCEAN_OK;
+}
+
+int ilog2_ceil_d(double x, int lo, int hi)
+{
+    int l = lo;
+    while (l < hi && (double)(1ll << l) < x) ++l;
+    return l;
+}
+
+uint32_t fmix32_host(uint32_t h)
+{
+    h ^= h >> 16;
+    h *= 0x85EBCA6Bu;
+    h ^= h >> 13;
+    h *= 0xC2B2AE35u;
+    h ^= h >> 16;
+    return h;
+}
+
+// Per-row work arrays, carved out of one allocation.
+struct Work {
+    void *base = nullptr;
+    Scalars *sc = nullptr;
+    int64_t *prod = nullptr;
+    int32_t *maxb = nullptr;
+    uint8_t *bin = nullptr;
+    int32_t *cap = nullptr;
+    int32_t *row_nnz = nullptr;
+    int32_t *row_nnz2 = nullptr;
+    int32_t *nnz_final = nullptr;   // also the exact counts of the symbolic pass
+    int32_t *bin_rows = nullptr;
+    int64_t *tmp_ptr = nullptr;
+    int64_t *tmp_ptr2 = nullptr;
+    int64_t *scan_tmp = nullptr;
+    double *est = nullptr;
+    int64_t *sample_rows = nullptr;
+    double *sample_est = nullptr;
+};
+
+int work_alloc(Ctx &c, Work &w, int64_t m, int64_t n_sample)
+{
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += up(bytes); return o; };
+    const size_t mm = (size_t)(m > 0 ? m : 1);
+    const size_t o_sc = take(sizeof(Scalars));
+    const size_t o_prod = take(mm * 8), o_maxb = take(mm * 4), o_bin = take(mm), o_cap = take(mm * 4);
+    const size_t o_nnz = take(mm * 4), o_nnz2 = take(mm * 4), o_nnzf = take(mm * 4), o_rows = take(mm * 4);
+    const size_t o_tp = take((mm + 1) * 8), o_tp2 = take((mm + 1) * 8);
+    const size_t o_scan = take((size_t)scan_tmp_elems(m) * 8 + 8);
+    const size_t o_est = take(mm * 8);
+    const size_t o_sr = take((size_t)(n_sample + 1) * 8), o_se = take((size_t)(n_sample + 1) * 8);
+    char *b = static_cast<char *>(c.alloc(off));
+    if (!b) return fail(OCEAN_EALLOC, "workspace allocation failed");
+    w.base = b;
+    w.sc = reinterpret_cast<Scalars *>(b + o_sc);
+    w.prod = reinterpret_cast<int64_t *>(b + o_prod);
+    w.maxb = reinterpret_cast<int32_t *>(b + o_maxb);
+    w.bin = reinterpret_cast<uint8_t *>(b + o_bin);
+    w.cap = reinterpret_cast<int32_t *>(b + o_cap);
+    w.row_nnz = reinterpret_cast<int32_t *>(b + o_nnz);
+    w.row_nnz2 = reinterpret_cast<int32_t *>(b + o_nnz2);
+    w.nnz_final = reinterpret_cast<int32_t *>(b + o_nnzf);
+    w.bin_rows = reinterpret_cast<int32_t *>(b + o_rows);
+    w.tmp_ptr = reinterpret_cast<int64_t *>(b + o_tp);
+    w.tmp_ptr2 = reinterpret_cast<int64_t *>(b + o_tp2);
+    w.scan_tmp = reinterpret_cast<int64_t *>(b + o_scan);
+    w.est = reinterpret_cast<double *>(b + o_est);
+    w.sample_rows = reinterpret_cast<int64_t *>(b + o_sr);
+    w.sample_est = reinterpret_cast<double *>(b + o_se);
+    HIP_TRY(hipMemsetAsync(w.sc, 0, sizeof(Scalars), c.s));
+    return OCEAN_OK;
+}
+
+int zero_bins(Ctx &c, Work &w)
+{
+    HIP_TRY(hipMemsetAsync(w.sc->bin_count, 0,
+                           sizeof(unsigned long long) * (2 * OCEAN_MAX_BINS + 2 + 4), c.s));   // counts, cursors, max_cap, ovf, queues
+    return OCEAN_OK;
+}
+
+// ---- analysis: validation + products per row ------------------------------------------------------
+int run_analysis(Ctx &c, Work &w, const Csr &A, const Csr &B, bool validate, ocean_stats *st)
+{
+    if (validate) HIP_TRY(launch_validate(A, B, &w.sc->flags, c.s));
+    HIP_TRY(launch_row_products(A, B.rp, B.rows, w.prod, w.maxb, w.sc->totals, &w.sc->flags, c.s));
+    OC_TRY(fetch_scalars(c, w.sc));
+    if (c.h->flags & 1) return fail(OCEAN_EINVAL, "A is not a valid CSR matrix (row offsets or column ids out of range)");
+    if (c.h->flags & 2) return fail(OCEAN_EINVAL, "B is not a valid CSR matrix (row offsets or column ids out of range)");
+    if (c.h->flags & 4) return fail(OCEAN_EINVAL, "a column id of A is outside [0, rows(B))");
+    if (st) {
+        st->products = (int64_t)c.h->totals[0];
+        st->max_row_products = (int64_t)c.h->totals[1];
+        st->er = A.nnz > 0 ? (double)st->products / (double)A.nnz : 0.0;
+        st->avg_products = A.rows > 0 ? (double)st->products / (double)A.rows : 0.0;
+    }
+    return OCEAN_OK;
+}
+
+// ---- exact symbolic pass ---------------------------------------------------------------------------
+int run_symbolic(Ctx &c, Work &w, const Csr &A, const Csr &B, int gb_log2, int32_t *nnz_out, ocean_stats *st)
+{
+    BinParams bp{};
+    bp.mode = 3;
+    bp.coef = 1.0;
+    bp.n_bins = SB_COUNT;
+    for (int b = 0; b < SB_COUNT; ++b) bp.slots[b] = kSymbolicSlots[b];
+    bp.n_cols = B.cols;
+    OC_TRY(zero_bins(c, w));
+    HIP_TRY(launch_fill_i32(nnz_out, A.rows, 0, c.s));
+    HIP_TRY(launch_classify(A.rows, bp, 1.0, w.prod, nullptr, nullptr, nullptr, w.bin, nullptr, w.sc->bin_count,
+                            nullptr, c.s));
+    HIP_TRY(launch_scatter(A.rows, SB_COUNT, w.bin, w.sc->bin_count, w.sc->bin_cursor, w.bin_rows, c.s));
+    OC_TRY(fetch_scalars(c, w.sc));
+    int64_t start[SB_COUNT + 1];
+    start[0] = 0;
+    for (int b = 0; b < SB_COUNT; ++b) {
+        start[b + 1] = start[b] + (int64_t)c.h->bin_count[b];
+        if (st) st->symbolic_rows_per_bin[b] = (int64_t)c.h->bin_count[b];
+    }
+    for (int b = SB_COUNT - 1; b >= 0; --b) {
+        SymLaunch l{w.bin_rows + start[b], start[b + 1] - start[b], b};
+        if (l.count == 0) continue;
+        const int n_wg = (int)(l.count < c.n_cu ? l.count : c.n_cu);
+        HIP_TRY(launch_symbolic_bin(A, B, l, gb_log2, nnz_out, n_wg, &w.sc->queue[0], c.s));
+    }
+    return OCEAN_OK;
+}
+
+// ---- numeric bins ------------------------------------------------------------------------------------
+// Launches every non-empty bin, largest tables first.  Scratch for the hybrid
+// and global bins is obtained here and kept until the caller releases all.
+int run_numeric(Ctx &c, Work &w, const Csr &A, const Csr &B, int dtype, int gb_log2, const unsigned long long *count,
+                int64_t max_cap_global, double global_coef, const int64_t *out_ptr, int32_t *out_col, void *out_val,
+                int32_t *row_nnz, int queue_base)
+{
+    int64_t start[NB_COUNT + 1];
+    start[0] = 0;
+    for (int b = 0; b < NB_COUNT; ++b) start[b + 1] = start[b] + (int64_t)count[b];
+    const size_t vbytes = dtype == OCEAN_F64 ? 8 : 4;
+    for (int b = NB_COUNT - 1; b >= 0; --b) {
+        NumLaunch l{};
+        l.rows = w.bin_rows + start[b];
+        l.count = start[b + 1] - start[b];
+        l.bin = b;
+        l.out_ptr = out_ptr;
+        l.out_col = out_col;
+        l.out_val = out_val;
+        l.row_nnz = row_nnz;
+        l.coef = global_coef;
+        if (l.count == 0) continue;
+        if (b == NB_HYBRID) {
+            l.n_wg = (int)(l.count < c.n_cu ? l.count : c.n_cu);
+            const size_t bytes = (size_t)l.n_wg * 32768 * vbytes;
+            l.slab = c.alloc(bytes);
+            if (!l.slab) return fail(OCEAN_EALLOC, "value slab allocation failed");
+            HIP_TRY(hipMemsetAsync(l.slab, 0, bytes, c.s));
+            l.queue = &w.sc->queue[queue_base];
+        } else if (b == NB_GLOBAL) {
+            int gbits = 10;
+            while (gbits < 31 && (double)(1ll << gbits) < global_coef * (double)max_cap_global) ++gbits;
+            int n_wg = (int)(l.count < c.n_cu ? l.count : c.n_cu);
+            void *gk = nullptr, *gv = nullptr;
+            for (;;) {
+                const size_t slots = (size_t)n_wg << gbits;
+                gk = c.alloc(slots * 4);
+                gv = gk ? c.alloc(slots * vbytes) : nullptr;
+                if (gk && gv) break;
+                if (gk) c.release(gk);
+                gk = nullptr;
+                if (n_wg == 1) return fail(OCEAN_EALLOC, "global hash table allocation failed");
+                n_wg = n_wg / 2;
+            }
+            const size_t slots = (size_t)n_wg << gbits;
+            HIP_TRY(hipMemsetAsync(gk, 0xFF, slots * 4, c.s));
+            HIP_TRY(hipMemsetAsync(gv, 0, slots * vbytes, c.s));
+            l.gkeys = static_cast<int32_t *>(gk);
+            l.gvals = gv;
+            l.gbits = gbits;
+            l.n_wg = n_wg;
+            l.queue = &w.sc->queue[queue_base + 1];
+        }
+        HIP_TRY(launch_numeric_bin(A, B, dtype, l, gb_log2, c.s));
+    }
+    return OCEAN_OK;
+}
+
+void fill_defaults(ocean_options *o)
+{
+    std::memset(o, 0, sizeof(*o));
+    o->workflow = OCEAN_WF_AUTO;
+    o->hll_registers = 0;
+    o->upper_bound_avg_products = 64.0;
+    o->er_threshold = 8.0;
+    o->cr_threshold = 8.0;
+    o->expand_coef = 0.0;
+    o->exact_load_coef = 1.5;
+    o->sample_ratio = 0.03;
+    o->sample_min = 600;
+    o->sample_max = 10000;
+    o->sample_seed = 1;
+    o->estimate_scale = 1.0;
+    o->validate_inputs = 1;
+    o->allocator = nullptr;
+}
+
+int64_t sample_size_of(int64_t rows, const ocean_options &o)
+{
+    int64_t want = (int64_t)std::ceil(o.sample_ratio * (double)rows);
+    if (want > o.sample_max) want = o.sample_max;
+    if (want < o.sample_min) want = o.sample_min;
+    return want < rows ? want : rows;
+}
+
+void sample_rows_of(int64_t rows, const ocean_options &o, int64_t *out)
+{
+    const int64_t ns = sample_size_of(rows, o);
+    for (int64_t t = 0; t < ns; ++t) {
+        const int64_t lo = (int64_t)((__int128)t * rows / ns);
+        const int64_t hi = (int64_t)((__int128)(t + 1) * rows / ns);
+        const uint32_t h = fmix32_host(o.sample_seed + 0x9E3779B9u * (uint32_t)(t + 1));
+        out[t] = lo + (int64_t)(h % (uint64_t)(hi - lo));
+    }
+}
+
+int registers_of(double er, const ocean_options &o)
+{
+    if (o.hll_registers == 32 || o.hll_registers == 64 || o.hll_registers == 128) return o.hll_registers;
+    return er < 48.0 ? 32 : 64;
+}
+
+int select_of(double avg, double er, double cr, const ocean_options &o)
+{
+    if (avg < o.upper_bound_avg_products) return OCEAN_WF_UPPER_BOUND;
+    if (er >= o.er_threshold && cr >= o.cr_threshold) return OCEAN_WF_HLL;
+    return OCEAN_WF_SYMBOLIC;
+}
+
+// The whole pipeline.  Everything obtained from the allocator is tracked in c;
+// the caller releases what is left on any exit path.
+int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C, const ocean_options &o,
+                ocean_stats *st)
+{
+    const Csr A = view(Ain), B = view(Bin);
+    const int64_t m = A.rows, n = B.cols;
+    const int dtype = Ain->dtype;
+    const size_t vbytes = dtype == OCEAN_F64 ? 8 : 4;
+    C->rows = m;
+    C->cols = n;
+    C->dtype = dtype;
+
+    int64_t *c_rp = static_cast<int64_t *>(c.alloc((size_t)(m + 1) * 8));
+    if (!c_rp) return fail(OCEAN_EALLOC, "row_ptr allocation failed");
+    if (m == 0 || A.nnz == 0 || B.nnz == 0) {
+        HIP_TRY(hipMemsetAsync(c_rp, 0, (size_t)(m + 1) * 8, c.s));
+        HIP_TRY(hipStreamSynchronize(c.s));
+        C->row_ptr = c_rp;
+        c.detach(c_rp);
+        return OCEAN_OK;
+    }
+
+    const int64_t n_sample = sample_size_of(m, o);
+    Work w;
+    OC_TRY(mark(c, OCEAN_ST_ANALYSIS));
+    OC_TRY(work_alloc(c, w, m, n_sample));
+    ocean_stats local{};
+    ocean_stats *S = st ? st : &local;
+    OC_TRY(run_analysis(c, w, A, B, o.validate_inputs != 0, S));
+    const int64_t P = S->products;
+    if (P == 0) {
+        HIP_TRY(hipMemsetAsync(c_rp, 0, (size_t)(m + 1) * 8, c.s));
+        HIP_TRY(hipStreamSynchronize(c.s));
+        C->row_ptr = c_rp;
+        c.detach(c_rp);
+        return OCEAN_OK;
+    }
+    const int gb_log2 = ilog2_ceil_d(S->er, 0, 6);   // lanes sharing one row of B ~ its typical length
+    const int64_t max_ub = S->max_row_products < n ? S->max_row_products : n;
+
+    // ---- workflow choice (Table 1) ----
+    int workflow = o.workflow;
+    int m_regs = 0;
+    uint8_t *sketches = nullptr;
+    auto build_sketches = [&]() -> int {
+        if (sketches) return OCEAN_OK;
+        m_regs = registers_of(S->er, o);
+        sketches = static_cast<uint8_t *>(c.alloc((size_t)B.rows * m_regs));
+        if (!sketches) return fail(OCEAN_EALLOC, "sketch allocation failed");
+        OC_TRY(mark(c, OCEAN_ST_SKETCH));
+        HIP_TRY(launch_hll_sketch(B, m_regs, sketches, c.s));
+        return OCEAN_OK;
+    };
+    if (workflow == OCEAN_WF_AUTO) {
+        if (S->avg_products < o.upper_bound_avg_products) {
+            workflow = OCEAN_WF_UPPER_BOUND;
+        } else {
+            OC_TRY(build_sketches());
+            OC_TRY(mark(c, OCEAN_ST_SAMPLE));
+            std::vector<int64_t> rows_h((size_t)n_sample);
+            sample_rows_of(m, o, rows_h.data());
+            HIP_TRY(hipMemcpyAsync(w.sample_rows, rows_h.data(), (size_t)n_sample * 8, hipMemcpyHostToDevice, c.s));
+            HIP_TRY(launch_hll_merge(A, sketches, m_regs, w.sample_rows, n_sample, w.prod, w.maxb, nullptr, n,
+                                     w.sample_est, nullptr, c.s));
+            HIP_TRY(launch_sample_reduce(w.sample_rows, n_sample, w.prod, w.sample_est, w.sc->sample_sums, c.s));
+            OC_TRY(fetch_scalars(c, w.sc));   // also keeps rows_h alive until the copy is done
+            const double den = c.h->sample_sums[1];
+            S->sampled_cr = den > 0.0 ? c.h->sample_sums[0] / den : 1.0;
+            S->sampled_rows = (int32_t)n_sample;
+            workflow = select_of(S->avg_products, S->er, S->sampled_cr, o);
+        }
+    }
+
+    int32_t *t_col = nullptr;   // output region of the first attempt (C itself on the two-pass path)
+    void *t_val = nullptr;
+    int64_t total_slots = 0;
+    const int64_t *out_ptr = nullptr;
+    for (;;) {   // at most two rounds: an estimation workflow may fall back to the two-pass one when memory is short
+        // ---- size prediction ----
+        OC_TRY(mark(c, OCEAN_ST_PREDICT));
+        BinParams bp{};
+        bp.n_bins = NB_COUNT;
+        for (int b = 0; b < NB_COUNT; ++b) bp.slots[b] = kNumericSlots[b];
+        bp.n_cols = n;
+        double global_coef = 1.25;
+        if (workflow == OCEAN_WF_HLL) {
+            OC_TRY(build_sketches());
+            OC_TRY(mark(c, OCEAN_ST_PREDICT));
+            HIP_TRY(launch_hll_merge(A, sketches, m_regs, nullptr, m, w.prod, w.maxb, nullptr, n, w.est, nullptr, c.s));
+            bp.mode = 1;
+            bp.coef = o.expand_coef > 0.0 ? o.expand_coef : (m_regs == 32 ? 2.0 : 1.5);
+        } else if (workflow == OCEAN_WF_SYMBOLIC) {
+            OC_TRY(run_symbolic(c, w, A, B, gb_log2, w.nnz_final, S));
+            bp.mode = 2;
+            bp.coef = o.exact_load_coef;
+            global_coef = o.exact_load_coef;
+        } else {
+            bp.mode = 0;
+            bp.coef = 1.0;
+        }
+        S->workflow = workflow;
+        S->hll_registers = m_regs;
+
+        // ---- binning + output placement ----
+        OC_TRY(mark(c, OCEAN_ST_BINNING));
+        OC_TRY(zero_bins(c, w));
+        int64_t *ptr = workflow == OCEAN_WF_SYMBOLIC ? c_rp : w.tmp_ptr;
+        HIP_TRY(launch_classify(m, bp, o.estimate_scale, w.prod, w.est, w.nnz_final, nullptr, w.bin, w.cap,
+                                w.sc->bin_count, &w.sc->max_cap, c.s));
+        HIP_TRY(launch_scan_i32_to_i64(w.cap, m, ptr, w.scan_tmp, c.s));
+        HIP_TRY(launch_scatter(m, NB_COUNT, w.bin, w.sc->bin_count, w.sc->bin_cursor, w.bin_rows, c.s));
+        HIP_TRY(hipMemcpyAsync(&w.sc->totals[0], ptr + m, 8, hipMemcpyDeviceToDevice, c.s));   // total slots
+        OC_TRY(fetch_scalars(c, w.sc));
+        total_slots = (int64_t)c.h->totals[0];
+        for (int b = 0; b < NB_COUNT; ++b) S->rows_per_bin[b] = (int64_t)c.h->bin_count[b];
+        t_col = static_cast<int32_t *>(c.alloc((size_t)total_slots * 4));
+        t_val = t_col ? c.alloc((size_t)total_slots * vbytes) : nullptr;
+        if (!t_col || !t_val) {
+            if (t_col) c.release(t_col);
+            t_col = nullptr;
+            if (workflow != OCEAN_WF_SYMBOLIC && o.workflow == OCEAN_WF_AUTO) {
+                // Section 5.2: with too little memory for the estimation workflow, take the two-pass one
+                workflow = OCEAN_WF_SYMBOLIC;
+                S->fell_back = 1;
+                continue;
+            }
+            return fail(OCEAN_EALLOC, "output allocation failed");
+        }
+        out_ptr = ptr;
+        break;
+    }
+    unsigned long long bin_count[OCEAN_MAX_BINS];
+    std::memcpy(bin_count, c.h->bin_count, sizeof(bin_count));
+    const int64_t max_cap = (int64_t)c.h->max_cap;
+    double global_coef = workflow == OCEAN_WF_SYMBOLIC ? o.exact_load_coef : 1.25;
+
+    // ---- numeric ----
+    OC_TRY(mark(c, OCEAN_ST_NUMERIC));
+    HIP_TRY(launch_fill_i32(w.row_nnz, m, 0, c.s));
+    OC_TRY(run_numeric(c, w, A, B, dtype, gb_log2, bin_count, max_cap, global_coef, out_ptr, t_col, t_val, w.row_nnz, 0));
+
+    if (workflow == OCEAN_WF_SYMBOLIC) {
+        OC_TRY(mark(c, -1));
+        HIP_TRY(hipStreamSynchronize(c.s));
+        S->nnz_c = total_slots;
+        C->row_ptr = c_rp;
+        C->col_idx = t_col;
+        C->val = t_val;
+        C->nnz = total_slots;
+        c.detach(c_rp);
+        c.detach(t_col);
+        c.detach(t_val);
+        return OCEAN_OK;
+    }
+
+    // ---- overflow rows: redo them with bound-sized tables (Section 3.2) ----
+    S->temp_slots = total_slots;
+    OC_TRY(mark(c, OCEAN_ST_RETRY));
+    HIP_TRY(launch_count_overflow(m, w.row_nnz, &w.sc->ovf_count, c.s));
+    // optimistic: if nothing overflowed this scan already is the final row_ptr
+    HIP_TRY(launch_scan_i32_to_i64(w.row_nnz, m, c_rp, w.scan_tmp, c.s));
+    HIP_TRY(hipMemcpyAsync(&w.sc->totals[0], c_rp + m, 8, hipMemcpyDeviceToDevice, c.s));
+    OC_TRY(fetch_scalars(c, w.sc));
+    const int64_t n_ovf = (int64_t)c.h->ovf_count;
+    S->overflow_rows = n_ovf;
+    int64_t nnz_c = (int64_t)c.h->totals[0];
+    const int32_t *final_nnz = w.row_nnz;
+    int32_t *r_col = nullptr;
+    void *r_val = nullptr;
+    if (n_ovf > 0) {
+        BinParams bp{};
+        bp.mode = 0;
+        bp.coef = 1.0;
+        bp.n_bins = NB_COUNT;
+        for (int b = 0; b < NB_COUNT; ++b) bp.slots[b] = kNumericSlots[b];
+        bp.n_cols = n;
+        OC_TRY(zero_bins(c, w));
+        HIP_TRY(launch_classify(m, bp, 1.0, w.prod, nullptr, nullptr, w.row_nnz, w.bin, w.cap, w.sc->bin_count,
+                                &w.sc->max_cap, c.s));
+        HIP_TRY(launch_scan_i32_to_i64(w.cap, m, w.tmp_ptr2, w.scan_tmp, c.s));
+        HIP_TRY(launch_scatter(m, NB_COUNT, w.bin, w.sc->bin_count, w.sc->bin_cursor, w.bin_rows, c.s));
+        HIP_TRY(hipMemcpyAsync(&w.sc->totals[0], w.tmp_ptr2 + m, 8, hipMemcpyDeviceToDevice, c.s));
+        OC_TRY(fetch_scalars(c, w.sc));
+        const int64_t slots2 = (int64_t)c.h->totals[0];
+        r_col = static_cast<int32_t *>(c.alloc((size_t)slots2 * 4));
+        r_val = r_col ? c.alloc((size_t)slots2 * vbytes) : nullptr;
+        if (!r_col || !r_val) return fail(OCEAN_EALLOC, "retry output allocation failed");
+        unsigned long long bc2[OCEAN_MAX_BINS];
+        std::memcpy(bc2, c.h->bin_count, sizeof(bc2));
+        HIP_TRY(launch_fill_i32(w.row_nnz2, m, 0, c.s));
+        OC_TRY(run_numeric(c, w, A, B, dtype, gb_log2, bc2, (int64_t)c.h->max_cap, 1.25, w.tmp_ptr2, r_col, r_val,
+                           w.row_nnz2, 2));
+        HIP_TRY(launch_final_nnz(m, w.row_nnz, w.row_nnz2, w.nnz_final, c.s));
+        HIP_TRY(launch_scan_i32_to_i64(w.nnz_final, m, c_rp, w.scan_tmp, c.s));
+        HIP_TRY(hipMemcpyAsync(&w.sc->totals[0], c_rp + m, 8, hipMemcpyDeviceToDevice, c.s));
+        OC_TRY(fetch_scalars(c, w.sc));
+        nnz_c = (int64_t)c.h->totals[0];
+        final_nnz = w.nnz_final;
+    }
+    (void)final_nnz;
+    (void)max_ub;
+
+    // ---- compaction ----
+    OC_TRY(mark(c, OCEAN_ST_COMPACT));
+    int32_t *c_col = static_cast<int32_t *>(c.alloc((size_t)nnz_c * 4));
+    void *c_val = c_col ? c.alloc((size_t)nnz_c * vbytes) : nullptr;
+    if (!c_col || !c_val) return fail(OCEAN_EALLOC, "output allocation failed");
+    const int g_log2 = ilog2_ceil_d((double)nnz_c / (double)m, 2, 6);
+    HIP_TRY(launch_compact(m, dtype, c_rp, w.row_nnz, out_ptr, t_col, t_val, w.tmp_ptr2, r_col, r_val, c_col, c_val,
+                           g_log2, c.s));
+    OC_TRY(mark(c, -1));
+    HIP_TRY(hipStreamSynchronize(c.s));
+    S->nnz_c = nnz_c;
+    C->row_ptr = c_rp;
+    C->col_idx = c_col;
+    C->val = c_val;
+    C->nnz = nnz_c;
+    c.detach(c_rp);
+    c.detach(c_col);
+    c.detach(c_val);
+    return OCEAN_OK;
+}
+
+}  // namespace
+
+// =====================================================================================================
+extern "C" {
+
+void ocean_default_options(ocean_options *opt)
+{
+    if (opt) fill_defaults(opt);
+}
+
+int ocean_spgemm(const ocean_csr *A, const ocean_csr *B, ocean_csr *C, const ocean_options *opt, ocean_stats *stats,
+                 ocean_stream_t stream)
+{
+    g_err.clear();
+    if (!C) return fail(OCEAN_EINVAL, "C is null");
+    std::memset(C, 0, sizeof(*C));
+    if (stats) std::memset(stats, 0, sizeof(*stats));
+    OC_TRY(check_csr(A, "A"));
+    OC_TRY(check_csr(B, "B"));
+    if (A->cols != B->rows) return fail(OCEAN_EINVAL, "A.cols != B.rows");
+    if (A->dtype != B->dtype) return fail(OCEAN_EINVAL, "A and B differ in dtype");
+    if ((A->nnz > 0 && !A->val) || (B->nnz > 0 && !B->val)) return fail(OCEAN_EINVAL, "val is null");
+    ocean_options o;
+    if (opt) o = *opt;
+    else fill_defaults(&o);
+    if (o.workflow < OCEAN_WF_AUTO || o.workflow > OCEAN_WF_SYMBOLIC) return fail(OCEAN_EINVAL, "unknown workflow");
+    if (o.hll_registers != 0 && o.hll_registers != 32 && o.hll_registers != 64 && o.hll_registers != 128)
+        return fail(OCEAN_EINVAL, "hll_registers must be 0, 32, 64 or 128");
+    if (!(o.estimate_scale > 0.0) || !(o.exact_load_coef >= 1.0) || o.expand_coef < 0.0 || !(o.sample_ratio >= 0.0) ||
+        o.sample_min < 1 || o.sample_max < o.sample_min)
+        return fail(OCEAN_EINVAL, "option out of range");
+    const auto t0 = std::chrono::steady_clock::now();
+    Ctx c;
+    OC_TRY(ctx_init(c, &o, stream));
+    int rc = spgemm_impl(c, A, B, C, o, stats);
+    if (rc != OCEAN_OK) {
+        (void)hipStreamSynchronize(c.s);
+        std::memset(C, 0, sizeof(*C));
+    } else {
+        collect_times(c, stats);
+    }
+    c.release_all();
+    if (stats) {
+        stats->peak_bytes = (int64_t)c.peak;
+        stats->total_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    }
+    return rc;
+}
+
+int ocean_csr_release(ocean_csr *C, const ocean_allocator *allocator)
+{
+    if (!C) return fail(OCEAN_EINVAL, "C is null");
+    void *ptrs[3] = {C->row_ptr, C->col_idx, C->val};
+    for (void *p : ptrs) {
+        if (!p) continue;
+        if (allocator && allocator->release) allocator->release(allocator->ctx, p);
+        else (void)hipFree(p);
+    }
+    std::memset(C, 0, sizeof(*C));
+    return OCEAN_OK;
+}
+
+int ocean_row_products(const ocean_csr *A, const ocean_csr *B, int64_t *prod, int64_t *total, int64_t *max_row,
+                       ocean_stream_t stream)
+{
+    g_err.clear();
+    OC_TRY(check_csr(A, "A"));
+    OC_TRY(check_csr(B, "B"));
+    if (A->cols != B->rows) return fail(OCEAN_EINVAL, "A.cols != B.rows");
+    if (!prod && A->rows > 0) return fail(OCEAN_EINVAL, "prod is null");
+    Ctx c;
+    OC_TRY(ctx_init(c, nullptr, stream));
+    const size_t mm = (size_t)(A->rows > 0 ? A->rows : 1);
+    char *buf = static_cast<char *>(c.alloc(up(sizeof(Scalars)) + mm * 4));
+    if (!buf) return fail(OCEAN_EALLOC, "workspace allocation failed");
+    Scalars *sc = reinterpret_cast<Scalars *>(buf);
+    int32_t *maxb = reinterpret_cast<int32_t *>(buf + up(sizeof(Scalars)));
+    int rc = [&]() -> int {
+        HIP_TRY(hipMemsetAsync(sc, 0, sizeof(Scalars), c.s));
+        HIP_TRY(launch_row_products(view(A), B->row_ptr, B->rows, prod, maxb, sc->totals, &sc->flags, c.s));
+        OC_TRY(fetch_scalars(c, sc));
+        if (c.h->flags & 4) return fail(OCEAN_EINVAL, "a column id of A is outside [0, rows(B))");
+        if (total) *total = (int64_t)c.h->totals[0];
+        if (max_row) *max_row = (int64_t)c.h->totals[1];
+        return OCEAN_OK;
+    }();
+    (void)hipStreamSynchronize(c.s);
+    c.release_all();
+    return rc;
+}
+
+int ocean_hll_sketch_rows(const ocean_csr *B, int32_t m, uint8_t *sketches, ocean_stream_t stream)
+{
+    g_err.clear();
+    OC_TRY(check_csr(B, "B"));
+    if (m != 32 && m != 64 && m != 128) return fail(OCEAN_EINVAL, "m must be 32, 64 or 128");
+    if (!sketches && B->rows > 0) return fail(OCEAN_EINVAL, "sketches is null");
+    HIP_TRY(launch_hll_sketch(view(B), m, sketches, static_cast<hipStream_t>(stream)));
+    return OCEAN_OK;
+}
+
+int ocean_hll_merge_estimate(const ocean_csr *A, const uint8_t *sketches, int32_t m, const int64_t *rows,
+                             int64_t n_rows, const int64_t *prod, const int64_t *b_row_ptr, int64_t b_cols,
+                             double *est, uint8_t *merged, ocean_stream_t stream)
+{
+    g_err.clear();
+    OC_TRY(check_csr(A, "A"));
+    if (m != 32 && m != 64 && m != 128) return fail(OCEAN_EINVAL, "m must be 32, 64 or 128");
+    if (n_rows < 0 || (!rows && n_rows != A->rows)) return fail(OCEAN_EINVAL, "n_rows must equal A.rows when rows is null");
+    if (n_rows > 0 && (!sketches || !est)) return fail(OCEAN_EINVAL, "sketches / est is null");
+    if (prod && !b_row_ptr) return fail(OCEAN_EINVAL, "b_row_ptr is needed to limit the estimates");
+    HIP_TRY(launch_hll_merge(view(A), sketches, m, rows, n_rows, prod, nullptr, prod ? b_row_ptr : nullptr, b_cols, est,
+                             merged, static_cast<hipStream_t>(stream)));
+    return OCEAN_OK;
+}
+
+int ocean_symbolic(const ocean_csr *A, const ocean_csr *B, int32_t *nnz_per_row, const ocean_options *opt,
+                   ocean_stats *stats, ocean_stream_t stream)
+{
+    g_err.clear();
+    if (stats) std::memset(stats, 0, sizeof(*stats));
+    OC_TRY(check_csr(A, "A"));
+    OC_TRY(check_csr(B, "B"));
+    if (A->cols != B->rows) return fail(OCEAN_EINVAL, "A.cols != B.rows");
+    if (!nnz_per_row && A->rows > 0) return fail(OCEAN_EINVAL, "nnz_per_row is null");
+    if (A->rows == 0) return OCEAN_OK;
+    ocean_options o;
+    if (opt) o = *opt;
+    else fill_defaults(&o);
+    Ctx c;
+    OC_TRY(ctx_init(c, &o, stream));
+    ocean_stats local{};
+    ocean_stats *S = stats ? stats : &local;
+    int rc = [&]() -> int {
+        Work w;
+        OC_TRY(work_alloc(c, w, A->rows, 0));
+        const Csr a = view(A), b = view(B);
+        OC_TRY(run_analysis(c, w, a, b, o.validate_inputs != 0, S));
+        const int gb_log2 = ilog2_ceil_d(S->er, 0, 6);
+        OC_TRY(run_symbolic(c, w, a, b, gb_log2, nnz_per_row, S));
+        HIP_TRY(hipStreamSynchronize(c.s));
+        return OCEAN_OK;
+    }();
+    if (rc != OCEAN_OK) (void)hipStreamSynchronize(c.s);
+    c.release_all();
+    if (stats) stats->peak_bytes = (int64_t)c.peak;
+    return rc;
+}
+
+int32_t ocean_select_workflow(double avg_products, double er, double cr, const ocean_options *opt)
+{
+    ocean_options o;
+    if (opt) o = *opt;
+    else fill_defaults(&o);
+    return select_of(avg_products, er, cr, o);
+}
+
+int32_t ocean_hll_register_count(double er, const ocean_options *opt)
+{
+    ocean_options o;
+    if (opt) o = *opt;
+    else fill_defaults(&o);
+    return registers_of(er, o);
+}
+
+int64_t ocean_sample_size(int64_t rows, const ocean_options *opt)
+{
+    ocean_options o;
+    if (opt) o = *opt;
+    else fill_defaults(&o);
+    return rows <= 0 ? 0 : sample_size_of(rows, o);
+}
+
+int ocean_sample_rows(int64_t rows, const ocean_options *opt, int64_t *rows_out)
+{
+    ocean_options o;
+    if (opt) o = *opt;
+    else fill_defaults(&o);
+    if (rows <= 0) return OCEAN_OK;
+    if (!rows_out) return fail(OCEAN_EINVAL, "rows_out is null");
+    sample_rows_of(rows, o, rows_out);
+    return OCEAN_OK;
+}
+
+int ocean_bin_layout(int32_t *numeric_slots, int32_t *n_numeric, int32_t *symbolic_slots, int32_t *n_symbolic)
+{
+    if (n_numeric) *n_numeric = NB_COUNT;
+    if (n_symbolic) *n_symbolic = SB_COUNT;
+    for (int b = 0; b < OCEAN_MAX_BINS; ++b) {
+        if (numeric_slots) numeric_slots[b] = b < NB_COUNT ? kNumericSlots[b] : 0;
+        if (symbolic_slots) symbolic_slots[b] = b < SB_COUNT ? kSymbolicSlots[b] : 0;
+    }
+    return OCEAN_OK;
+}
+
+const char *ocean_last_error(void) { return g_err.c_str(); }
+
+int ocean_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,173 @@
+// Internal declarations shared by the HIP translation units of the library.
+// gfx950 only: wave64, 160 KB LDS per workgroup, native LDS/global fp64 atomic add.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ocean_spgemm.h"
+
+namespace ocean {
+
+constexpr int WAVE = 64;
+constexpr int32_t EMPTY_KEY = -1;          // column ids are >= 0
+constexpr int32_t SORT_PAD = 0x7fffffff;   // sorts after every valid column id
+
+// ---------------------------------------------------------------- bins ----
+// Numeric bins (Section 4.3 uses five halving configurations plus a
+// multi-short-row and a long-row one; the sizes here are re-derived for 160 KB
+// of LDS and 64-wide waves).  slots = hash-table entries of the bin.
+enum NumericBin {
+    NB_G16 = 0,   // 16 lanes per row, 4 rows per wave, 64 slots
+    NB_W64,       // one wave per row, 256 slots
+    NB_S512,      // one workgroup per row from here on
+    NB_S1K,
+    NB_S2K,
+    NB_S4K,
+    NB_S8K,       // largest table with keys and values both in LDS
+    NB_HYBRID,    // 32768 keys in LDS, values in a global slab (Section 3.3, enhanced hash accumulator)
+    NB_GLOBAL,    // whole table in global memory
+    NB_COUNT
+};
+constexpr int32_t kNumericSlots[NB_COUNT] = {64, 256, 512, 1024, 2048, 4096, 8192, 32768, 0x7fffffff};
+
+enum SymbolicBin {
+    SB_G16 = 0,   // 64 keys
+    SB_W64,       // 256 keys
+    SB_S1K,
+    SB_S4K,
+    SB_S16K,
+    SB_S32K,      // 128 KB of keys
+    SB_BITMAP,    // LDS bitmap over column windows
+    SB_COUNT
+};
+constexpr int32_t kSymbolicSlots[SB_COUNT] = {64, 256, 1024, 4096, 16384, 32768, 0x7fffffff};
+
+constexpr int32_t BIN_NONE = 255;          // row takes no part in this launch set
+
+// ------------------------------------------------------------- CSR view ----
+struct Csr {
+    const int64_t *rp;
+    const int32_t *col;
+    const void *val;
+    int64_t rows, cols, nnz;
+};
+
+// ------------------------------------------------------ device helpers ----
+#if defined(__HIPCC__)
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (WAVE - 1)); }
+
+// Orders this wave's LDS/global accesses for the compiler; the hardware runs a
+// wave's LDS instructions in issue order, so lanes of one wave see each
+// other's earlier writes after this point.
+__device__ __forceinline__ void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+__device__ __forceinline__ uint32_t fmix32(uint32_t h)
+{
+    h ^= h >> 16;
+    h *= 0x85EBCA6Bu;
+    h ^= h >> 13;
+    h *= 0xC2B2AE35u;
+    h ^= h >> 16;
+    return h;
+}
+
+// Hash used by the HLL sketches (the same function must build every sketch
+// that is merged, Section 3.1).
+__device__ __forceinline__ uint32_t hll_hash(int32_t col) { return fmix32((uint32_t)col + 0x9E3779B9u); }
+
+// Fibonacci hashing for the accumulator tables: top `bits` bits of key * golden ratio.
+__device__ __forceinline__ uint32_t table_hash(int32_t key, int bits)
+{
+    return ((uint32_t)key * 0x9E3779B1u) >> (32 - bits);
+}
+
+template <typename T>
+__device__ __forceinline__ T group_reduce_sum(T v, int width)
+{
+    for (int off = width >> 1; off > 0; off >>= 1) v += __shfl_xor(v, off, WAVE);
+    return v;
+}
+template <typename T>
+__device__ __forceinline__ T group_reduce_max(T v, int width)
+{
+    for (int off = width >> 1; off > 0; off >>= 1) {
+        T o = __shfl_xor(v, off, WAVE);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+#endif
+
+// --------------------------------------------------- launcher prototypes ----
+// analysis.hip
+hipError_t launch_validate(const Csr &A, const Csr &B, int32_t *flags, hipStream_t s);
+hipError_t launch_row_products(const Csr &A, const int64_t *b_rp, int64_t b_rows, int64_t *prod, int32_t *maxb,
+                               unsigned long long *totals /*[0]=P,[1]=max*/, int32_t *flags, hipStream_t s);
+hipError_t launch_hll_sketch(const Csr &B, int m, uint8_t *sketches, hipStream_t s);
+hipError_t launch_hll_merge(const Csr &A, const uint8_t *sketches, int m, const int64_t *rows, int64_t n_rows,
+                            const int64_t *prod, const int32_t *maxb, const int64_t *b_rp, int64_t b_cols,
+                            double *est, uint8_t *merged, hipStream_t s);
+hipError_t launch_sample_reduce(const int64_t *rows, int64_t n_rows, const int64_t *prod, const double *est,
+                                double *out /*[0]=sum prod,[1]=sum est*/, hipStream_t s);
+
+// binning.hip
+struct BinParams {
+    int mode;            // 0 upper bound, 1 estimate, 2 exact nnz, 3 symbolic pass (see k_classify)
+    double coef;         // table slots per predicted entry
+    int n_bins;
+    int32_t slots[OCEAN_MAX_BINS];
+    int64_t n_cols;
+};
+hipError_t launch_classify(int64_t m, const BinParams &p, double scale, const int64_t *prod, const double *est,
+                           const int32_t *nnz_exact, const int32_t *row_mask, uint8_t *bin_of_row, int32_t *cap,
+                           unsigned long long *bin_count, unsigned long long *max_cap, hipStream_t s);
+hipError_t launch_scatter(int64_t m, int n_bins, const uint8_t *bin_of_row, const unsigned long long *bin_count,
+                          unsigned long long *bin_cursor, int32_t *bin_rows, hipStream_t s);
+hipError_t launch_scan_i32_to_i64(const int32_t *in, int64_t n, int64_t *out /*n+1*/, int64_t *block_tmp,
+                                  hipStream_t s);
+int64_t scan_tmp_elems(int64_t n);
+hipError_t launch_fill_i32(int32_t *p, int64_t n, int32_t v, hipStream_t s);
+hipError_t launch_fill_u64(unsigned long long *p, int64_t n, unsigned long long v, hipStream_t s);
+hipError_t launch_count_overflow(int64_t m, const int32_t *row_nnz, unsigned long long *count, hipStream_t s);
+hipError_t launch_final_nnz(int64_t m, const int32_t *nnz1, const int32_t *nnz2, int32_t *out, hipStream_t s);
+
+// symbolic.hip
+struct SymLaunch {
+    const int32_t *rows;   // row ids of this bin
+    int64_t count;
+    int bin;
+};
+hipError_t launch_symbolic_bin(const Csr &A, const Csr &B, const SymLaunch &l, int gb_log2, int32_t *nnz_out,
+                               int n_wg, unsigned long long *queue, hipStream_t s);
+
+// numeric.hip
+struct NumLaunch {
+    const int32_t *rows;
+    int64_t count;
+    int bin;
+    const int64_t *out_ptr;   // [m+1]: start of each row's output region; capacity = out_ptr[i+1]-out_ptr[i]
+    int32_t *out_col;
+    void *out_val;
+    int32_t *row_nnz;         // written per row: entries produced, or -1 on overflow
+    // scratch of NB_HYBRID / NB_GLOBAL
+    void *slab;               // hybrid: n_wg slabs of 32768 values, all zero on entry and on exit
+    int32_t *gkeys;           // global: n_wg tables of 2^gbits keys, all EMPTY on entry and on exit
+    void *gvals;              // global: n_wg tables of 2^gbits values, all zero on entry and on exit
+    int gbits;
+    int n_wg;                 // persistent workgroups of the hybrid / global kernels
+    unsigned long long *queue; // their shared row counter, zero on entry
+    double coef;              // global: table slots per reserved output entry
+};
+hipError_t launch_numeric_bin(const Csr &A, const Csr &B, int dtype, const NumLaunch &l, int gb_log2, hipStream_t s);
+
+// compact.hip
+hipError_t launch_compact(int64_t m, int dtype, const int64_t *c_rp, const int32_t *nnz1, const int64_t *ptr1,
+                          const int32_t *col1, const void *val1, const int64_t *ptr2, const int32_t *col2,
+                          const void *val2, int32_t *c_col, void *c_val, int g_log2, hipStream_t s);
+
+}  // namespace ocean

@@ -1,0 +1,229 @@
+"""GPU parity tests: every stage of the HIP path, called through the C ABI,
+against the CPU oracle on the same seeded inputs.  Structure (row_ptr, col_idx)
+must be bit-exact; values must satisfy |c - c_ref| <= tol * sum_k |a_ik*b_kj|
+with tol = 1e-12 for fp64 and 1e-5 for fp32."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import hll as ohll
+from oracle import spgemm as O
+from oracle import workflow as owf
+from paper_2604_19004_amd import workloads as W
+from paper_2604_19004_amd.workloads import CSR
+
+pytestmark = pytest.mark.gpu
+
+TOL = {np.dtype(np.float64): 1e-12, np.dtype(np.float32): 1e-5}
+
+
+@pytest.fixture(scope="module")
+def ob():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2604_19004_amd import binding
+    binding.load()
+    return binding
+
+
+_cache = {}
+
+
+def workload(name, small):
+    key = (name, small)
+    if key not in _cache:
+        A, B, _ = W.make(name, small=small)
+        _cache[key] = (A, B, O.multiply_rows(A, B), O.row_products(A, B))
+    return _cache[key]
+
+
+def check_result(Cd, ref, A, label=""):
+    rp = Cd.row_ptr.cpu().numpy()
+    col = Cd.col_idx.cpu().numpy()
+    val = Cd.val.cpu().numpy()
+    assert rp.dtype == np.int64 and col.dtype == np.int32
+    assert np.array_equal(rp, ref.row_ptr), f"{label}: row_ptr differs"
+    assert np.array_equal(col, ref.col_idx), f"{label}: col_idx differs"
+    tol = TOL[np.dtype(A.val.dtype)]
+    err = np.abs(val.astype(np.float64) - ref.val)
+    bound = tol * ref.absval
+    bad = np.nonzero(err > bound)[0]
+    assert bad.size == 0, f"{label}: {bad.size} values off, worst ratio {np.max(err[bad] / np.maximum(bound[bad], 1e-300))}"
+
+
+# ------------------------------------------------------------------ stages
+@pytest.mark.parametrize("name", ["er", "laplacian", "rmat", "rect", "clustered"])
+def test_row_products(ob, name):
+    A, B, ref, prod = workload(name, True)
+    dA, dB = ob.to_device(A), ob.to_device(B)
+    p, total, mx = ob.row_products(dA, dB)
+    assert np.array_equal(p.cpu().numpy(), prod)
+    assert total == int(prod.sum()) and mx == int(prod.max())
+
+
+@pytest.mark.parametrize("name", ["er", "rmat", "rect"])
+@pytest.mark.parametrize("m", [32, 64, 128])
+def test_hll_sketch_merge_estimate(ob, name, m):
+    import torch
+    A, B, ref, prod = workload(name, True)
+    dA, dB = ob.to_device(A), ob.to_device(B)
+    S = ob.hll_sketch_rows(dB, m)
+    S_ref = ohll.sketch_rows(B, m)
+    assert np.array_equal(S.cpu().numpy(), S_ref)                       # byte-exact sketches
+    est, merged = ob.hll_merge_estimate(dA, S, m, want_merged=True)
+    merged_ref = ohll.merge_rows(A, S_ref)
+    assert np.array_equal(merged.cpu().numpy(), merged_ref)
+    np.testing.assert_allclose(est.cpu().numpy(), ohll.estimate(merged_ref), rtol=1e-12, atol=0)
+    # limited estimates + a row subset
+    rows = np.arange(0, A.rows, 7, dtype=np.int64)
+    est2, _ = ob.hll_merge_estimate(dA, S, m, rows=torch.from_numpy(rows).cuda(), prod=torch.from_numpy(prod).cuda(), B=dB)
+    np.testing.assert_allclose(est2.cpu().numpy(), ohll.estimate_rows(A, B, m, rows=rows), rtol=1e-12, atol=0)
+
+
+@pytest.mark.parametrize("name", ["er", "laplacian", "rmat", "rect", "clustered"])
+def test_symbolic_exact(ob, name):
+    A, B, ref, prod = workload(name, True)
+    nnz, st = ob.symbolic(ob.to_device(A), ob.to_device(B))
+    assert np.array_equal(nnz.cpu().numpy().astype(np.int64), np.diff(ref.row_ptr))
+    assert st["products"] == int(prod.sum())
+
+
+def test_host_helpers_match_oracle(ob):
+    for rows in (1, 100, 4096, 200000, 1 << 20):
+        assert ob.sample_size(rows) == owf.sample_size(rows)
+        assert np.array_equal(ob.sample_rows(rows, ob.default_options(sample_seed=5)), owf.sample_rows(rows, 5))
+    for avg, er, cr in [(63.9, 100, 100), (64, 8, 8), (64, 7.99, 8), (64, 8, 7.99), (1e6, 1e6, 1.0)]:
+        assert ob.select_workflow(avg, er, cr) == owf.select_workflow(avg, er, cr)
+    for er in (1.0, 47.99, 48.0, 1300.0):
+        assert ob.hll_register_count(er) == owf.hll_registers(er)
+
+
+# ------------------------------------------------------------ whole path
+WORKFLOWS = ["upper_bound", "hll", "symbolic", "auto"]
+
+
+def wf_id(ob, name):
+    return {"auto": ob.WF_AUTO, "upper_bound": ob.WF_UPPER_BOUND, "hll": ob.WF_HLL, "symbolic": ob.WF_SYMBOLIC}[name]
+
+
+@pytest.mark.parametrize("wf", WORKFLOWS)
+@pytest.mark.parametrize("name", ["er", "laplacian", "rmat", "rect", "clustered"])
+def test_spgemm_small(ob, name, wf):
+    A, B, ref, prod = workload(name, True)
+    Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(B), workflow=wf_id(ob, wf))
+    check_result(Cd, ref, A, f"{name}/{wf}")
+    assert st["products"] == int(prod.sum()) and st["nnz_c"] == int(ref.row_ptr[-1])
+    if wf != "auto":
+        assert st["workflow"] == wf
+    else:
+        # the analysis step must agree with the oracle's reading of Table 1
+        avg, er = prod.sum() / A.rows, prod.sum() / A.nnz
+        if avg < 64:
+            assert st["workflow"] == "upper_bound"
+        else:
+            m = owf.hll_registers(er)
+            rows = owf.sample_rows(A.rows, 1)
+            cr = owf.sampled_cr(prod[rows].astype(np.float64), ohll.estimate_rows(A, B, m, rows=rows))
+            assert st["sampled_cr"] == pytest.approx(cr, rel=1e-9)
+            assert st["workflow"] == {owf.HLL: "hll", owf.SYMBOLIC: "symbolic"}[owf.select_workflow(avg, er, cr)]
+            assert st["hll_registers"] == m
+
+
+@pytest.mark.parametrize("scale", [0.25, 0.6])
+@pytest.mark.parametrize("name", ["rmat", "rect", "clustered"])
+def test_overflow_retry_is_exact(ob, name, scale):
+    A, B, ref, prod = workload(name, True)
+    Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(B), workflow=ob.WF_HLL, estimate_scale=scale)
+    check_result(Cd, ref, A, f"{name}/hll scale {scale}")
+    if scale <= 0.25:
+        assert st["overflow_rows"] > 0
+
+
+@pytest.mark.parametrize("regs", [32, 64, 128])
+def test_forced_register_counts(ob, regs):
+    A, B, ref, prod = workload("clustered", True)
+    Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(B), workflow=ob.WF_HLL, hll_registers=regs)
+    check_result(Cd, ref, A, f"clustered/hll m={regs}")
+    assert st["hll_registers"] == regs
+
+
+@pytest.mark.parametrize("wf", ["upper_bound", "hll", "symbolic"])
+def test_full_size_er_and_laplacian(ob, wf):
+    for name in ("er", "laplacian"):
+        A, B, ref, prod = workload(name, False)
+        Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(B), workflow=wf_id(ob, wf))
+        check_result(Cd, ref, A, f"{name}/{wf}")
+        if name == "laplacian":
+            # all products are small integers: values are exact
+            assert np.array_equal(Cd.val.cpu().numpy(), ref.val)
+
+
+def test_structure_is_identical_across_runs(ob):
+    A, B, ref, prod = workload("rmat", True)
+    dA, dB = ob.to_device(A), ob.to_device(B)
+    first, _ = ob.spgemm(dA, dB, workflow=ob.WF_HLL)
+    for _ in range(3):
+        again, _ = ob.spgemm(dA, dB, workflow=ob.WF_HLL)
+        assert np.array_equal(first.col_idx.cpu().numpy(), again.col_idx.cpu().numpy())
+        assert np.array_equal(first.row_ptr.cpu().numpy(), again.row_ptr.cpu().numpy())
+
+
+# ------------------------------------------------------------ edge cases
+def _csr(rows, cols, rp, ci, v, dtype=np.float64):
+    return CSR(rows, cols, np.asarray(rp, np.int64), np.asarray(ci, np.int32), np.asarray(v, dtype))
+
+
+@pytest.mark.parametrize("wf", ["upper_bound", "hll", "symbolic", "auto"])
+def test_edge_cases(ob, wf):
+    cases = {
+        "1x1": (_csr(1, 1, [0, 1], [0], [3.0]), _csr(1, 1, [0, 1], [0], [-2.0])),
+        "A empty": (_csr(3, 4, [0, 0, 0, 0], [], []), _csr(4, 5, [0, 1, 2, 3, 4], [0, 1, 2, 3], [1., 2., 3., 4.])),
+        "B empty": (_csr(2, 3, [0, 2, 3], [0, 2, 1], [1., 2., 3.]), _csr(3, 6, [0, 0, 0, 0], [], [])),
+        "zero rows": (_csr(0, 3, [0], [], []), _csr(3, 2, [0, 1, 1, 2], [0, 1], [1., 1.])),
+        "products but empty rows": (_csr(3, 3, [0, 1, 1, 2], [1, 0], [2., 5.]), _csr(3, 4, [0, 2, 2, 3], [0, 3, 1], [1., 1., 1.])),
+        "cancellation": (_csr(1, 2, [0, 2], [0, 1], [1., -1.]), _csr(2, 3, [0, 1, 3], [0, 0, 2], [1., 1., 7.])),
+        "duplicates unsorted": (_csr(1, 2, [0, 2], [1, 1], [2., 3.]), _csr(2, 4, [0, 0, 3], [3, 0, 3], [1., 10., 100.])),
+        "fp32": (_csr(2, 2, [0, 2, 3], [0, 1, 1], [.5, .25, 2.], np.float32), _csr(2, 3, [0, 1, 3], [2, 0, 1], [4., 8., 16.], np.float32)),
+    }
+    # one row reaching every column through a full row of B, plus rows of very different sizes
+    n = 3000
+    full_B = _csr(4, n, [0, n, n + 1, n + 1, n + 3], list(range(n)) + [5] + [7, n - 1], np.ones(n + 3))
+    cases["dense row"] = (_csr(3, 4, [0, 2, 3, 5], [0, 3, 1, 1, 3], [1., 2., 3., 4., 5.]), full_B)
+    for label, (A, B) in cases.items():
+        ref = O.multiply_rows(A, B)
+        Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(B), workflow=wf_id(ob, wf))
+        assert (Cd.rows, Cd.cols) == (A.rows, B.cols)
+        check_result(Cd, ref, A, f"{label}/{wf}")
+
+
+def test_heavy_rows_reach_hybrid_and_global_bins(ob):
+    # a few rows of A that reference many long rows of B: their outputs exceed every LDS table
+    rng = np.random.default_rng(11)
+    n = 1 << 18
+    Bm = W.erdos_renyi(4096, 64, seed=12, cols=n)
+    rows_spec = [3000, 900, 350, 120, 30, 4, 1, 0]          # entries per row of A -> ~190k .. 0 outputs
+    rp = np.concatenate([[0], np.cumsum(rows_spec)]).astype(np.int64)
+    ci = np.concatenate([np.sort(rng.choice(4096, k, replace=False)) for k in rows_spec]).astype(np.int32)
+    A = CSR(len(rows_spec), 4096, rp, ci, rng.uniform(-1, 1, ci.size))
+    ref = O.multiply_rows(A, Bm)
+    for wf in ("symbolic", "hll", "upper_bound"):
+        Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(Bm), workflow=wf_id(ob, wf))
+        check_result(Cd, ref, A, f"heavy/{wf}")
+        assert st["rows_per_bin"][8] > 0                                    # global bin used
+        assert st["rows_per_bin"][7] > 0                                    # hybrid bin used
+    Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(Bm), workflow=ob.WF_HLL, estimate_scale=0.3)
+    check_result(Cd, ref, A, "heavy/hll overflow")
+    assert st["overflow_rows"] > 0
+
+
+def test_invalid_arguments_are_rejected(ob):
+    A = _csr(2, 3, [0, 1, 2], [0, 5], [1., 1.])          # column id 5 outside 3 columns
+    B = _csr(3, 2, [0, 1, 1, 2], [0, 1], [1., 1.])
+    with pytest.raises(ob.OceanError) as e:
+        ob.spgemm(ob.to_device(A), ob.to_device(B))
+    assert e.value.code == 1
+    with pytest.raises(ob.OceanError):
+        ob.spgemm(ob.to_device(B), ob.to_device(B))     # inner dimensions differ
+    with pytest.raises(ob.OceanError):
+        ob.spgemm(ob.to_device(B), ob.to_device(_csr(2, 2, [0, 1, 2], [0, 1], [1., 1.], np.float32)))   # dtype mix
