@@ -117,6 +117,12 @@ typedef struct ocean_stats {
     int64_t peak_bytes;        /* largest total obtained from the allocator at one time */
     float stage_ms[OCEAN_NUM_STAGES];
     float total_ms;            /* host wall clock of the call */
+    /* per numeric bin (first attempt only): kernel time from events on the call's stream, and the
+     * work it covered: intermediate products, entries of A read, entries of C produced */
+    float bin_ms[OCEAN_MAX_BINS];
+    int64_t bin_products[OCEAN_MAX_BINS];
+    int64_t bin_nnz_a[OCEAN_MAX_BINS];
+    int64_t bin_nnz_c[OCEAN_MAX_BINS];
 } ocean_stats;
 
 void ocean_default_options(ocean_options *opt /* host */);

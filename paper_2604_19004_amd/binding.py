@@ -49,7 +49,9 @@ class ocean_stats(C.Structure):
                 ("hll_registers", C.c_int32), ("sampled_rows", C.c_int32), ("fell_back", C.c_int32),
                 ("rows_per_bin", C.c_int64 * MAX_BINS), ("symbolic_rows_per_bin", C.c_int64 * MAX_BINS),
                 ("overflow_rows", C.c_int64), ("temp_slots", C.c_int64), ("peak_bytes", C.c_int64),
-                ("stage_ms", C.c_float * 8), ("total_ms", C.c_float)]
+                ("stage_ms", C.c_float * 8), ("total_ms", C.c_float), ("bin_ms", C.c_float * MAX_BINS),
+                ("bin_products", C.c_int64 * MAX_BINS), ("bin_nnz_a", C.c_int64 * MAX_BINS),
+                ("bin_nnz_c", C.c_int64 * MAX_BINS)]
 
     def as_dict(self) -> dict:
         d = {k: getattr(self, k) for k in ("products", "max_row_products", "nnz_c", "er", "avg_products", "sampled_cr",
@@ -58,6 +60,8 @@ class ocean_stats(C.Structure):
         d["workflow"] = WORKFLOW_NAMES.get(self.workflow, str(self.workflow))
         d["rows_per_bin"] = list(self.rows_per_bin)
         d["symbolic_rows_per_bin"] = list(self.symbolic_rows_per_bin)
+        for k in ("bin_ms", "bin_products", "bin_nnz_a", "bin_nnz_c"):
+            d[k] = list(getattr(self, k))
         d["stage_ms"] = {n: float(self.stage_ms[i]) for i, n in enumerate(STAGES)}
         return d
 

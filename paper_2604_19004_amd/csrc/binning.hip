@@ -266,4 +266,37 @@ hipError_t launch_final_nnz(int64_t m, const int32_t *nnz1, const int32_t *nnz2,
     return hipGetLastError();
 }
 
+// ------------------------------------------------------ per-bin work sums
+// For reporting only: intermediate products, entries of A and entries of C
+// handled by each numeric bin.  sums[3 * OCEAN_MAX_BINS], zero on entry.
+__global__ void __launch_bounds__(TPB)
+k_bin_work(int64_t m, const uint8_t *__restrict__ bin_of_row, const int64_t *__restrict__ prod,
+           const int64_t *__restrict__ a_rp, const int32_t *__restrict__ row_nnz, unsigned long long *sums)
+{
+    __shared__ unsigned long long s_sum[3 * OCEAN_MAX_BINS];
+    if (threadIdx.x < 3 * OCEAN_MAX_BINS) s_sum[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (i < m) {
+        const int b = bin_of_row[i];
+        if (b != BIN_NONE) {
+            atomicAdd(&s_sum[b], (unsigned long long)prod[i]);
+            atomicAdd(&s_sum[OCEAN_MAX_BINS + b], (unsigned long long)(a_rp[i + 1] - a_rp[i]));
+            const int32_t c = row_nnz[i];
+            if (c > 0) atomicAdd(&s_sum[2 * OCEAN_MAX_BINS + b], (unsigned long long)c);
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < 3 * OCEAN_MAX_BINS && s_sum[threadIdx.x]) atomicAdd(&sums[threadIdx.x], s_sum[threadIdx.x]);
+}
+
+hipError_t launch_bin_work(int64_t m, const uint8_t *bin_of_row, const int64_t *prod, const int64_t *a_rp,
+                           const int32_t *row_nnz, unsigned long long *sums, hipStream_t s)
+{
+    if (m == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_bin_work, dim3((unsigned)((m + TPB - 1) / TPB)), dim3(TPB), 0, s, m, bin_of_row, prod, a_rp,
+                       row_nnz, sums);
+    return hipGetLastError();
+}
+
 }  // namespace ocean

@@ -47,6 +47,7 @@ struct Scalars {
     double sample_sums[2];
     int32_t flags;
     int32_t pad;
+    unsigned long long bin_work[3 * OCEAN_MAX_BINS];   // products, entries of A, entries of C per numeric bin
 };
 
 constexpr size_t ALIGN = 256;
@@ -62,6 +63,7 @@ struct Ctx {
     // stage timing
     std::vector<hipEvent_t> ev;
     std::vector<int> ev_stage;
+    std::vector<std::pair<int, int>> bin_ev;   // (numeric bin, index of the event recorded before its launch)
 
     void *alloc(size_t bytes)
     {
@@ -158,6 +160,12 @@ void collect_times(Ctx &c, ocean_stats *st)
     for (size_t i = 0; i + 1 < c.ev.size(); ++i) {
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, c.ev[i], c.ev[i + 1]) == hipSuccess && c.ev_stage[i] >= 0) st->stage_ms[c.ev_stage[i]] += ms;
+    }
+    for (int b = 0; b < OCEAN_MAX_BINS; ++b) st->bin_ms[b] = 0.f;
+    for (const auto &be : c.bin_ev) {
+        float ms = 0.f;
+        if ((size_t)be.second + 1 < c.ev.size() && hipEventElapsedTime(&ms, c.ev[be.second], c.ev[be.second + 1]) == hipSuccess)
+            st->bin_ms[be.first] += ms;
     }
 }
 
@@ -312,7 +320,7 @@ int run_symbolic(Ctx &c, Work &w, const Csr &A, const Csr &B, int gb_log2, int32
 // and global bins is obtained here and kept until the caller releases all.
 int run_numeric(Ctx &c, Work &w, const Csr &A, const Csr &B, int dtype, int gb_log2, const unsigned long long *count,
                 int64_t max_cap_global, double global_coef, const int64_t *out_ptr, int32_t *out_col, void *out_val,
-                int32_t *row_nnz, int queue_base)
+                int32_t *row_nnz, int queue_base, int stage, bool time_bins)
 {
     int64_t start[NB_COUNT + 1];
     start[0] = 0;
@@ -360,8 +368,13 @@ int run_numeric(Ctx &c, Work &w, const Csr &A, const Csr &B, int dtype, int gb_l
             l.n_wg = n_wg;
             l.queue = &w.sc->queue[queue_base + 1];
         }
+        if (time_bins) {
+            c.bin_ev.emplace_back(b, (int)c.ev.size());
+            OC_TRY(mark(c, stage));
+        }
         HIP_TRY(launch_numeric_bin(A, B, dtype, l, gb_log2, c.s));
     }
+    if (time_bins) OC_TRY(mark(c, stage));
     return OCEAN_OK;
 }
 
@@ -556,11 +569,24 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
     // ---- numeric ----
     OC_TRY(mark(c, OCEAN_ST_NUMERIC));
     HIP_TRY(launch_fill_i32(w.row_nnz, m, 0, c.s));
-    OC_TRY(run_numeric(c, w, A, B, dtype, gb_log2, bin_count, max_cap, global_coef, out_ptr, t_col, t_val, w.row_nnz, 0));
+    OC_TRY(run_numeric(c, w, A, B, dtype, gb_log2, bin_count, max_cap, global_coef, out_ptr, t_col, t_val, w.row_nnz, 0,
+                       OCEAN_ST_NUMERIC, st != nullptr));
+    if (st) {
+        HIP_TRY(hipMemsetAsync(w.sc->bin_work, 0, sizeof(w.sc->bin_work), c.s));
+        HIP_TRY(launch_bin_work(m, w.bin, w.prod, A.rp, w.row_nnz, w.sc->bin_work, c.s));
+    }
 
+    auto copy_bin_work = [&]() {
+        for (int b = 0; b < OCEAN_MAX_BINS; ++b) {
+            S->bin_products[b] = (int64_t)c.h->bin_work[b];
+            S->bin_nnz_a[b] = (int64_t)c.h->bin_work[OCEAN_MAX_BINS + b];
+            S->bin_nnz_c[b] = (int64_t)c.h->bin_work[2 * OCEAN_MAX_BINS + b];
+        }
+    };
     if (workflow == OCEAN_WF_SYMBOLIC) {
         OC_TRY(mark(c, -1));
-        HIP_TRY(hipStreamSynchronize(c.s));
+        OC_TRY(fetch_scalars(c, w.sc));
+        copy_bin_work();
         S->nnz_c = total_slots;
         C->row_ptr = c_rp;
         C->col_idx = t_col;
@@ -580,6 +606,7 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
     HIP_TRY(launch_scan_i32_to_i64(w.row_nnz, m, c_rp, w.scan_tmp, c.s));
     HIP_TRY(hipMemcpyAsync(&w.sc->totals[0], c_rp + m, 8, hipMemcpyDeviceToDevice, c.s));
     OC_TRY(fetch_scalars(c, w.sc));
+    copy_bin_work();
     const int64_t n_ovf = (int64_t)c.h->ovf_count;
     S->overflow_rows = n_ovf;
     int64_t nnz_c = (int64_t)c.h->totals[0];
@@ -608,7 +635,7 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
         std::memcpy(bc2, c.h->bin_count, sizeof(bc2));
         HIP_TRY(launch_fill_i32(w.row_nnz2, m, 0, c.s));
         OC_TRY(run_numeric(c, w, A, B, dtype, gb_log2, bc2, (int64_t)c.h->max_cap, 1.25, w.tmp_ptr2, r_col, r_val,
-                           w.row_nnz2, 2));
+                           w.row_nnz2, 2, OCEAN_ST_RETRY, false));
         HIP_TRY(launch_final_nnz(m, w.row_nnz, w.row_nnz2, w.nnz_final, c.s));
         HIP_TRY(launch_scan_i32_to_i64(w.nnz_final, m, c_rp, w.scan_tmp, c.s));
         HIP_TRY(hipMemcpyAsync(&w.sc->totals[0], c_rp + m, 8, hipMemcpyDeviceToDevice, c.s));

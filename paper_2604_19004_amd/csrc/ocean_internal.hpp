@@ -134,6 +134,8 @@ int64_t scan_tmp_elems(int64_t n);
 hipError_t launch_fill_i32(int32_t *p, int64_t n, int32_t v, hipStream_t s);
 hipError_t launch_fill_u64(unsigned long long *p, int64_t n, unsigned long long v, hipStream_t s);
 hipError_t launch_count_overflow(int64_t m, const int32_t *row_nnz, unsigned long long *count, hipStream_t s);
+hipError_t launch_bin_work(int64_t m, const uint8_t *bin_of_row, const int64_t *prod, const int64_t *a_rp,
+                           const int32_t *row_nnz, unsigned long long *sums /*3*OCEAN_MAX_BINS, zero*/, hipStream_t s);
 hipError_t launch_final_nnz(int64_t m, const int32_t *nnz1, const int32_t *nnz2, int32_t *out, hipStream_t s);
 
 // symbolic.hip
