@@ -56,6 +56,9 @@ hipError_t launch_validate(const Csr &A, const Csr &B, int32_t *flags, hipStream
 }
 
 // ------------------------------------------------------------ row products
+// One group of 2^g_log2 lanes per row, a fixed number of workgroups striding
+// over the rows: the totals cost one atomic per workgroup, not one per row tile
+// (same-address atomics from all XCDs serialise in the memory fabric).
 __global__ void __launch_bounds__(TPB)
 k_row_products(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col, int64_t m,
                const int64_t *__restrict__ b_rp, int64_t b_rows, int g_log2, int64_t *__restrict__ prod,
@@ -64,32 +67,35 @@ k_row_products(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_c
     __shared__ long long s_sum[TPB / WAVE];
     __shared__ long long s_max[TPB / WAVE];
     const int G = 1 << g_log2;
-    const int64_t gt = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t row = gt >> g_log2;
-    const int sub = (int)(gt & (G - 1));
-    long long p = 0;
-    long long mx = 0;
+    const int R = TPB >> g_log2;
+    const int rl = threadIdx.x >> g_log2;
+    const int sub = threadIdx.x & (G - 1);
+    long long tsum = 0, tmax = 0;
     bool bad = false;
-    if (row < m) {
-        const int64_t e1 = a_rp[row + 1];
-        for (int64_t e = a_rp[row] + sub; e < e1; e += G) {
-            const int32_t k = a_col[e];
-            if ((uint32_t)k >= (uint64_t)b_rows) { bad = true; continue; }
-            const long long len = b_rp[k + 1] - b_rp[k];
-            p += len;
-            mx = len > mx ? len : mx;
+    for (int64_t base = (int64_t)blockIdx.x * R; base < m; base += (int64_t)gridDim.x * R) {
+        const int64_t row = base + rl;
+        long long p = 0, mx = 0;
+        if (row < m) {
+            const int64_t e1 = a_rp[row + 1];
+            for (int64_t e = a_rp[row] + sub; e < e1; e += G) {
+                const int32_t k = a_col[e];
+                if ((uint32_t)k >= (uint64_t)b_rows) { bad = true; continue; }
+                const long long len = b_rp[k + 1] - b_rp[k];
+                p += len;
+                mx = len > mx ? len : mx;
+            }
+        }
+        p = group_reduce_sum(p, G);
+        mx = group_reduce_max(mx, G);
+        if (row < m && sub == 0) {
+            prod[row] = p;
+            maxb[row] = (int32_t)(mx > 0x7fffffffLL ? 0x7fffffffLL : mx);
+            tsum += p;
+            tmax = p > tmax ? p : tmax;
         }
     }
-    p = group_reduce_sum(p, G);
-    mx = group_reduce_max(mx, G);
-    long long contrib = 0;
-    if (row < m && sub == 0) {
-        prod[row] = p;
-        maxb[row] = (int32_t)(mx > 0x7fffffffLL ? 0x7fffffffLL : mx);
-        contrib = p;
-    }
-    long long wsum = group_reduce_sum(contrib, WAVE);
-    long long wmax = group_reduce_max(contrib, WAVE);
+    const long long wsum = group_reduce_sum(tsum, WAVE);
+    const long long wmax = group_reduce_max(tmax, WAVE);
     const int w = threadIdx.x / WAVE;
     if (lane_id() == 0) { s_sum[w] = wsum; s_max[w] = wmax; }
     __syncthreads();
@@ -108,8 +114,9 @@ hipError_t launch_row_products(const Csr &A, const int64_t *b_rp, int64_t b_rows
     if (A.rows == 0) return hipSuccess;
     const double avg = A.rows ? (double)A.nnz / (double)A.rows : 0.0;
     const int g_log2 = ilog2_ceil(avg, 1, 6);
-    const int64_t threads = A.rows << g_log2;
-    const int64_t blocks = (threads + TPB - 1) / TPB;
+    const int R = TPB >> g_log2;
+    int64_t blocks = (A.rows + R - 1) / R;
+    if (blocks > 2048) blocks = 2048;
     hipLaunchKernelGGL(k_row_products, dim3((unsigned)blocks), dim3(TPB), 0, s, A.rp, A.col, A.rows, b_rp, b_rows,
                        g_log2, prod, maxb, totals, flags);
     return hipGetLastError();

@@ -29,8 +29,7 @@ k_classify(int64_t m, int mode, double coef, double scale, BinTable bt, int64_t 
     if (threadIdx.x < OCEAN_MAX_BINS) s_cnt[threadIdx.x] = 0;
     if (threadIdx.x == 0) s_maxcap = 0;
     __syncthreads();
-    const int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
-    if (i < m) {
+    for (int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x; i < m; i += (int64_t)gridDim.x * TPB) {
         int bin = BIN_NONE;
         long long c = 0;
         const bool active = (row_mask == nullptr) || (row_mask[i] < 0);
@@ -75,7 +74,8 @@ hipError_t launch_classify(int64_t m, const BinParams &p, double scale, const in
     BinTable bt;
     bt.n = p.n_bins;
     for (int b = 0; b < OCEAN_MAX_BINS; ++b) bt.slots[b] = b < p.n_bins ? p.slots[b] : 0;
-    const int64_t blocks = (m + TPB - 1) / TPB;
+    int64_t blocks = (m + TPB - 1) / TPB;
+    if (blocks > 1024) blocks = 1024;   // one set of atomics per workgroup: keep the workgroups few
     hipLaunchKernelGGL(k_classify, dim3((unsigned)blocks), dim3(TPB), 0, s, m, p.mode, p.coef, scale, bt, p.n_cols,
                        prod, est, nnz_exact, row_mask, bin_of_row, cap, bin_count, max_cap);
     return hipGetLastError();
@@ -83,6 +83,7 @@ hipError_t launch_classify(int64_t m, const BinParams &p, double scale, const in
 
 // Row ids grouped by bin: bin b occupies bin_rows[prefix(b) .. prefix(b)+count(b)).  A workgroup
 // counts its rows per bin in LDS, claims one contiguous range per bin, then fills it.
+constexpr int SC_ITEMS = 8;
 __global__ void __launch_bounds__(TPB)
 k_scatter(int64_t m, int n_bins, const uint8_t *__restrict__ bin_of_row,
           const unsigned long long *__restrict__ bin_count, unsigned long long *bin_cursor,
@@ -92,12 +93,18 @@ k_scatter(int64_t m, int n_bins, const uint8_t *__restrict__ bin_of_row,
     __shared__ unsigned long long s_base[OCEAN_MAX_BINS];
     if (threadIdx.x < OCEAN_MAX_BINS) s_cnt[threadIdx.x] = 0;
     __syncthreads();
-    const int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
-    int bin = BIN_NONE;
-    unsigned int rank = 0;
-    if (i < m) {
-        bin = bin_of_row[i];
-        if (bin != BIN_NONE) rank = atomicAdd(&s_cnt[bin], 1u);
+    const int64_t tile = (int64_t)blockIdx.x * TPB * SC_ITEMS;
+    int bin[SC_ITEMS];
+    unsigned int rank[SC_ITEMS];
+#pragma unroll
+    for (int q = 0; q < SC_ITEMS; ++q) {
+        const int64_t i = tile + (int64_t)q * TPB + threadIdx.x;
+        bin[q] = BIN_NONE;
+        rank[q] = 0;
+        if (i < m) {
+            bin[q] = bin_of_row[i];
+            if (bin[q] != BIN_NONE) rank[q] = atomicAdd(&s_cnt[bin[q]], 1u);
+        }
     }
     __syncthreads();
     if ((int)threadIdx.x < n_bins) {
@@ -107,14 +114,18 @@ k_scatter(int64_t m, int n_bins, const uint8_t *__restrict__ bin_of_row,
         s_base[threadIdx.x] = start + off;
     }
     __syncthreads();
-    if (bin != BIN_NONE) bin_rows[s_base[bin] + rank] = (int32_t)i;
+#pragma unroll
+    for (int q = 0; q < SC_ITEMS; ++q) {
+        const int64_t i = tile + (int64_t)q * TPB + threadIdx.x;
+        if (bin[q] != BIN_NONE) bin_rows[s_base[bin[q]] + rank[q]] = (int32_t)i;
+    }
 }
 
 hipError_t launch_scatter(int64_t m, int n_bins, const uint8_t *bin_of_row, const unsigned long long *bin_count,
                           unsigned long long *bin_cursor, int32_t *bin_rows, hipStream_t s)
 {
     if (m == 0) return hipSuccess;
-    const int64_t blocks = (m + TPB - 1) / TPB;
+    const int64_t blocks = (m + TPB * SC_ITEMS - 1) / (TPB * SC_ITEMS);
     hipLaunchKernelGGL(k_scatter, dim3((unsigned)blocks), dim3(TPB), 0, s, m, n_bins, bin_of_row, bin_count,
                        bin_cursor, bin_rows);
     return hipGetLastError();
@@ -276,8 +287,7 @@ k_bin_work(int64_t m, const uint8_t *__restrict__ bin_of_row, const int64_t *__r
     __shared__ unsigned long long s_sum[3 * OCEAN_MAX_BINS];
     if (threadIdx.x < 3 * OCEAN_MAX_BINS) s_sum[threadIdx.x] = 0;
     __syncthreads();
-    const int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
-    if (i < m) {
+    for (int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x; i < m; i += (int64_t)gridDim.x * TPB) {
         const int b = bin_of_row[i];
         if (b != BIN_NONE) {
             atomicAdd(&s_sum[b], (unsigned long long)prod[i]);
@@ -294,7 +304,9 @@ hipError_t launch_bin_work(int64_t m, const uint8_t *bin_of_row, const int64_t *
                            const int32_t *row_nnz, unsigned long long *sums, hipStream_t s)
 {
     if (m == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_bin_work, dim3((unsigned)((m + TPB - 1) / TPB)), dim3(TPB), 0, s, m, bin_of_row, prod, a_rp,
+    int64_t blocks = (m + TPB - 1) / TPB;
+    if (blocks > 512) blocks = 512;
+    hipLaunchKernelGGL(k_bin_work, dim3((unsigned)blocks), dim3(TPB), 0, s, m, bin_of_row, prod, a_rp,
                        row_nnz, sums);
     return hipGetLastError();
 }

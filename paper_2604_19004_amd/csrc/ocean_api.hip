@@ -64,6 +64,9 @@ struct Ctx {
     std::vector<hipEvent_t> ev;
     std::vector<int> ev_stage;
     std::vector<std::pair<int, int>> bin_ev;   // (numeric bin, index of the event recorded before its launch)
+    // column-window boundary table of B for the dense kernel (null: heavy rows use global hash tables)
+    uint32_t *bw = nullptr;
+    int n_win = 0;
 
     void *alloc(size_t bytes)
     {
@@ -344,6 +347,11 @@ int run_numeric(Ctx &c, Work &w, const Csr &A, const Csr &B, int dtype, int gb_l
             if (!l.slab) return fail(OCEAN_EALLOC, "value slab allocation failed");
             HIP_TRY(hipMemsetAsync(l.slab, 0, bytes, c.s));
             l.queue = &w.sc->queue[queue_base];
+        } else if (b == NB_GLOBAL && c.bw != nullptr) {
+            l.bw = c.bw;
+            l.n_win = c.n_win;
+            l.n_wg = (int)(l.count < c.n_cu ? l.count : c.n_cu);
+            l.queue = &w.sc->queue[queue_base + 1];
         } else if (b == NB_GLOBAL) {
             int gbits = 10;
             while (gbits < 31 && (double)(1ll << gbits) < global_coef * (double)max_cap_global) ++gbits;
@@ -470,6 +478,19 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
     const int gb_log2 = ilog2_ceil_d(S->er, 0, 6);   // lanes sharing one row of B ~ its typical length
     const int64_t max_ub = S->max_row_products < n ? S->max_row_products : n;
 
+    // Rows that may outgrow every LDS hash table are accumulated densely over column windows, which
+    // needs the window boundaries inside every (sorted) row of B.  Built only when such rows can exist
+    // and the table stays small; otherwise, or when a row of B turns out unsorted, they use global tables.
+    uint32_t *bw_try = nullptr;
+    if (max_ub > kNumericSlots[NB_HYBRID] && B.nnz < 0xffffffffLL) {
+        const int nw = dense_window_count(n, dtype);
+        const size_t bytes = (size_t)B.rows * ((size_t)nw + 1) * 4;
+        if (bytes <= ((size_t)6 << 30)) {
+            bw_try = static_cast<uint32_t *>(c.alloc(bytes));
+            if (bw_try) HIP_TRY(launch_window_table(B, dtype, bw_try, &c.n_win, &w.sc->flags, c.s));
+        }
+    }
+
     // ---- workflow choice (Table 1) ----
     int workflow = o.workflow;
     int m_regs = 0;
@@ -545,6 +566,7 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
         OC_TRY(fetch_scalars(c, w.sc));
         total_slots = (int64_t)c.h->totals[0];
         for (int b = 0; b < NB_COUNT; ++b) S->rows_per_bin[b] = (int64_t)c.h->bin_count[b];
+        c.bw = (bw_try != nullptr && !(c.h->flags & 8)) ? bw_try : nullptr;
         t_col = static_cast<int32_t *>(c.alloc((size_t)total_slots * 4));
         t_val = t_col ? c.alloc((size_t)total_slots * vbytes) : nullptr;
         if (!t_col || !t_val) {

@@ -164,7 +164,11 @@ struct NumLaunch {
     int n_wg;                 // persistent workgroups of the hybrid / global kernels
     unsigned long long *queue; // their shared row counter, zero on entry
     double coef;              // global: table slots per reserved output entry
+    const uint32_t *bw;       // dense kernel: window boundary table of B, or null to use the global-table kernel
+    int n_win;
 };
+hipError_t launch_window_table(const Csr &B, int dtype, uint32_t *bw, int *n_win_out, int32_t *flags, hipStream_t s);
+int dense_window_count(int64_t n_cols, int dtype);
 hipError_t launch_numeric_bin(const Csr &A, const Csr &B, int dtype, const NumLaunch &l, int gb_log2, hipStream_t s);
 
 // compact.hip

@@ -197,24 +197,58 @@ def test_edge_cases(ob, wf):
         check_result(Cd, ref, A, f"{label}/{wf}")
 
 
-def test_heavy_rows_reach_hybrid_and_global_bins(ob):
+def _heavy_case(dtype=np.float64, shuffle_b=False):
     # a few rows of A that reference many long rows of B: their outputs exceed every LDS table
     rng = np.random.default_rng(11)
     n = 1 << 18
     Bm = W.erdos_renyi(4096, 64, seed=12, cols=n)
+    Bm.val = Bm.val.astype(dtype)
+    if shuffle_b:   # same matrix, entries of every row in random order: B is no longer sorted
+        perm = rng.permuted(np.arange(Bm.nnz).reshape(4096, 64), axis=1).reshape(-1)
+        Bm = CSR(Bm.rows, Bm.cols, Bm.row_ptr, Bm.col_idx[perm].copy(), Bm.val[perm].copy())
     rows_spec = [3000, 900, 350, 120, 30, 4, 1, 0]          # entries per row of A -> ~190k .. 0 outputs
     rp = np.concatenate([[0], np.cumsum(rows_spec)]).astype(np.int64)
     ci = np.concatenate([np.sort(rng.choice(4096, k, replace=False)) for k in rows_spec]).astype(np.int32)
-    A = CSR(len(rows_spec), 4096, rp, ci, rng.uniform(-1, 1, ci.size))
+    A = CSR(len(rows_spec), 4096, rp, ci, rng.uniform(-1, 1, ci.size).astype(dtype))
+    return A, Bm
+
+
+@pytest.mark.parametrize("variant", ["f64", "f32", "f64-unsorted-B"])
+def test_heavy_rows_reach_hybrid_and_last_bin(ob, variant):
+    A, Bm = _heavy_case(np.float32 if variant == "f32" else np.float64, shuffle_b=variant.endswith("unsorted-B"))
     ref = O.multiply_rows(A, Bm)
     for wf in ("symbolic", "hll", "upper_bound"):
         Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(Bm), workflow=wf_id(ob, wf))
-        check_result(Cd, ref, A, f"heavy/{wf}")
-        assert st["rows_per_bin"][8] > 0                                    # global bin used
+        check_result(Cd, ref, A, f"heavy {variant}/{wf}")
+        assert st["rows_per_bin"][8] > 0                                    # dense-window / global-table bin used
         assert st["rows_per_bin"][7] > 0                                    # hybrid bin used
     Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(Bm), workflow=ob.WF_HLL, estimate_scale=0.3)
-    check_result(Cd, ref, A, "heavy/hll overflow")
+    check_result(Cd, ref, A, f"heavy {variant}/hll overflow")
     assert st["overflow_rows"] > 0
+
+
+def test_skewed_row_lengths_of_b(ob):
+    # rows of B from 0 to 20000 entries referenced by the same rows of A: exercises the short / medium /
+    # long / huge classes of the product traversal in every kernel size
+    rng = np.random.default_rng(21)
+    n = 50000
+    lens = np.array([0, 1, 3, 7, 8, 9, 40, 127, 128, 129, 700, 4095, 4096, 5000, 20000] * 4)
+    rng.shuffle(lens)
+    rp = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    ci = np.concatenate([np.sort(rng.choice(n, k, replace=False)) for k in lens]).astype(np.int32)
+    Bm = CSR(len(lens), n, rp, ci, rng.uniform(-1, 1, ci.size))
+    # rows of A with 1 .. 60 entries (all rows of B at most once per row)
+    cnt = np.array([1, 2, 5, 17, 33, 60, 60, 3, 64, 65, 130, 12] )
+    cnt = np.minimum(cnt, len(lens))
+    arp = np.concatenate([[0], np.cumsum(cnt)]).astype(np.int64)
+    aci = np.concatenate([np.sort(rng.choice(len(lens), k, replace=False)) for k in cnt]).astype(np.int32)
+    A = CSR(len(cnt), len(lens), arp, aci, rng.uniform(-1, 1, aci.size))
+    ref = O.multiply_rows(A, Bm)
+    for wf in ("symbolic", "hll", "upper_bound"):
+        Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(Bm), workflow=wf_id(ob, wf))
+        check_result(Cd, ref, A, f"skewed/{wf}")
+    nnz, _ = ob.symbolic(ob.to_device(A), ob.to_device(Bm))
+    assert np.array_equal(nnz.cpu().numpy().astype(np.int64), np.diff(ref.row_ptr))
 
 
 def test_invalid_arguments_are_rejected(ob):
