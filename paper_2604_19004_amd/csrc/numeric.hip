@@ -345,35 +345,39 @@ k_numeric_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col
 // Keys of a 32768-slot table stay in LDS; values are accumulated with
 // fire-and-forget atomics into this workgroup's slab in global memory (it is
 // 256 KB, so it lives in the L2 of the XCD the workgroup runs on).  The row is
-// emitted in ascending order without a sort: per window of WIN columns an LDS
-// bitmap of the present keys and its prefix popcount give every key its rank.
+// emitted in ascending order without a comparison sort: the (key, slot) pairs
+// are first dumped to a list in global memory, which frees the 128 KB of keys
+// for a bitmap over 512 K columns plus its per-word prefix popcount; a key's
+// rank in the row is then the number of set bits below it.
 constexpr int HY_BITS = 15;
 constexpr int HY_SLOTS = 1 << HY_BITS;
 constexpr int HY_THREADS = 1024;
-constexpr int HY_WIN = 131072;          // columns per ranking window
-constexpr int HY_WORDS = HY_WIN / 32;   // 4096
-constexpr int HY_QCAP = 256;
+constexpr int HY_WIN = 524288;          // columns per ranking window
+constexpr int HY_WORDS = HY_WIN / 32;   // 16384 bitmap words + 16384 prefix words = the key table's 128 KB
+constexpr int HY_QCAP = 1024;
 
 template <typename V>
 __global__ void __launch_bounds__(HY_THREADS)
 k_numeric_hybrid(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col, const V *__restrict__ a_val,
                  const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_col, const V *__restrict__ b_val,
                  const int32_t *__restrict__ rows, int64_t count, unsigned long long *queue,
-                 V *__restrict__ slab_all, const int64_t *__restrict__ out_ptr, int32_t *__restrict__ out_col,
-                 V *__restrict__ out_val, int32_t *__restrict__ row_nnz)
+                 V *__restrict__ slab_all, uint2 *__restrict__ pairs_all, const int64_t *__restrict__ out_ptr,
+                 int32_t *__restrict__ out_col, V *__restrict__ out_val, int32_t *__restrict__ row_nnz)
 {
     constexpr int PER = HY_SLOTS / HY_THREADS;   // 32 slots per thread
-    constexpr int WPT = HY_WORDS / HY_THREADS;   // 4 bitmap words per thread
+    constexpr int WPT = HY_WORDS / HY_THREADS;   // 16 bitmap words per thread
     __shared__ int32_t s_keys[HY_SLOTS];
-    __shared__ uint32_t s_bm[HY_WORDS];
-    __shared__ uint16_t s_pre[HY_WORDS];
     __shared__ TravQueue<V, HY_QCAP> s_q;
     __shared__ int s_wave[HY_THREADS / WAVE];
     __shared__ int s_ovf;
     __shared__ int s_min, s_max;
+    __shared__ unsigned int s_cnt;
     __shared__ long long s_row;
+    uint32_t *s_bm = reinterpret_cast<uint32_t *>(s_keys);   // valid only after the keys were dumped
+    uint32_t *s_pre = s_bm + HY_WORDS;
     const int tid = threadIdx.x;
     V *slab = slab_all + (size_t)blockIdx.x * HY_SLOTS;
+    uint2 *pairs = pairs_all + (size_t)blockIdx.x * HY_SLOTS;
 
     for (;;) {
         if (tid == 0) s_row = (long long)atomicAdd(queue, 1ull);
@@ -382,41 +386,54 @@ k_numeric_hybrid(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
         if (r >= count) break;   // uniform: every wave of the workgroup leaves here
         const int64_t row = rows[r];
         for (int s = tid; s < HY_SLOTS; s += HY_THREADS) s_keys[s] = EMPTY_KEY;
-        if (tid == 0) { s_ovf = 0; s_min = 0x7fffffff; s_max = -1; s_q.n = 0; s_q.n_huge = 0; }
+        if (tid == 0) { s_ovf = 0; s_min = 0x7fffffff; s_max = -1; s_cnt = 0; s_q.n = 0; s_q.n_huge = 0; }
         __syncthreads();
 
-        int kmin = 0x7fffffff, kmax = -1;
         TravState ts;
         wg_traverse<HY_THREADS, true>(a_col, a_val, a_rp[row], a_rp[row + 1],
                                       [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
                                       b_col, b_val, s_q, ts, [&](int32_t j, V v) {
                                           const int slot = lds_find_or_insert<HY_BITS>(s_keys, j);
-                                          if (slot >= 0) {
-                                              l2_add(&slab[slot], v);
-                                              kmin = j < kmin ? j : kmin;
-                                              kmax = j > kmax ? j : kmax;
-                                          } else {
-                                              s_ovf = 1;
-                                          }
+                                          if (slot >= 0) l2_add(&slab[slot], v);
+                                          else s_ovf = 1;
                                       });
+        __threadfence();   // the slab additions are in L2 before anyone exchanges them out
+        __syncthreads();
+
+        // dump (key, slot) pairs; one LDS atomic per wave and pass
+        int kmin = 0x7fffffff, kmax = -1;
+        for (int q = 0; q < PER; ++q) {
+            const int slot = q * HY_THREADS + tid;
+            const int32_t key = s_keys[slot];
+            const bool occ = key != EMPTY_KEY;
+            const unsigned long long m = __ballot(occ);
+            unsigned int base = 0;
+            if (lane_id() == 0 && m) base = atomicAdd(&s_cnt, (unsigned int)__popcll(m));
+            base = __shfl(base, 0, WAVE);
+            if (occ) {
+                pairs[base + __popcll(m & ((1ull << lane_id()) - 1ull))] = make_uint2((unsigned)key, (unsigned)slot);
+                kmin = key < kmin ? key : kmin;
+                kmax = key > kmax ? key : kmax;
+            }
+        }
         kmin = -group_reduce_max(-kmin, WAVE);
         kmax = group_reduce_max(kmax, WAVE);
         if (lane_id() == 0) { atomicMin(&s_min, kmin); atomicMax(&s_max, kmax); }
-        __threadfence();   // the slab additions are in L2 before anyone exchanges them out
+        __threadfence();   // the pairs are read back by other waves of this workgroup
         __syncthreads();
 
         const int64_t o = out_ptr[row];
         const int64_t cap = out_ptr[row + 1] - o;
         const int lo_key = s_min, hi_key = s_max;
+        const int c = (int)s_cnt;
         int done = 0;
         for (int64_t w0 = (int64_t)(lo_key >= 0 ? lo_key : 0) & ~(int64_t)(HY_WIN - 1); w0 <= (int64_t)hi_key; w0 += HY_WIN) {
 #pragma unroll
-            for (int q = 0; q < WPT; ++q) s_bm[tid * WPT + q] = 0u;
+            for (int q = 0; q < WPT; ++q) s_bm[q * HY_THREADS + tid] = 0u;
             __syncthreads();
-            for (int q = 0; q < PER; ++q) {
-                const int32_t key = s_keys[q * HY_THREADS + tid];
-                const int64_t d = (int64_t)key - w0;
-                if (key != EMPTY_KEY && d >= 0 && d < HY_WIN) atomicOr(&s_bm[d >> 5], 1u << (d & 31));
+            for (int i = tid; i < c; i += HY_THREADS) {
+                const int64_t d = (int64_t)(int32_t)__hip_atomic_load(&pairs[i].x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - w0;
+                if (d >= 0 && d < HY_WIN) atomicOr(&s_bm[d >> 5], 1u << (d & 31));
             }
             __syncthreads();
             int cnt[WPT];
@@ -426,13 +443,13 @@ k_numeric_hybrid(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
             int wtotal;
             int run = block_exclusive_scan_i32<HY_THREADS>(mine, s_wave, wtotal);
 #pragma unroll
-            for (int q = 0; q < WPT; ++q) { s_pre[tid * WPT + q] = (uint16_t)run; run += cnt[q]; }
+            for (int q = 0; q < WPT; ++q) { s_pre[tid * WPT + q] = (uint32_t)run; run += cnt[q]; }
             __syncthreads();
-            for (int q = 0; q < PER; ++q) {
-                const int slot = q * HY_THREADS + tid;
-                const int32_t key = s_keys[slot];
+            for (int i = tid; i < c; i += HY_THREADS) {
+                const int32_t key = (int32_t)__hip_atomic_load(&pairs[i].x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 const int64_t d = (int64_t)key - w0;
-                if (key != EMPTY_KEY && d >= 0 && d < HY_WIN) {
+                if (d >= 0 && d < HY_WIN) {
+                    const int slot = (int)__hip_atomic_load(&pairs[i].y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     const int rank = done + (int)s_pre[d >> 5] + __popc(s_bm[d >> 5] & ((1u << (d & 31)) - 1u));
                     const V val = __hip_atomic_exchange(&slab[slot], (V)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     if ((int64_t)rank < cap) { out_col[o + rank] = key; out_val[o + rank] = val; }
@@ -519,16 +536,21 @@ k_numeric_dense(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
             if (tid < WORDS) s_pre[tid] = (uint32_t)ex;
             __syncthreads();
             if (wtotal > 0) {
+                // every thread owns BPT consecutive bits of the bitmap and walks only the set ones
+                constexpr int BPT = WIN / DN_THREADS;   // 16 (fp64) or 32 (fp32)
                 const int32_t col0 = w * WIN;
-#pragma unroll 4
-                for (int j = tid; j < WIN; j += DN_THREADS) {
-                    const uint32_t bits = s_bm[j >> 5];
-                    if (bits & (1u << (j & 31))) {
-                        const long long rank = done + (long long)s_pre[j >> 5] + __popc(bits & ((1u << (j & 31)) - 1u));
-                        const V val = s_vals[j];
-                        s_vals[j] = (V)0;
-                        if (rank < cap) { out_col[o + rank] = col0 + j; out_val[o + rank] = val; }
-                    }
+                const int j0 = tid * BPT;
+                const uint32_t wbits = s_bm[j0 >> 5];
+                uint32_t bits = BPT == 32 ? wbits : ((wbits >> (j0 & 31)) & ((1u << (BPT & 31)) - 1u));
+                long long rank = done + (long long)s_pre[j0 >> 5] + __popc(wbits & ((1u << (j0 & 31)) - 1u));
+                while (bits) {
+                    const int b = __ffs((int)bits) - 1;
+                    bits &= bits - 1u;
+                    const int j = j0 + b;
+                    const V val = s_vals[j];
+                    s_vals[j] = (V)0;
+                    if (rank < cap) { out_col[o + rank] = col0 + j; out_val[o + rank] = val; }
+                    ++rank;
                 }
                 __syncthreads();
                 if (tid < WORDS) s_bm[tid] = 0u;
@@ -748,8 +770,8 @@ static hipError_t dispatch(const Csr &A, const Csr &B, const NumLaunch &l, int g
     case NB_S8K: OCEAN_WG(13, 1024); break;
     case NB_HYBRID:
         hipLaunchKernelGGL((k_numeric_hybrid<V>), dim3((unsigned)l.n_wg), dim3(HY_THREADS), 0, s, A.rp, A.col, av, B.rp,
-                           B.col, bv, l.rows, l.count, l.queue, static_cast<V *>(l.slab), l.out_ptr, l.out_col, ov,
-                           l.row_nnz);
+                           B.col, bv, l.rows, l.count, l.queue, static_cast<V *>(l.slab), static_cast<uint2 *>(l.pairs),
+                           l.out_ptr, l.out_col, ov, l.row_nnz);
         break;
     case NB_GLOBAL:
         if (l.bw != nullptr)

@@ -344,7 +344,8 @@ int run_numeric(Ctx &c, Work &w, const Csr &A, const Csr &B, int dtype, int gb_l
             l.n_wg = (int)(l.count < c.n_cu ? l.count : c.n_cu);
             const size_t bytes = (size_t)l.n_wg * 32768 * vbytes;
             l.slab = c.alloc(bytes);
-            if (!l.slab) return fail(OCEAN_EALLOC, "value slab allocation failed");
+            l.pairs = l.slab ? c.alloc((size_t)l.n_wg * 32768 * 8) : nullptr;
+            if (!l.slab || !l.pairs) return fail(OCEAN_EALLOC, "value slab allocation failed");
             HIP_TRY(hipMemsetAsync(l.slab, 0, bytes, c.s));
             l.queue = &w.sc->queue[queue_base];
         } else if (b == NB_GLOBAL && c.bw != nullptr) {

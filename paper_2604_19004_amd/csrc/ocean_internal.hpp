@@ -158,6 +158,7 @@ struct NumLaunch {
     int32_t *row_nnz;         // written per row: entries produced, or -1 on overflow
     // scratch of NB_HYBRID / NB_GLOBAL
     void *slab;               // hybrid: n_wg slabs of 32768 values, all zero on entry and on exit
+    void *pairs;              // hybrid: n_wg lists of 32768 (key, slot) pairs, scratch
     int32_t *gkeys;           // global: n_wg tables of 2^gbits keys, all EMPTY on entry and on exit
     void *gvals;              // global: n_wg tables of 2^gbits values, all zero on entry and on exit
     int gbits;
