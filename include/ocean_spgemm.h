@@ -81,7 +81,8 @@ typedef struct ocean_options {
     uint32_t sample_seed;
     double estimate_scale;           /* test hook: every estimate is multiplied by this before binning (1.0) */
     int32_t validate_inputs;         /* 1: check column ids and row offsets on the device first */
-    int32_t reserved;
+    int32_t force_hash_kernels;      /* 1: rows beyond the 8192-slot LDS table always use the hybrid (LDS keys, global
+                                        values) and global-table hash kernels, as they do when B's rows are unsorted */
     const ocean_allocator *allocator; /* host pointer, may be NULL */
 } ocean_options;
 

@@ -40,7 +40,7 @@ class ocean_options(C.Structure):
                 ("er_threshold", C.c_double), ("cr_threshold", C.c_double), ("expand_coef", C.c_double),
                 ("exact_load_coef", C.c_double), ("sample_ratio", C.c_double), ("sample_min", C.c_int32),
                 ("sample_max", C.c_int32), ("sample_seed", C.c_uint32), ("estimate_scale", C.c_double),
-                ("validate_inputs", C.c_int32), ("reserved", C.c_int32), ("allocator", C.POINTER(ocean_allocator))]
+                ("validate_inputs", C.c_int32), ("force_hash_kernels", C.c_int32), ("allocator", C.POINTER(ocean_allocator))]
 
 
 class ocean_stats(C.Structure):

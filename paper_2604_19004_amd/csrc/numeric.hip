@@ -7,10 +7,12 @@
 //   k_numeric_wg      one workgroup per row, keys + values + sort buffer in LDS (512..8192 slots)
 //   k_numeric_hybrid  32768 keys in LDS, values accumulated in a global slab (Section 3.3,
 //                     enhanced hash accumulator); rows leave sorted through an LDS bitmap rank
-//   k_numeric_dense   rows beyond any LDS hash table: dense accumulator + bitmap in LDS over
-//                     windows of columns (Section 2.2 dense accumulator, iterated over the row's
-//                     column range as in Section 3.2); needs B's rows sorted
-//   k_numeric_global  whole table in global memory: the fallback when B's rows are unsorted
+//   k_numeric_heavy   rows beyond the 8192-slot table when B's rows are sorted: column windows, each
+//                     accumulated in LDS either densely (values + bitmap, Section 2.2 dense
+//                     accumulator iterated over the row's column range as in Section 3.2) or, for
+//                     sparse stretches, in a hash table shared by several windows
+//   k_numeric_global  whole table in global memory, and k_numeric_hybrid: the path of such rows
+//                     when B's rows are unsorted (or the window table would be too large)
 //
 // A row reports overflow (row_nnz = -1) when its table fills up or when it
 // produced more entries than the space reserved for it; such rows are redone
@@ -32,36 +34,59 @@ __device__ __forceinline__ void l2_add(V *p, V v)
     __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Find the slot of `key` in an LDS table of 2^BITS slots, inserting it when
-// absent.  Linear probing; -1 when the table is full.
-template <int BITS>
-__device__ __forceinline__ int lds_find_or_insert(int32_t *keys, int32_t key)
-{
-    constexpr uint32_t MASK = (1u << BITS) - 1u;
-    uint32_t h = table_hash(key, BITS);
-    for (uint32_t probe = 0; probe <= MASK; ++probe) {
-        const int32_t cur = __hip_atomic_load(&keys[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        if (cur == key) return (int)h;
-        if (cur == EMPTY_KEY) {
-            const int32_t old = atomicCAS(&keys[h], EMPTY_KEY, key);
-            if (old == EMPTY_KEY || old == key) return (int)h;
-        }
-        h = (h + 1u) & MASK;
-    }
-    return -1;
-}
-
 // Slot of a key known to be present.
 template <int BITS>
 __device__ __forceinline__ int lds_find(const int32_t *keys, int32_t key)
 {
     constexpr uint32_t MASK = (1u << BITS) - 1u;
     uint32_t h = table_hash(key, BITS);
+    const uint32_t step = table_step(key, BITS);
     for (uint32_t probe = 0; probe <= MASK; ++probe) {
         if (keys[h] == key) return (int)h;
-        h = (h + 1u) & MASK;
+        h = (h + step) & MASK;
     }
     return 0;
+}
+
+// Add a batch of products to an LDS hash table (keys / vals of 2^BITS slots).
+// A wave waits for its slowest lane, so the cost of inserting is set by the
+// longest probe sequence among its lanes, not by the average.  Two measures
+// keep that short: probe strides depend on the key (double hashing, no
+// clustering), and every lane walks its own U products at its own pace - a
+// lane that has placed a product goes on to its next one while other lanes are
+// still probing, so the wave-wide loop runs for the largest per-lane SUM of
+// probes instead of the sum of per-product maxima.  One compare-and-swap per
+// lane and round; the value is added as soon as the slot is known.  Valid
+// products come first in a batch (cj < 0 ends it).  False when the table is full.
+template <int BITS, int U, typename V, typename AddFn>
+__device__ __forceinline__ bool lds_insert_batch(int32_t *keys, const int32_t (&cj)[U], const V (&cv)[U], AddFn add)
+{
+    constexpr uint32_t MASK = (1u << BITS) - 1u;
+    int idx = 0;
+    int32_t key = cj[0];
+    V val = cv[0];
+    uint32_t h = table_hash(key, BITS);
+    uint32_t step = table_step(key, BITS);
+    uint32_t rounds = 0;
+    bool ok = true;
+    while (key >= 0) {
+        const int32_t old = atomicCAS(&keys[h], EMPTY_KEY, key);
+        if (old == EMPTY_KEY || old == key) {
+            add((int)h, val);
+            ++idx;
+            key = -1;
+#pragma unroll
+            for (int u = 1; u < U; ++u)
+                if (idx == u) { key = cj[u]; val = cv[u]; }
+            h = table_hash(key, BITS);
+            step = table_step(key, BITS);
+            rounds = 0;
+        } else {
+            h = (h + step) & MASK;
+            if (++rounds > MASK) { ok = false; key = -1; }
+        }
+    }
+    return ok;
 }
 
 __device__ __forceinline__ int pow2_ceil_i32(int x)
@@ -70,32 +95,30 @@ __device__ __forceinline__ int pow2_ceil_i32(int x)
 }
 
 // ======================================================== group kernel ====
-// G lanes per row, 256/G rows per workgroup, no workgroup barrier anywhere:
-// the lanes of a row are part of one wave.
-template <typename V, int G, int BITS>
+// Four short rows per wave (16 lanes per row), 16 rows per workgroup, 64-slot
+// tables; no workgroup barrier anywhere: the lanes of a row are part of one wave.
+template <typename V>
 __global__ void __launch_bounds__(256)
 k_numeric_group(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col, const V *__restrict__ a_val,
                 const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_col, const V *__restrict__ b_val,
-                const int32_t *__restrict__ rows, int64_t count, int gb_log2,
-                const int64_t *__restrict__ out_ptr, int32_t *__restrict__ out_col, V *__restrict__ out_val,
-                int32_t *__restrict__ row_nnz)
+                const int32_t *__restrict__ rows, int64_t count, const int64_t *__restrict__ out_ptr,
+                int32_t *__restrict__ out_col, V *__restrict__ out_val, int32_t *__restrict__ row_nnz)
 {
+    constexpr int G = 16;
+    constexpr int BITS = 6;
     constexpr int SLOTS = 1 << BITS;
     constexpr int R = 256 / G;
     __shared__ int32_t s_keys[R * SLOTS];
     __shared__ int32_t s_sort[R * SLOTS];
     __shared__ V s_vals[R * SLOTS];
+    __shared__ FlatChunk<V, G> s_fc[R];
     const int rl = threadIdx.x / G;
     const int sub = threadIdx.x % G;
     int32_t *keys = s_keys + rl * SLOTS;
     int32_t *sbuf = s_sort + rl * SLOTS;
     V *vals = s_vals + rl * SLOTS;
-    const int gb = 1 << gb_log2;  // lanes that share one row of B (<= G)
-    const int sub_b = sub & (gb - 1);
-    const int part = sub >> gb_log2;
-    const int parts = G >> gb_log2;
     const int group_shift = (lane_id() / G) * G;
-    const unsigned long long group_mask = (G == 64) ? ~0ull : ((1ull << G) - 1ull);
+    const unsigned long long group_mask = (1ull << G) - 1ull;
 
     const int64_t r = (int64_t)blockIdx.x * R + rl;
     const bool live = r < count;
@@ -105,20 +128,25 @@ k_numeric_group(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     wave_sync();
 
     bool ovf = false;
-    if (live) {
-        const int64_t e1 = a_rp[row + 1];
-        for (int64_t e = a_rp[row] + part; e < e1; e += parts) {
+    const int64_t e0 = live ? a_rp[row] : 0;
+    const int64_t e1 = live ? a_rp[row + 1] : 0;
+    auto f = [&](const auto &cj, const auto &cv) {
+        if (!lds_insert_batch<BITS>(keys, cj, cv, [&](int slot, V v) { lds_add(&vals[slot], v); })) ovf = true;
+    };
+    // the four rows of a wave advance together: same number of 16-entry chunks for all of them
+    const int chunks = group_reduce_max((int)((e1 - e0 + G - 1) / G), WAVE);
+    for (int ch = 0; ch < chunks; ++ch) {
+        const int64_t e = e0 + (int64_t)ch * G + sub;
+        int64_t p0 = 0;
+        uint32_t len = 0;
+        V a = V();
+        if (e < e1) {
             const int64_t k = a_col[e];
-            const V a = a_val[e];
-            const int64_t p1 = b_rp[k + 1];
-            for (int64_t p = b_rp[k] + sub_b; p < p1; p += gb) {
-                const int32_t j = b_col[p];
-                const V v = a * b_val[p];
-                const int slot = lds_find_or_insert<BITS>(keys, j);
-                if (slot >= 0) lds_add(&vals[slot], v);
-                else ovf = true;
-            }
+            a = a_val[e];
+            p0 = b_rp[k];
+            len = (uint32_t)(b_rp[k + 1] - p0);
         }
+        group_flat<G, true>(s_fc[rl], p0, len, a, b_col, b_val, f);
     }
     wave_sync();
 
@@ -182,7 +210,7 @@ k_numeric_wave(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_c
     __shared__ int32_t s_keys[R * SLOTS];
     __shared__ int32_t s_sort[R * SLOTS];
     __shared__ V s_vals[R * SLOTS];
-    __shared__ WaveQueue<V> s_q[R];
+    __shared__ FlatChunk<V, WAVE> s_fc[R];
     const int rl = threadIdx.x / WAVE;
     const int sub = lane_id();
     int32_t *keys = s_keys + rl * SLOTS;
@@ -196,10 +224,8 @@ k_numeric_wave(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_c
     bool ovf = false;
     wave_traverse<true>(a_col, a_val, a_rp[row], a_rp[row + 1],
                         [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
-                        b_col, b_val, s_q[rl], [&](int32_t j, V v) {
-                            const int slot = lds_find_or_insert<BITS>(keys, j);
-                            if (slot >= 0) lds_add(&vals[slot], v);
-                            else ovf = true;
+                        b_col, b_val, s_fc[rl], [&](const auto &cj, const auto &cv) {
+                            if (!lds_insert_batch<BITS>(keys, cj, cv, [&](int slot, V v) { lds_add(&vals[slot], v); })) ovf = true;
                         });
     wave_sync();
     int c = 0;
@@ -277,7 +303,8 @@ k_numeric_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col
     __shared__ int32_t s_keys[SLOTS];
     __shared__ int32_t s_sort[SLOTS];
     __shared__ V s_vals[SLOTS];
-    __shared__ TravQueue<V, THREADS> s_q;
+    __shared__ FlatChunk<V, WAVE> s_fc[THREADS / WAVE];
+    __shared__ LongQueue<V, 256> s_q;
     __shared__ int s_wave[THREADS / WAVE];
     __shared__ int s_ovf;
     const int tid = threadIdx.x;
@@ -292,13 +319,11 @@ k_numeric_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col
     TravState ts;
     wg_traverse<THREADS, true>(a_col, a_val, a_rp[row], a_rp[row + 1],
                                [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
-                               b_col, b_val, s_q, ts, [&](int32_t j, V v) {
-                                   const int slot = lds_find_or_insert<BITS>(s_keys, j);
-                                   if (slot >= 0) lds_add(&s_vals[slot], v);
-                                   else s_ovf = 1;
+                               b_col, b_val, s_fc, s_q, ts, [&](const auto &cj, const auto &cv) {
+                                   if (!lds_insert_batch<BITS>(s_keys, cj, cv, [&](int slot, V v) { lds_add(&s_vals[slot], v); }))
+                                       s_ovf = 1;
                                });
-    // wg_traverse ends with a barrier (or did nothing for an empty row)
-    __syncthreads();
+    // wg_traverse ends with a barrier
 
     // compaction of the keys: each thread owns PER consecutive slots
     int mine = 0;
@@ -354,7 +379,7 @@ constexpr int HY_SLOTS = 1 << HY_BITS;
 constexpr int HY_THREADS = 1024;
 constexpr int HY_WIN = 524288;          // columns per ranking window
 constexpr int HY_WORDS = HY_WIN / 32;   // 16384 bitmap words + 16384 prefix words = the key table's 128 KB
-constexpr int HY_QCAP = 1024;
+constexpr int HY_QCAP = 256;
 
 template <typename V>
 __global__ void __launch_bounds__(HY_THREADS)
@@ -367,7 +392,8 @@ k_numeric_hybrid(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
     constexpr int PER = HY_SLOTS / HY_THREADS;   // 32 slots per thread
     constexpr int WPT = HY_WORDS / HY_THREADS;   // 16 bitmap words per thread
     __shared__ int32_t s_keys[HY_SLOTS];
-    __shared__ TravQueue<V, HY_QCAP> s_q;
+    __shared__ FlatChunk<V, WAVE> s_fc[HY_THREADS / WAVE];
+    __shared__ LongQueue<V, HY_QCAP> s_q;
     __shared__ int s_wave[HY_THREADS / WAVE];
     __shared__ int s_ovf;
     __shared__ int s_min, s_max;
@@ -392,10 +418,9 @@ k_numeric_hybrid(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
         TravState ts;
         wg_traverse<HY_THREADS, true>(a_col, a_val, a_rp[row], a_rp[row + 1],
                                       [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
-                                      b_col, b_val, s_q, ts, [&](int32_t j, V v) {
-                                          const int slot = lds_find_or_insert<HY_BITS>(s_keys, j);
-                                          if (slot >= 0) l2_add(&slab[slot], v);
-                                          else s_ovf = 1;
+                                      b_col, b_val, s_fc, s_q, ts, [&](const auto &cj, const auto &cv) {
+                                          if (!lds_insert_batch<HY_BITS>(s_keys, cj, cv, [&](int slot, V v) { l2_add(&slab[slot], v); }))
+                                              s_ovf = 1;
                                       });
         __threadfence();   // the slab additions are in L2 before anyone exchanges them out
         __syncthreads();
@@ -464,27 +489,43 @@ k_numeric_hybrid(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
     }
 }
 
-// ======================================================== dense kernel ====
-// Rows whose output exceeds every hash table.  The column range is cut into
-// windows of WIN columns; for one window the workgroup holds a dense array of
-// WIN values plus a presence bitmap in LDS, adds every product that falls into
-// the window (one LDS add + one LDS or, both without return), then walks the
-// bitmap: its prefix popcount places each present column directly at its
-// sorted position in the row's output.  bw[k*(n_win+1)+w] is the position in
-// B's arrays of the first entry of row k with column >= w*WIN (rows of B must
-// be sorted), so a window only visits its own products.  One workgroup takes
-// the windows of a row in turn, carrying the running output offset.
-constexpr int DN_THREADS = 1024;
+// ======================================================== heavy kernel ====
+// Rows whose output exceeds every LDS hash table, when B's rows are sorted.
+// The column range is cut into windows of WIN columns and
+// bw[k*(n_win+1)+w] is the position in B's arrays of the first entry of row k
+// with column >= w*WIN, so a window only visits its own products.  One
+// workgroup walks the windows of a row in turn, carrying the running output
+// offset, and chooses per window from the window's product count (an upper
+// bound of its entries):
+//   * many products: dense accumulator (Section 2.2) - WIN values + a presence
+//     bitmap in LDS, one LDS add + one LDS or per product, and the bitmap's
+//     prefix popcount places each present column at its sorted position;
+//   * few products: consecutive windows share an 8192-slot LDS hash table
+//     until their product counts add up to HCAP or the range spans RSPAN
+//     columns; the range is emitted in order through a bitmap over its span.
+// Everything is accumulated in LDS; nothing is ever overflowed by construction.
+// Memory latency bounds this path (entry -> window boundary -> products), so
+// the entries of the row and their window boundaries stay in registers across
+// windows (rows up to HV_R*1024 entries) and the next boundary is fetched one
+// window ahead.
+constexpr int HV_THREADS = 1024;
+constexpr int HV_R = 4;
+constexpr int HV_HBITS = 13;
+constexpr int HV_HSLOTS = 1 << HV_HBITS;
+constexpr int HV_HCAP = 6144;
+constexpr int HV_RSPAN = 131072;             // columns a hash range may span
+constexpr int HV_RWORDS = HV_RSPAN / 32;     // 4096 bitmap words
 
 template <typename V>
 struct DenseCfg {
     static constexpr int WIN = 131072 / (int)sizeof(V);   // 16384 columns (fp64), 32768 (fp32): 128 KB of values
     static constexpr int WORDS = WIN / 32;
+    static constexpr int LOG2 = sizeof(V) == 8 ? 14 : 15;
 };
 
 template <typename V>
-__global__ void __launch_bounds__(DN_THREADS)
-k_numeric_dense(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col, const V *__restrict__ a_val,
+__global__ void __launch_bounds__(HV_THREADS)
+k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col, const V *__restrict__ a_val,
                 const uint32_t *__restrict__ bw, int n_win, const int32_t *__restrict__ b_col,
                 const V *__restrict__ b_val, const int32_t *__restrict__ rows, int64_t count,
                 unsigned long long *queue, const int64_t *__restrict__ out_ptr, int32_t *__restrict__ out_col,
@@ -492,19 +533,35 @@ k_numeric_dense(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
 {
     constexpr int WIN = DenseCfg<V>::WIN;
     constexpr int WORDS = DenseCfg<V>::WORDS;
-    __shared__ V s_vals[WIN];
-    __shared__ uint32_t s_bm[WORDS];
-    __shared__ uint32_t s_pre[WORDS];
-    __shared__ TravQueue<V, DN_THREADS> s_q;
-    __shared__ int s_wave[DN_THREADS / WAVE];
+    constexpr int RWIN = HV_RSPAN / WIN;   // windows per hash range
+    // one 128 KB region, used either as the dense window or as hash table + range bitmap
+    __shared__ __align__(16) unsigned char s_u[131072];
+    __shared__ uint32_t s_dbm[WORDS];
+    __shared__ uint32_t s_dpre[WORDS];
+    __shared__ FlatChunk<V, WAVE> s_fc[HV_THREADS / WAVE];
+    __shared__ LongQueue<V, 128> s_q;
+    __shared__ int s_wave[HV_THREADS / WAVE];
+    __shared__ unsigned long long s_prod[3];
+    __shared__ int s_ovf;
     __shared__ long long s_row;
+    V *s_vals = reinterpret_cast<V *>(s_u);                                        // dense: WIN values
+    int32_t *s_keys = reinterpret_cast<int32_t *>(s_u);                            // hash: 8192 keys
+    V *s_hvals = reinterpret_cast<V *>(s_u + 32768);                               // hash: 8192 values
+    uint32_t *s_rbm = reinterpret_cast<uint32_t *>(s_u + 98304);                   // hash: range bitmap, 4096 words
+    uint16_t *s_rpre = reinterpret_cast<uint16_t *>(s_u + 98304 + 4 * HV_RWORDS);  // hash: prefix per word
     const int tid = threadIdx.x;
-    for (int j = tid; j < WIN; j += DN_THREADS) s_vals[j] = (V)0;
-    for (int j = tid; j < WORDS; j += DN_THREADS) s_bm[j] = 0u;
     const size_t stride = (size_t)n_win + 1;
 
+    for (int j = tid; j < WIN; j += HV_THREADS) s_vals[j] = (V)0;
+    for (int j = tid; j < WORDS; j += HV_THREADS) s_dbm[j] = 0u;
+    bool dense_clean = true;   // the region is an all-zero dense window
+
     for (;;) {
-        if (tid == 0) { s_row = (long long)atomicAdd(queue, 1ull); s_q.n = 0; s_q.n_huge = 0; }
+        if (tid == 0) {
+            s_row = (long long)atomicAdd(queue, 1ull);
+            s_q.n = 0; s_q.n_huge = 0; s_ovf = 0;
+            s_prod[0] = 0; s_prod[1] = 0; s_prod[2] = 0;
+        }
         __syncthreads();
         const int64_t r = s_row;
         if (r >= count) break;   // uniform exit
@@ -512,53 +569,213 @@ k_numeric_dense(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
         const int64_t e0 = a_rp[row], e1 = a_rp[row + 1];
         const int64_t o = out_ptr[row];
         const int64_t cap = out_ptr[row + 1] - o;
+        const bool cached = (e1 - e0) <= (int64_t)HV_R * HV_THREADS;
         long long done = 0;
-        TravState ts;   // the queue counters were reset with s_row and keep running over the windows of this row
-        for (int w = 0; w < n_win; ++w) {
-            const uint32_t *bww = bw + w;
-            wg_traverse<DN_THREADS, true>(a_col, a_val, e0, e1,
-                                          [&](int32_t k, int64_t &p0, int64_t &len) {
-                                              const uint32_t *t = bww + (size_t)k * stride;
-                                              const uint32_t a0 = t[0], a1 = t[1];
-                                              p0 = a0; len = (int64_t)a1 - (int64_t)a0;
-                                          },
-                                          b_col, b_val, s_q, ts, [&](int32_t j, V v) {
-                                              const unsigned d = (unsigned)(j - w * WIN);
-                                              if (d < (unsigned)WIN) {   // always true for a consistent window table
-                                                  lds_add(&s_vals[d], v);
-                                                  atomicOr(&s_bm[d >> 5], 1u << (d & 31));
-                                              }
-                                          });
-            // all adds of this window are done (wg_traverse ends with a barrier)
-            const uint32_t word = tid < WORDS ? s_bm[tid] : 0u;
-            int wtotal;
-            const int ex = block_exclusive_scan_i32<DN_THREADS>(__popc(word), s_wave, wtotal);
-            if (tid < WORDS) s_pre[tid] = (uint32_t)ex;
-            __syncthreads();
-            if (wtotal > 0) {
-                // every thread owns BPT consecutive bits of the bitmap and walks only the set ones
-                constexpr int BPT = WIN / DN_THREADS;   // 16 (fp64) or 32 (fp32)
-                const int32_t col0 = w * WIN;
-                const int j0 = tid * BPT;
-                const uint32_t wbits = s_bm[j0 >> 5];
-                uint32_t bits = BPT == 32 ? wbits : ((wbits >> (j0 & 31)) & ((1u << (BPT & 31)) - 1u));
-                long long rank = done + (long long)s_pre[j0 >> 5] + __popc(wbits & ((1u << (j0 & 31)) - 1u));
-                while (bits) {
-                    const int b = __ffs((int)bits) - 1;
-                    bits &= bits - 1u;
-                    const int j = j0 + b;
-                    const V val = s_vals[j];
-                    s_vals[j] = (V)0;
-                    if (rank < cap) { out_col[o + rank] = col0 + j; out_val[o + rank] = val; }
-                    ++rank;
+        TravState ts;
+
+        // this thread's entries of the row and their current window segment [cur, nxt)
+        int32_t ek[HV_R];
+        V ea[HV_R];
+        uint32_t cur[HV_R], nxt[HV_R];
+#pragma unroll
+        for (int i = 0; i < HV_R; ++i) {
+            ek[i] = -1; ea[i] = V(); cur[i] = 0; nxt[i] = 0;
+            const int64_t e = e0 + (int64_t)i * HV_THREADS + tid;
+            if (cached && e < e1) {
+                ek[i] = a_col[e];
+                ea[i] = a_val[e];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < HV_R; ++i) {
+            if (ek[i] >= 0) {
+                const uint32_t *t = bw + (size_t)ek[i] * stride;
+                cur[i] = t[0];
+                nxt[i] = t[1];
+            }
+        }
+
+        bool hash_active = false;
+        long long h_ub = 0;
+        int range_w0 = 0;
+
+        // emits the current hash range in ascending column order and empties its bitmap
+        auto emit_range = [&]() {
+            const int32_t col0 = range_w0 * WIN;
+#pragma unroll
+            for (int q = 0; q < HV_HSLOTS / HV_THREADS; ++q) {
+                const int32_t key = s_keys[q * HV_THREADS + tid];
+                if (key != EMPTY_KEY) {
+                    const int d = key - col0;
+                    atomicOr(&s_rbm[d >> 5], 1u << (d & 31));
                 }
-                __syncthreads();
-                if (tid < WORDS) s_bm[tid] = 0u;
-                done += wtotal;
             }
             __syncthreads();
+            constexpr int WPT = HV_RWORDS / HV_THREADS;   // 4
+            int cnt[WPT];
+            int mine = 0;
+#pragma unroll
+            for (int q = 0; q < WPT; ++q) { cnt[q] = __popc(s_rbm[tid * WPT + q]); mine += cnt[q]; }
+            int rtotal;
+            int run = block_exclusive_scan_i32<HV_THREADS>(mine, s_wave, rtotal);
+#pragma unroll
+            for (int q = 0; q < WPT; ++q) { s_rpre[tid * WPT + q] = (uint16_t)run; run += cnt[q]; }
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < HV_HSLOTS / HV_THREADS; ++q) {
+                const int slot = q * HV_THREADS + tid;
+                const int32_t key = s_keys[slot];
+                if (key != EMPTY_KEY) {
+                    const int d = key - col0;
+                    const long long rank = done + (long long)s_rpre[d >> 5] + __popc(s_rbm[d >> 5] & ((1u << (d & 31)) - 1u));
+                    if (rank < cap) { out_col[o + rank] = key; out_val[o + rank] = s_hvals[slot]; }
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < WPT; ++q) s_rbm[tid * WPT + q] = 0u;
+            done += rtotal;
+            __syncthreads();
+        };
+
+        for (int w = 0; w < n_win; ++w) {
+            // ---- products of this window
+            unsigned long long local = 0;
+            uint32_t pre[HV_R] = {0, 0, 0, 0};
+            if (cached) {
+#pragma unroll
+                for (int i = 0; i < HV_R; ++i) {
+                    local += (unsigned long long)(nxt[i] - cur[i]);
+                    pre[i] = nxt[i];
+                    if (ek[i] >= 0 && w + 2 <= n_win) pre[i] = bw[(size_t)ek[i] * stride + w + 2];   // one window ahead
+                }
+            } else {
+                for (int64_t e = e0 + tid; e < e1; e += HV_THREADS) {
+                    const uint32_t *t = bw + (size_t)a_col[e] * stride + w;
+                    local += (unsigned long long)(t[1] - t[0]);
+                }
+            }
+            local = group_reduce_sum(local, WAVE);
+            if (lane_id() == 0 && local) atomicAdd(&s_prod[w % 3], local);
+            __syncthreads();
+            const long long prod_w = (long long)s_prod[w % 3];
+            if (tid == 0) s_prod[(w + 2) % 3] = 0;
+            if (prod_w > 0) {
+                // ---- accumulator of this window
+                bool use_hash;
+                if (hash_active && h_ub + prod_w <= HV_HCAP && (w - range_w0) < RWIN) {
+                    use_hash = true;
+                } else {
+                    if (hash_active) { emit_range(); hash_active = false; }
+                    use_hash = prod_w <= HV_HCAP;
+                    if (use_hash) {
+                        for (int s = tid; s < HV_HSLOTS; s += HV_THREADS) { s_keys[s] = EMPTY_KEY; s_hvals[s] = (V)0; }
+                        // the range bitmap inside the region is already zero: the region is either an all-zero
+                        // dense window or was left by a range whose emission cleared its bitmap
+                        dense_clean = false;
+                        hash_active = true;
+                        h_ub = 0;
+                        range_w0 = w;
+                    } else if (!dense_clean) {
+                        for (int j = tid; j < WIN; j += HV_THREADS) s_vals[j] = (V)0;
+                        dense_clean = true;
+                    }
+                    __syncthreads();
+                }
+                // ---- accumulate
+                if (use_hash) {
+                    h_ub += prod_w;
+                    auto f = [&](const auto &cj, const auto &cv) {
+                        if (!lds_insert_batch<HV_HBITS>(s_keys, cj, cv, [&](int slot, V v) { lds_add(&s_hvals[slot], v); }))
+                            s_ovf = 1;
+                    };
+                    if (cached) {
+#pragma unroll
+                        for (int i = 0; i < HV_R; ++i) {
+                            if ((int64_t)i * HV_THREADS < e1 - e0)   // uniform: this slot holds entries of the row
+                                wave_chunk<HV_THREADS, true>(s_fc[tid / WAVE], &s_q, ts, (int64_t)cur[i],
+                                                             (int64_t)nxt[i] - (int64_t)cur[i], ea[i], b_col, b_val, f);
+                        }
+                        __syncthreads();
+                        queue_drain<HV_THREADS, true>(s_q, ts, b_col, b_val, f);
+                        __syncthreads();
+                    } else {
+                        const uint32_t *bww = bw + w;
+                        wg_traverse<HV_THREADS, true>(a_col, a_val, e0, e1,
+                                                      [&](int32_t k, int64_t &p0, int64_t &len) {
+                                                          const uint32_t *t = bww + (size_t)k * stride;
+                                                          const uint32_t a0 = t[0], a1 = t[1];
+                                                          p0 = a0; len = (int64_t)a1 - (int64_t)a0;
+                                                      },
+                                                      b_col, b_val, s_fc, s_q, ts, f);
+                    }
+                } else {
+                    auto f = [&](const auto &cj, const auto &cv) {
+                        constexpr int U = sizeof(cj) / sizeof(cj[0]);
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            const unsigned d = (unsigned)(cj[u] - w * WIN);
+                            if (cj[u] >= 0 && d < (unsigned)WIN) {   // d is in range for a consistent window table
+                                lds_add(&s_vals[d], cv[u]);
+                                atomicOr(&s_dbm[d >> 5], 1u << (d & 31));
+                            }
+                        }
+                    };
+                    if (cached) {
+#pragma unroll
+                        for (int i = 0; i < HV_R; ++i) {
+                            if ((int64_t)i * HV_THREADS < e1 - e0)   // uniform: this slot holds entries of the row
+                                wave_chunk<HV_THREADS, true>(s_fc[tid / WAVE], &s_q, ts, (int64_t)cur[i],
+                                                             (int64_t)nxt[i] - (int64_t)cur[i], ea[i], b_col, b_val, f);
+                        }
+                        __syncthreads();
+                        queue_drain<HV_THREADS, true>(s_q, ts, b_col, b_val, f);
+                        __syncthreads();
+                    } else {
+                        const uint32_t *bww = bw + w;
+                        wg_traverse<HV_THREADS, true>(a_col, a_val, e0, e1,
+                                                      [&](int32_t k, int64_t &p0, int64_t &len) {
+                                                          const uint32_t *t = bww + (size_t)k * stride;
+                                                          const uint32_t a0 = t[0], a1 = t[1];
+                                                          p0 = a0; len = (int64_t)a1 - (int64_t)a0;
+                                                      },
+                                                      b_col, b_val, s_fc, s_q, ts, f);
+                    }
+                    // ---- dense window -> output, in column order
+                    const uint32_t word = tid < WORDS ? s_dbm[tid] : 0u;
+                    int wtotal;
+                    const int ex = block_exclusive_scan_i32<HV_THREADS>(__popc(word), s_wave, wtotal);
+                    if (tid < WORDS) s_dpre[tid] = (uint32_t)ex;
+                    __syncthreads();
+                    constexpr int BPT = WIN / HV_THREADS;   // 16 (fp64) or 32 (fp32) bits of the bitmap per thread
+                    const int32_t col0 = w * WIN;
+                    const int j0 = tid * BPT;
+                    const uint32_t wbits = s_dbm[j0 >> 5];
+                    uint32_t bits = BPT == 32 ? wbits : ((wbits >> (j0 & 31)) & ((1u << (BPT & 31)) - 1u));
+                    long long rank = done + (long long)s_dpre[j0 >> 5] + __popc(wbits & ((1u << (j0 & 31)) - 1u));
+                    while (bits) {
+                        const int b = __ffs((int)bits) - 1;
+                        bits &= bits - 1u;
+                        const int j = j0 + b;
+                        const V val = s_vals[j];
+                        s_vals[j] = (V)0;
+                        if (rank < cap) { out_col[o + rank] = col0 + j; out_val[o + rank] = val; }
+                        ++rank;
+                    }
+                    __syncthreads();
+                    if (tid < WORDS) s_dbm[tid] = 0u;
+                    done += wtotal;
+                    __syncthreads();
+                }
+            }
+            // ---- next window's segments
+            if (cached) {
+#pragma unroll
+                for (int i = 0; i < HV_R; ++i) { cur[i] = nxt[i]; nxt[i] = pre[i]; }
+            }
         }
-        if (tid == 0) row_nnz[row] = done > cap ? -1 : (int32_t)done;
+        if (hash_active) emit_range();
+        if (tid == 0) row_nnz[row] = (s_ovf || done > cap) ? -1 : (int32_t)done;
         __syncthreads();
     }
 }
@@ -622,23 +839,7 @@ int dense_window_count(int64_t n_cols, int dtype)
 constexpr int GL_THREADS = 1024;
 constexpr int GL_WIN = 524288;
 constexpr int GL_WORDS = GL_WIN / 32;   // 16384
-constexpr int GL_QCAP = 1024;
-
-__device__ __forceinline__ int64_t gl_find_or_insert(int32_t *keys, int bits, int32_t key)
-{
-    const uint32_t mask = (1u << bits) - 1u;
-    uint32_t h = table_hash(key, bits);
-    for (uint32_t probe = 0; probe <= mask; ++probe) {
-        const int32_t cur = __hip_atomic_load(&keys[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (cur == key) return h;
-        if (cur == EMPTY_KEY) {
-            const int32_t old = atomicCAS(&keys[h], EMPTY_KEY, key);
-            if (old == EMPTY_KEY || old == key) return h;
-        }
-        h = (h + 1u) & mask;
-    }
-    return -1;
-}
+constexpr int GL_QCAP = 256;
 
 template <typename V>
 __global__ void __launch_bounds__(GL_THREADS)
@@ -652,7 +853,8 @@ k_numeric_global(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
     constexpr int WPT = GL_WORDS / GL_THREADS;   // 16 words per thread
     __shared__ uint32_t s_bm[GL_WORDS];
     __shared__ uint32_t s_pre[GL_WORDS];
-    __shared__ TravQueue<V, GL_QCAP> s_q;
+    __shared__ FlatChunk<V, WAVE> s_fc[GL_THREADS / WAVE];
+    __shared__ LongQueue<V, GL_QCAP> s_q;
     __shared__ int s_wave[GL_THREADS / WAVE];
     __shared__ int s_ovf;
     __shared__ int s_min, s_max;
@@ -683,14 +885,43 @@ k_numeric_global(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
         TravState ts;
         wg_traverse<GL_THREADS, true>(a_col, a_val, a_rp[row], a_rp[row + 1],
                                       [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
-                                      b_col, b_val, s_q, ts, [&](int32_t j, V v) {
-                                          const int64_t slot = gl_find_or_insert(gk, bits, j);
-                                          if (slot >= 0) {
-                                              l2_add(&gv[slot], v);
-                                              kmin = j < kmin ? j : kmin;
-                                              kmax = j > kmax ? j : kmax;
-                                          } else {
-                                              s_ovf = 1;
+                                      b_col, b_val, s_fc, s_q, ts, [&](const auto &cj, const auto &cv) {
+                                          constexpr int U = sizeof(cj) / sizeof(cj[0]);
+                                          const uint32_t mask = (1u << bits) - 1u;
+                                          uint32_t h[U], st[U];
+                                          bool pend[U];
+                                          bool any = false;
+#pragma unroll
+                                          for (int u = 0; u < U; ++u) {
+                                              pend[u] = cj[u] >= 0;
+                                              h[u] = table_hash(cj[u], bits);
+                                              st[u] = table_step(cj[u], bits);
+                                              any |= pend[u];
+                                              if (pend[u]) {
+                                                  kmin = cj[u] < kmin ? cj[u] : kmin;
+                                                  kmax = cj[u] > kmax ? cj[u] : kmax;
+                                              }
+                                          }
+                                          uint32_t rounds = 0;
+                                          while (any) {   // all unresolved products probe together: their L2 round trips overlap
+                                              int32_t old[U];
+#pragma unroll
+                                              for (int u = 0; u < U; ++u)
+                                                  if (pend[u]) old[u] = atomicCAS(&gk[h[u]], EMPTY_KEY, cj[u]);
+                                              any = false;
+#pragma unroll
+                                              for (int u = 0; u < U; ++u) {
+                                                  if (pend[u]) {
+                                                      if (old[u] == EMPTY_KEY || old[u] == cj[u]) {
+                                                          pend[u] = false;
+                                                          l2_add(&gv[h[u]], cv[u]);
+                                                      } else {
+                                                          h[u] = (h[u] + st[u]) & mask;
+                                                          any = true;
+                                                      }
+                                                  }
+                                              }
+                                              if (any && ++rounds > mask) { s_ovf = 1; break; }
                                           }
                                       });
         kmin = -group_reduce_max(-kmin, WAVE);
@@ -753,8 +984,8 @@ static hipError_t dispatch(const Csr &A, const Csr &B, const NumLaunch &l, int g
     switch (l.bin) {
     case NB_G16: {
         const int64_t blocks = (l.count + 15) / 16;
-        hipLaunchKernelGGL((k_numeric_group<V, 16, 6>), dim3((unsigned)blocks), dim3(256), 0, s, A.rp, A.col, av, B.rp,
-                           B.col, bv, l.rows, l.count, gb_log2 < 4 ? gb_log2 : 4, l.out_ptr, l.out_col, ov, l.row_nnz);
+        hipLaunchKernelGGL((k_numeric_group<V>), dim3((unsigned)blocks), dim3(256), 0, s, A.rp, A.col, av, B.rp, B.col, bv,
+                           l.rows, l.count, l.out_ptr, l.out_col, ov, l.row_nnz);
         break;
     }
     case NB_W64: {
@@ -769,13 +1000,17 @@ static hipError_t dispatch(const Csr &A, const Csr &B, const NumLaunch &l, int g
     case NB_S4K: OCEAN_WG(12, 1024); break;
     case NB_S8K: OCEAN_WG(13, 1024); break;
     case NB_HYBRID:
-        hipLaunchKernelGGL((k_numeric_hybrid<V>), dim3((unsigned)l.n_wg), dim3(HY_THREADS), 0, s, A.rp, A.col, av, B.rp,
-                           B.col, bv, l.rows, l.count, l.queue, static_cast<V *>(l.slab), static_cast<uint2 *>(l.pairs),
-                           l.out_ptr, l.out_col, ov, l.row_nnz);
+        if (l.bw != nullptr)
+            hipLaunchKernelGGL((k_numeric_heavy<V>), dim3((unsigned)l.n_wg), dim3(HV_THREADS), 0, s, A.rp, A.col, av, l.bw,
+                               l.n_win, B.col, bv, l.rows, l.count, l.queue, l.out_ptr, l.out_col, ov, l.row_nnz);
+        else
+            hipLaunchKernelGGL((k_numeric_hybrid<V>), dim3((unsigned)l.n_wg), dim3(HY_THREADS), 0, s, A.rp, A.col, av,
+                               B.rp, B.col, bv, l.rows, l.count, l.queue, static_cast<V *>(l.slab),
+                               static_cast<uint2 *>(l.pairs), l.out_ptr, l.out_col, ov, l.row_nnz);
         break;
     case NB_GLOBAL:
         if (l.bw != nullptr)
-            hipLaunchKernelGGL((k_numeric_dense<V>), dim3((unsigned)l.n_wg), dim3(DN_THREADS), 0, s, A.rp, A.col, av, l.bw,
+            hipLaunchKernelGGL((k_numeric_heavy<V>), dim3((unsigned)l.n_wg), dim3(HV_THREADS), 0, s, A.rp, A.col, av, l.bw,
                                l.n_win, B.col, bv, l.rows, l.count, l.queue, l.out_ptr, l.out_col, ov, l.row_nnz);
         else
             hipLaunchKernelGGL((k_numeric_global<V>), dim3((unsigned)l.n_wg), dim3(GL_THREADS), 0, s, A.rp, A.col, av,

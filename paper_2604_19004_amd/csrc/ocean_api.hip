@@ -340,7 +340,12 @@ int run_numeric(Ctx &c, Work &w, const Csr &A, const Csr &B, int dtype, int gb_l
         l.row_nnz = row_nnz;
         l.coef = global_coef;
         if (l.count == 0) continue;
-        if (b == NB_HYBRID) {
+        if (b == NB_HYBRID && c.bw != nullptr) {
+            l.bw = c.bw;
+            l.n_win = c.n_win;
+            l.n_wg = (int)(l.count < c.n_cu ? l.count : c.n_cu);
+            l.queue = &w.sc->queue[queue_base];
+        } else if (b == NB_HYBRID) {
             l.n_wg = (int)(l.count < c.n_cu ? l.count : c.n_cu);
             const size_t bytes = (size_t)l.n_wg * 32768 * vbytes;
             l.slab = c.alloc(bytes);
@@ -403,6 +408,7 @@ void fill_defaults(ocean_options *o)
     o->sample_seed = 1;
     o->estimate_scale = 1.0;
     o->validate_inputs = 1;
+    o->force_hash_kernels = 0;
     o->allocator = nullptr;
 }
 
@@ -483,7 +489,7 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
     // needs the window boundaries inside every (sorted) row of B.  Built only when such rows can exist
     // and the table stays small; otherwise, or when a row of B turns out unsorted, they use global tables.
     uint32_t *bw_try = nullptr;
-    if (max_ub > kNumericSlots[NB_HYBRID] && B.nnz < 0xffffffffLL) {
+    if (max_ub > kNumericSlots[NB_S8K] && B.nnz < 0xffffffffLL && !o.force_hash_kernels) {
         const int nw = dense_window_count(n, dtype);
         const size_t bytes = (size_t)B.rows * ((size_t)nw + 1) * 4;
         if (bytes <= ((size_t)6 << 30)) {

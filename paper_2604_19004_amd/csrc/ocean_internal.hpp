@@ -86,6 +86,16 @@ __device__ __forceinline__ uint32_t table_hash(int32_t key, int bits)
     return ((uint32_t)key * 0x9E3779B1u) >> (32 - bits);
 }
 
+// Probe stride of a key (double hashing): odd, so it visits every slot of a
+// power-of-two table.  A wave waits for its slowest lane, so what matters is
+// the longest probe sequence among 64 concurrent insertions; linear probing's
+// clustering makes that several times longer than with independent strides,
+// and LDS has no locality that would reward neighbouring slots.
+__device__ __forceinline__ uint32_t table_step(int32_t key, int bits)
+{
+    return ((((uint32_t)key * 0x85EBCA6Bu) >> (32 - bits)) << 1) | 1u;
+}
+
 template <typename T>
 __device__ __forceinline__ T group_reduce_sum(T v, int width)
 {

@@ -10,57 +10,76 @@
 
 namespace ocean {
 
-// 1: key was new, 0: already present, -1: table full
-template <int BITS>
-__device__ __forceinline__ int lds_insert_new(int32_t *keys, int32_t key)
-{
-    constexpr uint32_t MASK = (1u << BITS) - 1u;
-    uint32_t h = table_hash(key, BITS);
-    for (uint32_t probe = 0; probe <= MASK; ++probe) {
-        const int32_t cur = __hip_atomic_load(&keys[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        if (cur == key) return 0;
-        if (cur == EMPTY_KEY) {
-            const int32_t old = atomicCAS(&keys[h], EMPTY_KEY, key);
-            if (old == EMPTY_KEY) return 1;
-            if (old == key) return 0;
-        }
-        h = (h + 1u) & MASK;
-    }
-    return -1;
-}
-
 using NoVal = unsigned char;   // the symbolic pass carries no values
 
+// Insert a batch of column ids into a key-only LDS table and return how many
+// were new.  Double hashing, and every lane walks its own ids at its own pace
+// (one compare-and-swap per lane and round), so the wave-wide loop runs for the
+// largest per-lane sum of probes.  Valid ids come first in a batch.
+template <int BITS, int U>
+__device__ __forceinline__ int lds_count_new_batch(int32_t *keys, const int32_t (&cj)[U])
+{
+    constexpr uint32_t MASK = (1u << BITS) - 1u;
+    int idx = 0, fresh = 0;
+    int32_t key = cj[0];
+    uint32_t h = table_hash(key, BITS);
+    uint32_t step = table_step(key, BITS);
+    uint32_t rounds = 0;
+    while (key >= 0) {
+        const int32_t old = atomicCAS(&keys[h], EMPTY_KEY, key);
+        if (old == EMPTY_KEY || old == key) {
+            fresh += (old == EMPTY_KEY);
+            ++idx;
+            key = -1;
+#pragma unroll
+            for (int u = 1; u < U; ++u)
+                if (idx == u) key = cj[u];
+            h = table_hash(key, BITS);
+            step = table_step(key, BITS);
+            rounds = 0;
+        } else {
+            h = (h + step) & MASK;
+            if (++rounds > MASK) key = -1;   // cannot happen: tables are sized from the product count
+        }
+    }
+    return fresh;
+}
+
 // ---------------------------------------------------------- group kernel
-template <int G, int BITS>
 __global__ void __launch_bounds__(256)
 k_symbolic_group(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col,
                  const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_col,
-                 const int32_t *__restrict__ rows, int64_t count, int gb_log2, int32_t *__restrict__ nnz_out)
+                 const int32_t *__restrict__ rows, int64_t count, int32_t *__restrict__ nnz_out)
 {
+    constexpr int G = 16;
+    constexpr int BITS = 6;
     constexpr int SLOTS = 1 << BITS;
     constexpr int R = 256 / G;
     __shared__ int32_t s_keys[R * SLOTS];
+    __shared__ FlatChunk<NoVal, G> s_fc[R];
     const int rl = threadIdx.x / G;
     const int sub = threadIdx.x % G;
     int32_t *keys = s_keys + rl * SLOTS;
-    const int gb = 1 << gb_log2;
-    const int sub_b = sub & (gb - 1);
-    const int part = sub >> gb_log2;
-    const int parts = G >> gb_log2;
     const int64_t r = (int64_t)blockIdx.x * R + rl;
     const bool live = r < count;
     const int64_t row = live ? rows[r] : 0;
     for (int s = sub; s < SLOTS; s += G) keys[s] = EMPTY_KEY;
     wave_sync();
     int fresh = 0;
-    if (live) {
-        const int64_t e1 = a_rp[row + 1];
-        for (int64_t e = a_rp[row] + part; e < e1; e += parts) {
+    const int64_t e0 = live ? a_rp[row] : 0;
+    const int64_t e1 = live ? a_rp[row + 1] : 0;
+    auto f = [&](const auto &cj, const auto &) { fresh += lds_count_new_batch<BITS>(keys, cj); };
+    const int chunks = group_reduce_max((int)((e1 - e0 + G - 1) / G), WAVE);
+    for (int ch = 0; ch < chunks; ++ch) {
+        const int64_t e = e0 + (int64_t)ch * G + sub;
+        int64_t p0 = 0;
+        uint32_t len = 0;
+        if (e < e1) {
             const int64_t k = a_col[e];
-            const int64_t p1 = b_rp[k + 1];
-            for (int64_t p = b_rp[k] + sub_b; p < p1; p += gb) fresh += (lds_insert_new<BITS>(keys, b_col[p]) == 1);
+            p0 = b_rp[k];
+            len = (uint32_t)(b_rp[k + 1] - p0);
         }
+        group_flat<G, false>(s_fc[rl], p0, len, NoVal(), b_col, (const NoVal *)nullptr, f);
     }
     fresh = group_reduce_sum(fresh, G);
     if (live && sub == 0) nnz_out[row] = fresh;
@@ -75,7 +94,7 @@ k_symbolic_wave(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     constexpr int BITS = 8;
     constexpr int SLOTS = 1 << BITS;
     __shared__ int32_t s_keys[4 * SLOTS];
-    __shared__ WaveQueue<NoVal> s_q[4];
+    __shared__ FlatChunk<NoVal, WAVE> s_fc[4];
     const int rl = threadIdx.x / WAVE;
     const int sub = lane_id();
     int32_t *keys = s_keys + rl * SLOTS;
@@ -87,8 +106,8 @@ k_symbolic_wave(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     int fresh = 0;
     wave_traverse<false>(a_col, (const NoVal *)nullptr, a_rp[row], a_rp[row + 1],
                          [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
-                         b_col, (const NoVal *)nullptr, s_q[rl],
-                         [&](int32_t j, NoVal) { fresh += (lds_insert_new<BITS>(keys, j) == 1); });
+                         b_col, (const NoVal *)nullptr, s_fc[rl],
+                         [&](const auto &cj, const auto &) { fresh += lds_count_new_batch<BITS>(keys, cj); });
     fresh = group_reduce_sum(fresh, WAVE);
     if (sub == 0) nnz_out[row] = fresh;
 }
@@ -102,7 +121,8 @@ k_symbolic_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_co
 {
     constexpr int SLOTS = 1 << BITS;
     __shared__ int32_t s_keys[SLOTS];
-    __shared__ TravQueue<NoVal, THREADS> s_q;
+    __shared__ FlatChunk<NoVal, WAVE> s_fc[THREADS / WAVE];
+    __shared__ LongQueue<NoVal, 256> s_q;
     __shared__ int s_count;
     const int tid = threadIdx.x;
     const int64_t r = blockIdx.x;
@@ -115,8 +135,8 @@ k_symbolic_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_co
     TravState ts;
     wg_traverse<THREADS, false>(a_col, (const NoVal *)nullptr, a_rp[row], a_rp[row + 1],
                                 [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
-                                b_col, (const NoVal *)nullptr, s_q, ts,
-                                [&](int32_t j, NoVal) { fresh += (lds_insert_new<BITS>(s_keys, j) == 1); });
+                                b_col, (const NoVal *)nullptr, s_fc, s_q, ts,
+                                [&](const auto &cj, const auto &) { fresh += lds_count_new_batch<BITS>(s_keys, cj); });
     fresh = group_reduce_sum(fresh, WAVE);
     if (lane_id() == 0 && fresh) atomicAdd(&s_count, fresh);
     __syncthreads();
@@ -135,7 +155,8 @@ k_symbolic_bitmap(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ 
                   unsigned long long *queue, int32_t *__restrict__ nnz_out)
 {
     __shared__ uint32_t s_bm[BM_WORDS];
-    __shared__ TravQueue<NoVal, BM_THREADS> s_q;
+    __shared__ FlatChunk<NoVal, WAVE> s_fc[BM_THREADS / WAVE];
+    __shared__ LongQueue<NoVal, 256> s_q;
     __shared__ int s_count;
     __shared__ long long s_row;
     const int tid = threadIdx.x;
@@ -151,9 +172,13 @@ k_symbolic_bitmap(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ 
         for (int64_t w0 = 0; w0 < n_cols; w0 += BM_WIN) {
             wg_traverse<BM_THREADS, false>(a_col, (const NoVal *)nullptr, e0, e1,
                                            [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
-                                           b_col, (const NoVal *)nullptr, s_q, ts, [&](int32_t j, NoVal) {
-                                               const int64_t d = (int64_t)j - w0;
-                                               if (d >= 0 && d < BM_WIN) atomicOr(&s_bm[d >> 5], 1u << (d & 31));
+                                           b_col, (const NoVal *)nullptr, s_fc, s_q, ts, [&](const auto &cj, const auto &) {
+                                               constexpr int U = sizeof(cj) / sizeof(cj[0]);
+#pragma unroll
+                                               for (int u = 0; u < U; ++u) {
+                                                   const int64_t d = (int64_t)cj[u] - w0;
+                                                   if (cj[u] >= 0 && d >= 0 && d < BM_WIN) atomicOr(&s_bm[d >> 5], 1u << (d & 31));
+                                               }
                                            });
             __syncthreads();
             int c = 0;
@@ -177,8 +202,8 @@ hipError_t launch_symbolic_bin(const Csr &A, const Csr &B, const SymLaunch &l, i
                        B.rp, B.col, l.rows, l.count, nnz_out)
     switch (l.bin) {
     case SB_G16:
-        hipLaunchKernelGGL((k_symbolic_group<16, 6>), dim3((unsigned)((l.count + 15) / 16)), dim3(256), 0, s, A.rp, A.col,
-                           B.rp, B.col, l.rows, l.count, gb_log2 < 4 ? gb_log2 : 4, nnz_out);
+        hipLaunchKernelGGL(k_symbolic_group, dim3((unsigned)((l.count + 15) / 16)), dim3(256), 0, s, A.rp, A.col, B.rp, B.col,
+                           l.rows, l.count, nnz_out);
         break;
     case SB_W64:
         hipLaunchKernelGGL(k_symbolic_wave, dim3((unsigned)((l.count + 3) / 4)), dim3(256), 0, s, A.rp, A.col, B.rp, B.col,

@@ -213,16 +213,17 @@ def _heavy_case(dtype=np.float64, shuffle_b=False):
     return A, Bm
 
 
-@pytest.mark.parametrize("variant", ["f64", "f32", "f64-unsorted-B"])
+@pytest.mark.parametrize("variant", ["f64", "f32", "f64-unsorted-B", "f64-hash-kernels", "f32-hash-kernels"])
 def test_heavy_rows_reach_hybrid_and_last_bin(ob, variant):
-    A, Bm = _heavy_case(np.float32 if variant == "f32" else np.float64, shuffle_b=variant.endswith("unsorted-B"))
+    A, Bm = _heavy_case(np.float32 if variant.startswith("f32") else np.float64, shuffle_b=variant.endswith("unsorted-B"))
     ref = O.multiply_rows(A, Bm)
+    force = 1 if variant.endswith("hash-kernels") else 0
     for wf in ("symbolic", "hll", "upper_bound"):
-        Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(Bm), workflow=wf_id(ob, wf))
+        Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(Bm), workflow=wf_id(ob, wf), force_hash_kernels=force)
         check_result(Cd, ref, A, f"heavy {variant}/{wf}")
         assert st["rows_per_bin"][8] > 0                                    # dense-window / global-table bin used
         assert st["rows_per_bin"][7] > 0                                    # hybrid bin used
-    Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(Bm), workflow=ob.WF_HLL, estimate_scale=0.3)
+    Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(Bm), workflow=ob.WF_HLL, estimate_scale=0.3, force_hash_kernels=force)
     check_result(Cd, ref, A, f"heavy {variant}/hll overflow")
     assert st["overflow_rows"] > 0
 
