@@ -490,37 +490,39 @@ k_numeric_hybrid(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
 }
 
 // ======================================================== heavy kernel ====
-// Rows whose output exceeds every LDS hash table, when B's rows are sorted.
+// Rows whose output exceeds the 8192-slot LDS table, when B's rows are sorted.
 // The column range is cut into windows of WIN columns and
 // bw[k*(n_win+1)+w] is the position in B's arrays of the first entry of row k
-// with column >= w*WIN, so a window only visits its own products.  One
-// workgroup walks the windows of a row in turn, carrying the running output
-// offset, and chooses per window from the window's product count (an upper
-// bound of its entries):
-//   * many products: dense accumulator (Section 2.2) - WIN values + a presence
-//     bitmap in LDS, one LDS add + one LDS or per product, and the bitmap's
-//     prefix popcount places each present column at its sorted position;
-//   * few products: consecutive windows share an 8192-slot LDS hash table
-//     until their product counts add up to HCAP or the range spans RSPAN
-//     columns; the range is emitted in order through a bitmap over its span.
-// Everything is accumulated in LDS; nothing is ever overflowed by construction.
-// Memory latency bounds this path (entry -> window boundary -> products), so
-// the entries of the row and their window boundaries stay in registers across
-// windows (rows up to HV_R*1024 entries) and the next boundary is fetched one
-// window ahead.
+// with column >= w*WIN, so any run of windows can be visited on its own.  One
+// workgroup first counts the row's products per window (an upper bound of the
+// entries of that window), then walks the windows in order, carrying the
+// running output offset:
+//   * a window with more than HCAP products is accumulated densely (Section 2.2
+//     dense accumulator, iterated over the row's column range as in Section
+//     3.2): WIN values + a presence bitmap in LDS, one LDS add + one LDS or per
+//     product; the bitmap's prefix popcount places each present column at its
+//     sorted position;
+//   * consecutive windows whose product counts add up to at most HCAP share one
+//     pass: an 8192-slot LDS hash table takes all their products, and the table
+//     is emitted in column order through a bitmap rank, RSPAN columns at a time.
+// Everything is accumulated in LDS and no table can overflow by construction.
+// What bounds this path is the latency of its chain of dependent accesses
+// (entry -> window boundary -> products -> LDS), paid once per pass, which is
+// why sparse stretches are merged into few passes; the entries of the row stay
+// in registers across passes (rows up to HV_R*1024 entries).
 constexpr int HV_THREADS = 1024;
 constexpr int HV_R = 4;
 constexpr int HV_HBITS = 13;
 constexpr int HV_HSLOTS = 1 << HV_HBITS;
 constexpr int HV_HCAP = 6144;
-constexpr int HV_RSPAN = 131072;             // columns a hash range may span
+constexpr int HV_RSPAN = 131072;             // columns ranked per emission step
 constexpr int HV_RWORDS = HV_RSPAN / 32;     // 4096 bitmap words
+constexpr int HV_MAXWIN = 512;               // windows per row the kernel can plan for
 
 template <typename V>
 struct DenseCfg {
     static constexpr int WIN = 131072 / (int)sizeof(V);   // 16384 columns (fp64), 32768 (fp32): 128 KB of values
     static constexpr int WORDS = WIN / 32;
-    static constexpr int LOG2 = sizeof(V) == 8 ? 14 : 15;
 };
 
 template <typename V>
@@ -533,21 +535,21 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
 {
     constexpr int WIN = DenseCfg<V>::WIN;
     constexpr int WORDS = DenseCfg<V>::WORDS;
-    constexpr int RWIN = HV_RSPAN / WIN;   // windows per hash range
-    // one 128 KB region, used either as the dense window or as hash table + range bitmap
+    constexpr int RWIN = HV_RSPAN / WIN;   // windows per emission step
+    // one 128 KB region, used either as the dense window or as hash table + rank bitmap
     __shared__ __align__(16) unsigned char s_u[131072];
     __shared__ uint32_t s_dbm[WORDS];
     __shared__ uint32_t s_dpre[WORDS];
     __shared__ FlatChunk<V, WAVE> s_fc[HV_THREADS / WAVE];
     __shared__ LongQueue<V, 128> s_q;
     __shared__ int s_wave[HV_THREADS / WAVE];
-    __shared__ unsigned long long s_prod[3];
+    __shared__ uint32_t s_prodw[HV_MAXWIN];
     __shared__ int s_ovf;
     __shared__ long long s_row;
     V *s_vals = reinterpret_cast<V *>(s_u);                                        // dense: WIN values
     int32_t *s_keys = reinterpret_cast<int32_t *>(s_u);                            // hash: 8192 keys
     V *s_hvals = reinterpret_cast<V *>(s_u + 32768);                               // hash: 8192 values
-    uint32_t *s_rbm = reinterpret_cast<uint32_t *>(s_u + 98304);                   // hash: range bitmap, 4096 words
+    uint32_t *s_rbm = reinterpret_cast<uint32_t *>(s_u + 98304);                   // hash: rank bitmap, 4096 words
     uint16_t *s_rpre = reinterpret_cast<uint16_t *>(s_u + 98304 + 4 * HV_RWORDS);  // hash: prefix per word
     const int tid = threadIdx.x;
     const size_t stride = (size_t)n_win + 1;
@@ -560,8 +562,8 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
         if (tid == 0) {
             s_row = (long long)atomicAdd(queue, 1ull);
             s_q.n = 0; s_q.n_huge = 0; s_ovf = 0;
-            s_prod[0] = 0; s_prod[1] = 0; s_prod[2] = 0;
         }
+        for (int w = tid; w < n_win; w += HV_THREADS) s_prodw[w] = 0u;
         __syncthreads();
         const int64_t r = s_row;
         if (r >= count) break;   // uniform exit
@@ -573,208 +575,174 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
         long long done = 0;
         TravState ts;
 
-        // this thread's entries of the row and their current window segment [cur, nxt)
+        // this thread's entries of the row
         int32_t ek[HV_R];
         V ea[HV_R];
-        uint32_t cur[HV_R], nxt[HV_R];
 #pragma unroll
         for (int i = 0; i < HV_R; ++i) {
-            ek[i] = -1; ea[i] = V(); cur[i] = 0; nxt[i] = 0;
+            ek[i] = -1; ea[i] = V();
             const int64_t e = e0 + (int64_t)i * HV_THREADS + tid;
-            if (cached && e < e1) {
-                ek[i] = a_col[e];
-                ea[i] = a_val[e];
-            }
+            if (cached && e < e1) { ek[i] = a_col[e]; ea[i] = a_val[e]; }
         }
-#pragma unroll
-        for (int i = 0; i < HV_R; ++i) {
-            if (ek[i] >= 0) {
-                const uint32_t *t = bw + (size_t)ek[i] * stride;
-                cur[i] = t[0];
-                nxt[i] = t[1];
+        // ---- products of the row per window
+        auto count_entry = [&](int32_t k) {
+            const uint32_t *t = bw + (size_t)k * stride;
+            uint32_t prev = t[0];
+            for (int w = 0; w < n_win; ++w) {
+                const uint32_t nx = t[w + 1];
+                if (nx != prev) atomicAdd(&s_prodw[w], nx - prev);
+                prev = nx;
             }
-        }
-
-        bool hash_active = false;
-        long long h_ub = 0;
-        int range_w0 = 0;
-
-        // emits the current hash range in ascending column order and empties its bitmap
-        auto emit_range = [&]() {
-            const int32_t col0 = range_w0 * WIN;
-#pragma unroll
-            for (int q = 0; q < HV_HSLOTS / HV_THREADS; ++q) {
-                const int32_t key = s_keys[q * HV_THREADS + tid];
-                if (key != EMPTY_KEY) {
-                    const int d = key - col0;
-                    atomicOr(&s_rbm[d >> 5], 1u << (d & 31));
-                }
-            }
-            __syncthreads();
-            constexpr int WPT = HV_RWORDS / HV_THREADS;   // 4
-            int cnt[WPT];
-            int mine = 0;
-#pragma unroll
-            for (int q = 0; q < WPT; ++q) { cnt[q] = __popc(s_rbm[tid * WPT + q]); mine += cnt[q]; }
-            int rtotal;
-            int run = block_exclusive_scan_i32<HV_THREADS>(mine, s_wave, rtotal);
-#pragma unroll
-            for (int q = 0; q < WPT; ++q) { s_rpre[tid * WPT + q] = (uint16_t)run; run += cnt[q]; }
-            __syncthreads();
-#pragma unroll
-            for (int q = 0; q < HV_HSLOTS / HV_THREADS; ++q) {
-                const int slot = q * HV_THREADS + tid;
-                const int32_t key = s_keys[slot];
-                if (key != EMPTY_KEY) {
-                    const int d = key - col0;
-                    const long long rank = done + (long long)s_rpre[d >> 5] + __popc(s_rbm[d >> 5] & ((1u << (d & 31)) - 1u));
-                    if (rank < cap) { out_col[o + rank] = key; out_val[o + rank] = s_hvals[slot]; }
-                }
-            }
-            __syncthreads();
-#pragma unroll
-            for (int q = 0; q < WPT; ++q) s_rbm[tid * WPT + q] = 0u;
-            done += rtotal;
-            __syncthreads();
         };
+        if (cached) {
+#pragma unroll
+            for (int i = 0; i < HV_R; ++i)
+                if (ek[i] >= 0) count_entry(ek[i]);
+        } else {
+            for (int64_t e = e0 + tid; e < e1; e += HV_THREADS) count_entry(a_col[e]);
+        }
+        __syncthreads();
 
-        for (int w = 0; w < n_win; ++w) {
-            // ---- products of this window
-            unsigned long long local = 0;
-            uint32_t pre[HV_R] = {0, 0, 0, 0};
+        // ---- walk the windows
+        int w = 0;
+        while (w < n_win) {
+            const uint32_t pw = s_prodw[w];
+            if (pw == 0) { ++w; continue; }
+            const bool dense = pw > (uint32_t)HV_HCAP;
+            int w1 = w + 1;
+            if (!dense) {
+                uint32_t sum = pw;
+                while (w1 < n_win && sum + s_prodw[w1] <= (uint32_t)HV_HCAP) { sum += s_prodw[w1]; ++w1; }
+            }
+            // accumulator of this pass
+            if (dense) {
+                if (!dense_clean) {
+                    for (int j = tid; j < WIN; j += HV_THREADS) s_vals[j] = (V)0;
+                    dense_clean = true;
+                }
+            } else {
+                // (the rank bitmap inside the region is zero here: the region is either an all-zero dense
+                // window or was left by a hash pass whose emission cleared the bitmap)
+                for (int s = tid; s < HV_HSLOTS; s += HV_THREADS) { s_keys[s] = EMPTY_KEY; s_hvals[s] = (V)0; }
+                dense_clean = false;
+            }
+            __syncthreads();
+            // products of windows [w, w1)
+            const int32_t col0 = w * WIN;
+            auto f = [&](const auto &cj, const auto &cv) {
+                if (dense) {
+                    constexpr int U = sizeof(cj) / sizeof(cj[0]);
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const unsigned d = (unsigned)(cj[u] - col0);
+                        if (cj[u] >= 0 && d < (unsigned)WIN) {   // d is in range for a consistent window table
+                            lds_add(&s_vals[d], cv[u]);
+                            atomicOr(&s_dbm[d >> 5], 1u << (d & 31));
+                        }
+                    }
+                } else {
+                    if (!lds_insert_batch<HV_HBITS>(s_keys, cj, cv, [&](int slot, V v) { lds_add(&s_hvals[slot], v); }))
+                        s_ovf = 1;
+                }
+            };
             if (cached) {
 #pragma unroll
                 for (int i = 0; i < HV_R; ++i) {
-                    local += (unsigned long long)(nxt[i] - cur[i]);
-                    pre[i] = nxt[i];
-                    if (ek[i] >= 0 && w + 2 <= n_win) pre[i] = bw[(size_t)ek[i] * stride + w + 2];   // one window ahead
+                    if ((int64_t)i * HV_THREADS < e1 - e0) {   // uniform: this slot holds entries of the row
+                        uint32_t c0 = 0, c1 = 0;
+                        if (ek[i] >= 0) {
+                            const uint32_t *t = bw + (size_t)ek[i] * stride;
+                            c0 = t[w];
+                            c1 = t[w1];
+                        }
+                        wave_chunk<HV_THREADS, true>(s_fc[tid / WAVE], &s_q, ts, (int64_t)c0, (int64_t)c1 - (int64_t)c0,
+                                                     ea[i], b_col, b_val, f);
+                    }
                 }
+                __syncthreads();
+                queue_drain<HV_THREADS, true>(s_q, ts, b_col, b_val, f);
+                __syncthreads();
             } else {
-                for (int64_t e = e0 + tid; e < e1; e += HV_THREADS) {
-                    const uint32_t *t = bw + (size_t)a_col[e] * stride + w;
-                    local += (unsigned long long)(t[1] - t[0]);
-                }
+                wg_traverse<HV_THREADS, true>(a_col, a_val, e0, e1,
+                                              [&](int32_t k, int64_t &p0, int64_t &len) {
+                                                  const uint32_t *t = bw + (size_t)k * stride;
+                                                  const uint32_t c0 = t[w], c1 = t[w1];
+                                                  p0 = c0; len = (int64_t)c1 - (int64_t)c0;
+                                              },
+                                              b_col, b_val, s_fc, s_q, ts, f);
             }
-            local = group_reduce_sum(local, WAVE);
-            if (lane_id() == 0 && local) atomicAdd(&s_prod[w % 3], local);
-            __syncthreads();
-            const long long prod_w = (long long)s_prod[w % 3];
-            if (tid == 0) s_prod[(w + 2) % 3] = 0;
-            if (prod_w > 0) {
-                // ---- accumulator of this window
-                bool use_hash;
-                if (hash_active && h_ub + prod_w <= HV_HCAP && (w - range_w0) < RWIN) {
-                    use_hash = true;
-                } else {
-                    if (hash_active) { emit_range(); hash_active = false; }
-                    use_hash = prod_w <= HV_HCAP;
-                    if (use_hash) {
-                        for (int s = tid; s < HV_HSLOTS; s += HV_THREADS) { s_keys[s] = EMPTY_KEY; s_hvals[s] = (V)0; }
-                        // the range bitmap inside the region is already zero: the region is either an all-zero
-                        // dense window or was left by a range whose emission cleared its bitmap
-                        dense_clean = false;
-                        hash_active = true;
-                        h_ub = 0;
-                        range_w0 = w;
-                    } else if (!dense_clean) {
-                        for (int j = tid; j < WIN; j += HV_THREADS) s_vals[j] = (V)0;
-                        dense_clean = true;
-                    }
-                    __syncthreads();
+            if (dense) {
+                // ---- dense window -> output, in column order
+                const uint32_t word = tid < WORDS ? s_dbm[tid] : 0u;
+                int wtotal;
+                const int ex = block_exclusive_scan_i32<HV_THREADS>(__popc(word), s_wave, wtotal);
+                if (tid < WORDS) s_dpre[tid] = (uint32_t)ex;
+                __syncthreads();
+                constexpr int BPT = WIN / HV_THREADS;   // 16 (fp64) or 32 (fp32) bits of the bitmap per thread
+                const int j0 = tid * BPT;
+                const uint32_t wbits = s_dbm[j0 >> 5];
+                uint32_t bits = BPT == 32 ? wbits : ((wbits >> (j0 & 31)) & ((1u << (BPT & 31)) - 1u));
+                long long rank = done + (long long)s_dpre[j0 >> 5] + __popc(wbits & ((1u << (j0 & 31)) - 1u));
+                while (bits) {
+                    const int b = __ffs((int)bits) - 1;
+                    bits &= bits - 1u;
+                    const int j = j0 + b;
+                    const V val = s_vals[j];
+                    s_vals[j] = (V)0;
+                    if (rank < cap) { out_col[o + rank] = col0 + j; out_val[o + rank] = val; }
+                    ++rank;
                 }
-                // ---- accumulate
-                if (use_hash) {
-                    h_ub += prod_w;
-                    auto f = [&](const auto &cj, const auto &cv) {
-                        if (!lds_insert_batch<HV_HBITS>(s_keys, cj, cv, [&](int slot, V v) { lds_add(&s_hvals[slot], v); }))
-                            s_ovf = 1;
-                    };
-                    if (cached) {
+                __syncthreads();
+                if (tid < WORDS) s_dbm[tid] = 0u;
+                done += wtotal;
+                __syncthreads();
+            } else {
+                // ---- hash table -> output, RSPAN columns at a time
+                for (int ws = w; ws < w1; ws += RWIN) {
+                    const int we = ws + RWIN < w1 ? ws + RWIN : w1;
+                    uint32_t any = 0;
+                    for (int x = ws; x < we; ++x) any |= s_prodw[x];
+                    if (any == 0) continue;   // uniform
+                    const int32_t lo = ws * WIN;
+                    const int64_t hi = (int64_t)we * WIN;
 #pragma unroll
-                        for (int i = 0; i < HV_R; ++i) {
-                            if ((int64_t)i * HV_THREADS < e1 - e0)   // uniform: this slot holds entries of the row
-                                wave_chunk<HV_THREADS, true>(s_fc[tid / WAVE], &s_q, ts, (int64_t)cur[i],
-                                                             (int64_t)nxt[i] - (int64_t)cur[i], ea[i], b_col, b_val, f);
+                    for (int q = 0; q < HV_HSLOTS / HV_THREADS; ++q) {
+                        const int32_t key = s_keys[q * HV_THREADS + tid];
+                        if (key != EMPTY_KEY && key >= lo && (int64_t)key < hi) {
+                            const int d = key - lo;
+                            atomicOr(&s_rbm[d >> 5], 1u << (d & 31));
                         }
-                        __syncthreads();
-                        queue_drain<HV_THREADS, true>(s_q, ts, b_col, b_val, f);
-                        __syncthreads();
-                    } else {
-                        const uint32_t *bww = bw + w;
-                        wg_traverse<HV_THREADS, true>(a_col, a_val, e0, e1,
-                                                      [&](int32_t k, int64_t &p0, int64_t &len) {
-                                                          const uint32_t *t = bww + (size_t)k * stride;
-                                                          const uint32_t a0 = t[0], a1 = t[1];
-                                                          p0 = a0; len = (int64_t)a1 - (int64_t)a0;
-                                                      },
-                                                      b_col, b_val, s_fc, s_q, ts, f);
-                    }
-                } else {
-                    auto f = [&](const auto &cj, const auto &cv) {
-                        constexpr int U = sizeof(cj) / sizeof(cj[0]);
-#pragma unroll
-                        for (int u = 0; u < U; ++u) {
-                            const unsigned d = (unsigned)(cj[u] - w * WIN);
-                            if (cj[u] >= 0 && d < (unsigned)WIN) {   // d is in range for a consistent window table
-                                lds_add(&s_vals[d], cv[u]);
-                                atomicOr(&s_dbm[d >> 5], 1u << (d & 31));
-                            }
-                        }
-                    };
-                    if (cached) {
-#pragma unroll
-                        for (int i = 0; i < HV_R; ++i) {
-                            if ((int64_t)i * HV_THREADS < e1 - e0)   // uniform: this slot holds entries of the row
-                                wave_chunk<HV_THREADS, true>(s_fc[tid / WAVE], &s_q, ts, (int64_t)cur[i],
-                                                             (int64_t)nxt[i] - (int64_t)cur[i], ea[i], b_col, b_val, f);
-                        }
-                        __syncthreads();
-                        queue_drain<HV_THREADS, true>(s_q, ts, b_col, b_val, f);
-                        __syncthreads();
-                    } else {
-                        const uint32_t *bww = bw + w;
-                        wg_traverse<HV_THREADS, true>(a_col, a_val, e0, e1,
-                                                      [&](int32_t k, int64_t &p0, int64_t &len) {
-                                                          const uint32_t *t = bww + (size_t)k * stride;
-                                                          const uint32_t a0 = t[0], a1 = t[1];
-                                                          p0 = a0; len = (int64_t)a1 - (int64_t)a0;
-                                                      },
-                                                      b_col, b_val, s_fc, s_q, ts, f);
-                    }
-                    // ---- dense window -> output, in column order
-                    const uint32_t word = tid < WORDS ? s_dbm[tid] : 0u;
-                    int wtotal;
-                    const int ex = block_exclusive_scan_i32<HV_THREADS>(__popc(word), s_wave, wtotal);
-                    if (tid < WORDS) s_dpre[tid] = (uint32_t)ex;
-                    __syncthreads();
-                    constexpr int BPT = WIN / HV_THREADS;   // 16 (fp64) or 32 (fp32) bits of the bitmap per thread
-                    const int32_t col0 = w * WIN;
-                    const int j0 = tid * BPT;
-                    const uint32_t wbits = s_dbm[j0 >> 5];
-                    uint32_t bits = BPT == 32 ? wbits : ((wbits >> (j0 & 31)) & ((1u << (BPT & 31)) - 1u));
-                    long long rank = done + (long long)s_dpre[j0 >> 5] + __popc(wbits & ((1u << (j0 & 31)) - 1u));
-                    while (bits) {
-                        const int b = __ffs((int)bits) - 1;
-                        bits &= bits - 1u;
-                        const int j = j0 + b;
-                        const V val = s_vals[j];
-                        s_vals[j] = (V)0;
-                        if (rank < cap) { out_col[o + rank] = col0 + j; out_val[o + rank] = val; }
-                        ++rank;
                     }
                     __syncthreads();
-                    if (tid < WORDS) s_dbm[tid] = 0u;
-                    done += wtotal;
+                    constexpr int WPT = HV_RWORDS / HV_THREADS;   // 4
+                    int cnt[WPT];
+                    int mine = 0;
+#pragma unroll
+                    for (int q = 0; q < WPT; ++q) { cnt[q] = __popc(s_rbm[tid * WPT + q]); mine += cnt[q]; }
+                    int rtotal;
+                    int run = block_exclusive_scan_i32<HV_THREADS>(mine, s_wave, rtotal);
+#pragma unroll
+                    for (int q = 0; q < WPT; ++q) { s_rpre[tid * WPT + q] = (uint16_t)run; run += cnt[q]; }
+                    __syncthreads();
+#pragma unroll
+                    for (int q = 0; q < HV_HSLOTS / HV_THREADS; ++q) {
+                        const int slot = q * HV_THREADS + tid;
+                        const int32_t key = s_keys[slot];
+                        if (key != EMPTY_KEY && key >= lo && (int64_t)key < hi) {
+                            const int d = key - lo;
+                            const long long rank = done + (long long)s_rpre[d >> 5] + __popc(s_rbm[d >> 5] & ((1u << (d & 31)) - 1u));
+                            if (rank < cap) { out_col[o + rank] = key; out_val[o + rank] = s_hvals[slot]; }
+                        }
+                    }
+                    __syncthreads();
+#pragma unroll
+                    for (int q = 0; q < WPT; ++q) s_rbm[tid * WPT + q] = 0u;
+                    done += rtotal;
                     __syncthreads();
                 }
             }
-            // ---- next window's segments
-            if (cached) {
-#pragma unroll
-                for (int i = 0; i < HV_R; ++i) { cur[i] = nxt[i]; nxt[i] = pre[i]; }
-            }
+            w = w1;
         }
-        if (hash_active) emit_range();
         if (tid == 0) row_nnz[row] = (s_ovf || done > cap) ? -1 : (int32_t)done;
         __syncthreads();
     }

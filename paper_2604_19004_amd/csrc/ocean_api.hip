@@ -492,7 +492,7 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
     if (max_ub > kNumericSlots[NB_S8K] && B.nnz < 0xffffffffLL && !o.force_hash_kernels) {
         const int nw = dense_window_count(n, dtype);
         const size_t bytes = (size_t)B.rows * ((size_t)nw + 1) * 4;
-        if (bytes <= ((size_t)6 << 30)) {
+        if (nw <= 512 && bytes <= ((size_t)6 << 30)) {   // the heavy-row kernel plans at most 512 windows per row
             bw_try = static_cast<uint32_t *>(c.alloc(bytes));
             if (bw_try) HIP_TRY(launch_window_table(B, dtype, bw_try, &c.n_win, &w.sc->flags, c.s));
         }

@@ -60,9 +60,12 @@ struct FlatChunk {
 
 // G lanes (a power of two <= 64, consecutive lanes of one wave) flatten the G
 // segments (p0, len, a) they hold, len < 2^24.  Every lane of the group calls it.
+// Several waves may flatten the same chunk (each with its own FlatChunk copy)
+// and share its batches: this one takes batches first, first+stride, ...
 template <int G, bool HAS_VAL, typename V, typename F>
 __device__ __forceinline__ void group_flat(FlatChunk<V, G> &c, int64_t p0, uint32_t len, V a,
-                                           const int32_t *__restrict__ b_col, const V *__restrict__ b_val, F &f)
+                                           const int32_t *__restrict__ b_col, const V *__restrict__ b_val, F &f,
+                                           uint32_t first = 0, uint32_t stride = 1)
 {
     const int sub = lane_id() & (G - 1);
     uint32_t incl = len;
@@ -77,7 +80,7 @@ __device__ __forceinline__ void group_flat(FlatChunk<V, G> &c, int64_t p0, uint3
     c.pbase[sub] = (long long)p0 - (long long)(incl - len);
     c.a[sub] = a;
     wave_sync();
-    for (uint32_t q0 = 0; q0 < total; q0 += G * FLAT_U) {
+    for (uint32_t q0 = first * (G * FLAT_U); q0 < total; q0 += stride * (G * FLAT_U)) {
         int32_t cj[FLAT_U];
         V cv[FLAT_U];
 #pragma unroll
@@ -161,15 +164,17 @@ __device__ __forceinline__ void queue_drain(LongQueue<V, CAP> &q, TravState &st,
 
 // One wave handles the 64 segments (p0, len, a) its lanes hold: the long ones go to the queue (or
 // are walked right away by the whole wave when there is no queue / it is full), the rest is flattened.
+// With stride > 1 the same 64 segments are given to `stride` waves, which share the flattened part
+// (this wave takes batches first, first+stride, ...); only the wave with first == 0 handles the long ones.
 template <int THREADS, bool HAS_VAL, typename V, int CAP, typename F>
 __device__ __forceinline__ void wave_chunk(FlatChunk<V, WAVE> &c, LongQueue<V, CAP> *q, const TravState &st, int64_t p0,
                                            int64_t len, V a, const int32_t *__restrict__ b_col,
-                                           const V *__restrict__ b_val, F &f)
+                                           const V *__restrict__ b_val, F &f, uint32_t first = 0, uint32_t stride = 1)
 {
     const bool is_long = len >= T_LONG;
     bool pushed = false;
-    if (is_long && q != nullptr) pushed = queue_push<THREADS>(*q, st, p0, len, a);
-    unsigned long long m = __ballot(is_long && !pushed);
+    if (is_long && q != nullptr && first == 0) pushed = queue_push<THREADS>(*q, st, p0, len, a);
+    unsigned long long m = __ballot(is_long && !pushed && first == 0);
     while (m) {
         const int src = __ffsll((long long)m) - 1;
         m &= m - 1ull;
@@ -179,7 +184,7 @@ __device__ __forceinline__ void wave_chunk(FlatChunk<V, WAVE> &c, LongQueue<V, C
         if constexpr (HAS_VAL) sa = __shfl(a, src, WAVE);
         exec_segment<WAVE, FLAT_U, HAS_VAL>(b_col, b_val, sp0, slen, lane_id(), sa, f);
     }
-    group_flat<WAVE, HAS_VAL>(c, p0, is_long ? 0u : (uint32_t)len, a, b_col, b_val, f);
+    group_flat<WAVE, HAS_VAL>(c, p0, is_long ? 0u : (uint32_t)len, a, b_col, b_val, f, first, stride);
 }
 
 // Workgroup version.  Every thread of the (1-D) workgroup must call it.  q.n
@@ -192,10 +197,15 @@ __device__ __forceinline__ void wg_traverse(const int32_t *__restrict__ a_col, c
                                             const V *__restrict__ b_val, FlatChunk<V, WAVE> *chunks,
                                             LongQueue<V, CAP> &q, TravState &st, F f)
 {
+    constexpr int NW = THREADS / WAVE;
     const int tid = threadIdx.x;
     const int wave = tid / WAVE;
-    // every wave takes its own chunks of 64 entries; no barrier inside this loop
-    for (int64_t base = e0 + (int64_t)wave * WAVE; base < e1; base += THREADS) {
+    // A row with many entries: every wave takes its own chunks of 64 entries.  A row with few: all
+    // waves read the same chunks and share the products of each.  No barrier inside either loop.
+    const bool shared = (e1 - e0) < (int64_t)WAVE * NW / 2;
+    const int64_t first_base = shared ? e0 : e0 + (int64_t)wave * WAVE;
+    const int64_t base_step = shared ? WAVE : THREADS;
+    for (int64_t base = first_base; base < e1; base += base_step) {
         const int64_t e = base + (tid & (WAVE - 1));
         int64_t p0 = 0, len = 0;
         V a = V();
@@ -204,7 +214,8 @@ __device__ __forceinline__ void wg_traverse(const int32_t *__restrict__ a_col, c
             if constexpr (HAS_VAL) a = a_val[e];
             seg(k, p0, len);
         }
-        wave_chunk<THREADS, HAS_VAL>(chunks[wave], &q, st, p0, len, a, b_col, b_val, f);
+        wave_chunk<THREADS, HAS_VAL>(chunks[wave], &q, st, p0, len, a, b_col, b_val, f, shared ? (uint32_t)wave : 0u,
+                                     shared ? (uint32_t)NW : 1u);
     }
     __syncthreads();
     queue_drain<THREADS, HAS_VAL>(q, st, b_col, b_val, f);
