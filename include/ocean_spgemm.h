@@ -29,7 +29,8 @@ enum { OCEAN_F64 = 0, OCEAN_F32 = 1 };
 
 enum {
     OCEAN_OK = 0,
-    OCEAN_EINVAL = 1, /* null / inconsistent arguments, A.cols != B.rows, dtype mismatch, invalid CSR content */
+    OCEAN_EINVAL = 1, /* null / inconsistent arguments, A.cols != B.rows, dtype mismatch, invalid CSR content,
+                         or a single row of A*B with 2^31 or more intermediate products */
     OCEAN_EALLOC = 2, /* the allocator could not provide memory */
     OCEAN_EHIP = 3    /* a HIP runtime call failed */
 };

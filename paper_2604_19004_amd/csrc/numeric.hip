@@ -303,8 +303,7 @@ k_numeric_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col
     __shared__ int32_t s_keys[SLOTS];
     __shared__ int32_t s_sort[SLOTS];
     __shared__ V s_vals[SLOTS];
-    __shared__ FlatChunk<V, WAVE> s_fc[THREADS / WAVE];
-    __shared__ LongQueue<V, 256> s_q;
+    __shared__ WgChunk<V, THREADS> s_fc;
     __shared__ int s_wave[THREADS / WAVE];
     __shared__ int s_ovf;
     const int tid = threadIdx.x;
@@ -313,13 +312,12 @@ k_numeric_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col
     const int64_t row = rows[r];
 
     for (int s = tid; s < SLOTS; s += THREADS) { s_keys[s] = EMPTY_KEY; s_vals[s] = (V)0; }
-    if (tid == 0) { s_ovf = 0; s_q.n = 0; s_q.n_huge = 0; }
+    if (tid == 0) s_ovf = 0;
     __syncthreads();
 
-    TravState ts;
     wg_traverse<THREADS, true>(a_col, a_val, a_rp[row], a_rp[row + 1],
                                [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
-                               b_col, b_val, s_fc, s_q, ts, [&](const auto &cj, const auto &cv) {
+                               b_col, b_val, s_fc, [&](const auto &cj, const auto &cv) {
                                    if (!lds_insert_batch<BITS>(s_keys, cj, cv, [&](int slot, V v) { lds_add(&s_vals[slot], v); }))
                                        s_ovf = 1;
                                });
@@ -379,7 +377,6 @@ constexpr int HY_SLOTS = 1 << HY_BITS;
 constexpr int HY_THREADS = 1024;
 constexpr int HY_WIN = 524288;          // columns per ranking window
 constexpr int HY_WORDS = HY_WIN / 32;   // 16384 bitmap words + 16384 prefix words = the key table's 128 KB
-constexpr int HY_QCAP = 256;
 
 template <typename V>
 __global__ void __launch_bounds__(HY_THREADS)
@@ -392,8 +389,7 @@ k_numeric_hybrid(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
     constexpr int PER = HY_SLOTS / HY_THREADS;   // 32 slots per thread
     constexpr int WPT = HY_WORDS / HY_THREADS;   // 16 bitmap words per thread
     __shared__ int32_t s_keys[HY_SLOTS];
-    __shared__ FlatChunk<V, WAVE> s_fc[HY_THREADS / WAVE];
-    __shared__ LongQueue<V, HY_QCAP> s_q;
+    __shared__ WgChunk<V, HY_THREADS> s_fc;
     __shared__ int s_wave[HY_THREADS / WAVE];
     __shared__ int s_ovf;
     __shared__ int s_min, s_max;
@@ -412,13 +408,12 @@ k_numeric_hybrid(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
         if (r >= count) break;   // uniform: every wave of the workgroup leaves here
         const int64_t row = rows[r];
         for (int s = tid; s < HY_SLOTS; s += HY_THREADS) s_keys[s] = EMPTY_KEY;
-        if (tid == 0) { s_ovf = 0; s_min = 0x7fffffff; s_max = -1; s_cnt = 0; s_q.n = 0; s_q.n_huge = 0; }
+        if (tid == 0) { s_ovf = 0; s_min = 0x7fffffff; s_max = -1; s_cnt = 0; }
         __syncthreads();
 
-        TravState ts;
         wg_traverse<HY_THREADS, true>(a_col, a_val, a_rp[row], a_rp[row + 1],
                                       [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
-                                      b_col, b_val, s_fc, s_q, ts, [&](const auto &cj, const auto &cv) {
+                                      b_col, b_val, s_fc, [&](const auto &cj, const auto &cv) {
                                           if (!lds_insert_batch<HY_BITS>(s_keys, cj, cv, [&](int slot, V v) { l2_add(&slab[slot], v); }))
                                               s_ovf = 1;
                                       });
@@ -508,10 +503,9 @@ k_numeric_hybrid(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
 // Everything is accumulated in LDS and no table can overflow by construction.
 // What bounds this path is the latency of its chain of dependent accesses
 // (entry -> window boundary -> products -> LDS), paid once per pass, which is
-// why sparse stretches are merged into few passes; the entries of the row stay
-// in registers across passes (rows up to HV_R*1024 entries).
+// why sparse stretches are merged into few passes and why every pass spreads
+// its products over the whole workgroup.
 constexpr int HV_THREADS = 1024;
-constexpr int HV_R = 4;
 constexpr int HV_HBITS = 13;
 constexpr int HV_HSLOTS = 1 << HV_HBITS;
 constexpr int HV_HCAP = 6144;
@@ -540,8 +534,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     __shared__ __align__(16) unsigned char s_u[131072];
     __shared__ uint32_t s_dbm[WORDS];
     __shared__ uint32_t s_dpre[WORDS];
-    __shared__ FlatChunk<V, WAVE> s_fc[HV_THREADS / WAVE];
-    __shared__ LongQueue<V, 128> s_q;
+    __shared__ WgChunk<V, HV_THREADS> s_fc;
     __shared__ int s_wave[HV_THREADS / WAVE];
     __shared__ uint32_t s_prodw[HV_MAXWIN];
     __shared__ int s_ovf;
@@ -561,7 +554,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     for (;;) {
         if (tid == 0) {
             s_row = (long long)atomicAdd(queue, 1ull);
-            s_q.n = 0; s_q.n_huge = 0; s_ovf = 0;
+            s_ovf = 0;
         }
         for (int w = tid; w < n_win; w += HV_THREADS) s_prodw[w] = 0u;
         __syncthreads();
@@ -571,35 +564,26 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
         const int64_t e0 = a_rp[row], e1 = a_rp[row + 1];
         const int64_t o = out_ptr[row];
         const int64_t cap = out_ptr[row + 1] - o;
-        const bool cached = (e1 - e0) <= (int64_t)HV_R * HV_THREADS;
+        const int64_t ne = e1 - e0;
         long long done = 0;
-        TravState ts;
 
-        // this thread's entries of the row
-        int32_t ek[HV_R];
-        V ea[HV_R];
-#pragma unroll
-        for (int i = 0; i < HV_R; ++i) {
-            ek[i] = -1; ea[i] = V();
-            const int64_t e = e0 + (int64_t)i * HV_THREADS + tid;
-            if (cached && e < e1) { ek[i] = a_col[e]; ea[i] = a_val[e]; }
-        }
-        // ---- products of the row per window
-        auto count_entry = [&](int32_t k) {
-            const uint32_t *t = bw + (size_t)k * stride;
-            uint32_t prev = t[0];
-            for (int w = 0; w < n_win; ++w) {
-                const uint32_t nx = t[w + 1];
-                if (nx != prev) atomicAdd(&s_prodw[w], nx - prev);
-                prev = nx;
+        // the first HV_THREADS entries of the row stay in registers over all passes
+        int32_t ek = 0;
+        V ea = V();
+        if (tid < ne) { ek = a_col[e0 + tid]; ea = a_val[e0 + tid]; }
+        // ---- products of the row per window: one (entry, window) pair per thread and step
+        {
+            const int de = HV_THREADS / n_win, dw = HV_THREADS % n_win;
+            int64_t e = tid / n_win;
+            int w = tid % n_win;
+            while (e < ne) {
+                const uint32_t *t = bw + (size_t)a_col[e0 + e] * stride;
+                const uint32_t d = t[w + 1] - t[w];
+                if (d) atomicAdd(&s_prodw[w], d);
+                e += de;
+                w += dw;
+                if (w >= n_win) { w -= n_win; ++e; }
             }
-        };
-        if (cached) {
-#pragma unroll
-            for (int i = 0; i < HV_R; ++i)
-                if (ek[i] >= 0) count_entry(ek[i]);
-        } else {
-            for (int64_t e = e0 + tid; e < e1; e += HV_THREADS) count_entry(a_col[e]);
         }
         __syncthreads();
 
@@ -645,31 +629,20 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                         s_ovf = 1;
                 }
             };
-            if (cached) {
-#pragma unroll
-                for (int i = 0; i < HV_R; ++i) {
-                    if ((int64_t)i * HV_THREADS < e1 - e0) {   // uniform: this slot holds entries of the row
-                        uint32_t c0 = 0, c1 = 0;
-                        if (ek[i] >= 0) {
-                            const uint32_t *t = bw + (size_t)ek[i] * stride;
-                            c0 = t[w];
-                            c1 = t[w1];
-                        }
-                        wave_chunk<HV_THREADS, true>(s_fc[tid / WAVE], &s_q, ts, (int64_t)c0, (int64_t)c1 - (int64_t)c0,
-                                                     ea[i], b_col, b_val, f);
-                    }
+            for (int64_t base = 0; base < ne; base += HV_THREADS) {
+                int32_t k = ek;
+                V a = ea;
+                const bool have = base + tid < ne;
+                if (base > 0 && have) { k = a_col[e0 + base + tid]; a = a_val[e0 + base + tid]; }
+                uint32_t c0 = 0, c1 = 0;
+                if (have) {
+                    const uint32_t *t = bw + (size_t)k * stride;
+                    c0 = t[w];
+                    c1 = t[w1];
                 }
-                __syncthreads();
-                queue_drain<HV_THREADS, true>(s_q, ts, b_col, b_val, f);
-                __syncthreads();
-            } else {
-                wg_traverse<HV_THREADS, true>(a_col, a_val, e0, e1,
-                                              [&](int32_t k, int64_t &p0, int64_t &len) {
-                                                  const uint32_t *t = bw + (size_t)k * stride;
-                                                  const uint32_t c0 = t[w], c1 = t[w1];
-                                                  p0 = c0; len = (int64_t)c1 - (int64_t)c0;
-                                              },
-                                              b_col, b_val, s_fc, s_q, ts, f);
+                const int64_t left = ne - base;
+                wg_flat_chunk<HV_THREADS, true>(s_fc, left < HV_THREADS ? (int)left : HV_THREADS, (int64_t)c0, c1 - c0, a,
+                                                b_col, b_val, f);
             }
             if (dense) {
                 // ---- dense window -> output, in column order
@@ -807,7 +780,6 @@ int dense_window_count(int64_t n_cols, int dtype)
 constexpr int GL_THREADS = 1024;
 constexpr int GL_WIN = 524288;
 constexpr int GL_WORDS = GL_WIN / 32;   // 16384
-constexpr int GL_QCAP = 256;
 
 template <typename V>
 __global__ void __launch_bounds__(GL_THREADS)
@@ -821,8 +793,7 @@ k_numeric_global(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
     constexpr int WPT = GL_WORDS / GL_THREADS;   // 16 words per thread
     __shared__ uint32_t s_bm[GL_WORDS];
     __shared__ uint32_t s_pre[GL_WORDS];
-    __shared__ FlatChunk<V, WAVE> s_fc[GL_THREADS / WAVE];
-    __shared__ LongQueue<V, GL_QCAP> s_q;
+    __shared__ WgChunk<V, GL_THREADS> s_fc;
     __shared__ int s_wave[GL_THREADS / WAVE];
     __shared__ int s_ovf;
     __shared__ int s_min, s_max;
@@ -846,14 +817,13 @@ k_numeric_global(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
             while (bits < gbits_max && (double)(1ll << bits) < want) ++bits;
         }
         const int64_t slots = 1ll << bits;
-        if (tid == 0) { s_ovf = 0; s_min = 0x7fffffff; s_max = -1; s_q.n = 0; s_q.n_huge = 0; }
+        if (tid == 0) { s_ovf = 0; s_min = 0x7fffffff; s_max = -1; }
         __syncthreads();
 
         int kmin = 0x7fffffff, kmax = -1;
-        TravState ts;
         wg_traverse<GL_THREADS, true>(a_col, a_val, a_rp[row], a_rp[row + 1],
                                       [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
-                                      b_col, b_val, s_fc, s_q, ts, [&](const auto &cj, const auto &cv) {
+                                      b_col, b_val, s_fc, [&](const auto &cj, const auto &cv) {
                                           constexpr int U = sizeof(cj) / sizeof(cj[0]);
                                           const uint32_t mask = (1u << bits) - 1u;
                                           uint32_t h[U], st[U];

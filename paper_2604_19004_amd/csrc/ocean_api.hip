@@ -279,6 +279,8 @@ int run_analysis(Ctx &c, Work &w, const Csr &A, const Csr &B, bool validate, oce
     if (c.h->flags & 1) return fail(OCEAN_EINVAL, "A is not a valid CSR matrix (row offsets or column ids out of range)");
     if (c.h->flags & 2) return fail(OCEAN_EINVAL, "B is not a valid CSR matrix (row offsets or column ids out of range)");
     if (c.h->flags & 4) return fail(OCEAN_EINVAL, "a column id of A is outside [0, rows(B))");
+    if (c.h->totals[1] >= (1ull << 31))   // the kernels number the products of a row in 32 bits
+        return fail(OCEAN_EINVAL, "a row of A*B has 2^31 or more intermediate products");
     if (st) {
         st->products = (int64_t)c.h->totals[0];
         st->max_row_products = (int64_t)c.h->totals[1];

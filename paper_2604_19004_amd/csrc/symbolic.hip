@@ -121,21 +121,19 @@ k_symbolic_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_co
 {
     constexpr int SLOTS = 1 << BITS;
     __shared__ int32_t s_keys[SLOTS];
-    __shared__ FlatChunk<NoVal, WAVE> s_fc[THREADS / WAVE];
-    __shared__ LongQueue<NoVal, 256> s_q;
+    __shared__ WgChunk<NoVal, THREADS> s_fc;
     __shared__ int s_count;
     const int tid = threadIdx.x;
     const int64_t r = blockIdx.x;
     if (r >= count) return;
     const int64_t row = rows[r];
     for (int s = tid; s < SLOTS; s += THREADS) s_keys[s] = EMPTY_KEY;
-    if (tid == 0) { s_count = 0; s_q.n = 0; s_q.n_huge = 0; }
+    if (tid == 0) s_count = 0;
     __syncthreads();
     int fresh = 0;
-    TravState ts;
     wg_traverse<THREADS, false>(a_col, (const NoVal *)nullptr, a_rp[row], a_rp[row + 1],
                                 [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
-                                b_col, (const NoVal *)nullptr, s_fc, s_q, ts,
+                                b_col, (const NoVal *)nullptr, s_fc,
                                 [&](const auto &cj, const auto &) { fresh += lds_count_new_batch<BITS>(s_keys, cj); });
     fresh = group_reduce_sum(fresh, WAVE);
     if (lane_id() == 0 && fresh) atomicAdd(&s_count, fresh);
@@ -155,24 +153,22 @@ k_symbolic_bitmap(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ 
                   unsigned long long *queue, int32_t *__restrict__ nnz_out)
 {
     __shared__ uint32_t s_bm[BM_WORDS];
-    __shared__ FlatChunk<NoVal, WAVE> s_fc[BM_THREADS / WAVE];
-    __shared__ LongQueue<NoVal, 256> s_q;
+    __shared__ WgChunk<NoVal, BM_THREADS> s_fc;
     __shared__ int s_count;
     __shared__ long long s_row;
     const int tid = threadIdx.x;
     for (int s = tid; s < BM_WORDS; s += BM_THREADS) s_bm[s] = 0u;
     for (;;) {
-        if (tid == 0) { s_row = (long long)atomicAdd(queue, 1ull); s_count = 0; s_q.n = 0; s_q.n_huge = 0; }
+        if (tid == 0) { s_row = (long long)atomicAdd(queue, 1ull); s_count = 0; }
         __syncthreads();
         const int64_t r = s_row;
         if (r >= count) break;   // uniform exit
         const int64_t row = rows[r];
         const int64_t e0 = a_rp[row], e1 = a_rp[row + 1];
-        TravState ts;   // reset with the queue counters above; runs on over the windows of this row
         for (int64_t w0 = 0; w0 < n_cols; w0 += BM_WIN) {
             wg_traverse<BM_THREADS, false>(a_col, (const NoVal *)nullptr, e0, e1,
                                            [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
-                                           b_col, (const NoVal *)nullptr, s_fc, s_q, ts, [&](const auto &cj, const auto &) {
+                                           b_col, (const NoVal *)nullptr, s_fc, [&](const auto &cj, const auto &) {
                                                constexpr int U = sizeof(cj) / sizeof(cj[0]);
 #pragma unroll
                                                for (int u = 0; u < U; ++u) {

@@ -8,13 +8,15 @@
 // flight together.  Rows of B referenced by one row of A differ wildly in
 // length on power-law matrices; a fixed "lanes per row of B" mapping leaves
 // most lanes idle.  Therefore:
-//   * entries A_ik whose row of B is shorter than T_LONG are FLATTENED: a wave
-//     takes 64 entries, prefix-sums their lengths, and lane l then handles
-//     products l, l+64, ... of the concatenated segments, finding the entry of
-//     a product by a 6-step search over the prefix sums kept in LDS;
-//   * longer rows of B are walked 64-wide by a whole wave (coalesced), queued
-//     in LDS first so that the waves of a workgroup share them evenly, and the
-//     very long ones (>= 4*THREADS) by the whole workgroup.
+//   * a workgroup FLATTENS the products of a row: it takes up to THREADS
+//     entries A_ik, prefix-sums the lengths of their rows of B, and thread t
+//     then handles products t, t+THREADS, ... of the concatenated segments,
+//     finding the entry of a product by a binary search over the prefix sums
+//     kept in LDS (consecutive lanes mostly fall into one row of B, so the
+//     loads stay coalesced);
+//   * a wave or a 16-lane group that owns a short row does the same over its
+//     64 or 16 entries; rows of B of T_LONG or more entries are walked 64-wide
+//     there.
 // Products reach the accumulator in batches: f(cj, cv) receives U column ids
 // (negative = none) and values a*b per lane, so that the accumulator's own
 // dependent LDS round trips (hash probes) overlap across the batch.
@@ -26,7 +28,6 @@ namespace ocean {
 
 constexpr int T_LONG = 128;
 constexpr int FLAT_U = 4;
-constexpr int MAX_HUGE = 8;
 
 // Products p0 + lane, p0 + lane + STRIDE, ... of one segment, UNROLL loads in flight per lane.
 template <int STRIDE, int UNROLL, bool HAS_VAL, typename V, typename F>
@@ -60,12 +61,9 @@ struct FlatChunk {
 
 // G lanes (a power of two <= 64, consecutive lanes of one wave) flatten the G
 // segments (p0, len, a) they hold, len < 2^24.  Every lane of the group calls it.
-// Several waves may flatten the same chunk (each with its own FlatChunk copy)
-// and share its batches: this one takes batches first, first+stride, ...
 template <int G, bool HAS_VAL, typename V, typename F>
 __device__ __forceinline__ void group_flat(FlatChunk<V, G> &c, int64_t p0, uint32_t len, V a,
-                                           const int32_t *__restrict__ b_col, const V *__restrict__ b_val, F &f,
-                                           uint32_t first = 0, uint32_t stride = 1)
+                                           const int32_t *__restrict__ b_col, const V *__restrict__ b_val, F &f)
 {
     const int sub = lane_id() & (G - 1);
     uint32_t incl = len;
@@ -80,7 +78,7 @@ __device__ __forceinline__ void group_flat(FlatChunk<V, G> &c, int64_t p0, uint3
     c.pbase[sub] = (long long)p0 - (long long)(incl - len);
     c.a[sub] = a;
     wave_sync();
-    for (uint32_t q0 = first * (G * FLAT_U); q0 < total; q0 += stride * (G * FLAT_U)) {
+    for (uint32_t q0 = 0; q0 < total; q0 += G * FLAT_U) {
         int32_t cj[FLAT_U];
         V cv[FLAT_U];
 #pragma unroll
@@ -101,80 +99,14 @@ __device__ __forceinline__ void group_flat(FlatChunk<V, G> &c, int64_t p0, uint3
     wave_sync();   // the chunk arrays may be rewritten now
 }
 
-// Queue of the long segments of a row, shared by the waves of a workgroup.
-template <typename V, int CAP>
-struct LongQueue {
-    unsigned long long p0[CAP];
-    int32_t len[CAP];          // negative: registered as huge
-    V a[CAP];
-    int32_t huge[MAX_HUGE];
-    unsigned int n;            // running counters: they only grow while a row is processed
-    unsigned int n_huge;
-};
-
-// Values of the queue's running counters when the queue was last drained, kept
-// in registers by every thread.  Reset it together with q.n / q.n_huge; carry
-// it over when the same row is traversed again (one call per column window).
-struct TravState {
-    unsigned start = 0, hstart = 0;
-};
-
-// Queue one long segment.  False when the queue is full: the caller walks it itself.
-template <int THREADS, typename V, int CAP>
-__device__ __forceinline__ bool queue_push(LongQueue<V, CAP> &q, const TravState &st, int64_t p0, int64_t len, V a)
-{
-    constexpr int T_HUGE = 4 * THREADS;
-    const unsigned idx = atomicAdd(&q.n, 1u) - st.start;
-    if (idx >= (unsigned)CAP) return false;
-    q.p0[idx] = (unsigned long long)p0;
-    q.a[idx] = a;
-    int32_t l32 = (int32_t)len;
-    if (len >= T_HUGE) {
-        const unsigned h = atomicAdd(&q.n_huge, 1u) - st.hstart;
-        if (h < (unsigned)MAX_HUGE) { q.huge[h] = (int32_t)idx; l32 = -l32; }
-    }
-    q.len[idx] = l32;
-    return true;
-}
-
-// Walk everything queued since st (all pushes must be visible: barrier before) and advance st.
-// Every thread of the workgroup calls it; no barrier inside.
-template <int THREADS, bool HAS_VAL, typename V, int CAP, typename F>
-__device__ __forceinline__ void queue_drain(LongQueue<V, CAP> &q, TravState &st, const int32_t *__restrict__ b_col,
-                                            const V *__restrict__ b_val, F &f)
-{
-    constexpr int NW = THREADS / WAVE;
-    const int tid = threadIdx.x;
-    const int lane = tid & (WAVE - 1), wave = tid / WAVE;
-    const unsigned total = q.n - st.start;
-    const unsigned htotal = q.n_huge - st.hstart;
-    const int nq = (int)(total < (unsigned)CAP ? total : (unsigned)CAP);
-    const int nh = (int)(htotal < (unsigned)MAX_HUGE ? htotal : (unsigned)MAX_HUGE);
-    for (int i = wave; i < nq; i += NW) {
-        const int32_t len = q.len[i];
-        if (len > 0) exec_segment<WAVE, FLAT_U, HAS_VAL>(b_col, b_val, (int64_t)q.p0[i], len, lane, q.a[i], f);
-    }
-    for (int h = 0; h < nh; ++h) {
-        const int i = q.huge[h];
-        exec_segment<THREADS, FLAT_U, HAS_VAL>(b_col, b_val, (int64_t)q.p0[i], -(int64_t)q.len[i], tid, q.a[i], f);
-    }
-    st.start += total;
-    st.hstart += htotal;
-}
-
-// One wave handles the 64 segments (p0, len, a) its lanes hold: the long ones go to the queue (or
-// are walked right away by the whole wave when there is no queue / it is full), the rest is flattened.
-// With stride > 1 the same 64 segments are given to `stride` waves, which share the flattened part
-// (this wave takes batches first, first+stride, ...); only the wave with first == 0 handles the long ones.
-template <int THREADS, bool HAS_VAL, typename V, int CAP, typename F>
-__device__ __forceinline__ void wave_chunk(FlatChunk<V, WAVE> &c, LongQueue<V, CAP> *q, const TravState &st, int64_t p0,
-                                           int64_t len, V a, const int32_t *__restrict__ b_col,
-                                           const V *__restrict__ b_val, F &f, uint32_t first = 0, uint32_t stride = 1)
+// One wave handles the 64 segments (p0, len, a) its lanes hold: the long ones are walked 64-wide
+// by the whole wave, one after the other, the rest is flattened.
+template <bool HAS_VAL, typename V, typename F>
+__device__ __forceinline__ void wave_chunk(FlatChunk<V, WAVE> &c, int64_t p0, int64_t len, V a,
+                                           const int32_t *__restrict__ b_col, const V *__restrict__ b_val, F &f)
 {
     const bool is_long = len >= T_LONG;
-    bool pushed = false;
-    if (is_long && q != nullptr && first == 0) pushed = queue_push<THREADS>(*q, st, p0, len, a);
-    unsigned long long m = __ballot(is_long && !pushed && first == 0);
+    unsigned long long m = __ballot(is_long);
     while (m) {
         const int src = __ffsll((long long)m) - 1;
         m &= m - 1ull;
@@ -184,52 +116,16 @@ __device__ __forceinline__ void wave_chunk(FlatChunk<V, WAVE> &c, LongQueue<V, C
         if constexpr (HAS_VAL) sa = __shfl(a, src, WAVE);
         exec_segment<WAVE, FLAT_U, HAS_VAL>(b_col, b_val, sp0, slen, lane_id(), sa, f);
     }
-    group_flat<WAVE, HAS_VAL>(c, p0, is_long ? 0u : (uint32_t)len, a, b_col, b_val, f, first, stride);
+    group_flat<WAVE, HAS_VAL>(c, p0, is_long ? 0u : (uint32_t)len, a, b_col, b_val, f);
 }
 
-// Workgroup version.  Every thread of the (1-D) workgroup must call it.  q.n
-// and q.n_huge must be visible (barrier) on entry and equal to st (zero after a
-// reset).  seg(k, p0, len) gives the segment of B's arrays that entry k expands
-// to.  chunks: one FlatChunk per wave.  Ends with a barrier.
-template <int THREADS, bool HAS_VAL, typename V, int CAP, typename SegFn, typename F>
-__device__ __forceinline__ void wg_traverse(const int32_t *__restrict__ a_col, const V *__restrict__ a_val,
-                                            int64_t e0, int64_t e1, SegFn seg, const int32_t *__restrict__ b_col,
-                                            const V *__restrict__ b_val, FlatChunk<V, WAVE> *chunks,
-                                            LongQueue<V, CAP> &q, TravState &st, F f)
-{
-    constexpr int NW = THREADS / WAVE;
-    const int tid = threadIdx.x;
-    const int wave = tid / WAVE;
-    // A row with many entries: every wave takes its own chunks of 64 entries.  A row with few: all
-    // waves read the same chunks and share the products of each.  No barrier inside either loop.
-    const bool shared = (e1 - e0) < (int64_t)WAVE * NW / 2;
-    const int64_t first_base = shared ? e0 : e0 + (int64_t)wave * WAVE;
-    const int64_t base_step = shared ? WAVE : THREADS;
-    for (int64_t base = first_base; base < e1; base += base_step) {
-        const int64_t e = base + (tid & (WAVE - 1));
-        int64_t p0 = 0, len = 0;
-        V a = V();
-        if (e < e1) {
-            const int32_t k = a_col[e];
-            if constexpr (HAS_VAL) a = a_val[e];
-            seg(k, p0, len);
-        }
-        wave_chunk<THREADS, HAS_VAL>(chunks[wave], &q, st, p0, len, a, b_col, b_val, f, shared ? (uint32_t)wave : 0u,
-                                     shared ? (uint32_t)NW : 1u);
-    }
-    __syncthreads();
-    queue_drain<THREADS, HAS_VAL>(q, st, b_col, b_val, f);
-    __syncthreads();
-}
-
-// Wave version: the 64 lanes of one wave walk one row; no workgroup barrier, no queue.
+// Wave version: the 64 lanes of one wave walk one row; no workgroup barrier.
 template <bool HAS_VAL, typename V, typename SegFn, typename F>
 __device__ __forceinline__ void wave_traverse(const int32_t *__restrict__ a_col, const V *__restrict__ a_val,
                                               int64_t e0, int64_t e1, SegFn seg, const int32_t *__restrict__ b_col,
                                               const V *__restrict__ b_val, FlatChunk<V, WAVE> &c, F f)
 {
     const int lane = lane_id();
-    const TravState st;
     for (int64_t base = e0; base < e1; base += WAVE) {
         const int64_t e = base + lane;
         int64_t p0 = 0, len = 0;
@@ -239,7 +135,117 @@ __device__ __forceinline__ void wave_traverse(const int32_t *__restrict__ a_col,
             if constexpr (HAS_VAL) a = a_val[e];
             seg(k, p0, len);
         }
-        wave_chunk<WAVE, HAS_VAL>(c, static_cast<LongQueue<V, 1> *>(nullptr), st, p0, len, a, b_col, b_val, f);
+        wave_chunk<HAS_VAL>(c, p0, len, a, b_col, b_val, f);
+    }
+}
+
+// LDS scratch of a workgroup-wide flattened chunk of up to THREADS entries.
+template <typename V, int THREADS>
+struct WgChunk {
+    uint32_t excl[THREADS];
+    long long pbase[THREADS];
+    V a[THREADS];
+    uint32_t wsum[THREADS / WAVE];
+    uint32_t total;
+};
+
+// The whole workgroup flattens the `nent` (1..THREADS) segments held by its first nent threads
+// (p0, len, a; len = 0 in the other threads): the products of the concatenation are dealt out
+// evenly to the waves whatever the lengths of the single segments, so a row with three entries
+// that point to long rows of B keeps every wave as busy as a row with a thousand short ones.  The
+// products of one chunk must number less than 2^31.  Every thread calls it; the chunk arrays must
+// be free on entry (the call ends with a barrier).
+template <int THREADS, bool HAS_VAL, typename V, typename F>
+__device__ __forceinline__ void wg_flat_chunk(WgChunk<V, THREADS> &c, int nent, int64_t p0, uint32_t len, V a,
+                                              const int32_t *__restrict__ b_col, const V *__restrict__ b_val, F &f)
+{
+    constexpr int NW = THREADS / WAVE;
+    const int tid = threadIdx.x;
+    const int lane = tid & (WAVE - 1), wave = tid / WAVE;
+    uint32_t incl = len;
+#pragma unroll
+    for (int off = 1; off < WAVE; off <<= 1) {
+        const uint32_t o = __shfl_up(incl, off, WAVE);
+        if (lane >= off) incl += o;
+    }
+    if (nent > WAVE) {   // uniform
+        if (lane == WAVE - 1) c.wsum[wave] = incl;
+        __syncthreads();
+        uint32_t before = 0;
+#pragma unroll
+        for (int i = 0; i < NW; ++i) {
+            const uint32_t x = c.wsum[i];
+            if (i < wave) before += x;
+        }
+        incl += before;
+    }
+    if (tid < nent) {
+        c.excl[tid] = incl - len;
+        c.pbase[tid] = (long long)p0 - (long long)(incl - len);
+        c.a[tid] = a;
+    }
+    if (tid == nent - 1) c.total = incl;
+    __syncthreads();
+    const uint32_t total = c.total;
+    // Every wave takes one contiguous span of the products, 64 at a time, so the entry of a lane's
+    // product moves forward slowly: it is searched once and then followed by galloping from the
+    // last position (one LDS read while the lane stays inside one row of B).
+    const uint32_t span = ((total + NW - 1) / NW + (WAVE - 1)) & ~(uint32_t)(WAVE - 1);
+    const uint32_t qs = (uint32_t)wave * span;
+    const uint32_t qe = qs + span < total ? qs + span : total;
+    if (qs < total) {   // uniform for the wave
+        int pos = 0;
+        {
+            const uint32_t q = qs + lane < total ? qs + lane : total - 1;
+            for (int step = nent > 1 ? 1 << (31 - __clz(nent - 1)) : 0; step > 0; step >>= 1) {
+                const int t = pos + step;
+                if (t < nent && c.excl[t] <= q) pos = t;   // last entry starting at or before q (skips empty ones)
+            }
+        }
+        for (uint32_t q0 = qs; q0 < qe; q0 += WAVE * FLAT_U) {
+            int32_t cj[FLAT_U];
+            V cv[FLAT_U];
+#pragma unroll
+            for (int u = 0; u < FLAT_U; ++u) {
+                const uint32_t q = q0 + u * WAVE + lane;
+                const bool ok = q < qe;
+                if (ok) {
+                    int step = 1;
+                    while (pos + step < nent && c.excl[pos + step] <= q) { pos += step; step <<= 1; }
+                    for (step >>= 1; step > 0; step >>= 1)
+                        if (pos + step < nent && c.excl[pos + step] <= q) pos += step;
+                }
+                const int64_t p = c.pbase[pos] + (long long)q;
+                cj[u] = ok ? b_col[p] : -1;
+                if constexpr (HAS_VAL) cv[u] = ok ? c.a[pos] * b_val[p] : V();
+                else cv[u] = V();
+            }
+            f(cj, cv);
+        }
+    }
+    __syncthreads();
+}
+
+// Workgroup version of the row traversal: chunks of THREADS entries of A, each flattened over the
+// whole workgroup.  Every thread of the (1-D) workgroup must call it.  seg(k, p0, len) gives the
+// segment of B's arrays that entry k expands to.  Ends with a barrier.
+template <int THREADS, bool HAS_VAL, typename V, typename SegFn, typename F>
+__device__ __forceinline__ void wg_traverse(const int32_t *__restrict__ a_col, const V *__restrict__ a_val,
+                                            int64_t e0, int64_t e1, SegFn seg, const int32_t *__restrict__ b_col,
+                                            const V *__restrict__ b_val, WgChunk<V, THREADS> &c, F f)
+{
+    const int tid = threadIdx.x;
+    for (int64_t base = e0; base < e1; base += THREADS) {
+        const int64_t e = base + tid;
+        int64_t p0 = 0, len = 0;
+        V a = V();
+        if (e < e1) {
+            const int32_t k = a_col[e];
+            if constexpr (HAS_VAL) a = a_val[e];
+            seg(k, p0, len);
+        }
+        const int64_t left = e1 - base;
+        wg_flat_chunk<THREADS, HAS_VAL>(c, left < THREADS ? (int)left : THREADS, p0, (uint32_t)len, a, b_col, b_val, f);
     }
 }
 
