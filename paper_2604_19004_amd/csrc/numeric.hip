@@ -290,6 +290,113 @@ __device__ __forceinline__ int block_exclusive_scan_i32(int v, int *s_wave, int 
     return wave_off + inc - v;
 }
 
+// Write the keys of an LDS hash table to the output in increasing column order
+// without sorting them.  Every thread holds PER keys of the table in registers
+// (EMPTY_KEY = none; key[q] sits in slot q*THREADS + tid).  The keys are counted
+// into NB = THREADS*PER buckets of W = 2^shift columns starting at kmin (all keys
+// lie in [kmin, kmin + NB*W)), and a prefix sum over the counts gives every
+// bucket its range [start, start + count) of the output, which is also its
+// private range of the NB-word array `grouped`.  Inside a bucket the rank of a
+// key is found in one of two ways, whichever is cheap for that bucket:
+//   * a bucket with fewer keys than the W/32 words of a bitmap over its columns
+//     lists its keys in its range (the atomic that counted a key also returned
+//     its arrival index) and a key counts the smaller ones among them;
+//   * a bucket with at least that many keys (a cluster of columns) has room in
+//     its range for that bitmap: the keys set their bits and a key's rank is the
+//     number of set bits below its own.
+// So clustered and scattered columns cost about the same, a few LDS accesses
+// per key.  hist: NB/2 + 1 words, zeroed, two 16-bit counts per word.  Returns
+// the number of keys; with CHECK, -1 (and nothing written) when some listed
+// bucket holds more than `limit` keys, for the caller to sort instead.
+// Barriers inside; ends without one.  `grouped` may be the table's own key
+// array, provided every thread has read its keys before the call (barrier).
+template <int THREADS, int PER, bool CHECK, typename V>
+__device__ __forceinline__ int bucket_emit(const int32_t (&key)[PER], const V *s_vals, int32_t kmin, int shift,
+                                           uint32_t *hist, int32_t *grouped, int *s_wave, int *s_flag, int limit,
+                                           int64_t o, int64_t cap, long long done, int32_t *__restrict__ out_col,
+                                           V *__restrict__ out_val)
+{
+    static_assert(PER % 2 == 0, "two buckets per word");
+    constexpr int NB = THREADS * PER;
+    const int tid = threadIdx.x;
+    const int words = shift > 5 ? 1 << (shift - 5) : 1;   // bitmap words of one bucket
+    const uint32_t wmask = (1u << shift) - 1u;
+    int arrival[PER];
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+        arrival[q] = 0;
+        if (key[q] != EMPTY_KEY) {
+            const uint32_t b = (uint32_t)(key[q] - kmin) >> shift;
+            const uint32_t old = atomicAdd(&hist[b >> 1], 1u << ((b & 1u) * 16));
+            arrival[q] = (int)((old >> ((b & 1u) * 16)) & 0xffffu);
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < PER; ++q) grouped[q * THREADS + tid] = 0;
+    // counts -> starts, in place; this thread owns buckets tid*PER .. tid*PER + PER - 1
+    uint32_t wv[PER / 2];
+    int sum = 0, kmax = 0;
+#pragma unroll
+    for (int j = 0; j < PER / 2; ++j) {
+        wv[j] = hist[tid * (PER / 2) + j];
+        const int c0 = (int)(wv[j] & 0xffffu), c1 = (int)(wv[j] >> 16);
+        sum += c0 + c1;
+        if (c0 < words) kmax = max(kmax, c0);
+        if (c1 < words) kmax = max(kmax, c1);
+    }
+    if (CHECK && kmax > limit) *s_flag = 1;
+    int total;
+    int base = block_exclusive_scan_i32<THREADS>(sum, s_wave, total);
+#pragma unroll
+    for (int j = 0; j < PER / 2; ++j) {
+        const int c0 = (int)(wv[j] & 0xffffu), c1 = (int)(wv[j] >> 16);
+        hist[tid * (PER / 2) + j] = (uint32_t)base | ((uint32_t)(base + c0) << 16);
+        base += c0 + c1;
+    }
+    if (tid == THREADS - 1) hist[NB / 2] = (uint32_t)total;
+    __syncthreads();
+    if (CHECK && *s_flag) return -1;   // uniform
+    auto start_of = [&](uint32_t b) { return (int)((hist[b >> 1] >> ((b & 1u) * 16)) & 0xffffu); };
+    int lo[PER];
+    bool bitmap[PER];
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+        lo[q] = 0; bitmap[q] = false;
+        if (key[q] != EMPTY_KEY) {
+            const uint32_t x = (uint32_t)(key[q] - kmin);
+            const uint32_t b = x >> shift, d = x & wmask;
+            lo[q] = start_of(b);
+            bitmap[q] = start_of(b + 1) - lo[q] >= words;
+            if (bitmap[q]) atomicOr(reinterpret_cast<uint32_t *>(&grouped[lo[q] + (int)(d >> 5)]), 1u << (d & 31u));
+            else grouped[lo[q] + arrival[q]] = key[q];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+        if (key[q] != EMPTY_KEY) {
+            const uint32_t x = (uint32_t)(key[q] - kmin);
+            const uint32_t b = x >> shift, d = x & wmask;
+            int r = lo[q];
+            if (bitmap[q]) {
+                const int dw = (int)(d >> 5);
+                for (int j = 0; j < dw; ++j) r += __popc((uint32_t)grouped[lo[q] + j]);
+                r += __popc((uint32_t)grouped[lo[q] + dw] & ((1u << (d & 31u)) - 1u));
+            } else {
+                const int hi = start_of(b + 1);
+                for (int i = lo[q]; i < hi; ++i) r += grouped[i] < key[q];
+            }
+            const long long rank = done + r;
+            if (rank < cap) {
+                out_col[o + rank] = key[q];
+                out_val[o + rank] = s_vals[q * THREADS + tid];
+            }
+        }
+    }
+    return total;
+}
+
 // ==================================================== workgroup kernel ====
 template <typename V, int BITS, int THREADS>
 __global__ void __launch_bounds__(THREADS)
@@ -303,16 +410,20 @@ k_numeric_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col
     __shared__ int32_t s_keys[SLOTS];
     __shared__ int32_t s_sort[SLOTS];
     __shared__ V s_vals[SLOTS];
-    __shared__ WgChunk<V, THREADS> s_fc;
+    // the traversal's chunk and, after it, the bucket counts of the ordered write-out share one buffer
+    __shared__ __align__(16) unsigned char s_scratch[sizeof(WgChunk<V, THREADS>)];
+    static_assert(sizeof(WgChunk<V, THREADS>) >= (SLOTS / 2 + 1) * sizeof(uint32_t), "bucket counts fit the chunk buffer");
     __shared__ int s_wave[THREADS / WAVE];
-    __shared__ int s_ovf;
+    __shared__ int s_ovf, s_min, s_max, s_flag;
+    WgChunk<V, THREADS> &s_fc = *reinterpret_cast<WgChunk<V, THREADS> *>(s_scratch);
+    uint32_t *s_hist = reinterpret_cast<uint32_t *>(s_scratch);
     const int tid = threadIdx.x;
     const int64_t r = blockIdx.x;
     if (r >= count) return;
     const int64_t row = rows[r];
 
     for (int s = tid; s < SLOTS; s += THREADS) { s_keys[s] = EMPTY_KEY; s_vals[s] = (V)0; }
-    if (tid == 0) s_ovf = 0;
+    if (tid == 0) { s_ovf = 0; s_min = 0x7fffffff; s_max = -1; s_flag = 0; }
     __syncthreads();
 
     wg_traverse<THREADS, true>(a_col, a_val, a_rp[row], a_rp[row + 1],
@@ -323,18 +434,46 @@ k_numeric_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col
                                });
     // wg_traverse ends with a barrier
 
-    // compaction of the keys: each thread owns PER consecutive slots
-    int mine = 0;
-#pragma unroll
-    for (int q = 0; q < PER; ++q) mine += (s_keys[tid * PER + q] != EMPTY_KEY);
-    int c;
-    int pos = block_exclusive_scan_i32<THREADS>(mine, s_wave, c);
+    const int64_t o = out_ptr[row];
+    const int64_t cap = out_ptr[row + 1] - o;
+    // ---- ordered write-out through column buckets
+    int32_t key[PER];
+    int lmin = 0x7fffffff, lmax = -1;
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
-        const int32_t key = s_keys[tid * PER + q];
-        if (key != EMPTY_KEY) s_sort[pos++] = key;
+        key[q] = s_keys[q * THREADS + tid];
+        if (key[q] != EMPTY_KEY) { lmin = min(lmin, key[q]); lmax = max(lmax, key[q]); }
     }
+    for (int j = tid; j < SLOTS / 2 + 1; j += THREADS) s_hist[j] = 0u;
+    lmax = group_reduce_max(lmax, WAVE);
+    lmin = -group_reduce_max(-lmin, WAVE);
+    if (lane_id() == 0 && lmax >= 0) { atomicMin(&s_min, lmin); atomicMax(&s_max, lmax); }
+    __syncthreads();
+    const int kmin = s_min, kmax = s_max;
+    if (kmax < 0) {   // uniform: the row has no entries
+        if (tid == 0) row_nnz[row] = 0;
+        return;
+    }
+    int shift = 0;
+    while ((((uint32_t)(kmax - kmin)) >> shift) >= (uint32_t)SLOTS) ++shift;
+    constexpr bool CHECK = SLOTS >= 4096;   // smaller tables: even one bucket with every key is cheap to rank
+    int c = bucket_emit<THREADS, PER, CHECK>(key, s_vals, kmin, shift, s_hist, s_sort, s_wave, &s_flag, 1024, o, cap, 0,
+                                             out_col, out_val);
+    if (c >= 0) {
+        if (tid == 0) row_nnz[row] = (s_ovf || (int64_t)c > cap) ? -1 : c;
+        return;
+    }
+
+    // ---- columns too clustered for the buckets: compact the keys, sort them (bitonic), look the values up
+    int mine = 0;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) mine += (key[q] != EMPTY_KEY);
+    int pos = block_exclusive_scan_i32<THREADS>(mine, s_wave, c);
+#pragma unroll
+    for (int q = 0; q < PER; ++q)
+        if (key[q] != EMPTY_KEY) s_sort[pos++] = key[q];
     const int N = pow2_ceil_i32(c);
+    __syncthreads();
     for (int s = c + tid; s < N; s += THREADS) s_sort[s] = SORT_PAD;
     __syncthreads();
 
@@ -350,15 +489,13 @@ k_numeric_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col
         }
     }
 
-    const int64_t o = out_ptr[row];
-    const int64_t cap = out_ptr[row + 1] - o;
     if (s_ovf || (int64_t)c > cap) {
         if (tid == 0) row_nnz[row] = -1;
     } else {
         for (int t = tid; t < c; t += THREADS) {
-            const int32_t key = s_sort[t];
-            out_col[o + t] = key;
-            out_val[o + t] = s_vals[lds_find<BITS>(s_keys, key)];
+            const int32_t k2 = s_sort[t];
+            out_col[o + t] = k2;
+            out_val[o + t] = s_vals[lds_find<BITS>(s_keys, k2)];
         }
         if (tid == 0) row_nnz[row] = c;
     }
@@ -499,7 +636,7 @@ k_numeric_hybrid(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
 //     sorted position;
 //   * consecutive windows whose product counts add up to at most HCAP share one
 //     pass: an 8192-slot LDS hash table takes all their products, and the table
-//     is emitted in column order through a bitmap rank, RSPAN columns at a time.
+//     is written out in column order through column buckets (bucket_emit).
 // Everything is accumulated in LDS and no table can overflow by construction.
 // What bounds this path is the latency of its chain of dependent accesses
 // (entry -> window boundary -> products -> LDS), paid once per pass, which is
@@ -509,8 +646,6 @@ constexpr int HV_THREADS = 1024;
 constexpr int HV_HBITS = 13;
 constexpr int HV_HSLOTS = 1 << HV_HBITS;
 constexpr int HV_HCAP = 6144;
-constexpr int HV_RSPAN = 131072;             // columns ranked per emission step
-constexpr int HV_RWORDS = HV_RSPAN / 32;     // 4096 bitmap words
 constexpr int HV_MAXWIN = 512;               // windows per row the kernel can plan for
 
 template <typename V>
@@ -529,8 +664,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
 {
     constexpr int WIN = DenseCfg<V>::WIN;
     constexpr int WORDS = DenseCfg<V>::WORDS;
-    constexpr int RWIN = HV_RSPAN / WIN;   // windows per emission step
-    // one 128 KB region, used either as the dense window or as hash table + rank bitmap
+    // one 128 KB region, used either as the dense window or as hash table + bucket counts
     __shared__ __align__(16) unsigned char s_u[131072];
     __shared__ uint32_t s_dbm[WORDS];
     __shared__ uint32_t s_dpre[WORDS];
@@ -542,8 +676,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     V *s_vals = reinterpret_cast<V *>(s_u);                                        // dense: WIN values
     int32_t *s_keys = reinterpret_cast<int32_t *>(s_u);                            // hash: 8192 keys
     V *s_hvals = reinterpret_cast<V *>(s_u + 32768);                               // hash: 8192 values
-    uint32_t *s_rbm = reinterpret_cast<uint32_t *>(s_u + 98304);                   // hash: rank bitmap, 4096 words
-    uint16_t *s_rpre = reinterpret_cast<uint16_t *>(s_u + 98304 + 4 * HV_RWORDS);  // hash: prefix per word
+    uint32_t *s_hist = reinterpret_cast<uint32_t *>(s_u + 98304);                  // hash: bucket counts of the write-out
     const int tid = threadIdx.x;
     const size_t stride = (size_t)n_win + 1;
 
@@ -605,8 +738,6 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                     dense_clean = true;
                 }
             } else {
-                // (the rank bitmap inside the region is zero here: the region is either an all-zero dense
-                // window or was left by a hash pass whose emission cleared the bitmap)
                 for (int s = tid; s < HV_HSLOTS; s += HV_THREADS) { s_keys[s] = EMPTY_KEY; s_hvals[s] = (V)0; }
                 dense_clean = false;
             }
@@ -670,49 +801,17 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                 done += wtotal;
                 __syncthreads();
             } else {
-                // ---- hash table -> output, RSPAN columns at a time
-                for (int ws = w; ws < w1; ws += RWIN) {
-                    const int we = ws + RWIN < w1 ? ws + RWIN : w1;
-                    uint32_t any = 0;
-                    for (int x = ws; x < we; ++x) any |= s_prodw[x];
-                    if (any == 0) continue;   // uniform
-                    const int32_t lo = ws * WIN;
-                    const int64_t hi = (int64_t)we * WIN;
+                // ---- hash table -> output in column order, through column buckets over the pass's windows
+                int32_t key[HV_HSLOTS / HV_THREADS];
 #pragma unroll
-                    for (int q = 0; q < HV_HSLOTS / HV_THREADS; ++q) {
-                        const int32_t key = s_keys[q * HV_THREADS + tid];
-                        if (key != EMPTY_KEY && key >= lo && (int64_t)key < hi) {
-                            const int d = key - lo;
-                            atomicOr(&s_rbm[d >> 5], 1u << (d & 31));
-                        }
-                    }
-                    __syncthreads();
-                    constexpr int WPT = HV_RWORDS / HV_THREADS;   // 4
-                    int cnt[WPT];
-                    int mine = 0;
-#pragma unroll
-                    for (int q = 0; q < WPT; ++q) { cnt[q] = __popc(s_rbm[tid * WPT + q]); mine += cnt[q]; }
-                    int rtotal;
-                    int run = block_exclusive_scan_i32<HV_THREADS>(mine, s_wave, rtotal);
-#pragma unroll
-                    for (int q = 0; q < WPT; ++q) { s_rpre[tid * WPT + q] = (uint16_t)run; run += cnt[q]; }
-                    __syncthreads();
-#pragma unroll
-                    for (int q = 0; q < HV_HSLOTS / HV_THREADS; ++q) {
-                        const int slot = q * HV_THREADS + tid;
-                        const int32_t key = s_keys[slot];
-                        if (key != EMPTY_KEY && key >= lo && (int64_t)key < hi) {
-                            const int d = key - lo;
-                            const long long rank = done + (long long)s_rpre[d >> 5] + __popc(s_rbm[d >> 5] & ((1u << (d & 31)) - 1u));
-                            if (rank < cap) { out_col[o + rank] = key; out_val[o + rank] = s_hvals[slot]; }
-                        }
-                    }
-                    __syncthreads();
-#pragma unroll
-                    for (int q = 0; q < WPT; ++q) s_rbm[tid * WPT + q] = 0u;
-                    done += rtotal;
-                    __syncthreads();
-                }
+                for (int q = 0; q < HV_HSLOTS / HV_THREADS; ++q) key[q] = s_keys[q * HV_THREADS + tid];
+                for (int j = tid; j < HV_HSLOTS / 2 + 1; j += HV_THREADS) s_hist[j] = 0u;
+                __syncthreads();   // the key array is rewritten below: everybody holds its keys now
+                int shift = 0;
+                while ((((uint32_t)(w1 - w) * (uint32_t)WIN - 1u) >> shift) >= (uint32_t)HV_HSLOTS) ++shift;
+                done += bucket_emit<HV_THREADS, HV_HSLOTS / HV_THREADS, false>(key, s_hvals, col0, shift, s_hist, s_keys, s_wave,
+                                                                             nullptr, 0, o, cap, done, out_col, out_val);
+                __syncthreads();
             }
             w = w1;
         }
