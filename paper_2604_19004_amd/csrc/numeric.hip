@@ -308,10 +308,12 @@ __device__ __forceinline__ int block_exclusive_scan_i32(int v, int *s_wave, int 
 // per key.  hist: NB/2 + 1 words, zeroed, two 16-bit counts per word.  Returns
 // the number of keys; with CHECK, -1 (and nothing written) when some listed
 // bucket holds more than `limit` keys, for the caller to sort instead.
-// Barriers inside; ends without one.  `grouped` may be the table's own key
-// array, provided every thread has read its keys before the call (barrier).
+// Barriers inside; ends without one.  The table's values are overwritten (the
+// keys and values are put in order inside LDS and copied out from there).
+// `grouped` may be the table's own key array, provided every thread has read
+// its keys before the call (barrier).
 template <int THREADS, int PER, bool CHECK, typename V>
-__device__ __forceinline__ int bucket_emit(const int32_t (&key)[PER], const V *s_vals, int32_t kmin, int shift,
+__device__ __forceinline__ int bucket_emit(const int32_t (&key)[PER], V *s_vals, int32_t kmin, int shift,
                                            uint32_t *hist, int32_t *grouped, int *s_wave, int *s_flag, int limit,
                                            int64_t o, int64_t cap, long long done, int32_t *__restrict__ out_col,
                                            V *__restrict__ out_val)
@@ -373,8 +375,12 @@ __device__ __forceinline__ int bucket_emit(const int32_t (&key)[PER], const V *s
         }
     }
     __syncthreads();
+    int rank[PER];
+    V val[PER];
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
+        rank[q] = 0;
+        val[q] = V();
         if (key[q] != EMPTY_KEY) {
             const uint32_t x = (uint32_t)(key[q] - kmin);
             const uint32_t b = x >> shift, d = x & wmask;
@@ -387,12 +393,22 @@ __device__ __forceinline__ int bucket_emit(const int32_t (&key)[PER], const V *s
                 const int hi = start_of(b + 1);
                 for (int i = lo[q]; i < hi; ++i) r += grouped[i] < key[q];
             }
-            const long long rank = done + r;
-            if (rank < cap) {
-                out_col[o + rank] = key[q];
-                out_val[o + rank] = s_vals[q * THREADS + tid];
-            }
+            rank[q] = r;
+            val[q] = s_vals[q * THREADS + tid];
         }
+    }
+    __syncthreads();
+    // permute keys and values into place inside LDS (every thread holds its own in registers), so
+    // that the row leaves with coalesced stores
+#pragma unroll
+    for (int q = 0; q < PER; ++q)
+        if (key[q] != EMPTY_KEY) { grouped[rank[q]] = key[q]; s_vals[rank[q]] = val[q]; }
+    __syncthreads();
+    const long long room = cap - done;
+    const int n_out = (long long)total < room ? total : (room > 0 ? (int)room : 0);
+    for (int i = tid; i < n_out; i += THREADS) {
+        out_col[o + done + i] = grouped[i];
+        out_val[o + done + i] = s_vals[i];
     }
     return total;
 }
@@ -1034,7 +1050,7 @@ static hipError_t dispatch(const Csr &A, const Csr &B, const NumLaunch &l, int g
     case NB_S512: OCEAN_WG(9, 128); break;
     case NB_S1K: OCEAN_WG(10, 256); break;
     case NB_S2K: OCEAN_WG(11, 512); break;
-    case NB_S4K: OCEAN_WG(12, 1024); break;
+    case NB_S4K: OCEAN_WG(12, 512); break;
     case NB_S8K: OCEAN_WG(13, 1024); break;
     case NB_HYBRID:
         if (l.bw != nullptr)

@@ -202,9 +202,12 @@ __device__ __forceinline__ void wg_flat_chunk(WgChunk<V, THREADS> &c, int nent, 
                 if (t < nent && c.excl[t] <= q) pos = t;   // last entry starting at or before q (skips empty ones)
             }
         }
-        for (uint32_t q0 = qs; q0 < qe; q0 += WAVE * FLAT_U) {
-            int32_t cj[FLAT_U];
-            V cv[FLAT_U];
+        // The loads of the next batch are issued before the current one goes to the accumulator, so
+        // a wave's memory latency hides behind its own LDS work.
+        int32_t cj[FLAT_U], nj[FLAT_U];
+        V cb[FLAT_U], nb[FLAT_U];   // values of B; multiplied by A's value only when the batch is used
+        int cp[FLAT_U], np[FLAT_U];
+        auto fetch = [&](uint32_t q0, int32_t (&fj)[FLAT_U], V (&fb)[FLAT_U], int (&fp)[FLAT_U]) {
 #pragma unroll
             for (int u = 0; u < FLAT_U; ++u) {
                 const uint32_t q = q0 + u * WAVE + lane;
@@ -216,11 +219,25 @@ __device__ __forceinline__ void wg_flat_chunk(WgChunk<V, THREADS> &c, int nent, 
                         if (pos + step < nent && c.excl[pos + step] <= q) pos += step;
                 }
                 const int64_t p = c.pbase[pos] + (long long)q;
-                cj[u] = ok ? b_col[p] : -1;
-                if constexpr (HAS_VAL) cv[u] = ok ? c.a[pos] * b_val[p] : V();
+                fj[u] = ok ? b_col[p] : -1;
+                if constexpr (HAS_VAL) fb[u] = ok ? b_val[p] : V();
+                else fb[u] = V();
+                fp[u] = pos;
+            }
+        };
+        fetch(qs, cj, cb, cp);
+        for (uint32_t q0 = qs; q0 < qe; q0 += WAVE * FLAT_U) {
+            const uint32_t qn = q0 + WAVE * FLAT_U;
+            if (qn < qe) fetch(qn, nj, nb, np);   // uniform for the wave
+            V cv[FLAT_U];
+#pragma unroll
+            for (int u = 0; u < FLAT_U; ++u) {
+                if constexpr (HAS_VAL) cv[u] = c.a[cp[u]] * cb[u];
                 else cv[u] = V();
             }
             f(cj, cv);
+#pragma unroll
+            for (int u = 0; u < FLAT_U; ++u) { cj[u] = nj[u]; cb[u] = nb[u]; cp[u] = np[u]; }
         }
     }
     __syncthreads();
