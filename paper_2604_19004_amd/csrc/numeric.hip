@@ -736,17 +736,33 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
         }
         __syncthreads();
 
-        // ---- walk the windows
-        int w = 0;
+        // ---- walk the windows, pass by pass
+        // next pass from window `from` on: a window with more than HCAP products on its own (dense), or
+        // a run of windows with at most HCAP products together (hash); p0 == n_win when nothing is left
+        auto plan = [&](int from, int &p0, int &p1, bool &pdense) {
+            int x = from;
+            while (x < n_win && s_prodw[x] == 0) ++x;
+            p0 = x; p1 = x; pdense = false;
+            if (x >= n_win) return;
+            uint32_t sum = s_prodw[x];
+            pdense = sum > (uint32_t)HV_HCAP;
+            p1 = x + 1;
+            if (!pdense)
+                while (p1 < n_win && sum + s_prodw[p1] <= (uint32_t)HV_HCAP) { sum += s_prodw[p1]; ++p1; }
+        };
+        int w, w1;
+        bool dense;
+        plan(0, w, w1, dense);
+        // window boundaries of this thread's entry: those of the next pass are fetched one pass ahead
+        const bool have0 = tid < ne;
+        const uint32_t *t0 = bw + (size_t)ek * stride;
+        uint32_t c_lo = have0 ? t0[w] : 0u, c_hi = have0 ? t0[w1] : 0u;
         while (w < n_win) {
-            const uint32_t pw = s_prodw[w];
-            if (pw == 0) { ++w; continue; }
-            const bool dense = pw > (uint32_t)HV_HCAP;
-            int w1 = w + 1;
-            if (!dense) {
-                uint32_t sum = pw;
-                while (w1 < n_win && sum + s_prodw[w1] <= (uint32_t)HV_HCAP) { sum += s_prodw[w1]; ++w1; }
-            }
+            int nx0, nx1;
+            bool nxdense;
+            plan(w1, nx0, nx1, nxdense);
+            // (no entry has products in the windows skipped between two passes: the next pass starts at c_hi)
+            const uint32_t n_hi = have0 ? t0[nx1] : 0u;
             // accumulator of this pass
             if (dense) {
                 if (!dense_clean) {
@@ -781,11 +797,14 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                 V a = ea;
                 const bool have = base + tid < ne;
                 if (base > 0 && have) { k = a_col[e0 + base + tid]; a = a_val[e0 + base + tid]; }
-                uint32_t c0 = 0, c1 = 0;
-                if (have) {
-                    const uint32_t *t = bw + (size_t)k * stride;
-                    c0 = t[w];
-                    c1 = t[w1];
+                uint32_t c0 = c_lo, c1 = c_hi;
+                if (base > 0) {
+                    c0 = c1 = 0;
+                    if (have) {
+                        const uint32_t *t = bw + (size_t)k * stride;
+                        c0 = t[w];
+                        c1 = t[w1];
+                    }
                 }
                 const int64_t left = ne - base;
                 wg_flat_chunk<HV_THREADS, true>(s_fc, left < HV_THREADS ? (int)left : HV_THREADS, (int64_t)c0, c1 - c0, a,
@@ -829,7 +848,8 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                                                                              nullptr, 0, o, cap, done, out_col, out_val);
                 __syncthreads();
             }
-            w = w1;
+            c_lo = c_hi; c_hi = n_hi;
+            w = nx0; w1 = nx1; dense = nxdense;
         }
         if (tid == 0) row_nnz[row] = (s_ovf || done > cap) ? -1 : (int32_t)done;
         __syncthreads();
