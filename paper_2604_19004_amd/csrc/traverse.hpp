@@ -145,6 +145,7 @@ struct WgChunk {
     uint32_t excl[THREADS];
     long long pbase[THREADS];
     V a[THREADS];
+    uint16_t first[THREADS + 2];   // entry of the first product of every block of 2^bshift products
     uint32_t wsum[THREADS / WAVE];
     uint32_t total;
 };
@@ -152,14 +153,19 @@ struct WgChunk {
 // The whole workgroup flattens the `nent` (1..THREADS) segments held by its first nent threads
 // (p0, len, a; len = 0 in the other threads): the products of the concatenation are dealt out
 // evenly to the waves whatever the lengths of the single segments, so a row with three entries
-// that point to long rows of B keeps every wave as busy as a row with a thousand short ones.  The
-// products of one chunk must number less than 2^31.  Every thread calls it; the chunk arrays must
-// be free on entry (the call ends with a barrier).
+// that point to long rows of B keeps every wave as busy as a row with a thousand short ones.
+// Every wave takes one contiguous span of the products, 256 at a time.  The entry a product
+// belongs to is found by a binary search over the prefix sums, narrowed beforehand to the few
+// entries its batch of 256 can touch: a table built once per chunk gives the entry of the first
+// product of every block of products.  The searches of a batch have the same, wave-uniform
+// number of steps and run interleaved.  The products of one chunk must number less than 2^31.
+// Every thread calls it; the chunk arrays must be free on entry (the call ends with a barrier).
 template <int THREADS, bool HAS_VAL, typename V, typename F>
 __device__ __forceinline__ void wg_flat_chunk(WgChunk<V, THREADS> &c, int nent, int64_t p0, uint32_t len, V a,
                                               const int32_t *__restrict__ b_col, const V *__restrict__ b_val, F &f)
 {
     constexpr int NW = THREADS / WAVE;
+    static_assert(THREADS <= 1024, "entry ids are kept in 16 bits and one block table entry per thread");
     const int tid = threadIdx.x;
     const int lane = tid & (WAVE - 1), wave = tid / WAVE;
     uint32_t incl = len;
@@ -187,42 +193,60 @@ __device__ __forceinline__ void wg_flat_chunk(WgChunk<V, THREADS> &c, int nent, 
     if (tid == nent - 1) c.total = incl;
     __syncthreads();
     const uint32_t total = c.total;
-    // Every wave takes one contiguous span of the products, 64 at a time, so the entry of a lane's
-    // product moves forward slowly: it is searched once and then followed by galloping from the
-    // last position (one LDS read while the lane stays inside one row of B).
-    const uint32_t span = ((total + NW - 1) / NW + (WAVE - 1)) & ~(uint32_t)(WAVE - 1);
-    const uint32_t qs = (uint32_t)wave * span;
-    const uint32_t qe = qs + span < total ? qs + span : total;
-    if (qs < total) {   // uniform for the wave
-        int pos = 0;
-        {
-            const uint32_t q = qs + lane < total ? qs + lane : total - 1;
-            for (int step = nent > 1 ? 1 << (31 - __clz(nent - 1)) : 0; step > 0; step >>= 1) {
+    if (total == 0) {   // uniform
+        __syncthreads();
+        return;
+    }
+    // blocks of 2^bshift products, at least 256 products each and fewer than THREADS of them
+    int bshift = 8;
+    while (((total - 1) >> bshift) >= (uint32_t)(THREADS - 1)) ++bshift;
+    const int nblk = (int)((total - 1) >> bshift) + 1;
+    const int top = nent > 1 ? 1 << (31 - __clz(nent - 1)) : 0;
+    if (tid <= nblk) {
+        int pos = nent - 1;
+        if (tid < nblk) {
+            const uint32_t q = (uint32_t)tid << bshift;
+            pos = 0;
+            for (int step = top; step > 0; step >>= 1) {
                 const int t = pos + step;
                 if (t < nent && c.excl[t] <= q) pos = t;   // last entry starting at or before q (skips empty ones)
             }
         }
+        c.first[tid] = (uint16_t)pos;
+    }
+    __syncthreads();
+    const uint32_t span = ((total + NW - 1) / NW + (WAVE - 1)) & ~(uint32_t)(WAVE - 1);
+    const uint32_t qs = (uint32_t)wave * span;
+    const uint32_t qe = qs + span < total ? qs + span : total;
+    if (qs < total) {   // uniform for the wave
         // The loads of the next batch are issued before the current one goes to the accumulator, so
         // a wave's memory latency hides behind its own LDS work.
         int32_t cj[FLAT_U], nj[FLAT_U];
         V cb[FLAT_U], nb[FLAT_U];   // values of B; multiplied by A's value only when the batch is used
         int cp[FLAT_U], np[FLAT_U];
         auto fetch = [&](uint32_t q0, int32_t (&fj)[FLAT_U], V (&fb)[FLAT_U], int (&fp)[FLAT_U]) {
+            const uint32_t qlast = q0 + WAVE * FLAT_U - 1 < qe - 1 ? q0 + WAVE * FLAT_U - 1 : qe - 1;
+            const int lo = c.first[q0 >> bshift];
+            const int hi = c.first[(qlast >> bshift) + 1];   // the entry of a later product, or the last entry
+            const int width = __builtin_amdgcn_readfirstlane(hi - lo);
+#pragma unroll
+            for (int u = 0; u < FLAT_U; ++u) fp[u] = lo;
+            for (int step = width > 0 ? 1 << (31 - __clz(width)) : 0; step > 0; step >>= 1) {
+#pragma unroll
+                for (int u = 0; u < FLAT_U; ++u) {
+                    const uint32_t q = q0 + u * WAVE + lane;
+                    const int t = fp[u] + step;
+                    if (t <= hi && c.excl[t] <= q) fp[u] = t;
+                }
+            }
 #pragma unroll
             for (int u = 0; u < FLAT_U; ++u) {
                 const uint32_t q = q0 + u * WAVE + lane;
                 const bool ok = q < qe;
-                if (ok) {
-                    int step = 1;
-                    while (pos + step < nent && c.excl[pos + step] <= q) { pos += step; step <<= 1; }
-                    for (step >>= 1; step > 0; step >>= 1)
-                        if (pos + step < nent && c.excl[pos + step] <= q) pos += step;
-                }
-                const int64_t p = c.pbase[pos] + (long long)q;
+                const int64_t p = c.pbase[fp[u]] + (long long)q;
                 fj[u] = ok ? b_col[p] : -1;
                 if constexpr (HAS_VAL) fb[u] = ok ? b_val[p] : V();
                 else fb[u] = V();
-                fp[u] = pos;
             }
         };
         fetch(qs, cj, cb, cp);
