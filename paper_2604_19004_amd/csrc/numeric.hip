@@ -707,8 +707,8 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
         }
         for (int w = tid; w < n_win; w += HV_THREADS) s_prodw[w] = 0u;
         __syncthreads();
-        const int64_t r = s_row;
-        if (r >= count) break;   // uniform exit
+        if (s_row >= count) break;   // uniform exit
+        const int64_t r = count - 1 - s_row;   // from the end of the list, where the rows with the largest bounds are
         const int64_t row = rows[r];
         const int64_t e0 = a_rp[row], e1 = a_rp[row + 1];
         const int64_t o = out_ptr[row];
@@ -1073,9 +1073,7 @@ static hipError_t dispatch(const Csr &A, const Csr &B, const NumLaunch &l, int g
     case NB_S4K: OCEAN_WG(12, 512); break;
     case NB_S8K: OCEAN_WG(13, 1024); break;
     case NB_HYBRID:
-        if (l.bw != nullptr)
-            hipLaunchKernelGGL((k_numeric_heavy<V>), dim3((unsigned)l.n_wg), dim3(HV_THREADS), 0, s, A.rp, A.col, av, l.bw,
-                               l.n_win, B.col, bv, l.rows, l.count, l.queue, l.out_ptr, l.out_col, ov, l.row_nnz);
+        if (l.bw != nullptr) return hipErrorInvalidValue;   // such rows go with the last bin
         else
             hipLaunchKernelGGL((k_numeric_hybrid<V>), dim3((unsigned)l.n_wg), dim3(HY_THREADS), 0, s, A.rp, A.col, av,
                                B.rp, B.col, bv, l.rows, l.count, l.queue, static_cast<V *>(l.slab),

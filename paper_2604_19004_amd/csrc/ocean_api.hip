@@ -341,13 +341,15 @@ int run_numeric(Ctx &c, Work &w, const Csr &A, const Csr &B, int dtype, int gb_l
         l.out_val = out_val;
         l.row_nnz = row_nnz;
         l.coef = global_coef;
+        if (c.bw != nullptr && b == NB_HYBRID) continue;   // went with the last bin, see below
+        if (c.bw != nullptr && b == NB_GLOBAL) {
+            // the windowed kernel takes the rows of the last two bins in one launch (their row lists
+            // are adjacent), heaviest class first
+            l.rows = w.bin_rows + start[NB_HYBRID];
+            l.count = start[NB_GLOBAL + 1] - start[NB_HYBRID];
+        }
         if (l.count == 0) continue;
-        if (b == NB_HYBRID && c.bw != nullptr) {
-            l.bw = c.bw;
-            l.n_win = c.n_win;
-            l.n_wg = (int)(l.count < c.n_cu ? l.count : c.n_cu);
-            l.queue = &w.sc->queue[queue_base];
-        } else if (b == NB_HYBRID) {
+        if (b == NB_HYBRID) {
             l.n_wg = (int)(l.count < c.n_cu ? l.count : c.n_cu);
             const size_t bytes = (size_t)l.n_wg * 32768 * vbytes;
             l.slab = c.alloc(bytes);
