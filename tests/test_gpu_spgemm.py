@@ -159,6 +159,81 @@ def test_full_size_er_and_laplacian(ob, wf):
             assert np.array_equal(Cd.val.cpu().numpy(), ref.val)
 
 
+@pytest.mark.parametrize("name", ["rect", "clustered"])
+def test_full_size_rect_and_clustered(ob, name):
+    """Full BASELINE sizes, every element against the oracle, in the workflows bench.py times."""
+    A, B, ref, prod = workload(name, False)
+    dA, dB = ob.to_device(A), ob.to_device(B)
+    for wf in ("auto", "hll", "upper_bound"):
+        print(f"full size {name}/{wf}", flush=True)
+        Cd, st = ob.spgemm(dA, dB, workflow=wf_id(ob, wf))
+        check_result(Cd, ref, A, f"{name}/{wf}")
+        assert st["products"] == int(prod.sum()) and st["nnz_c"] == ref.col_idx.size
+        del Cd
+    _cache.pop((name, False), None)   # the reference of a full-size product is large
+
+
+def test_full_size_rmat_sampled_rows_and_invariants(ob):
+    """R-MAT scale 20 as bench.py runs it (AUTO).  C (116 GB) cannot go through the oracle whole: rows are
+    sampled - every numeric bin, the heaviest rows, the rows with the most entries of A - and compared
+    element by element; the rest is covered by properties that hold at any size."""
+    import torch
+    A, B, _ = W.make("rmat")
+    prod = O.row_products(A, B)
+    dA, dB = ob.to_device(A), ob.to_device(B)
+    print("full size rmat/auto", flush=True)
+    Cd, st = ob.spgemm(dA, dB, workflow=ob.WF_AUTO)
+    assert st["workflow"] == "symbolic"                      # Table 1: sampled CR < 8
+    assert st["products"] == int(prod.sum())
+    rp = Cd.row_ptr.cpu().numpy()
+    nnz = np.diff(rp)
+    assert rp[0] == 0 and np.all(nnz >= 0) and rp[-1] == st["nnz_c"] == Cd.col_idx.numel()
+    # size invariants per row: longest referenced row of B <= nnz <= min(products, n); empty iff no products
+    assert np.all(nnz <= np.minimum(prod, B.cols)) and np.array_equal(nnz == 0, prod == 0)
+    # the exact symbolic pass, called on its own, agrees with the produced structure
+    sym, _ = ob.symbolic(dA, dB)
+    sym = sym.cpu().numpy()
+    assert np.array_equal(sym.astype(np.int64), nnz)
+    # columns strictly ascending inside rows, checked over a contiguous 2^28-entry stretch of C on the device
+    lo = int(rp[A.rows // 3]); hi = int(min(lo + (1 << 28), rp[-1]))
+    seg = Cd.col_idx[lo:hi]
+    starts = torch.from_numpy(rp[(rp > lo) & (rp < hi)] - lo).to(seg.device)
+    desc = (seg[1:] <= seg[:-1])
+    desc[starts - 1] = False                                  # row boundaries may step down
+    assert not bool(desc.any())
+    del seg, desc, starts
+    # sampled rows against the oracle
+    rng = np.random.default_rng(7)
+    order = np.argsort(nnz)
+    picks = [rng.choice(A.rows, 150, replace=False), np.argsort(prod)[-4:], np.argsort(np.diff(A.row_ptr))[-3:]]
+    for q in (0.5, 0.8, 0.9, 0.95, 0.99, 0.999):               # rows around the quantiles of the row length: every bin
+        c = int(q * A.rows)
+        picks.append(order[c - 3:c + 3])
+    rows = np.unique(np.concatenate(picks))
+    for r in rows:
+        ref = O.multiply_rows(A, B, int(r), int(r) + 1)
+        s, e = int(rp[r]), int(rp[r + 1])
+        assert e - s == ref.col_idx.size, f"row {r}: {e - s} entries, oracle {ref.col_idx.size}"
+        assert np.array_equal(Cd.col_idx[s:e].cpu().numpy(), ref.col_idx), f"row {r}: columns differ"
+        err = np.abs(Cd.val[s:e].cpu().numpy() - ref.val)
+        assert np.all(err <= 1e-12 * ref.absval), f"row {r}: values off"
+    # C x = A (B x) for a random x on a block of rows (all values are positive: a relative tolerance applies)
+    x = rng.random(B.cols)
+    r0, r1 = A.rows // 2, A.rows // 2 + 4096
+    s, e = int(rp[r0]), int(rp[r1])
+    cval = Cd.val[s:e].cpu().numpy() * x[Cd.col_idx[s:e].cpu().numpy()]
+    bx = np.array([np.dot(B.val[B.row_ptr[k]:B.row_ptr[k + 1]], x[B.col_idx[B.row_ptr[k]:B.row_ptr[k + 1]]])
+                   for k in range(B.rows)]) if B.rows <= 4096 else None
+    if bx is None:   # B is large: row sums of B.*x through a sorted segment sum
+        seg = np.repeat(np.arange(B.rows), np.diff(B.row_ptr))
+        bx = np.bincount(seg, weights=B.val * x[B.col_idx], minlength=B.rows)
+    for r in range(r0, r1):
+        cx = cval[int(rp[r]) - s:int(rp[r + 1]) - s].sum()
+        ak = slice(int(A.row_ptr[r]), int(A.row_ptr[r + 1]))
+        abx = np.dot(A.val[ak], bx[A.col_idx[ak]])
+        assert abs(cx - abx) <= 1e-10 * abs(abx), f"row {r}: C x = {cx}, A (B x) = {abx}"
+
+
 def test_structure_is_identical_across_runs(ob):
     A, B, ref, prod = workload("rmat", True)
     dA, dB = ob.to_device(A), ob.to_device(B)
