@@ -58,45 +58,90 @@ hipError_t launch_validate(const Csr &A, const Csr &B, int32_t *flags, hipStream
 // ------------------------------------------------------------ row products
 // One group of 2^g_log2 lanes per row, a fixed number of workgroups striding
 // over the rows: the totals cost one atomic per workgroup, not one per row tile
-// (same-address atomics from all XCDs serialise in the memory fabric).
+// (same-address atomics from all XCDs serialise in the memory fabric).  A row
+// far longer than the average (power-law inputs have rows with tens of
+// thousands of entries) would keep its few lanes busy for milliseconds: such
+// rows are set aside in LDS and walked by the whole workgroup afterwards.
 __global__ void __launch_bounds__(TPB)
 k_row_products(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col, int64_t m,
                const int64_t *__restrict__ b_rp, int64_t b_rows, int g_log2, int64_t *__restrict__ prod,
                int32_t *__restrict__ maxb, unsigned long long *totals, int32_t *flags)
 {
+    constexpr int LIST = 128;
     __shared__ long long s_sum[TPB / WAVE];
     __shared__ long long s_max[TPB / WAVE];
+    __shared__ long long s_long[LIST];
+    __shared__ int s_nlong;
     const int G = 1 << g_log2;
     const int R = TPB >> g_log2;
     const int rl = threadIdx.x >> g_log2;
     const int sub = threadIdx.x & (G - 1);
+    const int64_t long_len = (int64_t)G * 32;
     long long tsum = 0, tmax = 0;
     bool bad = false;
+    if (threadIdx.x == 0) s_nlong = 0;
+    __syncthreads();
+    auto entry = [&](int64_t e, long long &p, long long &mx) {
+        const int32_t k = a_col[e];
+        if ((uint32_t)k >= (uint64_t)b_rows) { bad = true; return; }
+        const long long len = b_rp[k + 1] - b_rp[k];
+        p += len;
+        mx = len > mx ? len : mx;
+    };
     for (int64_t base = (int64_t)blockIdx.x * R; base < m; base += (int64_t)gridDim.x * R) {
         const int64_t row = base + rl;
         long long p = 0, mx = 0;
-        if (row < m) {
-            const int64_t e1 = a_rp[row + 1];
-            for (int64_t e = a_rp[row] + sub; e < e1; e += G) {
-                const int32_t k = a_col[e];
-                if ((uint32_t)k >= (uint64_t)b_rows) { bad = true; continue; }
-                const long long len = b_rp[k + 1] - b_rp[k];
-                p += len;
-                mx = len > mx ? len : mx;
+        bool mine = row < m;
+        if (mine) {
+            const int64_t e0 = a_rp[row], e1 = a_rp[row + 1];
+            if (e1 - e0 > long_len) {   // uniform for the group
+                int slot = LIST;
+                if (sub == 0) slot = atomicAdd(&s_nlong, 1);
+                slot = __shfl(slot, (int)(threadIdx.x & (WAVE - 1)) & ~(G - 1), WAVE);
+                if (slot < LIST) {
+                    if (sub == 0) s_long[slot] = row;
+                    mine = false;   // the workgroup takes it below
+                }
             }
+            if (mine)
+                for (int64_t e = e0 + sub; e < e1; e += G) entry(e, p, mx);
         }
         p = group_reduce_sum(p, G);
         mx = group_reduce_max(mx, G);
-        if (row < m && sub == 0) {
+        if (mine && sub == 0) {
             prod[row] = p;
             maxb[row] = (int32_t)(mx > 0x7fffffffLL ? 0x7fffffffLL : mx);
             tsum += p;
             tmax = p > tmax ? p : tmax;
         }
     }
+    __syncthreads();
+    const int nlong = s_nlong < LIST ? s_nlong : LIST;
+    const int w = threadIdx.x / WAVE;
+    for (int i = 0; i < nlong; ++i) {
+        const int64_t row = s_long[i];
+        const int64_t e0 = a_rp[row], e1 = a_rp[row + 1];
+        long long p0 = 0, p1 = 0, m0 = 0, m1 = 0;   // two chains in flight per thread
+        for (int64_t e = e0 + threadIdx.x; e < e1; e += 2 * TPB) {
+            entry(e, p0, m0);
+            if (e + TPB < e1) entry(e + TPB, p1, m1);
+        }
+        const long long wsum = group_reduce_sum(p0 + p1, WAVE);
+        const long long wmax = group_reduce_max(m0 > m1 ? m0 : m1, WAVE);
+        if (lane_id() == 0) { s_sum[w] = wsum; s_max[w] = wmax; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            long long p = 0, mx = 0;
+            for (int j = 0; j < TPB / WAVE; ++j) { p += s_sum[j]; mx = s_max[j] > mx ? s_max[j] : mx; }
+            prod[row] = p;
+            maxb[row] = (int32_t)(mx > 0x7fffffffLL ? 0x7fffffffLL : mx);
+            tsum += p;
+            tmax = p > tmax ? p : tmax;
+        }
+        __syncthreads();
+    }
     const long long wsum = group_reduce_sum(tsum, WAVE);
     const long long wmax = group_reduce_max(tmax, WAVE);
-    const int w = threadIdx.x / WAVE;
     if (lane_id() == 0) { s_sum[w] = wsum; s_max[w] = wmax; }
     __syncthreads();
     if (threadIdx.x == 0) {

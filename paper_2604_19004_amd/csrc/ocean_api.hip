@@ -347,6 +347,11 @@ int run_numeric(Ctx &c, Work &w, const Csr &A, const Csr &B, int dtype, int gb_l
             // are adjacent), heaviest class first
             l.rows = w.bin_rows + start[NB_HYBRID];
             l.count = start[NB_GLOBAL + 1] - start[NB_HYBRID];
+            // longest rows first (the kernel takes rows from the end of the list); skipped when memory is short
+            const size_t sort_bytes = sort_rows_scratch_bytes(l.count);
+            void *sort_tmp = sort_bytes ? c.alloc(sort_bytes) : nullptr;
+            if (sort_tmp)
+                HIP_TRY(launch_sort_rows_by_products(w.prod, w.bin_rows + start[NB_HYBRID], l.count, sort_tmp, c.s));
         }
         if (l.count == 0) continue;
         if (b == NB_HYBRID) {

@@ -157,6 +157,10 @@ struct SymLaunch {
 hipError_t launch_symbolic_bin(const Csr &A, const Csr &B, const SymLaunch &l, int gb_log2, int32_t *nnz_out,
                                int n_wg, unsigned long long *queue, hipStream_t s);
 
+// order.hip
+size_t sort_rows_scratch_bytes(int64_t count);
+hipError_t launch_sort_rows_by_products(const int64_t *prod, int32_t *rows, int64_t count, void *scratch, hipStream_t s);
+
 // numeric.hip
 struct NumLaunch {
     const int32_t *rows;
