@@ -56,8 +56,9 @@ __device__ __forceinline__ int lds_find(const int32_t *keys, int32_t key)
 // lane that has placed a product goes on to its next one while other lanes are
 // still probing, so the wave-wide loop runs for the largest per-lane SUM of
 // probes instead of the sum of per-product maxima.  One compare-and-swap per
-// lane and round; the value is added as soon as the slot is known.  Valid
-// products come first in a batch (cj < 0 ends it).  False when the table is full.
+// lane and round; the value is added as soon as the slot is known
+// (add(slot, value, whether the key is new to the table)).  Valid products come
+// first in a batch (cj < 0 ends it).  False when the table is full.
 template <int BITS, int U, typename V, typename AddFn>
 __device__ __forceinline__ bool lds_insert_batch(int32_t *keys, const int32_t (&cj)[U], const V (&cv)[U], AddFn add)
 {
@@ -72,7 +73,7 @@ __device__ __forceinline__ bool lds_insert_batch(int32_t *keys, const int32_t (&
     while (key >= 0) {
         const int32_t old = atomicCAS(&keys[h], EMPTY_KEY, key);
         if (old == EMPTY_KEY || old == key) {
-            add((int)h, val);
+            add((int)h, val, old == EMPTY_KEY);
             ++idx;
             key = -1;
 #pragma unroll
@@ -131,7 +132,7 @@ k_numeric_group(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     const int64_t e0 = live ? a_rp[row] : 0;
     const int64_t e1 = live ? a_rp[row + 1] : 0;
     auto f = [&](const auto &cj, const auto &cv) {
-        if (!lds_insert_batch<BITS>(keys, cj, cv, [&](int slot, V v) { lds_add(&vals[slot], v); })) ovf = true;
+        if (!lds_insert_batch<BITS>(keys, cj, cv, [&](int slot, V v, bool) { lds_add(&vals[slot], v); })) ovf = true;
     };
     // the four rows of a wave advance together: same number of 16-entry chunks for all of them
     const int chunks = group_reduce_max((int)((e1 - e0 + G - 1) / G), WAVE);
@@ -225,7 +226,7 @@ k_numeric_wave(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_c
     wave_traverse<true>(a_col, a_val, a_rp[row], a_rp[row + 1],
                         [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
                         b_col, b_val, s_fc[rl], [&](const auto &cj, const auto &cv) {
-                            if (!lds_insert_batch<BITS>(keys, cj, cv, [&](int slot, V v) { lds_add(&vals[slot], v); })) ovf = true;
+                            if (!lds_insert_batch<BITS>(keys, cj, cv, [&](int slot, V v, bool) { lds_add(&vals[slot], v); })) ovf = true;
                         });
     wave_sync();
     int c = 0;
@@ -445,7 +446,7 @@ k_numeric_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col
     wg_traverse<THREADS, true>(a_col, a_val, a_rp[row], a_rp[row + 1],
                                [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
                                b_col, b_val, s_fc, [&](const auto &cj, const auto &cv) {
-                                   if (!lds_insert_batch<BITS>(s_keys, cj, cv, [&](int slot, V v) { lds_add(&s_vals[slot], v); }))
+                                   if (!lds_insert_batch<BITS>(s_keys, cj, cv, [&](int slot, V v, bool) { lds_add(&s_vals[slot], v); }))
                                        s_ovf = 1;
                                });
     // wg_traverse ends with a barrier
@@ -567,7 +568,7 @@ k_numeric_hybrid(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
         wg_traverse<HY_THREADS, true>(a_col, a_val, a_rp[row], a_rp[row + 1],
                                       [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
                                       b_col, b_val, s_fc, [&](const auto &cj, const auto &cv) {
-                                          if (!lds_insert_batch<HY_BITS>(s_keys, cj, cv, [&](int slot, V v) { l2_add(&slab[slot], v); }))
+                                          if (!lds_insert_batch<HY_BITS>(s_keys, cj, cv, [&](int slot, V v, bool) { l2_add(&slab[slot], v); }))
                                               s_ovf = 1;
                                       });
         __threadfence();   // the slab additions are in L2 before anyone exchanges them out
@@ -651,8 +652,10 @@ k_numeric_hybrid(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
 //     product; the bitmap's prefix popcount places each present column at its
 //     sorted position;
 //   * consecutive windows whose product counts add up to at most HCAP share one
-//     pass: an 8192-slot LDS hash table takes all their products, and the table
-//     is written out in column order through column buckets (bucket_emit).
+//     pass (of at most 16 windows): an 8192-slot LDS hash table takes all their
+//     products, a key that enters the table also sets its bit in a bitmap over
+//     the columns of the pass, and the rank of a key in the output is the
+//     number of set bits below its own.
 // Everything is accumulated in LDS and no table can overflow by construction.
 // What bounds this path is the latency of its chain of dependent accesses
 // (entry -> window boundary -> products -> LDS), paid once per pass, which is
@@ -691,8 +694,15 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     __shared__ long long s_row;
     V *s_vals = reinterpret_cast<V *>(s_u);                                        // dense: WIN values
     int32_t *s_keys = reinterpret_cast<int32_t *>(s_u);                            // hash: 8192 keys
-    V *s_hvals = reinterpret_cast<V *>(s_u + 32768);                               // hash: 8192 values
-    uint32_t *s_hist = reinterpret_cast<uint32_t *>(s_u + 98304);                  // hash: bucket counts of the write-out
+    V *s_hvals = reinterpret_cast<V *>(s_u + HV_HSLOTS * 4);                       // hash: 8192 values
+    // hash: presence bitmap over the columns of the pass, one bit per column, set when a key enters the table
+    uint32_t *s_hbm = reinterpret_cast<uint32_t *>(s_u + HV_HSLOTS * (4 + sizeof(V)));
+    constexpr int HBM_WORDS = (131072 - HV_HSLOTS * (4 + (int)sizeof(V))) / 4;
+    constexpr int HBM_WPT = HBM_WORDS / HV_THREADS;        // bitmap words per thread
+    constexpr int MAX_RUN = HBM_WORDS * 32 / WIN;          // windows one hash pass may span
+    static_assert(HBM_WORDS % HV_THREADS == 0 && MAX_RUN >= 1, "bitmap of a hash pass");
+    uint16_t *s_hpre = reinterpret_cast<uint16_t *>(s_u);  // hash write-out: entries before each bitmap word (over the keys)
+    static_assert(HBM_WORDS * 2 <= HV_HSLOTS * 4, "the prefix array fits where the keys were");
     const int tid = threadIdx.x;
     const size_t stride = (size_t)n_win + 1;
 
@@ -748,7 +758,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
             pdense = sum > (uint32_t)HV_HCAP;
             p1 = x + 1;
             if (!pdense)
-                while (p1 < n_win && sum + s_prodw[p1] <= (uint32_t)HV_HCAP) { sum += s_prodw[p1]; ++p1; }
+                while (p1 < n_win && p1 - x < MAX_RUN && sum + s_prodw[p1] <= (uint32_t)HV_HCAP) { sum += s_prodw[p1]; ++p1; }
         };
         int w, w1;
         bool dense;
@@ -788,7 +798,13 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                         }
                     }
                 } else {
-                    if (!lds_insert_batch<HV_HBITS>(s_keys, cj, cv, [&](int slot, V v) { lds_add(&s_hvals[slot], v); }))
+                    if (!lds_insert_batch<HV_HBITS>(s_keys, cj, cv, [&](int slot, V v, bool fresh) {
+                            lds_add(&s_hvals[slot], v);
+                            if (fresh) {
+                                const uint32_t d = (uint32_t)(s_keys[slot] - col0);
+                                atomicOr(&s_hbm[d >> 5], 1u << (d & 31u));
+                            }
+                        }))
                         s_ovf = 1;
                 }
             };
@@ -836,16 +852,48 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                 done += wtotal;
                 __syncthreads();
             } else {
-                // ---- hash table -> output in column order, through column buckets over the pass's windows
-                int32_t key[HV_HSLOTS / HV_THREADS];
+                // ---- hash table -> output in column order: the rank of a key is the number of set bits
+                // below its own in the bitmap of the pass
+                constexpr int PER = HV_HSLOTS / HV_THREADS;
+                int32_t key[PER];
 #pragma unroll
-                for (int q = 0; q < HV_HSLOTS / HV_THREADS; ++q) key[q] = s_keys[q * HV_THREADS + tid];
-                for (int j = tid; j < HV_HSLOTS / 2 + 1; j += HV_THREADS) s_hist[j] = 0u;
-                __syncthreads();   // the key array is rewritten below: everybody holds its keys now
-                int shift = 0;
-                while ((((uint32_t)(w1 - w) * (uint32_t)WIN - 1u) >> shift) >= (uint32_t)HV_HSLOTS) ++shift;
-                done += bucket_emit<HV_THREADS, HV_HSLOTS / HV_THREADS, false>(key, s_hvals, col0, shift, s_hist, s_keys, s_wave,
-                                                                             nullptr, 0, o, cap, done, out_col, out_val);
+                for (int q = 0; q < PER; ++q) key[q] = s_keys[q * HV_THREADS + tid];
+                int cnt[HBM_WPT];
+                int mine = 0;
+#pragma unroll
+                for (int q = 0; q < HBM_WPT; ++q) { cnt[q] = __popc(s_hbm[tid * HBM_WPT + q]); mine += cnt[q]; }
+                int htotal;
+                int run = block_exclusive_scan_i32<HV_THREADS>(mine, s_wave, htotal);   // barriers: every thread holds its keys now
+#pragma unroll
+                for (int q = 0; q < HBM_WPT; ++q) { s_hpre[tid * HBM_WPT + q] = (uint16_t)run; run += cnt[q]; }
+                __syncthreads();
+                int rank[PER];
+                V val[PER];
+#pragma unroll
+                for (int q = 0; q < PER; ++q) {
+                    rank[q] = 0;
+                    val[q] = V();
+                    if (key[q] != EMPTY_KEY) {
+                        const uint32_t d = (uint32_t)(key[q] - col0);
+                        rank[q] = (int)s_hpre[d >> 5] + __popc(s_hbm[d >> 5] & ((1u << (d & 31u)) - 1u));
+                        val[q] = s_hvals[q * HV_THREADS + tid];
+                    }
+                }
+                __syncthreads();
+                // keys and values into place inside LDS, then out with coalesced stores
+#pragma unroll
+                for (int q = 0; q < PER; ++q)
+                    if (key[q] != EMPTY_KEY) { s_keys[rank[q]] = key[q]; s_hvals[rank[q]] = val[q]; }
+#pragma unroll
+                for (int q = 0; q < HBM_WPT; ++q) s_hbm[tid * HBM_WPT + q] = 0u;
+                __syncthreads();
+                const long long room = cap - done;
+                const int n_out = (long long)htotal < room ? htotal : (room > 0 ? (int)room : 0);
+                for (int i = tid; i < n_out; i += HV_THREADS) {
+                    out_col[o + done + i] = s_keys[i];
+                    out_val[o + done + i] = s_hvals[i];
+                }
+                done += htotal;
                 __syncthreads();
             }
             c_lo = c_hi; c_hi = n_hi;
