@@ -209,7 +209,8 @@ __device__ __forceinline__ void wg_flat_chunk(WgChunk<V, THREADS> &c, int nent, 
             pos = 0;
             for (int step = top; step > 0; step >>= 1) {
                 const int t = pos + step;
-                if (t < nent && c.excl[t] <= q) pos = t;   // last entry starting at or before q (skips empty ones)
+                const uint32_t ex = c.excl[t < nent ? t : nent - 1];   // unconditional read: no branch around it
+                pos = (t < nent && ex <= q) ? t : pos;   // last entry starting at or before q (skips empty ones)
             }
         }
         c.first[tid] = (uint16_t)pos;
@@ -232,11 +233,18 @@ __device__ __forceinline__ void wg_flat_chunk(WgChunk<V, THREADS> &c, int nent, 
 #pragma unroll
             for (int u = 0; u < FLAT_U; ++u) fp[u] = lo;
             for (int step = width > 0 ? 1 << (31 - __clz(width)) : 0; step > 0; step >>= 1) {
+                // the reads of one step are unconditional (index clamped) so that they are issued together
+                int t[FLAT_U];
+                uint32_t ex[FLAT_U];
+#pragma unroll
+                for (int u = 0; u < FLAT_U; ++u) {
+                    t[u] = fp[u] + step;
+                    ex[u] = c.excl[t[u] <= hi ? t[u] : hi];
+                }
 #pragma unroll
                 for (int u = 0; u < FLAT_U; ++u) {
                     const uint32_t q = q0 + u * WAVE + lane;
-                    const int t = fp[u] + step;
-                    if (t <= hi && c.excl[t] <= q) fp[u] = t;
+                    fp[u] = (t[u] <= hi && ex[u] <= q) ? t[u] : fp[u];
                 }
             }
 #pragma unroll
