@@ -645,27 +645,32 @@ k_numeric_hybrid(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
 // with column >= w*WIN, so any run of windows can be visited on its own.  One
 // workgroup first counts the row's products per window (an upper bound of the
 // entries of that window), then walks the windows in order, carrying the
-// running output offset:
+// running output offset.  Both kinds of pass accumulate in LDS only, need no
+// hash table, and leave their entries in column order:
 //   * a window with more than HCAP products is accumulated densely (Section 2.2
 //     dense accumulator, iterated over the row's column range as in Section
 //     3.2): WIN values + a presence bitmap in LDS, one LDS add + one LDS or per
 //     product; the bitmap's prefix popcount places each present column at its
 //     sorted position;
-//   * consecutive windows whose product counts add up to at most HCAP share one
-//     pass (of at most 16 windows): an 8192-slot LDS hash table takes all their
-//     products, a key that enters the table also sets its bit in a bitmap over
-//     the columns of the pass, and the rank of a key in the output is the
-//     number of set bits below its own.
-// Everything is accumulated in LDS and no table can overflow by construction.
+//   * consecutive windows with at most HCAP products together (a sparse stretch
+//     of up to SPAN columns) share one pass in the manner of an
+//     expand-sort-compress accumulator whose sort is a bitmap rank: every
+//     product is written to LDS at its own number (no atomics) and marks its
+//     column in a bitmap over the stretch; the prefix popcount of the bitmap is
+//     the position of each column in the output, so a second sweep over the
+//     staged products adds each value at its column's rank.  No probing, no
+//     compare-and-swap, no divergence.
 // What bounds this path is the latency of its chain of dependent accesses
 // (entry -> window boundary -> products -> LDS), paid once per pass, which is
 // why sparse stretches are merged into few passes and why every pass spreads
 // its products over the whole workgroup.
 constexpr int HV_THREADS = 1024;
-constexpr int HV_HBITS = 13;
-constexpr int HV_HSLOTS = 1 << HV_HBITS;
-constexpr int HV_HCAP = 6144;
-constexpr int HV_MAXWIN = 512;               // windows per row the kernel can plan for
+constexpr int HV_PPT = 6;                          // products of a sparse pass per thread
+constexpr int HV_HCAP = HV_PPT * HV_THREADS;       // products one sparse pass takes: 6144
+constexpr int HV_SPAN = 262144;                    // columns one sparse pass may span
+constexpr int HV_BMWORDS = HV_SPAN / 32;           // 8192 words of presence bitmap
+constexpr int HV_BMWPT = HV_BMWORDS / HV_THREADS;  // bitmap words per thread
+constexpr int HV_MAXWIN = 512;                     // windows per row the kernel can plan for
 
 template <typename V>
 struct DenseCfg {
@@ -693,16 +698,15 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     __shared__ int s_ovf;
     __shared__ long long s_row;
     V *s_vals = reinterpret_cast<V *>(s_u);                                        // dense: WIN values
-    int32_t *s_keys = reinterpret_cast<int32_t *>(s_u);                            // hash: 8192 keys
-    V *s_hvals = reinterpret_cast<V *>(s_u + HV_HSLOTS * 4);                       // hash: 8192 values
-    // hash: presence bitmap over the columns of the pass, one bit per column, set when a key enters the table
-    uint32_t *s_hbm = reinterpret_cast<uint32_t *>(s_u + HV_HSLOTS * (4 + sizeof(V)));
-    constexpr int HBM_WORDS = (131072 - HV_HSLOTS * (4 + (int)sizeof(V))) / 4;
-    constexpr int HBM_WPT = HBM_WORDS / HV_THREADS;        // bitmap words per thread
-    constexpr int MAX_RUN = HBM_WORDS * 32 / WIN;          // windows one hash pass may span
-    static_assert(HBM_WORDS % HV_THREADS == 0 && MAX_RUN >= 1, "bitmap of a hash pass");
-    uint16_t *s_hpre = reinterpret_cast<uint16_t *>(s_u);  // hash write-out: entries before each bitmap word (over the keys)
-    static_assert(HBM_WORDS * 2 <= HV_HSLOTS * 4, "the prefix array fits where the keys were");
+    // sparse pass: staged products (column, value) by product number; once every thread holds its
+    // products in registers the same memory takes the output (columns, accumulated values) by rank
+    int32_t *s_scol = reinterpret_cast<int32_t *>(s_u);
+    V *s_sval = reinterpret_cast<V *>(s_u + HV_HCAP * 4);
+    uint16_t *s_hpre = reinterpret_cast<uint16_t *>(s_u + HV_HCAP * 12);            // entries before each bitmap word
+    uint32_t *s_hbm = reinterpret_cast<uint32_t *>(s_u + 131072 - HV_BMWORDS * 4);  // presence bitmap of the stretch
+    static_assert(HV_HCAP * 12 + HV_BMWORDS * 2 + HV_BMWORDS * 4 <= 131072, "staging, prefix and bitmap fit the region");
+    constexpr int MAX_RUN = HV_SPAN / WIN;   // windows one sparse pass may span
+    static_assert(MAX_RUN >= 1, "a sparse pass spans at least one window");
     const int tid = threadIdx.x;
     const size_t stride = (size_t)n_win + 1;
 
@@ -780,15 +784,17 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                     dense_clean = true;
                 }
             } else {
-                for (int s = tid; s < HV_HSLOTS; s += HV_THREADS) { s_keys[s] = EMPTY_KEY; s_hvals[s] = (V)0; }
+                // (the bitmap of a sparse pass is all zero here: the region is either an all-zero dense
+                // window or was left by a sparse pass, which clears its bitmap)
                 dense_clean = false;
             }
             __syncthreads();
             // products of windows [w, w1)
             const int32_t col0 = w * WIN;
-            auto f = [&](const auto &cj, const auto &cv) {
+            uint32_t staged = 0;   // products of this pass staged so far (sparse pass, uniform)
+            auto f = [&](const auto &cj, const auto &cv, uint32_t q0) {
+                constexpr int U = sizeof(cj) / sizeof(cj[0]);
                 if (dense) {
-                    constexpr int U = sizeof(cj) / sizeof(cj[0]);
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
                         const unsigned d = (unsigned)(cj[u] - col0);
@@ -798,14 +804,16 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                         }
                     }
                 } else {
-                    if (!lds_insert_batch<HV_HBITS>(s_keys, cj, cv, [&](int slot, V v, bool fresh) {
-                            lds_add(&s_hvals[slot], v);
-                            if (fresh) {
-                                const uint32_t d = (uint32_t)(s_keys[slot] - col0);
-                                atomicOr(&s_hbm[d >> 5], 1u << (d & 31u));
-                            }
-                        }))
-                        s_ovf = 1;
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const uint32_t at = staged + q0 + (uint32_t)u * WAVE + (uint32_t)(tid & (WAVE - 1));
+                        const uint32_t d = (uint32_t)(cj[u] - col0);
+                        if (cj[u] >= 0 && at < (uint32_t)HV_HCAP && d < (uint32_t)HV_SPAN) {   // both hold by construction
+                            s_scol[at] = cj[u];
+                            s_sval[at] = cv[u];
+                            atomicOr(&s_hbm[d >> 5], 1u << (d & 31u));
+                        }
+                    }
                 }
             };
             for (int64_t base = 0; base < ne; base += HV_THREADS) {
@@ -823,8 +831,8 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                     }
                 }
                 const int64_t left = ne - base;
-                wg_flat_chunk<HV_THREADS, true>(s_fc, left < HV_THREADS ? (int)left : HV_THREADS, (int64_t)c0, c1 - c0, a,
-                                                b_col, b_val, f);
+                staged += wg_flat_chunk<HV_THREADS, true>(s_fc, left < HV_THREADS ? (int)left : HV_THREADS, (int64_t)c0,
+                                                          c1 - c0, a, b_col, b_val, f);
             }
             if (dense) {
                 // ---- dense window -> output, in column order
@@ -852,46 +860,51 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                 done += wtotal;
                 __syncthreads();
             } else {
-                // ---- hash table -> output in column order: the rank of a key is the number of set bits
-                // below its own in the bitmap of the pass
-                constexpr int PER = HV_HSLOTS / HV_THREADS;
-                int32_t key[PER];
-#pragma unroll
-                for (int q = 0; q < PER; ++q) key[q] = s_keys[q * HV_THREADS + tid];
-                int cnt[HBM_WPT];
+                // ---- sparse pass: rank of every column = set bits below it in the bitmap of the stretch
+                int cnt[HV_BMWPT];
                 int mine = 0;
 #pragma unroll
-                for (int q = 0; q < HBM_WPT; ++q) { cnt[q] = __popc(s_hbm[tid * HBM_WPT + q]); mine += cnt[q]; }
+                for (int q = 0; q < HV_BMWPT; ++q) { cnt[q] = __popc(s_hbm[tid * HV_BMWPT + q]); mine += cnt[q]; }
                 int htotal;
-                int run = block_exclusive_scan_i32<HV_THREADS>(mine, s_wave, htotal);   // barriers: every thread holds its keys now
+                int run = block_exclusive_scan_i32<HV_THREADS>(mine, s_wave, htotal);
 #pragma unroll
-                for (int q = 0; q < HBM_WPT; ++q) { s_hpre[tid * HBM_WPT + q] = (uint16_t)run; run += cnt[q]; }
+                for (int q = 0; q < HV_BMWPT; ++q) { s_hpre[tid * HV_BMWPT + q] = (uint16_t)run; run += cnt[q]; }
                 __syncthreads();
-                int rank[PER];
-                V val[PER];
+                // every thread takes its share of the staged products into registers, with their ranks
+                if (staged > (uint32_t)HV_HCAP) staged = HV_HCAP;   // cannot happen: passes are planned from the counts
+                int32_t pc[HV_PPT];
+                V pv[HV_PPT];
+                int pr[HV_PPT];
 #pragma unroll
-                for (int q = 0; q < PER; ++q) {
-                    rank[q] = 0;
-                    val[q] = V();
-                    if (key[q] != EMPTY_KEY) {
-                        const uint32_t d = (uint32_t)(key[q] - col0);
-                        rank[q] = (int)s_hpre[d >> 5] + __popc(s_hbm[d >> 5] & ((1u << (d & 31u)) - 1u));
-                        val[q] = s_hvals[q * HV_THREADS + tid];
+                for (int i = 0; i < HV_PPT; ++i) {
+                    const uint32_t at = (uint32_t)i * HV_THREADS + tid;
+                    pc[i] = -1; pv[i] = V(); pr[i] = 0;
+                    if (at < staged) {
+                        pc[i] = s_scol[at];
+                        pv[i] = s_sval[at];
+                        const uint32_t d = (uint32_t)(pc[i] - col0);
+                        pr[i] = (int)s_hpre[d >> 5] + __popc(s_hbm[d >> 5] & ((1u << (d & 31u)) - 1u));
                     }
                 }
                 __syncthreads();
-                // keys and values into place inside LDS, then out with coalesced stores
+                // the staging memory becomes the output of the pass: columns and zeroed values by rank
+                for (int i = tid; i < htotal; i += HV_THREADS) s_sval[i] = (V)0;
 #pragma unroll
-                for (int q = 0; q < PER; ++q)
-                    if (key[q] != EMPTY_KEY) { s_keys[rank[q]] = key[q]; s_hvals[rank[q]] = val[q]; }
+                for (int q = 0; q < HV_BMWPT; ++q) s_hbm[tid * HV_BMWPT + q] = 0u;
+                __syncthreads();
 #pragma unroll
-                for (int q = 0; q < HBM_WPT; ++q) s_hbm[tid * HBM_WPT + q] = 0u;
+                for (int i = 0; i < HV_PPT; ++i) {
+                    if (pc[i] >= 0) {
+                        s_scol[pr[i]] = pc[i];          // products of one column all write the same id
+                        lds_add(&s_sval[pr[i]], pv[i]);
+                    }
+                }
                 __syncthreads();
                 const long long room = cap - done;
                 const int n_out = (long long)htotal < room ? htotal : (room > 0 ? (int)room : 0);
                 for (int i = tid; i < n_out; i += HV_THREADS) {
-                    out_col[o + done + i] = s_keys[i];
-                    out_val[o + done + i] = s_hvals[i];
+                    out_col[o + done + i] = s_scol[i];
+                    out_val[o + done + i] = s_sval[i];
                 }
                 done += htotal;
                 __syncthreads();

@@ -22,6 +22,8 @@
 // dependent LDS round trips (hash probes) overlap across the batch.
 #pragma once
 
+#include <type_traits>
+
 #include "ocean_internal.hpp"
 
 namespace ocean {
@@ -160,8 +162,9 @@ struct WgChunk {
 // product of every block of products.  The searches of a batch have the same, wave-uniform
 // number of steps and run interleaved.  The products of one chunk must number less than 2^31.
 // Every thread calls it; the chunk arrays must be free on entry (the call ends with a barrier).
+// Returns the number of products of the chunk.
 template <int THREADS, bool HAS_VAL, typename V, typename F>
-__device__ __forceinline__ void wg_flat_chunk(WgChunk<V, THREADS> &c, int nent, int64_t p0, uint32_t len, V a,
+__device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS> &c, int nent, int64_t p0, uint32_t len, V a,
                                               const int32_t *__restrict__ b_col, const V *__restrict__ b_val, F &f)
 {
     constexpr int NW = THREADS / WAVE;
@@ -195,7 +198,7 @@ __device__ __forceinline__ void wg_flat_chunk(WgChunk<V, THREADS> &c, int nent, 
     const uint32_t total = c.total;
     if (total == 0) {   // uniform
         __syncthreads();
-        return;
+        return 0;
     }
     // blocks of 2^bshift products, at least 256 products each and fewer than THREADS of them
     int bshift = 8;
@@ -267,12 +270,16 @@ __device__ __forceinline__ void wg_flat_chunk(WgChunk<V, THREADS> &c, int nent, 
                 if constexpr (HAS_VAL) cv[u] = c.a[cp[u]] * cb[u];
                 else cv[u] = V();
             }
-            f(cj, cv);
+            // an accumulator may ask for the number of the batch's first product inside the chunk: the
+            // product of lane l, position u is number q0 + u*64 + l
+            if constexpr (std::is_invocable_v<F &, int32_t(&)[FLAT_U], V(&)[FLAT_U], uint32_t>) f(cj, cv, q0);
+            else f(cj, cv);
 #pragma unroll
             for (int u = 0; u < FLAT_U; ++u) { cj[u] = nj[u]; cb[u] = nb[u]; cp[u] = np[u]; }
         }
     }
     __syncthreads();
+    return total;
 }
 
 // Workgroup version of the row traversal: chunks of THREADS entries of A, each flattened over the
