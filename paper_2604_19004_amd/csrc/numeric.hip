@@ -788,7 +788,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                 // window or was left by a sparse pass, which clears its bitmap)
                 dense_clean = false;
             }
-            __syncthreads();
+            // (no barrier: the traversal below has barriers of its own before the first product arrives)
             // products of windows [w, w1)
             const int32_t col0 = w * WIN;
             uint32_t staged = 0;   // products of this pass staged so far (sparse pass, uniform)

@@ -311,8 +311,17 @@ int run_symbolic(Ctx &c, Work &w, const Csr &A, const Csr &B, int gb_log2, int32
         start[b + 1] = start[b] + (int64_t)c.h->bin_count[b];
         if (st) st->symbolic_rows_per_bin[b] = (int64_t)c.h->bin_count[b];
     }
+    // With at most 2^20 columns the bitmap kernel covers a row in one window, and one pass over such a
+    // window costs less than building a key table of 16384 or 32768 slots: those two bins go with it
+    // (the row lists of consecutive bins are adjacent).
+    const bool wide_bitmap = B.cols <= (1 << 20);
     for (int b = SB_COUNT - 1; b >= 0; --b) {
         SymLaunch l{w.bin_rows + start[b], start[b + 1] - start[b], b};
+        if (wide_bitmap && (b == SB_S16K || b == SB_S32K)) continue;
+        if (wide_bitmap && b == SB_BITMAP) {
+            l.rows = w.bin_rows + start[SB_S16K];
+            l.count = start[SB_COUNT] - start[SB_S16K];
+        }
         if (l.count == 0) continue;
         const int n_wg = (int)(l.count < c.n_cu ? l.count : c.n_cu);
         HIP_TRY(launch_symbolic_bin(A, B, l, gb_log2, nnz_out, n_wg, &w.sc->queue[0], c.s));

@@ -161,8 +161,8 @@ k_symbolic_bitmap(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ 
     for (;;) {
         if (tid == 0) { s_row = (long long)atomicAdd(queue, 1ull); s_count = 0; }
         __syncthreads();
-        const int64_t r = s_row;
-        if (r >= count) break;   // uniform exit
+        if (s_row >= count) break;   // uniform exit
+        const int64_t r = count - 1 - s_row;   // from the end of the list, where the rows with the largest bounds are
         const int64_t row = rows[r];
         const int64_t e0 = a_rp[row], e1 = a_rp[row + 1];
         for (int64_t w0 = 0; w0 < n_cols; w0 += BM_WIN) {
