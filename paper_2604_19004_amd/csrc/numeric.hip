@@ -740,12 +740,28 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
             int64_t e = tid / n_win;
             int w = tid % n_win;
             while (e < ne) {
-                const uint32_t *t = bw + (size_t)a_col[e0 + e] * stride;
-                const uint32_t d = t[w + 1] - t[w];
-                if (d) atomicAdd(&s_prodw[w], d);
-                e += de;
-                w += dw;
-                if (w >= n_win) { w -= n_win; ++e; }
+                // four pairs per turn, so that their dependent loads (entry -> boundaries) overlap
+                int64_t pe[4];
+                int pw[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    pe[i] = e; pw[i] = w;
+                    e += de;
+                    w += dw;
+                    if (w >= n_win) { w -= n_win; ++e; }
+                }
+                int32_t k[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) k[i] = pe[i] < ne ? a_col[e0 + pe[i]] : 0;
+                uint32_t d[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t *t = bw + (size_t)k[i] * stride;
+                    d[i] = pe[i] < ne ? t[pw[i] + 1] - t[pw[i]] : 0u;
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (d[i]) atomicAdd(&s_prodw[pw[i]], d[i]);
             }
         }
         __syncthreads();
