@@ -92,7 +92,7 @@ def cpu_baseline(A, B, name):
     from oracle import spgemm as O
     prod = O.row_products(A, B)
     total = int(prod.sum())
-    target = 8.0e9                                     # products: ~10-30 s of oracle work on 16 host threads
+    target = 1.6e10                                    # products: ~10-30 s of oracle work on 16 host threads
     if total <= target:
         blocks = [(0, A.rows)]
     else:
