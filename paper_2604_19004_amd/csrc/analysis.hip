@@ -59,52 +59,76 @@ hipError_t launch_validate(const Csr &A, const Csr &B, int32_t *flags, hipStream
 // One group of 2^g_log2 lanes per row, a fixed number of workgroups striding
 // over the rows: the totals cost one atomic per workgroup, not one per row tile
 // (same-address atomics from all XCDs serialise in the memory fabric).  A row
-// far longer than the average (power-law inputs have rows with tens of
-// thousands of entries) would keep its few lanes busy for milliseconds: such
-// rows are set aside in LDS and walked by the whole workgroup afterwards.
+// far longer than the average would keep its few lanes busy for a long time,
+// and on power-law inputs such rows cluster (their indices share bit patterns,
+// so whole workgroups would get nothing else): they are put on a list and a
+// second kernel gives each of them a workgroup of its own.
+__device__ __forceinline__ void block_totals(long long tsum, long long tmax, long long *s_sum, long long *s_max,
+                                             unsigned long long *totals)
+{
+    const long long wsum = group_reduce_sum(tsum, WAVE);
+    const long long wmax = group_reduce_max(tmax, WAVE);
+    const int w = threadIdx.x / WAVE;
+    if (lane_id() == 0) { s_sum[w] = wsum; s_max[w] = wmax; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        long long bs = 0, bm = 0;
+        for (int i = 0; i < TPB / WAVE; ++i) { bs += s_sum[i]; bm = s_max[i] > bm ? s_max[i] : bm; }
+        if (bs) atomicAdd(&totals[0], (unsigned long long)bs);
+        if (bm) atomicMax(&totals[1], (unsigned long long)bm);
+    }
+}
+
 __global__ void __launch_bounds__(TPB)
 k_row_products(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col, int64_t m,
                const int64_t *__restrict__ b_rp, int64_t b_rows, int g_log2, int64_t *__restrict__ prod,
-               int32_t *__restrict__ maxb, unsigned long long *totals, int32_t *flags)
+               int32_t *__restrict__ maxb, unsigned long long *totals, int32_t *flags,
+               int32_t *__restrict__ long_rows, unsigned long long *long_count)
 {
-    constexpr int LIST = 128;
     __shared__ long long s_sum[TPB / WAVE];
     __shared__ long long s_max[TPB / WAVE];
-    __shared__ long long s_long[LIST];
-    __shared__ int s_nlong;
     const int G = 1 << g_log2;
     const int R = TPB >> g_log2;
     const int rl = threadIdx.x >> g_log2;
     const int sub = threadIdx.x & (G - 1);
-    const int64_t long_len = (int64_t)G * 32;
+    const int64_t long_len = (int64_t)G * 16;
     long long tsum = 0, tmax = 0;
     bool bad = false;
-    if (threadIdx.x == 0) s_nlong = 0;
-    __syncthreads();
-    auto entry = [&](int64_t e, long long &p, long long &mx) {
-        const int32_t k = a_col[e];
-        if ((uint32_t)k >= (uint64_t)b_rows) { bad = true; return; }
-        const long long len = b_rp[k + 1] - b_rp[k];
-        p += len;
-        mx = len > mx ? len : mx;
-    };
     for (int64_t base = (int64_t)blockIdx.x * R; base < m; base += (int64_t)gridDim.x * R) {
         const int64_t row = base + rl;
         long long p = 0, mx = 0;
         bool mine = row < m;
         if (mine) {
             const int64_t e0 = a_rp[row], e1 = a_rp[row + 1];
-            if (e1 - e0 > long_len) {   // uniform for the group
-                int slot = LIST;
-                if (sub == 0) slot = atomicAdd(&s_nlong, 1);
-                slot = __shfl(slot, (int)(threadIdx.x & (WAVE - 1)) & ~(G - 1), WAVE);
-                if (slot < LIST) {
-                    if (sub == 0) s_long[slot] = row;
-                    mine = false;   // the workgroup takes it below
+            if (long_rows != nullptr && e1 - e0 > long_len) {   // uniform for the group
+                if (sub == 0) long_rows[atomicAdd(long_count, 1ull)] = (int32_t)row;
+                mine = false;
+            }
+            if (mine) {
+                // four independent chains (entry -> row offsets of B) in flight per lane; reads are
+                // unconditional (index clamped) so that they are issued together
+                for (int64_t e = e0 + sub; e < e1; e += 4 * G) {
+                    int32_t k[4];
+                    bool ok[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int64_t idx = e + (int64_t)i * G;
+                        ok[i] = idx < e1;
+                        k[i] = a_col[ok[i] ? idx : e];
+                        if ((uint32_t)k[i] >= (uint64_t)b_rows) { bad = true; k[i] = 0; ok[i] = false; }
+                    }
+                    long long len[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) len[i] = b_rows > 0 ? b_rp[k[i] + 1] - b_rp[k[i]] : 0;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        if (ok[i]) {
+                            p += len[i];
+                            mx = len[i] > mx ? len[i] : mx;
+                        }
+                    }
                 }
             }
-            if (mine)
-                for (int64_t e = e0 + sub; e < e1; e += G) entry(e, p, mx);
         }
         p = group_reduce_sum(p, G);
         mx = group_reduce_max(mx, G);
@@ -115,46 +139,71 @@ k_row_products(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_c
             tmax = p > tmax ? p : tmax;
         }
     }
-    __syncthreads();
-    const int nlong = s_nlong < LIST ? s_nlong : LIST;
-    const int w = threadIdx.x / WAVE;
-    for (int i = 0; i < nlong; ++i) {
-        const int64_t row = s_long[i];
-        const int64_t e0 = a_rp[row], e1 = a_rp[row + 1];
-        long long p0 = 0, p1 = 0, m0 = 0, m1 = 0;   // two chains in flight per thread
-        for (int64_t e = e0 + threadIdx.x; e < e1; e += 2 * TPB) {
-            entry(e, p0, m0);
-            if (e + TPB < e1) entry(e + TPB, p1, m1);
-        }
-        const long long wsum = group_reduce_sum(p0 + p1, WAVE);
-        const long long wmax = group_reduce_max(m0 > m1 ? m0 : m1, WAVE);
-        if (lane_id() == 0) { s_sum[w] = wsum; s_max[w] = wmax; }
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            long long p = 0, mx = 0;
-            for (int j = 0; j < TPB / WAVE; ++j) { p += s_sum[j]; mx = s_max[j] > mx ? s_max[j] : mx; }
-            prod[row] = p;
-            maxb[row] = (int32_t)(mx > 0x7fffffffLL ? 0x7fffffffLL : mx);
-            tsum += p;
-            tmax = p > tmax ? p : tmax;
-        }
-        __syncthreads();
-    }
-    const long long wsum = group_reduce_sum(tsum, WAVE);
-    const long long wmax = group_reduce_max(tmax, WAVE);
-    if (lane_id() == 0) { s_sum[w] = wsum; s_max[w] = wmax; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        long long bs = 0, bm = 0;
-        for (int i = 0; i < TPB / WAVE; ++i) { bs += s_sum[i]; bm = s_max[i] > bm ? s_max[i] : bm; }
-        if (bs) atomicAdd(&totals[0], (unsigned long long)bs);
-        if (bm) atomicMax(&totals[1], (unsigned long long)bm);
-    }
+    block_totals(tsum, tmax, s_sum, s_max, totals);
     if (__ballot(bad) != 0 && lane_id() == 0) atomicOr(flags, 4);
 }
 
+// The listed long rows: one workgroup per row at a time.
+__global__ void __launch_bounds__(TPB)
+k_row_products_long(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col,
+                    const int64_t *__restrict__ b_rp, int64_t b_rows, int64_t *__restrict__ prod,
+                    int32_t *__restrict__ maxb, unsigned long long *totals, int32_t *flags,
+                    const int32_t *__restrict__ long_rows, const unsigned long long *long_count)
+{
+    __shared__ long long s_sum[TPB / WAVE];
+    __shared__ long long s_max[TPB / WAVE];
+    const int64_t n = (int64_t)*long_count;
+    const int w = threadIdx.x / WAVE;
+    long long tsum = 0, tmax = 0;
+    bool bad = false;
+    for (int64_t i = blockIdx.x; i < n; i += gridDim.x) {
+        const int64_t row = long_rows[i];
+        const int64_t e0 = a_rp[row], e1 = a_rp[row + 1];
+        long long p = 0, mx = 0;
+        for (int64_t e = e0 + threadIdx.x; e < e1; e += 4 * TPB) {
+            int32_t k[4];
+            bool ok[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int64_t idx = e + (int64_t)j * TPB;
+                ok[j] = idx < e1;
+                k[j] = a_col[ok[j] ? idx : e];
+                if ((uint32_t)k[j] >= (uint64_t)b_rows) { bad = true; k[j] = 0; ok[j] = false; }
+            }
+            long long len[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) len[j] = b_rows > 0 ? b_rp[k[j] + 1] - b_rp[k[j]] : 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (ok[j]) {
+                    p += len[j];
+                    mx = len[j] > mx ? len[j] : mx;
+                }
+            }
+        }
+        const long long wsum = group_reduce_sum(p, WAVE);
+        const long long wmax = group_reduce_max(mx, WAVE);
+        if (lane_id() == 0) { s_sum[w] = wsum; s_max[w] = wmax; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            long long rp = 0, rm = 0;
+            for (int j = 0; j < TPB / WAVE; ++j) { rp += s_sum[j]; rm = s_max[j] > rm ? s_max[j] : rm; }
+            prod[row] = rp;
+            maxb[row] = (int32_t)(rm > 0x7fffffffLL ? 0x7fffffffLL : rm);
+            tsum += rp;
+            tmax = rp > tmax ? rp : tmax;
+        }
+        __syncthreads();
+    }
+    block_totals(tsum, tmax, s_sum, s_max, totals);
+    if (__ballot(bad) != 0 && lane_id() == 0) atomicOr(flags, 4);
+}
+
+// long_rows: scratch for A.rows row ids, long_count: a zeroed device counter; both may be null
+// (then every row is handled by its lane group).
 hipError_t launch_row_products(const Csr &A, const int64_t *b_rp, int64_t b_rows, int64_t *prod, int32_t *maxb,
-                               unsigned long long *totals, int32_t *flags, hipStream_t s)
+                               unsigned long long *totals, int32_t *flags, int32_t *long_rows,
+                               unsigned long long *long_count, hipStream_t s)
 {
     if (A.rows == 0) return hipSuccess;
     const double avg = A.rows ? (double)A.nnz / (double)A.rows : 0.0;
@@ -162,8 +211,12 @@ hipError_t launch_row_products(const Csr &A, const int64_t *b_rp, int64_t b_rows
     const int R = TPB >> g_log2;
     int64_t blocks = (A.rows + R - 1) / R;
     if (blocks > 2048) blocks = 2048;
+    if (long_count == nullptr) long_rows = nullptr;
     hipLaunchKernelGGL(k_row_products, dim3((unsigned)blocks), dim3(TPB), 0, s, A.rp, A.col, A.rows, b_rp, b_rows,
-                       g_log2, prod, maxb, totals, flags);
+                       g_log2, prod, maxb, totals, flags, long_rows, long_count);
+    if (long_rows != nullptr)
+        hipLaunchKernelGGL(k_row_products_long, dim3(2048), dim3(TPB), 0, s, A.rp, A.col, b_rp, b_rows, prod, maxb,
+                           totals, flags, long_rows, long_count);
     return hipGetLastError();
 }
 

@@ -274,7 +274,9 @@ int zero_bins(Ctx &c, Work &w)
 int run_analysis(Ctx &c, Work &w, const Csr &A, const Csr &B, bool validate, ocean_stats *st)
 {
     if (validate) HIP_TRY(launch_validate(A, B, &w.sc->flags, c.s));
-    HIP_TRY(launch_row_products(A, B.rp, B.rows, w.prod, w.maxb, w.sc->totals, &w.sc->flags, c.s));
+    // (the row list of the bins and the last row counter are free at this point: scratch of the long-row list)
+    HIP_TRY(launch_row_products(A, B.rp, B.rows, w.prod, w.maxb, w.sc->totals, &w.sc->flags, w.bin_rows, &w.sc->queue[3],
+                                c.s));
     OC_TRY(fetch_scalars(c, w.sc));
     if (c.h->flags & 1) return fail(OCEAN_EINVAL, "A is not a valid CSR matrix (row offsets or column ids out of range)");
     if (c.h->flags & 2) return fail(OCEAN_EINVAL, "B is not a valid CSR matrix (row offsets or column ids out of range)");
@@ -793,7 +795,7 @@ int ocean_row_products(const ocean_csr *A, const ocean_csr *B, int64_t *prod, in
     int32_t *maxb = reinterpret_cast<int32_t *>(buf + up(sizeof(Scalars)));
     int rc = [&]() -> int {
         HIP_TRY(hipMemsetAsync(sc, 0, sizeof(Scalars), c.s));
-        HIP_TRY(launch_row_products(view(A), B->row_ptr, B->rows, prod, maxb, sc->totals, &sc->flags, c.s));
+        HIP_TRY(launch_row_products(view(A), B->row_ptr, B->rows, prod, maxb, sc->totals, &sc->flags, nullptr, nullptr, c.s));
         OC_TRY(fetch_scalars(c, sc));
         if (c.h->flags & 4) return fail(OCEAN_EINVAL, "a column id of A is outside [0, rows(B))");
         if (total) *total = (int64_t)c.h->totals[0];
