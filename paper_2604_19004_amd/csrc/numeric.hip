@@ -647,13 +647,14 @@ k_numeric_hybrid(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
 // entries of that window), then walks the windows in order, carrying the
 // running output offset.  Both kinds of pass accumulate in LDS only, need no
 // hash table, and leave their entries in column order:
-//   * a window with more than HCAP products is accumulated densely (Section 2.2
+//   * a window with more than 8192 products is accumulated densely (Section 2.2
 //     dense accumulator, iterated over the row's column range as in Section
 //     3.2): WIN values + a presence bitmap in LDS, one LDS add + one LDS or per
 //     product; the bitmap's prefix popcount places each present column at its
 //     sorted position;
-//   * consecutive windows with at most HCAP products together (a sparse stretch
-//     of up to SPAN columns) share one pass in the manner of an
+//   * consecutive windows whose products fit the staging memory left beside
+//     their bitmap (a sparse stretch: up to 8192 products over 10 windows, fewer
+//     over more) share one pass in the manner of an
 //     expand-sort-compress accumulator whose sort is a bitmap rank: every
 //     product is written to LDS at its own number (no atomics) and marks its
 //     column in a bitmap over the stretch; the prefix popcount of the bitmap is
@@ -665,11 +666,8 @@ k_numeric_hybrid(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
 // why sparse stretches are merged into few passes and why every pass spreads
 // its products over the whole workgroup.
 constexpr int HV_THREADS = 1024;
-constexpr int HV_PPT = 6;                          // products of a sparse pass per thread
-constexpr int HV_HCAP = HV_PPT * HV_THREADS;       // products one sparse pass takes: 6144
-constexpr int HV_SPAN = 262144;                    // columns one sparse pass may span
-constexpr int HV_BMWORDS = HV_SPAN / 32;           // 8192 words of presence bitmap
-constexpr int HV_BMWPT = HV_BMWORDS / HV_THREADS;  // bitmap words per thread
+constexpr int HV_PPT = 8;                          // products of a sparse pass per thread, at most
+constexpr int HV_HCAP = HV_PPT * HV_THREADS;       // products one sparse pass takes at most: 8192
 constexpr int HV_MAXWIN = 512;                     // windows per row the kernel can plan for
 
 template <typename V>
@@ -700,13 +698,15 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     V *s_vals = reinterpret_cast<V *>(s_u);                                        // dense: WIN values
     // sparse pass: staged products (column, value) by product number; once every thread holds its
     // products in registers the same memory takes the output (columns, accumulated values) by rank
+    // Its memory is laid out per pass: the more windows a stretch spans, the more of the region goes to
+    // the bitmap (WIN/8 bytes per window) and its prefix counts (WIN/16), the less to staged products
+    // (4 + sizeof(V) bytes each, in multiples of one product per thread).
+    constexpr int OV = WIN / 8 + WIN / 16;
+    auto sparse_cap = [](int run) {
+        const int c = (131072 - run * OV) / (4 + (int)sizeof(V)) / HV_THREADS * HV_THREADS;
+        return c > HV_HCAP ? HV_HCAP : (c < 0 ? 0 : c);
+    };
     int32_t *s_scol = reinterpret_cast<int32_t *>(s_u);
-    V *s_sval = reinterpret_cast<V *>(s_u + HV_HCAP * 4);
-    uint16_t *s_hpre = reinterpret_cast<uint16_t *>(s_u + HV_HCAP * 12);            // entries before each bitmap word
-    uint32_t *s_hbm = reinterpret_cast<uint32_t *>(s_u + 131072 - HV_BMWORDS * 4);  // presence bitmap of the stretch
-    static_assert(HV_HCAP * 12 + HV_BMWORDS * 2 + HV_BMWORDS * 4 <= 131072, "staging, prefix and bitmap fit the region");
-    constexpr int MAX_RUN = HV_SPAN / WIN;   // windows one sparse pass may span
-    static_assert(MAX_RUN >= 1, "a sparse pass spans at least one window");
     const int tid = threadIdx.x;
     const size_t stride = (size_t)n_win + 1;
 
@@ -767,18 +767,25 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
         __syncthreads();
 
         // ---- walk the windows, pass by pass
-        // next pass from window `from` on: a window with more than HCAP products on its own (dense), or
-        // a run of windows with at most HCAP products together (hash); p0 == n_win when nothing is left
+        // next pass from window `from` on: a window with more products than a sparse pass can stage (dense),
+        // or a run of windows whose products fit the staging memory that is left beside the run's bitmap
+        // (sparse); p0 == n_win when nothing is left
         auto plan = [&](int from, int &p0, int &p1, bool &pdense) {
             int x = from;
             while (x < n_win && s_prodw[x] == 0) ++x;
             p0 = x; p1 = x; pdense = false;
             if (x >= n_win) return;
             uint32_t sum = s_prodw[x];
-            pdense = sum > (uint32_t)HV_HCAP;
+            pdense = sum > (uint32_t)sparse_cap(1);
             p1 = x + 1;
-            if (!pdense)
-                while (p1 < n_win && p1 - x < MAX_RUN && sum + s_prodw[p1] <= (uint32_t)HV_HCAP) { sum += s_prodw[p1]; ++p1; }
+            if (!pdense) {
+                while (p1 < n_win) {
+                    const uint32_t nx = sum + s_prodw[p1];
+                    if (nx > (uint32_t)sparse_cap(p1 + 1 - x)) break;   // (a window beyond any capacity ends the run as well)
+                    sum = nx;
+                    ++p1;
+                }
+            }
         };
         int w, w1;
         bool dense;
@@ -793,6 +800,12 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
             plan(w1, nx0, nx1, nxdense);
             // (no entry has products in the windows skipped between two passes: the next pass starts at c_hi)
             const uint32_t n_hi = have0 ? t0[nx1] : 0u;
+            // memory of a sparse pass (see above)
+            const int scap = sparse_cap(w1 - w);
+            V *s_sval = reinterpret_cast<V *>(s_u + (size_t)scap * 4);
+            uint16_t *s_hpre = reinterpret_cast<uint16_t *>(s_u + (size_t)scap * (4 + sizeof(V)));
+            uint32_t *s_hbm = reinterpret_cast<uint32_t *>(s_u + (size_t)scap * (4 + sizeof(V)) + (size_t)(w1 - w) * (WIN / 16));
+            const int hwords = (w1 - w) * (WIN / 32);
             // accumulator of this pass
             if (dense) {
                 if (!dense_clean) {
@@ -800,8 +813,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                     dense_clean = true;
                 }
             } else {
-                // (the bitmap of a sparse pass is all zero here: the region is either an all-zero dense
-                // window or was left by a sparse pass, which clears its bitmap)
+                for (int j = tid; j < (w1 - w) * (WIN / 32); j += HV_THREADS) s_hbm[j] = 0u;
                 dense_clean = false;
             }
             // (no barrier: the traversal below has barriers of its own before the first product arrives)
@@ -824,7 +836,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                     for (int u = 0; u < U; ++u) {
                         const uint32_t at = staged + q0 + (uint32_t)u * WAVE + (uint32_t)(tid & (WAVE - 1));
                         const uint32_t d = (uint32_t)(cj[u] - col0);
-                        if (cj[u] >= 0 && at < (uint32_t)HV_HCAP && d < (uint32_t)HV_SPAN) {   // both hold by construction
+                        if (cj[u] >= 0 && at < (uint32_t)scap && d < (uint32_t)hwords * 32u) {   // both hold by construction
                             s_scol[at] = cj[u];
                             s_sval[at] = cv[u];
                             atomicOr(&s_hbm[d >> 5], 1u << (d & 31u));
@@ -877,17 +889,21 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                 __syncthreads();
             } else {
                 // ---- sparse pass: rank of every column = set bits below it in the bitmap of the stretch
-                int cnt[HV_BMWPT];
+                const int wpt = (hwords + HV_THREADS - 1) / HV_THREADS;   // bitmap words per thread (consecutive)
                 int mine = 0;
-#pragma unroll
-                for (int q = 0; q < HV_BMWPT; ++q) { cnt[q] = __popc(s_hbm[tid * HV_BMWPT + q]); mine += cnt[q]; }
+                for (int q = 0; q < wpt; ++q) {
+                    const int j = tid * wpt + q;
+                    if (j < hwords) mine += __popc(s_hbm[j]);
+                }
                 int htotal;
                 int run = block_exclusive_scan_i32<HV_THREADS>(mine, s_wave, htotal);
-#pragma unroll
-                for (int q = 0; q < HV_BMWPT; ++q) { s_hpre[tid * HV_BMWPT + q] = (uint16_t)run; run += cnt[q]; }
+                for (int q = 0; q < wpt; ++q) {
+                    const int j = tid * wpt + q;
+                    if (j < hwords) { s_hpre[j] = (uint16_t)run; run += __popc(s_hbm[j]); }
+                }
                 __syncthreads();
                 // every thread takes its share of the staged products into registers, with their ranks
-                if (staged > (uint32_t)HV_HCAP) staged = HV_HCAP;   // cannot happen: passes are planned from the counts
+                if (staged > (uint32_t)scap) staged = scap;   // cannot happen: passes are planned from the counts
                 int32_t pc[HV_PPT];
                 V pv[HV_PPT];
                 int pr[HV_PPT];
@@ -905,8 +921,6 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                 __syncthreads();
                 // the staging memory becomes the output of the pass: columns and zeroed values by rank
                 for (int i = tid; i < htotal; i += HV_THREADS) s_sval[i] = (V)0;
-#pragma unroll
-                for (int q = 0; q < HV_BMWPT; ++q) s_hbm[tid * HV_BMWPT + q] = 0u;
                 __syncthreads();
 #pragma unroll
                 for (int i = 0; i < HV_PPT; ++i) {
