@@ -26,7 +26,17 @@ k_compact(int64_t m, int g_log2, const int64_t *__restrict__ c_rp, const int32_t
     const int64_t src = first ? ptr1[row] : ptr2[row];
     const int32_t *sc = first ? col1 : col2;
     const V *sv = first ? val1 : val2;
-    for (int64_t t = sub; t < n; t += G) {
+    // eight elements in flight per lane: a long row is bound by the latency of its loads otherwise
+    int64_t t = sub;
+    for (; t + 7 * (int64_t)G < n; t += 8 * (int64_t)G) {
+        int32_t cc[8];
+        V vv[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { cc[i] = sc[src + t + (int64_t)i * G]; vv[i] = sv[src + t + (int64_t)i * G]; }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { c_col[dst + t + (int64_t)i * G] = cc[i]; c_val[dst + t + (int64_t)i * G] = vv[i]; }
+    }
+    for (; t < n; t += G) {
         c_col[dst + t] = sc[src + t];
         c_val[dst + t] = sv[src + t];
     }
