@@ -10,7 +10,8 @@
 //   k_numeric_heavy   rows beyond the 8192-slot table when B's rows are sorted: column windows, each
 //                     accumulated in LDS either densely (values + bitmap, Section 2.2 dense
 //                     accumulator iterated over the row's column range as in Section 3.2) or, for
-//                     sparse stretches, in a hash table shared by several windows
+//                     sparse stretches of several windows, by staging the products in LDS and
+//                     adding them at the bitmap rank of their column (no hash table)
 //   k_numeric_global  whole table in global memory, and k_numeric_hybrid: the path of such rows
 //                     when B's rows are unsorted (or the window table would be too large)
 //
