@@ -26,10 +26,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-BIN_NAMES = ["k_numeric_group (16 lanes/row, 64 slots)", "k_numeric_wave (256 slots)", "k_numeric_wg<9> (512 slots)",
-             "k_numeric_wg<10> (1024 slots)", "k_numeric_wg<11> (2048 slots)", "k_numeric_wg<12> (4096 slots)",
-             "k_numeric_wg<13> (8192 slots)", "rows up to 32768 entries", "k_numeric_heavy (column windows in LDS)"]
-HYBRID_BIN, LAST_BIN = 7, 8
+BIN_NAMES = ["k_numeric_group<8> (8 lanes/row, 32 slots)", "k_numeric_group<16> (16 lanes/row, 64 slots)",
+             "k_numeric_wave (256 slots)", "k_numeric_wg<9> (512 slots)", "k_numeric_wg<10> (1024 slots)",
+             "k_numeric_wg<11> (2048 slots)", "k_numeric_wg<12> (4096 slots)", "k_numeric_wg<13> (8192 slots)",
+             "rows up to 32768 entries", "k_numeric_heavy (column windows in LDS)"]
+HYBRID_BIN, LAST_BIN = 8, 9   # the last two bins of ocean_bin_layout
 
 
 def model_bytes(nnz_a, products, nnz_c, rows, v):
@@ -67,7 +68,7 @@ def run_workload(ob, W, torch, name, workflow, steps, warmup):
         "stage_ms": {k: round(x, 4) for k, x in stage.items() if x > 0},
         "overflow_rows": st["overflow_rows"], "hll_registers": st["hll_registers"], "sampled_cr": st["sampled_cr"],
         "er": st["er"], "avg_products": st["avg_products"], "fell_back": st["fell_back"],
-        "peak_gib": st["peak_bytes"] / 2 ** 30, "rows_per_bin": st["rows_per_bin"][:9], "bin_ms": [round(x, 4) for x in bin_ms[:9]],
+        "peak_gib": st["peak_bytes"] / 2 ** 30, "rows_per_bin": st["rows_per_bin"][:len(BIN_NAMES)], "bin_ms": [round(x, 4) for x in bin_ms[:len(BIN_NAMES)]],
     }
     res["hbm_model_frac"] = res["hbm_model_bytes"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
     # dominant numeric kernel

@@ -2,7 +2,7 @@
 // open-addressing hash accumulators (Section 2.2) sized per bin, followed by
 // the per-row sort that makes the output CSR-compliant (Section 4.2).
 //
-//   k_numeric_group   four short rows per wave (16 lanes per row), 64-slot tables in LDS
+//   k_numeric_group   several short rows per wave (8 or 16 lanes per row), 32- or 64-slot tables in LDS
 //   k_numeric_wave    one wave per row, 256-slot table in LDS
 //   k_numeric_wg      one workgroup per row, keys + values + sort buffer in LDS (512..8192 slots)
 //   k_numeric_hybrid  32768 keys in LDS, values accumulated in a global slab (Section 3.3,
@@ -97,17 +97,18 @@ __device__ __forceinline__ int pow2_ceil_i32(int x)
 }
 
 // ======================================================== group kernel ====
-// Four short rows per wave (16 lanes per row), 16 rows per workgroup, 64-slot
-// tables; no workgroup barrier anywhere: the lanes of a row are part of one wave.
-template <typename V>
+// Several short rows per wave: G lanes per row (16 with 64-slot tables, 8 with
+// 32-slot tables), 256/G rows per workgroup; no workgroup barrier anywhere: the
+// lanes of a row are part of one wave.  These rows are bound by the latency of
+// their chain of dependent loads (row id -> offsets -> entries -> rows of B ->
+// products), so what counts is how many rows a CU has in flight.
+template <typename V, int G, int BITS>
 __global__ void __launch_bounds__(256)
 k_numeric_group(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col, const V *__restrict__ a_val,
                 const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_col, const V *__restrict__ b_val,
                 const int32_t *__restrict__ rows, int64_t count, const int64_t *__restrict__ out_ptr,
                 int32_t *__restrict__ out_col, V *__restrict__ out_val, int32_t *__restrict__ row_nnz)
 {
-    constexpr int G = 16;
-    constexpr int BITS = 6;
     constexpr int SLOTS = 1 << BITS;
     constexpr int R = 256 / G;
     __shared__ int32_t s_keys[R * SLOTS];
@@ -135,7 +136,7 @@ k_numeric_group(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     auto f = [&](const auto &cj, const auto &cv) {
         if (!lds_insert_batch<BITS>(keys, cj, cv, [&](int slot, V v, bool) { lds_add(&vals[slot], v); })) ovf = true;
     };
-    // the four rows of a wave advance together: same number of 16-entry chunks for all of them
+    // the rows of a wave advance together: same number of G-entry chunks for all of them
     const int chunks = group_reduce_max((int)((e1 - e0 + G - 1) / G), WAVE);
     for (int ch = 0; ch < chunks; ++ch) {
         const int64_t e = e0 + (int64_t)ch * G + sub;
@@ -1147,10 +1148,16 @@ static hipError_t dispatch(const Csr &A, const Csr &B, const NumLaunch &l, int g
     hipLaunchKernelGGL((k_numeric_wg<V, BITS, THREADS>), dim3((unsigned)l.count), dim3(THREADS), 0, s, A.rp, A.col, \
                        av, B.rp, B.col, bv, l.rows, l.count, l.out_ptr, l.out_col, ov, l.row_nnz)
     switch (l.bin) {
+    case NB_G8: {
+        const int64_t blocks = (l.count + 31) / 32;
+        hipLaunchKernelGGL((k_numeric_group<V, 8, 5>), dim3((unsigned)blocks), dim3(256), 0, s, A.rp, A.col, av, B.rp, B.col,
+                           bv, l.rows, l.count, l.out_ptr, l.out_col, ov, l.row_nnz);
+        break;
+    }
     case NB_G16: {
         const int64_t blocks = (l.count + 15) / 16;
-        hipLaunchKernelGGL((k_numeric_group<V>), dim3((unsigned)blocks), dim3(256), 0, s, A.rp, A.col, av, B.rp, B.col, bv,
-                           l.rows, l.count, l.out_ptr, l.out_col, ov, l.row_nnz);
+        hipLaunchKernelGGL((k_numeric_group<V, 16, 6>), dim3((unsigned)blocks), dim3(256), 0, s, A.rp, A.col, av, B.rp, B.col,
+                           bv, l.rows, l.count, l.out_ptr, l.out_col, ov, l.row_nnz);
         break;
     }
     case NB_W64: {

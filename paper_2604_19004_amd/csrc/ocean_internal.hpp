@@ -18,7 +18,8 @@ constexpr int32_t SORT_PAD = 0x7fffffff;   // sorts after every valid column id
 // multi-short-row and a long-row one; the sizes here are re-derived for 160 KB
 // of LDS and 64-wide waves).  slots = hash-table entries of the bin.
 enum NumericBin {
-    NB_G16 = 0,   // 16 lanes per row, 4 rows per wave, 64 slots
+    NB_G8 = 0,    // 8 lanes per row, 8 rows per wave, 32 slots
+    NB_G16,       // 16 lanes per row, 4 rows per wave, 64 slots
     NB_W64,       // one wave per row, 256 slots
     NB_S512,      // one workgroup per row from here on
     NB_S1K,
@@ -29,7 +30,7 @@ enum NumericBin {
     NB_GLOBAL,    // whole table in global memory
     NB_COUNT
 };
-constexpr int32_t kNumericSlots[NB_COUNT] = {64, 256, 512, 1024, 2048, 4096, 8192, 32768, 0x7fffffff};
+constexpr int32_t kNumericSlots[NB_COUNT] = {32, 64, 256, 512, 1024, 2048, 4096, 8192, 32768, 0x7fffffff};
 
 enum SymbolicBin {
     SB_G16 = 0,   // 64 keys
