@@ -143,8 +143,8 @@ def main():
                          "(scale for the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (rows of C are independent; see DESIGN.md for how it would "
-              "shard); --gpus must be 1", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU and --gpus must be 1 (rows of C are independent: several GPUs "
+              "would each take a block of rows of A against a replicated B)", file=sys.stderr)
         sys.exit(2)
     import torch
     if not torch.cuda.is_available():
