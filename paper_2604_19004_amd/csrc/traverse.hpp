@@ -235,6 +235,21 @@ __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS> &c, int ne
             const int width = __builtin_amdgcn_readfirstlane(hi - lo);
 #pragma unroll
             for (int u = 0; u < FLAT_U; ++u) fp[u] = lo;
+            if (!HAS_VAL && width == 0) {
+                // symbolic pass (whole rows of B, often long): the batch lies in one row of B, no search,
+                // one read of the segment's base
+                const long long base = c.pbase[lo];
+#pragma unroll
+                for (int u = 0; u < FLAT_U; ++u) {
+                    const uint32_t q = q0 + u * WAVE + lane;
+                    const bool ok = q < qe;
+                    const int64_t p = base + (long long)q;
+                    fj[u] = ok ? b_col[p] : -1;
+                    if constexpr (HAS_VAL) fb[u] = ok ? b_val[p] : V();
+                    else fb[u] = V();
+                }
+                return;
+            }
             for (int step = width > 0 ? 1 << (31 - __clz(width)) : 0; step > 0; step >>= 1) {
                 // the reads of one step are unconditional (index clamped) so that they are issued together
                 int t[FLAT_U];
