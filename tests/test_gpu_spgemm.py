@@ -304,6 +304,26 @@ def test_heavy_rows_reach_hybrid_and_last_bin(ob, variant):
     assert st["overflow_rows"] > 0
 
 
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_heavy_rows_spread_thin_over_many_windows(ob, dtype):
+    """Heavy rows whose products are few per column window: the sparse passes of the column-window kernel
+    then span long runs of windows with little staging memory each."""
+    rng = np.random.default_rng(21)
+    n = 1 << 20
+    Bm = W.erdos_renyi(20000, 2, seed=22, cols=n)
+    Bm.val = Bm.val.astype(dtype)
+    rows_spec = [12000, 6000, 5000, 2500, 17]
+    rp = np.concatenate([[0], np.cumsum(rows_spec)]).astype(np.int64)
+    ci = np.concatenate([np.sort(rng.choice(20000, k, replace=False)) for k in rows_spec]).astype(np.int32)
+    A = CSR(len(rows_spec), 20000, rp, ci, rng.uniform(-1, 1, ci.size).astype(dtype))
+    ref = O.multiply_rows(A, Bm)
+    for wf in ("symbolic", "hll", "upper_bound"):
+        Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(Bm), workflow=wf_id(ob, wf))
+        check_result(Cd, ref, A, f"thin heavy rows {np.dtype(dtype).name}/{wf}")
+        nb = len(ob.bin_layout()[0])
+        assert st["rows_per_bin"][nb - 1] + st["rows_per_bin"][nb - 2] >= 2
+
+
 def test_skewed_row_lengths_of_b(ob):
     # rows of B from 0 to 20000 entries referenced by the same rows of A: exercises the short / medium /
     # long / huge classes of the product traversal in every kernel size
