@@ -223,11 +223,9 @@ __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS> &c, int ne
     const uint32_t qs = (uint32_t)wave * span;
     const uint32_t qe = qs + span < total ? qs + span : total;
     if (qs < total) {   // uniform for the wave
-        // The loads of the next batch are issued before the current one goes to the accumulator, so
-        // a wave's memory latency hides behind its own LDS work.
-        int32_t cj[FLAT_U], nj[FLAT_U];
-        V cb[FLAT_U], nb[FLAT_U];   // values of B; multiplied by A's value only when the batch is used
-        int cp[FLAT_U], np[FLAT_U];
+        int32_t cj[FLAT_U];
+        V cb[FLAT_U];   // values of B
+        int cp[FLAT_U];
         auto fetch = [&](uint32_t q0, int32_t (&fj)[FLAT_U], V (&fb)[FLAT_U], int (&fp)[FLAT_U]) {
             const uint32_t qlast = q0 + WAVE * FLAT_U - 1 < qe - 1 ? q0 + WAVE * FLAT_U - 1 : qe - 1;
             const int lo = c.first[q0 >> bshift];
@@ -275,10 +273,8 @@ __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS> &c, int ne
                 else fb[u] = V();
             }
         };
-        fetch(qs, cj, cb, cp);
         for (uint32_t q0 = qs; q0 < qe; q0 += WAVE * FLAT_U) {
-            const uint32_t qn = q0 + WAVE * FLAT_U;
-            if (qn < qe) fetch(qn, nj, nb, np);   // uniform for the wave
+            fetch(q0, cj, cb, cp);
             V cv[FLAT_U];
 #pragma unroll
             for (int u = 0; u < FLAT_U; ++u) {
@@ -289,8 +285,6 @@ __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS> &c, int ne
             // product of lane l, position u is number q0 + u*64 + l
             if constexpr (std::is_invocable_v<F &, int32_t(&)[FLAT_U], V(&)[FLAT_U], uint32_t>) f(cj, cv, q0);
             else f(cj, cv);
-#pragma unroll
-            for (int u = 0; u < FLAT_U; ++u) { cj[u] = nj[u]; cb[u] = nb[u]; cp[u] = np[u]; }
         }
     }
     __syncthreads();
