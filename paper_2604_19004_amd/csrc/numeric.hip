@@ -871,19 +871,20 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                 const int ex = block_exclusive_scan_i32<HV_THREADS>(__popc(word), s_wave, wtotal);
                 if (tid < WORDS) s_dpre[tid] = (uint32_t)ex;
                 __syncthreads();
-                constexpr int BPT = WIN / HV_THREADS;   // 16 (fp64) or 32 (fp32) bits of the bitmap per thread
-                const int j0 = tid * BPT;
-                const uint32_t wbits = s_dbm[j0 >> 5];
-                uint32_t bits = BPT == 32 ? wbits : ((wbits >> (j0 & 31)) & ((1u << (BPT & 31)) - 1u));
-                long long rank = done + (long long)s_dpre[j0 >> 5] + __popc(wbits & ((1u << (j0 & 31)) - 1u));
-                while (bits) {
-                    const int b = __ffs((int)bits) - 1;
-                    bits &= bits - 1u;
-                    const int j = j0 + b;
-                    const V val = s_vals[j];
-                    s_vals[j] = (V)0;
-                    if (rank < cap) { out_col[o + rank] = col0 + j; out_val[o + rank] = val; }
-                    ++rank;
+                // Thread t looks at columns t, t + 1024, ...: in every step the lanes of a wave read
+                // consecutive values (no LDS bank conflicts) and the present ones among them go to
+                // consecutive places of the output (coalesced stores).
+                constexpr int STEPS = WIN / HV_THREADS;   // 16 (fp64) or 32 (fp32)
+#pragma unroll 4
+                for (int i = 0; i < STEPS; ++i) {
+                    const int j = i * HV_THREADS + tid;
+                    const uint32_t wbits = s_dbm[j >> 5];
+                    if ((wbits >> (j & 31)) & 1u) {
+                        const long long rank = done + (long long)s_dpre[j >> 5] + __popc(wbits & ((1u << (j & 31)) - 1u));
+                        const V val = s_vals[j];
+                        s_vals[j] = (V)0;
+                        if (rank < cap) { out_col[o + rank] = col0 + j; out_val[o + rank] = val; }
+                    }
                 }
                 __syncthreads();
                 if (tid < WORDS) s_dbm[tid] = 0u;
