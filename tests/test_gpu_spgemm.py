@@ -304,15 +304,16 @@ def test_heavy_rows_reach_hybrid_and_last_bin(ob, variant):
     assert st["overflow_rows"] > 0
 
 
+@pytest.mark.parametrize("n", [1 << 20, 3 << 20])
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
-def test_heavy_rows_spread_thin_over_many_windows(ob, dtype):
+def test_heavy_rows_spread_thin_over_many_windows(ob, dtype, n):
     """Heavy rows whose products are few per column window: the sparse passes of the column-window kernel
-    then span long runs of windows with little staging memory each."""
+    then span long runs of windows with little staging memory each.  With more than 2^20 columns the
+    symbolic pass needs several bitmap windows per row and uses its 16384- and 32768-slot key tables."""
     rng = np.random.default_rng(21)
-    n = 1 << 20
     Bm = W.erdos_renyi(20000, 2, seed=22, cols=n)
     Bm.val = Bm.val.astype(dtype)
-    rows_spec = [12000, 6000, 5000, 2500, 17]
+    rows_spec = [19000, 12000, 6000, 5000, 2500, 17]
     rp = np.concatenate([[0], np.cumsum(rows_spec)]).astype(np.int64)
     ci = np.concatenate([np.sort(rng.choice(20000, k, replace=False)) for k in rows_spec]).astype(np.int32)
     A = CSR(len(rows_spec), 20000, rp, ci, rng.uniform(-1, 1, ci.size).astype(dtype))
