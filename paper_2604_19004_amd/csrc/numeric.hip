@@ -968,18 +968,31 @@ k_window_table(const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_c
         for (int w = sub; w <= n_win; w += 16) t[w] = (uint32_t)p0;
         return;
     }
-    for (int64_t p = p0 + sub; p < p1; p += 16) {
-        const int32_t c = b_col[p];
-        const int wc = c >> win_log2;
-        int wprev = -1;
-        if (p > p0) {
-            const int32_t cp = b_col[p - 1];
-            unsorted |= cp > c;
-            wprev = cp >> win_log2;
+    for (int64_t q = p0 + sub; q < p1; q += 64) {
+        // four entries per lane and turn (unconditional reads, index clamped), so that a long row is
+        // not bound by the latency of one load after the other
+        int32_t c[4], cp[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int64_t p = q + 16 * i;
+            const int64_t pc = p < p1 ? p : p1 - 1;
+            c[i] = b_col[pc];
+            cp[i] = b_col[pc > p0 ? pc - 1 : p0];
         }
-        for (int w = wprev + 1; w <= wc; ++w) t[w] = (uint32_t)p;
-        if (p == p1 - 1)
-            for (int w = wc + 1; w <= n_win; ++w) t[w] = (uint32_t)p1;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int64_t p = q + 16 * i;
+            if (p >= p1) break;
+            const int wc = c[i] >> win_log2;
+            int wprev = -1;
+            if (p > p0) {
+                unsorted |= cp[i] > c[i];
+                wprev = cp[i] >> win_log2;
+            }
+            for (int w = wprev + 1; w <= wc; ++w) t[w] = (uint32_t)p;
+            if (p == p1 - 1)
+                for (int w = wc + 1; w <= n_win; ++w) t[w] = (uint32_t)p1;
+        }
     }
     if (unsorted) atomicOr(flags, 8);
 }
