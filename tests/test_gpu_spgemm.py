@@ -325,6 +325,45 @@ def test_heavy_rows_spread_thin_over_many_windows(ob, dtype, n):
         assert st["rows_per_bin"][nb - 1] + st["rows_per_bin"][nb - 2] >= 2
 
 
+def _random_case(rng, dtype):
+    """A random pair (A, B) with a random mix of row lengths: empty rows, a few very long rows, duplicates
+    within rows of A, and rows of B from one entry to most of the columns."""
+    m = int(rng.integers(1, 400))
+    k = int(rng.integers(1, 300))
+    n = int(rng.choice([1, 7, 64, 1000, 20000, 300000]))
+    def rows(nr, nc, sorted_rows, heavy):
+        lens = rng.geometric(rng.uniform(0.02, 0.6), nr) - 1
+        lens[rng.random(nr) < 0.15] = 0
+        if heavy and nr > 3:
+            lens[rng.integers(0, nr, 2)] = min(nc, int(rng.integers(nc // 2 + 1, nc + 1)))
+        lens = np.minimum(lens, nc)
+        rp = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+        ci = np.empty(int(rp[-1]), np.int32)
+        for i in range(nr):
+            c = rng.choice(nc, int(lens[i]), replace=False)
+            ci[rp[i]:rp[i + 1]] = np.sort(c) if sorted_rows else c
+        return rp, ci
+    a_rp, a_ci = rows(m, k, bool(rng.integers(0, 2)), True)
+    b_rp, b_ci = rows(k, n, True, n >= 64)
+    A = CSR(m, k, a_rp, a_ci, rng.uniform(-1, 1, a_ci.size).astype(dtype))
+    B = CSR(k, n, b_rp, b_ci, rng.uniform(-1, 1, b_ci.size).astype(dtype))
+    return A, B
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_matrices(ob, seed):
+    rng = np.random.default_rng(1000 + seed)
+    for case in range(6):
+        dtype = np.float32 if (seed + case) % 3 == 0 else np.float64
+        A, B = _random_case(rng, dtype)
+        ref = O.multiply_rows(A, B)
+        wf = ("auto", "upper_bound", "hll", "symbolic")[(seed + case) % 4]
+        scale = 0.4 if wf == "hll" and case % 2 else 1.0          # every other HLL case is forced to overflow
+        print(f"random case seed={seed} case={case} {A.rows}x{A.cols}x{B.cols} nnzA={A.nnz} nnzB={B.nnz} {wf}", flush=True)
+        Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(B), workflow=wf_id(ob, wf), estimate_scale=scale)
+        check_result(Cd, ref, A, f"random seed={seed} case={case} {wf}")
+
+
 def test_skewed_row_lengths_of_b(ob):
     # rows of B from 0 to 20000 entries referenced by the same rows of A: exercises the short / medium /
     # long / huge classes of the product traversal in every kernel size
