@@ -144,12 +144,16 @@ __device__ __forceinline__ void wave_traverse(const int32_t *__restrict__ a_col,
 // LDS scratch of a workgroup-wide flattened chunk of up to THREADS entries.
 template <typename V, int THREADS>
 struct WgChunk {
+    static constexpr uint32_t RANK_CAP = 16u * THREADS;   // most products of a chunk whose entries are found by rank
     uint32_t excl[THREADS];
     long long pbase[THREADS];
     V a[THREADS];
-    uint16_t first[THREADS + 2];   // entry of the first product of every block of 2^bshift products
+    union alignas(8) {
+        uint16_t first[THREADS + 2];       // entry of the first product of every block of 2^bshift products
+        uint32_t start[THREADS / 2 + 8];   // bit q set: a segment starts at product q (RANK_CAP bits + padding)
+    };
     uint32_t wsum[THREADS / WAVE];
-    uint32_t total;
+    uint32_t wcnt[THREADS / WAVE];
 };
 
 // The whole workgroup flattens the `nent` (1..THREADS) segments held by its first nent threads
@@ -157,10 +161,17 @@ struct WgChunk {
 // evenly to the waves whatever the lengths of the single segments, so a row with three entries
 // that point to long rows of B keeps every wave as busy as a row with a thousand short ones.
 // Every wave takes one contiguous span of the products, 256 at a time.  The entry a product
-// belongs to is found by a binary search over the prefix sums, narrowed beforehand to the few
-// entries its batch of 256 can touch: a table built once per chunk gives the entry of the first
-// product of every block of products.  The searches of a batch have the same, wave-uniform
-// number of steps and run interleaved.  The products of one chunk must number less than 2^31.
+// belongs to is found in one of two ways:
+//   * a chunk of at most 16 products per thread marks the first product of every non-empty
+//     segment in a bitmap; the entry of product q (counting non-empty entries only, which are
+//     stored compacted) is the number of marks at or before q, minus one: one broadcast read of
+//     the 64 marks of the wave's batch and a population count, on top of a running count that the
+//     wave carries along its span;
+//   * a larger chunk (long segments) uses a binary search over the prefix sums, narrowed
+//     beforehand to the few entries a batch of 256 can touch: a table built once per chunk gives
+//     the entry of the first product of every block of products.  The searches of a batch have
+//     the same, wave-uniform number of steps and run interleaved.
+// The products of one chunk must number less than 2^31.
 // Every thread calls it; the chunk arrays must be free on entry (the call ends with a barrier).
 // Returns the number of products of the chunk.
 template <int THREADS, bool HAS_VAL, typename V, typename F>
@@ -168,38 +179,108 @@ __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS> &c, int ne
                                               const int32_t *__restrict__ b_col, const V *__restrict__ b_val, F &f)
 {
     constexpr int NW = THREADS / WAVE;
-    static_assert(THREADS <= 1024, "entry ids are kept in 16 bits and one block table entry per thread");
+    constexpr uint32_t RANK_CAP = WgChunk<V, THREADS>::RANK_CAP;
+    constexpr int START_WORDS = THREADS / 2 + 8;
+    static_assert(THREADS <= 1024 && START_WORDS <= THREADS, "entry ids are kept in 16 bits and one block table entry per thread");
     const int tid = threadIdx.x;
     const int lane = tid & (WAVE - 1), wave = tid / WAVE;
+    if (tid < START_WORDS) c.start[tid] = 0u;
     uint32_t incl = len;
 #pragma unroll
     for (int off = 1; off < WAVE; off <<= 1) {
         const uint32_t o = __shfl_up(incl, off, WAVE);
         if (lane >= off) incl += o;
     }
-    if (nent > WAVE) {   // uniform
-        if (lane == WAVE - 1) c.wsum[wave] = incl;
-        __syncthreads();
-        uint32_t before = 0;
+    // non-empty segments are numbered on their own
+    const unsigned long long live = __ballot(len > 0);
+    if (lane == WAVE - 1) { c.wsum[wave] = incl; c.wcnt[wave] = (uint32_t)__popcll(live); }
+    __syncthreads();
+    uint32_t before = 0, cbefore = 0, total = 0;
 #pragma unroll
-        for (int i = 0; i < NW; ++i) {
-            const uint32_t x = c.wsum[i];
-            if (i < wave) before += x;
+    for (int i = 0; i < NW; ++i) {
+        const uint32_t x = c.wsum[i], y = c.wcnt[i];
+        if (i < wave) { before += x; cbefore += y; }
+        total += x;
+    }
+    incl += before;
+    if (total == 0) {   // uniform
+        __syncthreads();
+        return 0;
+    }
+    const uint32_t span = ((total + NW - 1) / NW + (WAVE - 1)) & ~(uint32_t)(WAVE - 1);
+    const uint32_t qs = (uint32_t)wave * span;
+    const uint32_t qe = qs + span < total ? qs + span : total;
+    int32_t cj[FLAT_U];
+    V cb[FLAT_U];   // values of B
+    int cp[FLAT_U];
+    if (total <= RANK_CAP) {   // uniform
+        const uint32_t ex = incl - len;
+        if (len > 0) {
+            const uint32_t ce = cbefore + __builtin_amdgcn_mbcnt_hi((uint32_t)(live >> 32),
+                                                                    __builtin_amdgcn_mbcnt_lo((uint32_t)live, 0u));
+            c.pbase[ce] = (long long)p0 - (long long)ex;
+            c.a[ce] = a;
+            atomicOr(&c.start[ex >> 5], 1u << (ex & 31u));
         }
-        incl += before;
+        __syncthreads();
+        if (qs < total) {   // uniform for the wave
+            const unsigned long long *marks = reinterpret_cast<const unsigned long long *>(c.start);
+            // segments that start before the wave's span
+            uint32_t run = 0;
+            for (uint32_t j = (uint32_t)lane; j < (qs >> 6); j += WAVE) run += (uint32_t)__popcll(marks[j]);
+#pragma unroll
+            for (int off = WAVE / 2; off > 0; off >>= 1) run += __shfl_xor(run, off, WAVE);
+            const unsigned long long upto = (2ull << lane) - 1ull;   // this lane's product and those before it
+            for (uint32_t q0 = qs; q0 < qe; q0 += WAVE * FLAT_U) {
+                // Every stage of a batch is straight-line code over its FLAT_U products, with
+                // unconditional reads (a lane past the end of the span reads product 0, which exists), so
+                // that the reads of one stage are in flight together.
+                unsigned long long m[FLAT_U];
+#pragma unroll
+                for (int u = 0; u < FLAT_U; ++u) m[u] = marks[(q0 >> 6) + u];   // one address for the wave
+                bool ok[FLAT_U];
+                uint32_t qq[FLAT_U];
+#pragma unroll
+                for (int u = 0; u < FLAT_U; ++u) {
+                    const uint32_t q = q0 + u * WAVE + lane;
+                    ok[u] = q < qe;
+                    const uint32_t rank = run + (uint32_t)__popcll(m[u] & upto);   // >= 1: product 0 starts a segment
+                    run += (uint32_t)__popcll(m[u]);
+                    cp[u] = ok[u] ? (int)rank - 1 : 0;
+                    qq[u] = ok[u] ? q : 0u;
+                }
+                long long pb[FLAT_U];
+                V av[FLAT_U];
+#pragma unroll
+                for (int u = 0; u < FLAT_U; ++u) {
+                    pb[u] = c.pbase[cp[u]];
+                    if constexpr (HAS_VAL) av[u] = c.a[cp[u]];
+                }
+#pragma unroll
+                for (int u = 0; u < FLAT_U; ++u) {
+                    const int64_t p = pb[u] + (long long)qq[u];
+                    cj[u] = ok[u] ? b_col[p] : -1;
+                    if constexpr (HAS_VAL) cb[u] = ok[u] ? b_val[p] : V();
+                }
+                V cv[FLAT_U];
+#pragma unroll
+                for (int u = 0; u < FLAT_U; ++u) {
+                    if constexpr (HAS_VAL) cv[u] = av[u] * cb[u];
+                    else cv[u] = V();
+                }
+                if constexpr (std::is_invocable_v<F &, int32_t(&)[FLAT_U], V(&)[FLAT_U], uint32_t>) f(cj, cv, q0);
+                else f(cj, cv);
+            }
+        }
+        __syncthreads();
+        return total;
     }
     if (tid < nent) {
         c.excl[tid] = incl - len;
         c.pbase[tid] = (long long)p0 - (long long)(incl - len);
         c.a[tid] = a;
     }
-    if (tid == nent - 1) c.total = incl;
     __syncthreads();
-    const uint32_t total = c.total;
-    if (total == 0) {   // uniform
-        __syncthreads();
-        return 0;
-    }
     // blocks of 2^bshift products, at least 256 products each and fewer than THREADS of them
     int bshift = 8;
     while (((total - 1) >> bshift) >= (uint32_t)(THREADS - 1)) ++bshift;
@@ -219,13 +300,7 @@ __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS> &c, int ne
         c.first[tid] = (uint16_t)pos;
     }
     __syncthreads();
-    const uint32_t span = ((total + NW - 1) / NW + (WAVE - 1)) & ~(uint32_t)(WAVE - 1);
-    const uint32_t qs = (uint32_t)wave * span;
-    const uint32_t qe = qs + span < total ? qs + span : total;
     if (qs < total) {   // uniform for the wave
-        int32_t cj[FLAT_U];
-        V cb[FLAT_U];   // values of B
-        int cp[FLAT_U];
         auto fetch = [&](uint32_t q0, int32_t (&fj)[FLAT_U], V (&fb)[FLAT_U], int (&fp)[FLAT_U]) {
             const uint32_t qlast = q0 + WAVE * FLAT_U - 1 < qe - 1 ? q0 + WAVE * FLAT_U - 1 : qe - 1;
             const int lo = c.first[q0 >> bshift];
@@ -263,11 +338,14 @@ __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS> &c, int ne
                     fp[u] = (t[u] <= hi && ex[u] <= q) ? t[u] : fp[u];
                 }
             }
+            long long pb[FLAT_U];
+#pragma unroll
+            for (int u = 0; u < FLAT_U; ++u) pb[u] = c.pbase[fp[u]];   // (reads of LDS together, ahead of the loads)
 #pragma unroll
             for (int u = 0; u < FLAT_U; ++u) {
                 const uint32_t q = q0 + u * WAVE + lane;
                 const bool ok = q < qe;
-                const int64_t p = c.pbase[fp[u]] + (long long)q;
+                const int64_t p = pb[u] + (long long)q;
                 fj[u] = ok ? b_col[p] : -1;
                 if constexpr (HAS_VAL) fb[u] = ok ? b_val[p] : V();
                 else fb[u] = V();
