@@ -273,23 +273,14 @@ k_numeric_wave(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_c
 template <int THREADS>
 __device__ __forceinline__ int block_exclusive_scan_i32(int v, int *s_wave, int &total)
 {
-    int inc = v;
-    for (int off = 1; off < WAVE; off <<= 1) {
-        const int o = __shfl_up(inc, off, WAVE);
-        if (lane_id() >= off) inc += o;
-    }
+    const int inc = (int)wave_inclusive_scan_u32((uint32_t)v);
     const int w = threadIdx.x / WAVE;
     if (lane_id() == WAVE - 1) s_wave[w] = inc;
     __syncthreads();
-    int wave_off = 0, tot = 0;
-#pragma unroll
-    for (int i = 0; i < THREADS / WAVE; ++i) {
-        const int x = s_wave[i];
-        if (i < w) wave_off += x;
-        tot += x;
-    }
+    uint32_t tot;
+    const int wave_off = (int)waves_before_u32<THREADS / WAVE>(reinterpret_cast<const uint32_t *>(s_wave), w, tot);
     __syncthreads();
-    total = tot;
+    total = (int)tot;
     return wave_off + inc - v;
 }
 

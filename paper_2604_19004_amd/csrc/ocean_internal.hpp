@@ -97,6 +97,43 @@ __device__ __forceinline__ uint32_t table_step(int32_t key, int bits)
     return ((((uint32_t)key * 0x85EBCA6Bu) >> (32 - bits)) << 1) | 1u;
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves, which
+// cost a vector instruction each and no trip to LDS: shifts by 1, 2, 4 and 8 lanes inside the
+// rows of 16 lanes, then lane 15 of rows 0 and 2 into rows 1 and 3, then lane 31 into the upper
+// half.  A lane without a source adds 0.  Every lane of the wave must be active.
+__device__ __forceinline__ uint32_t wave_inclusive_scan_u32(uint32_t v)
+{
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false);   // row_bcast:15, rows 1 and 3
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);   // row_bcast:31, rows 2 and 3
+    return v;
+}
+// Value of lane `l` (the same number in every lane) of v.
+__device__ __forceinline__ uint32_t wave_read_lane_u32(uint32_t v, int l)
+{
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, __builtin_amdgcn_readfirstlane(l));
+}
+// Sum over the wave, in every lane.
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v)
+{
+    return wave_read_lane_u32(wave_inclusive_scan_u32(v), WAVE - 1);
+}
+// Workgroup level of a two-level prefix sum: part[w] holds the sum of wave w (NW <= 64 waves).
+// Returns the sum of the waves before `wave`; total = sum of all.  Every lane must be active.
+template <int NW>
+__device__ __forceinline__ uint32_t waves_before_u32(const uint32_t *part, int wave, uint32_t &total)
+{
+    static_assert(NW <= WAVE, "one lane per wave");
+    const int lane = (int)(threadIdx.x & (WAVE - 1));
+    const uint32_t inc = wave_inclusive_scan_u32(lane < NW ? part[lane] : 0u);
+    total = wave_read_lane_u32(inc, NW - 1);
+    const uint32_t upto = wave_read_lane_u32(inc, wave > 0 ? wave - 1 : 0);
+    return wave > 0 ? upto : 0u;
+}
+
 template <typename T>
 __device__ __forceinline__ T group_reduce_sum(T v, int width)
 {

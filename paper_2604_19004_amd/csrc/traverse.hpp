@@ -185,23 +185,14 @@ __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS> &c, int ne
     const int tid = threadIdx.x;
     const int lane = tid & (WAVE - 1), wave = tid / WAVE;
     if (tid < START_WORDS) c.start[tid] = 0u;
-    uint32_t incl = len;
-#pragma unroll
-    for (int off = 1; off < WAVE; off <<= 1) {
-        const uint32_t o = __shfl_up(incl, off, WAVE);
-        if (lane >= off) incl += o;
-    }
+    uint32_t incl = wave_inclusive_scan_u32(len);
     // non-empty segments are numbered on their own
     const unsigned long long live = __ballot(len > 0);
     if (lane == WAVE - 1) { c.wsum[wave] = incl; c.wcnt[wave] = (uint32_t)__popcll(live); }
     __syncthreads();
-    uint32_t before = 0, cbefore = 0, total = 0;
-#pragma unroll
-    for (int i = 0; i < NW; ++i) {
-        const uint32_t x = c.wsum[i], y = c.wcnt[i];
-        if (i < wave) { before += x; cbefore += y; }
-        total += x;
-    }
+    uint32_t total, ctotal;
+    const uint32_t before = waves_before_u32<NW>(c.wsum, wave, total);
+    const uint32_t cbefore = waves_before_u32<NW>(c.wcnt, wave, ctotal);
     incl += before;
     if (total == 0) {   // uniform
         __syncthreads();
@@ -228,8 +219,7 @@ __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS> &c, int ne
             // segments that start before the wave's span
             uint32_t run = 0;
             for (uint32_t j = (uint32_t)lane; j < (qs >> 6); j += WAVE) run += (uint32_t)__popcll(marks[j]);
-#pragma unroll
-            for (int off = WAVE / 2; off > 0; off >>= 1) run += __shfl_xor(run, off, WAVE);
+            run = wave_sum_u32(run);
             const unsigned long long upto = (2ull << lane) - 1ull;   // this lane's product and those before it
             for (uint32_t q0 = qs; q0 < qe; q0 += WAVE * FLAT_U) {
                 // Every stage of a batch is straight-line code over its FLAT_U products, with
