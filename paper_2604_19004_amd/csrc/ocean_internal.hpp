@@ -111,6 +111,30 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan_u32(uint32_t v)
     v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);   // row_bcast:31, rows 2 and 3
     return v;
 }
+// The same inside every group of G = 8 or 16 consecutive lanes (sub = lane inside the group).
+template <int G>
+__device__ __forceinline__ uint32_t group_inclusive_scan_u32(uint32_t v, int sub)
+{
+    static_assert(G == 8 || G == 16, "groups inside one row of 16 lanes");
+    uint32_t o;
+    o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false); v += sub >= 1 ? o : 0u;
+    o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false); v += sub >= 2 ? o : 0u;
+    o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false); v += sub >= 4 ? o : 0u;
+    if (G == 16) { o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false); v += sub >= 8 ? o : 0u; }
+    return v;
+}
+// Sum over every group of G = 8 or 16 consecutive lanes, in each of its lanes (butterfly of
+// lane swaps: neighbours, pairs, mirrored halves of 8, mirrored rows of 16).
+template <int G>
+__device__ __forceinline__ uint32_t group_sum_u32(uint32_t v)
+{
+    static_assert(G == 8 || G == 16, "groups inside one row of 16 lanes");
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, false);    // quad_perm [1,0,3,2]
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xf, 0xf, false);    // quad_perm [2,3,0,1]
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xf, 0xf, false);   // row_half_mirror
+    if (G == 16) v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xf, 0xf, false);   // row_mirror
+    return v;
+}
 // Value of lane `l` (the same number in every lane) of v.
 __device__ __forceinline__ uint32_t wave_read_lane_u32(uint32_t v, int l)
 {

@@ -61,20 +61,21 @@ struct FlatChunk {
     V a[G];
 };
 
-// G lanes (a power of two <= 64, consecutive lanes of one wave) flatten the G
-// segments (p0, len, a) they hold, len < 2^24.  Every lane of the group calls it.
+// G lanes (8, 16 or the 64 of a wave; consecutive lanes of one wave) flatten the G segments
+// (p0, len, a) they hold, len < 2^24.  Every lane of the group calls it.
 template <int G, bool HAS_VAL, typename V, typename F>
 __device__ __forceinline__ void group_flat(FlatChunk<V, G> &c, int64_t p0, uint32_t len, V a,
                                            const int32_t *__restrict__ b_col, const V *__restrict__ b_val, F &f)
 {
     const int sub = lane_id() & (G - 1);
-    uint32_t incl = len;
-#pragma unroll
-    for (int off = 1; off < G; off <<= 1) {
-        const uint32_t o = __shfl_up(incl, off, G);
-        if (sub >= off) incl += o;
+    uint32_t incl, total;
+    if constexpr (G == WAVE) {
+        incl = wave_inclusive_scan_u32(len);
+        total = wave_read_lane_u32(incl, WAVE - 1);
+    } else {
+        incl = group_inclusive_scan_u32<G>(len, sub);
+        total = group_sum_u32<G>(len);
     }
-    const uint32_t total = __shfl(incl, G - 1, G);
     if (G == WAVE && total == 0) return;   // uniform for a whole wave
     c.excl[sub] = incl - len;
     c.pbase[sub] = (long long)p0 - (long long)(incl - len);
