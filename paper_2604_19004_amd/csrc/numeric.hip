@@ -685,7 +685,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     __shared__ uint32_t s_dpre[WORDS];
     __shared__ WgChunk<V, HV_THREADS> s_fc;
     __shared__ int s_wave[HV_THREADS / WAVE];
-    __shared__ uint32_t s_prodw[HV_MAXWIN];
+    __shared__ uint32_t s_pw[HV_MAXWIN + 1];   // s_pw[w]: products of the row in the windows before w
     __shared__ int s_ovf;
     __shared__ long long s_row;
     V *s_vals = reinterpret_cast<V *>(s_u);                                        // dense: WIN values
@@ -712,7 +712,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
             s_row = (long long)atomicAdd(queue, 1ull);
             s_ovf = 0;
         }
-        for (int w = tid; w < n_win; w += HV_THREADS) s_prodw[w] = 0u;
+        for (int w = tid; w <= n_win; w += HV_THREADS) s_pw[w] = 0u;
         __syncthreads();
         if (s_row >= count) break;   // uniform exit
         const int64_t r = count - 1 - s_row;   // from the end of the list, where the rows with the largest bounds are
@@ -754,8 +754,15 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                 }
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    if (d[i]) atomicAdd(&s_prodw[pw[i]], d[i]);
+                    if (d[i]) atomicAdd(&s_pw[pw[i] + 1], d[i]);
             }
+        }
+        __syncthreads();
+        {   // counts -> running sums (n_win <= HV_MAXWIN <= HV_THREADS: one window per thread)
+            const int mine = tid < n_win ? (int)s_pw[tid + 1] : 0;
+            int all;
+            const int before = block_exclusive_scan_i32<HV_THREADS>(mine, s_wave, all);
+            if (tid < n_win) s_pw[tid + 1] = (uint32_t)(before + mine);
         }
         __syncthreads();
 
@@ -763,21 +770,27 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
         // next pass from window `from` on: a window with more products than a sparse pass can stage (dense),
         // or a run of windows whose products fit the staging memory that is left beside the run's bitmap
         // (sparse); p0 == n_win when nothing is left
+        // Every wave plans for itself, 64 windows at a look: lane l holds the running sum behind window
+        // from + l, a ballot finds the first window with products, and since the products of a stretch
+        // grow with its length while its capacity shrinks, a second ballot finds how far the stretch goes.
+        const int lane = tid & (WAVE - 1);
         auto plan = [&](int from, int &p0, int &p1, bool &pdense) {
-            int x = from;
-            while (x < n_win && s_prodw[x] == 0) ++x;
-            p0 = x; p1 = x; pdense = false;
-            if (x >= n_win) return;
-            uint32_t sum = s_prodw[x];
-            pdense = sum > (uint32_t)sparse_cap(1);
-            p1 = x + 1;
-            if (!pdense) {
-                while (p1 < n_win) {
-                    const uint32_t nx = sum + s_prodw[p1];
-                    if (nx > (uint32_t)sparse_cap(p1 + 1 - x)) break;   // (a window beyond any capacity ends the run as well)
-                    sum = nx;
-                    ++p1;
-                }
+            p0 = n_win; p1 = n_win; pdense = false;
+            for (int x = from; x < n_win; x += WAVE) {   // uniform
+                const uint32_t before = s_pw[x];
+                const int wl = x + lane;   // this lane's window
+                const uint32_t upto = s_pw[(wl < n_win ? wl : n_win - 1) + 1] - before;   // products of [x, wl]
+                const unsigned long long some = __ballot(wl < n_win && upto > 0u);
+                if (some == 0ull) continue;
+                const int k = __ffsll((long long)some) - 1;   // windows x .. x+k-1 are empty
+                const unsigned long long fits = __ballot(lane >= k && wl < n_win && upto <= (uint32_t)sparse_cap(lane - k + 1));
+                // lanes k, k+1, ... that fit in a row: the stretch
+                const unsigned long long stop = ~(fits >> k);
+                const int run = stop ? __ffsll((long long)stop) - 1 : WAVE - k;
+                p0 = x + k;
+                pdense = run == 0;
+                p1 = p0 + (run == 0 ? 1 : run);
+                return;
             }
         };
         int w, w1;
