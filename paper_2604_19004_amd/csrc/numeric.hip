@@ -270,7 +270,9 @@ k_numeric_wave(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_c
 }
 
 // =================================================== workgroup helpers ====
-template <int THREADS>
+// s_wave: one word per wave.  With TRAILING_BARRIER = false the caller keeps s_wave untouched until
+// a later barrier of its own.
+template <int THREADS, bool TRAILING_BARRIER = true>
 __device__ __forceinline__ int block_exclusive_scan_i32(int v, int *s_wave, int &total)
 {
     const int inc = (int)wave_inclusive_scan_u32((uint32_t)v);
@@ -279,7 +281,7 @@ __device__ __forceinline__ int block_exclusive_scan_i32(int v, int *s_wave, int 
     __syncthreads();
     uint32_t tot;
     const int wave_off = (int)waves_before_u32<THREADS / WAVE>(reinterpret_cast<const uint32_t *>(s_wave), w, tot);
-    __syncthreads();
+    if (TRAILING_BARRIER) __syncthreads();
     total = (int)tot;
     return wave_off + inc - v;
 }
@@ -903,7 +905,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                     if (j < hwords) mine += __popc(s_hbm[j]);
                 }
                 int htotal;
-                int run = block_exclusive_scan_i32<HV_THREADS>(mine, s_wave, htotal);
+                int run = block_exclusive_scan_i32<HV_THREADS, false>(mine, s_wave, htotal);   // (barrier below)
                 for (int q = 0; q < wpt; ++q) {
                     const int j = tid * wpt + q;
                     if (j < hwords) { s_hpre[j] = (uint16_t)run; run += __popc(s_hbm[j]); }
@@ -921,14 +923,13 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                     if (at < staged) {
                         pc[i] = s_scol[at];
                         pv[i] = s_sval[at];
+                        s_sval[at] = (V)0;   // (htotal <= staged: the values of the output start from zero)
                         const uint32_t d = (uint32_t)(pc[i] - col0);
                         pr[i] = (int)s_hpre[d >> 5] + __popc(s_hbm[d >> 5] & ((1u << (d & 31u)) - 1u));
                     }
                 }
                 __syncthreads();
-                // the staging memory becomes the output of the pass: columns and zeroed values by rank
-                for (int i = tid; i < htotal; i += HV_THREADS) s_sval[i] = (V)0;
-                __syncthreads();
+                // the staging memory becomes the output of the pass: columns and values by rank
 #pragma unroll
                 for (int i = 0; i < HV_PPT; ++i) {
                     if (pc[i] >= 0) {
