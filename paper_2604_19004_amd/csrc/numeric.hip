@@ -661,13 +661,16 @@ k_numeric_hybrid(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
 // why sparse stretches are merged into few passes and why every pass spreads
 // its products over the whole workgroup.
 constexpr int HV_THREADS = 1024;
+constexpr int HV_REGION = 131072;                  // bytes of LDS that hold the accumulator of a pass
+constexpr int HV_WG_PER_CU = 1;                    // (two workgroups of half the size each measured 13 % slower)
 constexpr int HV_PPT = 8;                          // products of a sparse pass per thread, at most
 constexpr int HV_HCAP = HV_PPT * HV_THREADS;       // products one sparse pass takes at most: 8192
-constexpr int HV_MAXWIN = 512;                     // windows per row the kernel can plan for
+constexpr int HV_MAXWIN = 512;
+constexpr int ilog2_const(int x) { return x <= 1 ? 0 : 1 + ilog2_const(x >> 1); }                     // windows per row the kernel can plan for
 
 template <typename V>
 struct DenseCfg {
-    static constexpr int WIN = 131072 / (int)sizeof(V);   // 16384 columns (fp64), 32768 (fp32): 128 KB of values
+    static constexpr int WIN = HV_REGION / (int)sizeof(V);   // columns of a window: a region full of values
     static constexpr int WORDS = WIN / 32;
 };
 
@@ -682,14 +685,15 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     constexpr int WIN = DenseCfg<V>::WIN;
     constexpr int WORDS = DenseCfg<V>::WORDS;
     // one 128 KB region, used either as the dense window or as hash table + bucket counts
-    __shared__ __align__(16) unsigned char s_u[131072];
+    __shared__ __align__(16) unsigned char s_u[HV_REGION];
     __shared__ uint32_t s_dbm[WORDS];
-    __shared__ uint32_t s_dpre[WORDS];
     __shared__ WgChunk<V, HV_THREADS> s_fc;
     __shared__ int s_wave[HV_THREADS / WAVE];
     __shared__ uint32_t s_pw[HV_MAXWIN + 1];   // s_pw[w]: products of the row in the windows before w
     __shared__ int s_ovf;
     __shared__ long long s_row;
+    static_assert(WORDS <= HV_THREADS, "the prefix counts of a dense window reuse the chunk's array of prefix sums");
+    uint32_t *s_dpre = s_fc.excl;   // (free between the traversal of a pass and the next one)
     V *s_vals = reinterpret_cast<V *>(s_u);                                        // dense: WIN values
     // sparse pass: staged products (column, value) by product number; once every thread holds its
     // products in registers the same memory takes the output (columns, accumulated values) by rank
@@ -698,7 +702,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     // (4 + sizeof(V) bytes each, in multiples of one product per thread).
     constexpr int OV = WIN / 8 + WIN / 16;
     auto sparse_cap = [](int run) {
-        const int c = (131072 - run * OV) / (4 + (int)sizeof(V)) / HV_THREADS * HV_THREADS;
+        const int c = (HV_REGION - run * OV) / (4 + (int)sizeof(V)) / HV_THREADS * HV_THREADS;
         return c > HV_HCAP ? HV_HCAP : (c < 0 ? 0 : c);
     };
     int32_t *s_scol = reinterpret_cast<int32_t *>(s_u);
@@ -1004,7 +1008,7 @@ k_window_table(const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_c
 
 hipError_t launch_window_table(const Csr &B, int dtype, uint32_t *bw, int *n_win_out, int32_t *flags, hipStream_t s)
 {
-    const int win_log2 = dtype == OCEAN_F64 ? 14 : 15;
+    const int win_log2 = dtype == OCEAN_F64 ? ilog2_const(HV_REGION / 8) : ilog2_const(HV_REGION / 4);
     const int n_win = (int)((B.cols + (1ll << win_log2) - 1) >> win_log2);
     *n_win_out = n_win;
     if (B.rows == 0) return hipSuccess;
@@ -1014,9 +1018,11 @@ hipError_t launch_window_table(const Csr &B, int dtype, uint32_t *bw, int *n_win
     return hipGetLastError();
 }
 
+int heavy_workgroups_per_cu() { return HV_WG_PER_CU; }
+
 int dense_window_count(int64_t n_cols, int dtype)
 {
-    const int win_log2 = dtype == OCEAN_F64 ? 14 : 15;
+    const int win_log2 = dtype == OCEAN_F64 ? ilog2_const(HV_REGION / 8) : ilog2_const(HV_REGION / 4);
     return (int)((n_cols + (1ll << win_log2) - 1) >> win_log2);
 }
 

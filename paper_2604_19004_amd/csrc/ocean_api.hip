@@ -376,7 +376,8 @@ int run_numeric(Ctx &c, Work &w, const Csr &A, const Csr &B, int dtype, int gb_l
         } else if (b == NB_GLOBAL && c.bw != nullptr) {
             l.bw = c.bw;
             l.n_win = c.n_win;
-            l.n_wg = (int)(l.count < c.n_cu ? l.count : c.n_cu);
+            const int64_t resident = (int64_t)c.n_cu * heavy_workgroups_per_cu();
+            l.n_wg = (int)(l.count < resident ? l.count : resident);
             l.queue = &w.sc->queue[queue_base + 1];
         } else if (b == NB_GLOBAL) {
             int gbits = 10;

@@ -246,6 +246,7 @@ struct NumLaunch {
     int n_win;
 };
 hipError_t launch_window_table(const Csr &B, int dtype, uint32_t *bw, int *n_win_out, int32_t *flags, hipStream_t s);
+int heavy_workgroups_per_cu();   // workgroups of the column-window kernel that one compute unit holds
 int dense_window_count(int64_t n_cols, int dtype);
 hipError_t launch_numeric_bin(const Csr &A, const Csr &B, int dtype, const NumLaunch &l, int gb_log2, hipStream_t s);
 
