@@ -146,6 +146,8 @@ constexpr int BM_THREADS = 1024;
 constexpr int BM_WIN = 1 << 20;          // columns per window
 constexpr int BM_WORDS = BM_WIN / 32;    // 32768 words = 128 KB
 
+// ONE_WINDOW: B has at most BM_WIN columns, so every column id falls into the one window.
+template <bool ONE_WINDOW>
 __global__ void __launch_bounds__(BM_THREADS)
 k_symbolic_bitmap(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col,
                   const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_col,
@@ -172,8 +174,10 @@ k_symbolic_bitmap(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ 
                                                constexpr int U = sizeof(cj) / sizeof(cj[0]);
 #pragma unroll
                                                for (int u = 0; u < U; ++u) {
-                                                   const int64_t d = (int64_t)cj[u] - w0;
-                                                   if (cj[u] >= 0 && d >= 0 && d < BM_WIN) atomicOr(&s_bm[d >> 5], 1u << (d & 31));
+                                                   // (32-bit arithmetic: a column before the window wraps to a large number)
+                                                   const uint32_t d = (uint32_t)cj[u] - (uint32_t)w0;
+                                                   if (cj[u] >= 0 && (ONE_WINDOW || d < (uint32_t)BM_WIN))
+                                                       atomicOr(&s_bm[d >> 5], 1u << (d & 31u));
                                                }
                                            });
             __syncthreads();
@@ -210,8 +214,12 @@ hipError_t launch_symbolic_bin(const Csr &A, const Csr &B, const SymLaunch &l, i
     case SB_S16K: OCEAN_SYM_WG(14, 1024); break;
     case SB_S32K: OCEAN_SYM_WG(15, 1024); break;
     case SB_BITMAP:
-        hipLaunchKernelGGL(k_symbolic_bitmap, dim3((unsigned)n_wg), dim3(BM_THREADS), 0, s, A.rp, A.col, B.rp, B.col,
-                           l.rows, l.count, B.cols, queue, nnz_out);
+        if (B.cols <= BM_WIN)
+            hipLaunchKernelGGL(k_symbolic_bitmap<true>, dim3((unsigned)n_wg), dim3(BM_THREADS), 0, s, A.rp, A.col, B.rp,
+                               B.col, l.rows, l.count, B.cols, queue, nnz_out);
+        else
+            hipLaunchKernelGGL(k_symbolic_bitmap<false>, dim3((unsigned)n_wg), dim3(BM_THREADS), 0, s, A.rp, A.col, B.rp,
+                               B.col, l.rows, l.count, B.cols, queue, nnz_out);
         break;
     default: return hipErrorInvalidValue;
     }
