@@ -30,7 +30,7 @@ BIN_NAMES = ["k_numeric_group<8> (8 lanes/row, 32 slots)", "k_numeric_group<16> 
              "k_numeric_wave (256 slots)", "k_numeric_wg<9> (512 slots)", "k_numeric_wg<10> (1024 slots)",
              "k_numeric_wg<11> (2048 slots)", "k_numeric_wg<12> (4096 slots)", "k_numeric_wg<13> (8192 slots)",
              "rows up to 32768 entries", "k_numeric_heavy (column windows in LDS)"]
-HYBRID_BIN, LAST_BIN = 8, 9   # the last two bins of ocean_bin_layout
+LAST_BIN = 9   # the last bin of ocean_bin_layout
 
 
 def model_bytes(nnz_a, products, nnz_c, rows, v):
@@ -74,9 +74,11 @@ def run_workload(ob, W, torch, name, workflow, steps, warmup):
     # dominant numeric kernel
     b = max(range(ob.MAX_BINS), key=lambda i: bin_ms[i])
     if bin_ms[b] > 0:
-        # the rows of the last two bins run in one launch (timed under the last bin) when B's rows are sorted
-        merged = b == LAST_BIN and st["rows_per_bin"][HYBRID_BIN] > 0 and bin_ms[HYBRID_BIN] == 0.0
-        bins = [HYBRID_BIN, LAST_BIN] if merged else [b]
+        # when B's rows are sorted the rows of the last bins run in one launch, timed under the last bin: the bins
+        # right before it that hold rows but report no time of their own went with it
+        bins = [b]
+        while b == LAST_BIN and bins[0] > 0 and bin_ms[bins[0] - 1] == 0.0 and st["rows_per_bin"][bins[0] - 1] > 0:
+            bins.insert(0, bins[0] - 1)
         work = {k: sum(st[k][i] for i in bins) for k in ("bin_products", "bin_nnz_a", "bin_nnz_c")}
         units = work["bin_nnz_a"] + work["bin_products"] + work["bin_nnz_c"]
         achieved = units * (4 + v) / (bin_ms[b] * 1e-3) / 1e9

@@ -121,8 +121,9 @@ typedef struct ocean_stats {
     float total_ms;            /* host wall clock of the call */
     /* per numeric bin (first attempt only): kernel time from events on the call's stream, and the
      * work it covered: intermediate products, entries of A read, entries of C produced.  When B's rows
-     * are sorted the rows of the last two bins of ocean_bin_layout run in ONE launch of the
-     * column-window kernel: its time is reported under the last bin and bin_ms of the one before is 0. */
+     * are sorted and some row outgrows the largest LDS hash table, the rows of the last three bins of
+     * ocean_bin_layout run in ONE launch of the column-window kernel: its time is reported under the last
+     * bin and bin_ms of the two before it is 0. */
     float bin_ms[OCEAN_MAX_BINS];
     int64_t bin_products[OCEAN_MAX_BINS];
     int64_t bin_nnz_a[OCEAN_MAX_BINS];

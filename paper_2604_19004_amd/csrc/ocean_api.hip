@@ -338,6 +338,9 @@ int run_numeric(Ctx &c, Work &w, const Csr &A, const Csr &B, int dtype, int gb_l
                 int64_t max_cap_global, double global_coef, const int64_t *out_ptr, int32_t *out_col, void *out_val,
                 int32_t *row_nnz, int queue_base, int stage, bool time_bins)
 {
+    // With the window table, the column-window kernel takes every row beyond the 4096-slot table (measured:
+    // a row of the 8192-slot bin costs less there than a hash table of its own; smaller rows do not).
+    constexpr int HEAVY_FROM = NB_S8K;
     int64_t start[NB_COUNT + 1];
     start[0] = 0;
     for (int b = 0; b < NB_COUNT; ++b) start[b + 1] = start[b] + (int64_t)count[b];
@@ -352,17 +355,16 @@ int run_numeric(Ctx &c, Work &w, const Csr &A, const Csr &B, int dtype, int gb_l
         l.out_val = out_val;
         l.row_nnz = row_nnz;
         l.coef = global_coef;
-        if (c.bw != nullptr && b == NB_HYBRID) continue;   // went with the last bin, see below
+        if (c.bw != nullptr && b >= HEAVY_FROM && b < NB_GLOBAL) continue;   // went with the last bin, see below
         if (c.bw != nullptr && b == NB_GLOBAL) {
-            // the windowed kernel takes the rows of the last two bins in one launch (their row lists
-            // are adjacent), heaviest class first
-            l.rows = w.bin_rows + start[NB_HYBRID];
-            l.count = start[NB_GLOBAL + 1] - start[NB_HYBRID];
+            // the windowed kernel takes the rows of those bins in one launch (their row lists are adjacent)
+            l.rows = w.bin_rows + start[HEAVY_FROM];
+            l.count = start[NB_GLOBAL + 1] - start[HEAVY_FROM];
             // longest rows first (the kernel takes rows from the end of the list); skipped when memory is short
             const size_t sort_bytes = sort_rows_scratch_bytes(l.count);
             void *sort_tmp = sort_bytes ? c.alloc(sort_bytes) : nullptr;
             if (sort_tmp)
-                HIP_TRY(launch_sort_rows_by_products(w.prod, w.bin_rows + start[NB_HYBRID], l.count, sort_tmp, c.s));
+                HIP_TRY(launch_sort_rows_by_products(w.prod, w.bin_rows + start[HEAVY_FROM], l.count, sort_tmp, c.s));
         }
         if (l.count == 0) continue;
         if (b == NB_HYBRID) {
