@@ -7,7 +7,7 @@
 //   k_numeric_wg      one workgroup per row, keys + values + sort buffer in LDS (512..8192 slots)
 //   k_numeric_hybrid  32768 keys in LDS, values accumulated in a global slab (Section 3.3,
 //                     enhanced hash accumulator); rows leave sorted through an LDS bitmap rank
-//   k_numeric_heavy   rows beyond the 8192-slot table when B's rows are sorted: column windows, each
+//   k_numeric_heavy   rows beyond the 4096-slot table when B's rows are sorted: column windows, each
 //                     accumulated in LDS either densely (values + bitmap, Section 2.2 dense
 //                     accumulator iterated over the row's column range as in Section 3.2) or, for
 //                     sparse stretches of several windows, by staging the products in LDS and
@@ -634,7 +634,7 @@ k_numeric_hybrid(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
 }
 
 // ======================================================== heavy kernel ====
-// Rows whose output exceeds the 8192-slot LDS table, when B's rows are sorted.
+// Rows whose output exceeds the 4096-slot LDS table, when B's rows are sorted.
 // The column range is cut into windows of WIN columns and
 // bw[k*(n_win+1)+w] is the position in B's arrays of the first entry of row k
 // with column >= w*WIN, so any run of windows can be visited on its own.  One
@@ -642,31 +642,32 @@ k_numeric_hybrid(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
 // entries of that window), then walks the windows in order, carrying the
 // running output offset.  Both kinds of pass accumulate in LDS only, need no
 // hash table, and leave their entries in column order:
-//   * a window with more than 8192 products is accumulated densely (Section 2.2
-//     dense accumulator, iterated over the row's column range as in Section
-//     3.2): WIN values + a presence bitmap in LDS, one LDS add + one LDS or per
-//     product; the bitmap's prefix popcount places each present column at its
-//     sorted position;
+//   * a window with more products than a sparse pass can stage is accumulated
+//     densely (Section 2.2 dense accumulator, iterated over the row's column
+//     range as in Section 3.2): WIN values + a presence bitmap in LDS, one LDS
+//     add + one LDS or per product; the bitmap's prefix popcount places each
+//     present column at its sorted position;
 //   * consecutive windows whose products fit the staging memory left beside
-//     their bitmap (a sparse stretch: up to 8192 products over 10 windows, fewer
-//     over more) share one pass in the manner of an
+//     their bitmap (a sparse stretch: up to 10240 products over 2 windows, 8192
+//     over 10, fewer over more) share one pass in the manner of an
 //     expand-sort-compress accumulator whose sort is a bitmap rank: every
 //     product is written to LDS at its own number (no atomics) and marks its
 //     column in a bitmap over the stretch; the prefix popcount of the bitmap is
 //     the position of each column in the output, so a second sweep over the
 //     staged products adds each value at its column's rank.  No probing, no
 //     compare-and-swap, no divergence.
-// What bounds this path is the latency of its chain of dependent accesses
-// (entry -> window boundary -> products -> LDS), paid once per pass, which is
-// why sparse stretches are merged into few passes and why every pass spreads
-// its products over the whole workgroup.
+// More than half of the kernel's time is the gather of B's entries, which runs
+// at what the memory system gives for pieces of rows this short; the rest is
+// instruction issue of the work every pass repeats (planning, prefix sums,
+// barriers), which is why sparse stretches are merged into few passes and why
+// every pass spreads its products over the whole workgroup.
 constexpr int HV_THREADS = 1024;
 constexpr int HV_REGION = 131072;                  // bytes of LDS that hold the accumulator of a pass
 constexpr int HV_WG_PER_CU = 1;                    // (two workgroups of half the size each measured 13 % slower)
-constexpr int HV_PPT = 8;                          // products of a sparse pass per thread, at most
-constexpr int HV_HCAP = HV_PPT * HV_THREADS;       // products one sparse pass takes at most: 8192
-constexpr int HV_MAXWIN = 512;
-constexpr int ilog2_const(int x) { return x <= 1 ? 0 : 1 + ilog2_const(x >> 1); }                     // windows per row the kernel can plan for
+constexpr int HV_PPT = 10;                         // products of a sparse pass per thread, at most
+constexpr int HV_HCAP = HV_PPT * HV_THREADS;       // products one sparse pass takes at most: 10240
+constexpr int HV_MAXWIN = 512;                     // windows per row the kernel can plan for
+constexpr int ilog2_const(int x) { return x <= 1 ? 0 : 1 + ilog2_const(x >> 1); }
 
 template <typename V>
 struct DenseCfg {

@@ -2,21 +2,21 @@
 // nested loops, paper Section 2.1) by a whole workgroup, one wave or a group
 // of lanes.
 //
-// The kernels are bound by instruction issue and by dependent-access latency,
-// not by bandwidth, so what matters is that all 64 lanes of a wave carry a
-// product in every instruction and that independent memory operations are in
-// flight together.  Rows of B referenced by one row of A differ wildly in
-// length on power-law matrices; a fixed "lanes per row of B" mapping leaves
-// most lanes idle.  Therefore:
+// What matters is that all 64 lanes of a wave carry a product in every
+// instruction and that independent memory operations are in flight together.
+// Rows of B referenced by one row of A differ wildly in length on power-law
+// matrices; a fixed "lanes per row of B" mapping leaves most lanes idle.
+// Therefore:
 //   * a workgroup FLATTENS the products of a row: it takes up to THREADS
-//     entries A_ik, prefix-sums the lengths of their rows of B, and thread t
-//     then handles products t, t+THREADS, ... of the concatenated segments,
-//     finding the entry of a product by a binary search over the prefix sums
-//     kept in LDS (consecutive lanes mostly fall into one row of B, so the
-//     loads stay coalesced);
-//   * a wave or a 16-lane group that owns a short row does the same over its
-//     64 or 16 entries; rows of B of T_LONG or more entries are walked 64-wide
-//     there.
+//     entries A_ik, prefix-sums the lengths of their rows of B, and every wave
+//     handles one contiguous span of the concatenated segments, 64 consecutive
+//     products per load instruction (consecutive lanes mostly fall into one row
+//     of B, so the loads stay coalesced); the entry of a product is found by a
+//     bitmap rank or a binary search over the prefix sums kept in LDS;
+//   * a wave or a group of 8 or 16 lanes that owns a short row does the same
+//     over its 64, 8 or 16 entries; rows of B of T_LONG or more entries are
+//     walked 64-wide there.
+// Prefix sums inside a wave use DPP moves, not LDS permutes.
 // Products reach the accumulator in batches: f(cj, cv) receives U column ids
 // (negative = none) and values a*b per lane, so that the accumulator's own
 // dependent LDS round trips (hash probes) overlap across the batch.
