@@ -664,8 +664,8 @@ k_numeric_hybrid(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
 constexpr int HV_THREADS = 1024;
 constexpr int HV_REGION = 131072;                  // bytes of LDS that hold the accumulator of a pass
 constexpr int HV_WG_PER_CU = 1;                    // (two workgroups of half the size each measured 13 % slower)
-constexpr int HV_PPT = 10;                         // products of a sparse pass per thread, at most
-constexpr int HV_HCAP = HV_PPT * HV_THREADS;       // products one sparse pass takes at most: 10240
+constexpr int HV_PPT = 8;                          // products of a sparse pass per thread, at most
+constexpr int HV_HCAP = HV_PPT * HV_THREADS;       // products one sparse pass takes at most: 8192
 constexpr int HV_MAXWIN = 512;                     // windows per row the kernel can plan for
 constexpr int ilog2_const(int x) { return x <= 1 ? 0 : 1 + ilog2_const(x >> 1); }
 
@@ -857,52 +857,22 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                     }
                 }
             };
-            for (int64_t base = 0; base < ne; base += HV_THREADS) {
-                int32_t k = ek;
-                V a = ea;
-                const bool have = base + tid < ne;
-                if (base > 0 && have) { k = a_col[e0 + base + tid]; a = a_val[e0 + base + tid]; }
-                uint32_t c0 = c_lo, c1 = c_hi;
-                if (base > 0) {
-                    c0 = c1 = 0;
-                    if (have) {
-                        const uint32_t *t = bw + (size_t)k * stride;
-                        c0 = t[w];
-                        c1 = t[w1];
-                    }
-                }
-                const int64_t left = ne - base;
-                staged += wg_flat_chunk<HV_THREADS, true>(s_fc, left < HV_THREADS ? (int)left : HV_THREADS, (int64_t)c0,
-                                                          c1 - c0, a, b_col, b_val, f);
-            }
-            if (dense) {
-                // ---- dense window -> output, in column order
-                const uint32_t word = tid < WORDS ? s_dbm[tid] : 0u;
-                int wtotal;
-                const int ex = block_exclusive_scan_i32<HV_THREADS>(__popc(word), s_wave, wtotal);
-                if (tid < WORDS) s_dpre[tid] = (uint32_t)ex;
-                __syncthreads();
-                // Thread t looks at columns t, t + 1024, ...: in every step the lanes of a wave read
-                // consecutive values (no LDS bank conflicts) and the present ones among them go to
-                // consecutive places of the output (coalesced stores).
-                constexpr int STEPS = WIN / HV_THREADS;   // 16 (fp64) or 32 (fp32)
-#pragma unroll 4
-                for (int i = 0; i < STEPS; ++i) {
-                    const int j = i * HV_THREADS + tid;
-                    const uint32_t wbits = s_dbm[j >> 5];
-                    if ((wbits >> (j & 31)) & 1u) {
-                        const long long rank = done + (long long)s_dpre[j >> 5] + __popc(wbits & ((1u << (j & 31)) - 1u));
-                        const V val = s_vals[j];
-                        s_vals[j] = (V)0;
-                        if (rank < cap) { out_col[o + rank] = col0 + j; out_val[o + rank] = val; }
-                    }
-                }
-                __syncthreads();
-                if (tid < WORDS) s_dbm[tid] = 0u;
-                done += wtotal;
-                __syncthreads();
-            } else {
-                // ---- sparse pass: rank of every column = set bits below it in the bitmap of the stretch
+            if (!dense && ne <= HV_THREADS) {
+                // ---- sparse pass of a row whose entries fit one chunk: no staging, every product stays in the
+                // registers of the thread that fetched it, from the sweep that marks the columns to the sweep
+                // that adds the values at their ranks
+                constexpr int NBATCH = HV_PPT / FLAT_U;
+                static_assert(HV_PPT % FLAT_U == 0, "whole batches");
+                int32_t kc[HV_PPT];
+                V kv[HV_PPT];
+                auto mark = [&](int32_t col) {
+                    const uint32_t d = (uint32_t)(col - col0);
+                    if (d < (uint32_t)hwords * 32u) atomicOr(&s_hbm[d >> 5], 1u << (d & 31u));   // holds by construction
+                };
+                bool fits;
+                wg_flat_chunk_keep<HV_THREADS, NBATCH>(s_fc, (int)ne, (int64_t)c_lo, c_hi - c_lo, ea, b_col, b_val, kc, kv,
+                                                       mark, fits);
+                if (!fits && tid == 0) s_ovf = 1;   // cannot happen: passes are planned from the counts
                 const int wpt = (hwords + HV_THREADS - 1) / HV_THREADS;   // bitmap words per thread (consecutive)
                 int mine = 0;
                 for (int q = 0; q < wpt; ++q) {
@@ -915,31 +885,15 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                     const int j = tid * wpt + q;
                     if (j < hwords) { s_hpre[j] = (uint16_t)run; run += __popc(s_hbm[j]); }
                 }
+                for (int i = tid; i < htotal; i += HV_THREADS) s_sval[i] = (V)0;   // (htotal <= products <= scap)
                 __syncthreads();
-                // every thread takes its share of the staged products into registers, with their ranks
-                if (staged > (uint32_t)scap) staged = scap;   // cannot happen: passes are planned from the counts
-                int32_t pc[HV_PPT];
-                V pv[HV_PPT];
-                int pr[HV_PPT];
 #pragma unroll
                 for (int i = 0; i < HV_PPT; ++i) {
-                    const uint32_t at = (uint32_t)i * HV_THREADS + tid;
-                    pc[i] = -1; pv[i] = V(); pr[i] = 0;
-                    if (at < staged) {
-                        pc[i] = s_scol[at];
-                        pv[i] = s_sval[at];
-                        s_sval[at] = (V)0;   // (htotal <= staged: the values of the output start from zero)
-                        const uint32_t d = (uint32_t)(pc[i] - col0);
-                        pr[i] = (int)s_hpre[d >> 5] + __popc(s_hbm[d >> 5] & ((1u << (d & 31u)) - 1u));
-                    }
-                }
-                __syncthreads();
-                // the staging memory becomes the output of the pass: columns and values by rank
-#pragma unroll
-                for (int i = 0; i < HV_PPT; ++i) {
-                    if (pc[i] >= 0) {
-                        s_scol[pr[i]] = pc[i];          // products of one column all write the same id
-                        lds_add(&s_sval[pr[i]], pv[i]);
+                    const uint32_t d = (uint32_t)(kc[i] - col0);
+                    if (kc[i] >= 0 && d < (uint32_t)hwords * 32u) {
+                        const int rank = (int)s_hpre[d >> 5] + __popc(s_hbm[d >> 5] & ((1u << (d & 31u)) - 1u));
+                        s_scol[rank] = kc[i];           // products of one column all write the same id
+                        lds_add(&s_sval[rank], kv[i]);
                     }
                 }
                 __syncthreads();
@@ -951,6 +905,102 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                 }
                 done += htotal;
                 __syncthreads();
+            } else {
+                for (int64_t base = 0; base < ne; base += HV_THREADS) {
+                    int32_t k = ek;
+                    V a = ea;
+                    const bool have = base + tid < ne;
+                    if (base > 0 && have) { k = a_col[e0 + base + tid]; a = a_val[e0 + base + tid]; }
+                    uint32_t c0 = c_lo, c1 = c_hi;
+                    if (base > 0) {
+                        c0 = c1 = 0;
+                        if (have) {
+                            const uint32_t *t = bw + (size_t)k * stride;
+                            c0 = t[w];
+                            c1 = t[w1];
+                        }
+                    }
+                    const int64_t left = ne - base;
+                    staged += wg_flat_chunk<HV_THREADS, true>(s_fc, left < HV_THREADS ? (int)left : HV_THREADS, (int64_t)c0,
+                                                              c1 - c0, a, b_col, b_val, f);
+                }
+                if (dense) {
+                    // ---- dense window -> output, in column order
+                    const uint32_t word = tid < WORDS ? s_dbm[tid] : 0u;
+                    int wtotal;
+                    const int ex = block_exclusive_scan_i32<HV_THREADS>(__popc(word), s_wave, wtotal);
+                    if (tid < WORDS) s_dpre[tid] = (uint32_t)ex;
+                    __syncthreads();
+                    // Thread t looks at columns t, t + 1024, ...: in every step the lanes of a wave read
+                    // consecutive values (no LDS bank conflicts) and the present ones among them go to
+                    // consecutive places of the output (coalesced stores).
+                    constexpr int STEPS = WIN / HV_THREADS;   // 16 (fp64) or 32 (fp32)
+    #pragma unroll 4
+                    for (int i = 0; i < STEPS; ++i) {
+                        const int j = i * HV_THREADS + tid;
+                        const uint32_t wbits = s_dbm[j >> 5];
+                        if ((wbits >> (j & 31)) & 1u) {
+                            const long long rank = done + (long long)s_dpre[j >> 5] + __popc(wbits & ((1u << (j & 31)) - 1u));
+                            const V val = s_vals[j];
+                            s_vals[j] = (V)0;
+                            if (rank < cap) { out_col[o + rank] = col0 + j; out_val[o + rank] = val; }
+                        }
+                    }
+                    __syncthreads();
+                    if (tid < WORDS) s_dbm[tid] = 0u;
+                    done += wtotal;
+                    __syncthreads();
+                } else {
+                    // ---- sparse pass: rank of every column = set bits below it in the bitmap of the stretch
+                    const int wpt = (hwords + HV_THREADS - 1) / HV_THREADS;   // bitmap words per thread (consecutive)
+                    int mine = 0;
+                    for (int q = 0; q < wpt; ++q) {
+                        const int j = tid * wpt + q;
+                        if (j < hwords) mine += __popc(s_hbm[j]);
+                    }
+                    int htotal;
+                    int run = block_exclusive_scan_i32<HV_THREADS, false>(mine, s_wave, htotal);   // (barrier below)
+                    for (int q = 0; q < wpt; ++q) {
+                        const int j = tid * wpt + q;
+                        if (j < hwords) { s_hpre[j] = (uint16_t)run; run += __popc(s_hbm[j]); }
+                    }
+                    __syncthreads();
+                    // every thread takes its share of the staged products into registers, with their ranks
+                    if (staged > (uint32_t)scap) staged = scap;   // cannot happen: passes are planned from the counts
+                    int32_t pc[HV_PPT];
+                    V pv[HV_PPT];
+                    int pr[HV_PPT];
+    #pragma unroll
+                    for (int i = 0; i < HV_PPT; ++i) {
+                        const uint32_t at = (uint32_t)i * HV_THREADS + tid;
+                        pc[i] = -1; pv[i] = V(); pr[i] = 0;
+                        if (at < staged) {
+                            pc[i] = s_scol[at];
+                            pv[i] = s_sval[at];
+                            s_sval[at] = (V)0;   // (htotal <= staged: the values of the output start from zero)
+                            const uint32_t d = (uint32_t)(pc[i] - col0);
+                            pr[i] = (int)s_hpre[d >> 5] + __popc(s_hbm[d >> 5] & ((1u << (d & 31u)) - 1u));
+                        }
+                    }
+                    __syncthreads();
+                    // the staging memory becomes the output of the pass: columns and values by rank
+    #pragma unroll
+                    for (int i = 0; i < HV_PPT; ++i) {
+                        if (pc[i] >= 0) {
+                            s_scol[pr[i]] = pc[i];          // products of one column all write the same id
+                            lds_add(&s_sval[pr[i]], pv[i]);
+                        }
+                    }
+                    __syncthreads();
+                    const long long room = cap - done;
+                    const int n_out = (long long)htotal < room ? htotal : (room > 0 ? (int)room : 0);
+                    for (int i = tid; i < n_out; i += HV_THREADS) {
+                        out_col[o + done + i] = s_scol[i];
+                        out_val[o + done + i] = s_sval[i];
+                    }
+                    done += htotal;
+                    __syncthreads();
+                }
             }
             c_lo = c_hi; c_hi = n_hi;
             w = nx0; w1 = nx1; dense = nxdense;

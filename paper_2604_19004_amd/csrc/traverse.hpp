@@ -360,6 +360,99 @@ __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS> &c, int ne
     return total;
 }
 
+// The same flattening for a chunk whose products the caller keeps: every thread ends up with its
+// share of the products (column id, a*b) in registers, kc[i] < 0 where it has none, and mark(col)
+// has been called once per product.  Needs at most NB * FLAT_U products per thread
+// (total <= NB * FLAT_U * THREADS) and total <= WgChunk::RANK_CAP; otherwise nothing is fetched and
+// fits = false.  Every thread calls it; ends with a barrier; returns the number of products.
+template <int THREADS, int NB, typename V, typename M>
+__device__ __forceinline__ uint32_t wg_flat_chunk_keep(WgChunk<V, THREADS> &c, int nent, int64_t p0, uint32_t len, V a,
+                                                   const int32_t *__restrict__ b_col, const V *__restrict__ b_val,
+                                                   int32_t (&kc)[NB * FLAT_U], V (&kv)[NB * FLAT_U], M &mark,
+                                                   bool &fits)
+{
+    constexpr int NW = THREADS / WAVE;
+    constexpr uint32_t RANK_CAP = WgChunk<V, THREADS>::RANK_CAP;
+    constexpr int START_WORDS = THREADS / 2 + 8;
+    const int tid = threadIdx.x;
+    const int lane = tid & (WAVE - 1), wave = tid / WAVE;
+    if (tid < START_WORDS) c.start[tid] = 0u;
+    uint32_t incl = wave_inclusive_scan_u32(len);
+    const unsigned long long live = __ballot(len > 0);
+    if (lane == WAVE - 1) { c.wsum[wave] = incl; c.wcnt[wave] = (uint32_t)__popcll(live); }
+#pragma unroll
+    for (int i = 0; i < NB * FLAT_U; ++i) { kc[i] = -1; kv[i] = V(); }
+    __syncthreads();
+    uint32_t total, ctotal;
+    const uint32_t before = waves_before_u32<NW>(c.wsum, wave, total);
+    const uint32_t cbefore = waves_before_u32<NW>(c.wcnt, wave, ctotal);
+    incl += before;
+    fits = total <= RANK_CAP && total <= (uint32_t)(NB * FLAT_U * THREADS);
+    if (total == 0 || !fits) {   // uniform
+        __syncthreads();
+        return total;
+    }
+    const uint32_t ex = incl - len;
+    if (len > 0) {
+        const uint32_t ce = cbefore + __builtin_amdgcn_mbcnt_hi((uint32_t)(live >> 32),
+                                                                __builtin_amdgcn_mbcnt_lo((uint32_t)live, 0u));
+        c.pbase[ce] = (long long)p0 - (long long)ex;
+        c.a[ce] = a;
+        atomicOr(&c.start[ex >> 5], 1u << (ex & 31u));
+    }
+    __syncthreads();
+    const uint32_t span = ((total + NW - 1) / NW + (WAVE - 1)) & ~(uint32_t)(WAVE - 1);   // <= NB * FLAT_U * WAVE
+    const uint32_t qs = (uint32_t)wave * span;
+    const uint32_t qe = qs + span < total ? qs + span : total;
+    if (qs < total) {   // uniform for the wave
+        const unsigned long long *marks = reinterpret_cast<const unsigned long long *>(c.start);
+        uint32_t run = 0;
+        for (uint32_t j = (uint32_t)lane; j < (qs >> 6); j += WAVE) run += (uint32_t)__popcll(marks[j]);
+        run = wave_sum_u32(run);
+        const unsigned long long upto = (2ull << lane) - 1ull;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const uint32_t q0 = qs + (uint32_t)b * WAVE * FLAT_U;
+            if (q0 < qe) {   // uniform for the wave
+                unsigned long long m[FLAT_U];
+#pragma unroll
+                for (int u = 0; u < FLAT_U; ++u) m[u] = marks[(q0 >> 6) + u];
+                bool ok[FLAT_U];
+                int cp[FLAT_U];
+#pragma unroll
+                for (int u = 0; u < FLAT_U; ++u) {
+                    const uint32_t q = q0 + u * WAVE + lane;
+                    ok[u] = q < qe;
+                    const uint32_t rank = run + (uint32_t)__popcll(m[u] & upto);
+                    run += (uint32_t)__popcll(m[u]);
+                    cp[u] = ok[u] ? (int)rank - 1 : 0;
+                }
+                long long pb[FLAT_U];
+                V av[FLAT_U];
+#pragma unroll
+                for (int u = 0; u < FLAT_U; ++u) {
+                    pb[u] = c.pbase[cp[u]];
+                    av[u] = c.a[cp[u]];
+                }
+                V cb[FLAT_U];
+#pragma unroll
+                for (int u = 0; u < FLAT_U; ++u) {
+                    const int64_t p = pb[u] + (long long)(q0 + u * WAVE + lane);
+                    kc[b * FLAT_U + u] = ok[u] ? b_col[p] : -1;
+                    cb[u] = ok[u] ? b_val[p] : V();
+                }
+#pragma unroll
+                for (int u = 0; u < FLAT_U; ++u) {
+                    kv[b * FLAT_U + u] = av[u] * cb[u];
+                    if (kc[b * FLAT_U + u] >= 0) mark(kc[b * FLAT_U + u]);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    return total;
+}
+
 // Workgroup version of the row traversal: chunks of THREADS entries of A, each flattened over the
 // whole workgroup.  Every thread of the (1-D) workgroup must call it.  seg(k, p0, len) gives the
 // segment of B's arrays that entry k expands to.  Ends with a barrier.
