@@ -176,8 +176,11 @@ k_symbolic_bitmap(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ 
                                                for (int u = 0; u < U; ++u) {
                                                    // (32-bit arithmetic: a column before the window wraps to a large number)
                                                    const uint32_t d = (uint32_t)cj[u] - (uint32_t)w0;
+                                                   // Only the number of set bits matters, so neighbouring columns (the
+                                                   // sorted entries of one row of B in neighbouring lanes) go to
+                                                   // neighbouring words, i.e. different LDS banks, not to one word.
                                                    if (cj[u] >= 0 && (ONE_WINDOW || d < (uint32_t)BM_WIN))
-                                                       atomicOr(&s_bm[d >> 5], 1u << (d & 31u));
+                                                       atomicOr(&s_bm[d & (uint32_t)(BM_WORDS - 1)], 1u << (d / (uint32_t)BM_WORDS));
                                                }
                                            });
             __syncthreads();
