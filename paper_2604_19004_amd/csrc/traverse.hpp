@@ -151,7 +151,7 @@ struct WgChunk {
     V a[THREADS];
     union alignas(8) {
         uint16_t first[THREADS + 2];       // entry of the first product of every block of 2^bshift products
-        uint32_t start[THREADS / 2 + 8];   // bit q set: a segment starts at product q (RANK_CAP bits + padding)
+        uint32_t start[THREADS / 2 + 32];  // bit q set: a segment starts at product q (RANK_CAP bits + padding for batches of up to 16 per lane)
     };
     uint32_t wsum[THREADS / WAVE];
     uint32_t wcnt[THREADS / WAVE];
@@ -172,16 +172,17 @@ struct WgChunk {
 //     beforehand to the few entries a batch of 256 can touch: a table built once per chunk gives
 //     the entry of the first product of every block of products.  The searches of a batch have
 //     the same, wave-uniform number of steps and run interleaved.
-// The products of one chunk must number less than 2^31.
+// WU is the number of products per lane and batch.  The products of one chunk must number less
+// than 2^31.
 // Every thread calls it; the chunk arrays must be free on entry (the call ends with a barrier).
 // Returns the number of products of the chunk.
-template <int THREADS, bool HAS_VAL, typename V, typename F>
+template <int THREADS, bool HAS_VAL, int WU = FLAT_U, typename V, typename F>
 __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS> &c, int nent, int64_t p0, uint32_t len, V a,
                                               const int32_t *__restrict__ b_col, const V *__restrict__ b_val, F &f)
 {
     constexpr int NW = THREADS / WAVE;
     constexpr uint32_t RANK_CAP = WgChunk<V, THREADS>::RANK_CAP;
-    constexpr int START_WORDS = THREADS / 2 + 8;
+    constexpr int START_WORDS = THREADS / 2 + 32;
     static_assert(THREADS <= 1024 && START_WORDS <= THREADS, "entry ids are kept in 16 bits and one block table entry per thread");
     const int tid = threadIdx.x;
     const int lane = tid & (WAVE - 1), wave = tid / WAVE;
@@ -202,9 +203,9 @@ __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS> &c, int ne
     const uint32_t span = ((total + NW - 1) / NW + (WAVE - 1)) & ~(uint32_t)(WAVE - 1);
     const uint32_t qs = (uint32_t)wave * span;
     const uint32_t qe = qs + span < total ? qs + span : total;
-    int32_t cj[FLAT_U];
-    V cb[FLAT_U];   // values of B
-    int cp[FLAT_U];
+    int32_t cj[WU];
+    V cb[WU];   // values of B
+    int cp[WU];
     if (total <= RANK_CAP) {   // uniform
         const uint32_t ex = incl - len;
         if (len > 0) {
@@ -222,17 +223,17 @@ __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS> &c, int ne
             for (uint32_t j = (uint32_t)lane; j < (qs >> 6); j += WAVE) run += (uint32_t)__popcll(marks[j]);
             run = wave_sum_u32(run);
             const unsigned long long upto = (2ull << lane) - 1ull;   // this lane's product and those before it
-            for (uint32_t q0 = qs; q0 < qe; q0 += WAVE * FLAT_U) {
-                // Every stage of a batch is straight-line code over its FLAT_U products, with
+            for (uint32_t q0 = qs; q0 < qe; q0 += WAVE * WU) {
+                // Every stage of a batch is straight-line code over its WU products, with
                 // unconditional reads (a lane past the end of the span reads product 0, which exists), so
                 // that the reads of one stage are in flight together.
-                unsigned long long m[FLAT_U];
+                unsigned long long m[WU];
 #pragma unroll
-                for (int u = 0; u < FLAT_U; ++u) m[u] = marks[(q0 >> 6) + u];   // one address for the wave
-                bool ok[FLAT_U];
-                uint32_t qq[FLAT_U];
+                for (int u = 0; u < WU; ++u) m[u] = marks[(q0 >> 6) + u];   // one address for the wave
+                bool ok[WU];
+                uint32_t qq[WU];
 #pragma unroll
-                for (int u = 0; u < FLAT_U; ++u) {
+                for (int u = 0; u < WU; ++u) {
                     const uint32_t q = q0 + u * WAVE + lane;
                     ok[u] = q < qe;
                     const uint32_t rank = run + (uint32_t)__popcll(m[u] & upto);   // >= 1: product 0 starts a segment
@@ -240,26 +241,26 @@ __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS> &c, int ne
                     cp[u] = ok[u] ? (int)rank - 1 : 0;
                     qq[u] = ok[u] ? q : 0u;
                 }
-                long long pb[FLAT_U];
-                V av[FLAT_U];
+                long long pb[WU];
+                V av[WU];
 #pragma unroll
-                for (int u = 0; u < FLAT_U; ++u) {
+                for (int u = 0; u < WU; ++u) {
                     pb[u] = c.pbase[cp[u]];
                     if constexpr (HAS_VAL) av[u] = c.a[cp[u]];
                 }
 #pragma unroll
-                for (int u = 0; u < FLAT_U; ++u) {
+                for (int u = 0; u < WU; ++u) {
                     const int64_t p = pb[u] + (long long)qq[u];
                     cj[u] = ok[u] ? b_col[p] : -1;
                     if constexpr (HAS_VAL) cb[u] = ok[u] ? b_val[p] : V();
                 }
-                V cv[FLAT_U];
+                V cv[WU];
 #pragma unroll
-                for (int u = 0; u < FLAT_U; ++u) {
+                for (int u = 0; u < WU; ++u) {
                     if constexpr (HAS_VAL) cv[u] = av[u] * cb[u];
                     else cv[u] = V();
                 }
-                if constexpr (std::is_invocable_v<F &, int32_t(&)[FLAT_U], V(&)[FLAT_U], uint32_t>) f(cj, cv, q0);
+                if constexpr (std::is_invocable_v<F &, int32_t(&)[WU], V(&)[WU], uint32_t>) f(cj, cv, q0);
                 else f(cj, cv);
             }
         }
@@ -292,19 +293,19 @@ __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS> &c, int ne
     }
     __syncthreads();
     if (qs < total) {   // uniform for the wave
-        auto fetch = [&](uint32_t q0, int32_t (&fj)[FLAT_U], V (&fb)[FLAT_U], int (&fp)[FLAT_U]) {
-            const uint32_t qlast = q0 + WAVE * FLAT_U - 1 < qe - 1 ? q0 + WAVE * FLAT_U - 1 : qe - 1;
+        auto fetch = [&](uint32_t q0, int32_t (&fj)[WU], V (&fb)[WU], int (&fp)[WU]) {
+            const uint32_t qlast = q0 + WAVE * WU - 1 < qe - 1 ? q0 + WAVE * WU - 1 : qe - 1;
             const int lo = c.first[q0 >> bshift];
             const int hi = c.first[(qlast >> bshift) + 1];   // the entry of a later product, or the last entry
             const int width = __builtin_amdgcn_readfirstlane(hi - lo);
 #pragma unroll
-            for (int u = 0; u < FLAT_U; ++u) fp[u] = lo;
+            for (int u = 0; u < WU; ++u) fp[u] = lo;
             if (!HAS_VAL && width == 0) {
                 // symbolic pass (whole rows of B, often long): the batch lies in one row of B, no search,
                 // one read of the segment's base
                 const long long base = c.pbase[lo];
 #pragma unroll
-                for (int u = 0; u < FLAT_U; ++u) {
+                for (int u = 0; u < WU; ++u) {
                     const uint32_t q = q0 + u * WAVE + lane;
                     const bool ok = q < qe;
                     const int64_t p = base + (long long)q;
@@ -316,24 +317,24 @@ __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS> &c, int ne
             }
             for (int step = width > 0 ? 1 << (31 - __clz(width)) : 0; step > 0; step >>= 1) {
                 // the reads of one step are unconditional (index clamped) so that they are issued together
-                int t[FLAT_U];
-                uint32_t ex[FLAT_U];
+                int t[WU];
+                uint32_t ex[WU];
 #pragma unroll
-                for (int u = 0; u < FLAT_U; ++u) {
+                for (int u = 0; u < WU; ++u) {
                     t[u] = fp[u] + step;
                     ex[u] = c.excl[t[u] <= hi ? t[u] : hi];
                 }
 #pragma unroll
-                for (int u = 0; u < FLAT_U; ++u) {
+                for (int u = 0; u < WU; ++u) {
                     const uint32_t q = q0 + u * WAVE + lane;
                     fp[u] = (t[u] <= hi && ex[u] <= q) ? t[u] : fp[u];
                 }
             }
-            long long pb[FLAT_U];
+            long long pb[WU];
 #pragma unroll
-            for (int u = 0; u < FLAT_U; ++u) pb[u] = c.pbase[fp[u]];   // (reads of LDS together, ahead of the loads)
+            for (int u = 0; u < WU; ++u) pb[u] = c.pbase[fp[u]];   // (reads of LDS together, ahead of the loads)
 #pragma unroll
-            for (int u = 0; u < FLAT_U; ++u) {
+            for (int u = 0; u < WU; ++u) {
                 const uint32_t q = q0 + u * WAVE + lane;
                 const bool ok = q < qe;
                 const int64_t p = pb[u] + (long long)q;
@@ -342,17 +343,17 @@ __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS> &c, int ne
                 else fb[u] = V();
             }
         };
-        for (uint32_t q0 = qs; q0 < qe; q0 += WAVE * FLAT_U) {
+        for (uint32_t q0 = qs; q0 < qe; q0 += WAVE * WU) {
             fetch(q0, cj, cb, cp);
-            V cv[FLAT_U];
+            V cv[WU];
 #pragma unroll
-            for (int u = 0; u < FLAT_U; ++u) {
+            for (int u = 0; u < WU; ++u) {
                 if constexpr (HAS_VAL) cv[u] = c.a[cp[u]] * cb[u];
                 else cv[u] = V();
             }
             // an accumulator may ask for the number of the batch's first product inside the chunk: the
             // product of lane l, position u is number q0 + u*64 + l
-            if constexpr (std::is_invocable_v<F &, int32_t(&)[FLAT_U], V(&)[FLAT_U], uint32_t>) f(cj, cv, q0);
+            if constexpr (std::is_invocable_v<F &, int32_t(&)[WU], V(&)[WU], uint32_t>) f(cj, cv, q0);
             else f(cj, cv);
         }
     }
@@ -373,7 +374,7 @@ __device__ __forceinline__ uint32_t wg_flat_chunk_keep(WgChunk<V, THREADS> &c, i
 {
     constexpr int NW = THREADS / WAVE;
     constexpr uint32_t RANK_CAP = WgChunk<V, THREADS>::RANK_CAP;
-    constexpr int START_WORDS = THREADS / 2 + 8;
+    constexpr int START_WORDS = THREADS / 2 + 32;
     const int tid = threadIdx.x;
     const int lane = tid & (WAVE - 1), wave = tid / WAVE;
     if (tid < START_WORDS) c.start[tid] = 0u;
@@ -456,7 +457,7 @@ __device__ __forceinline__ uint32_t wg_flat_chunk_keep(WgChunk<V, THREADS> &c, i
 // Workgroup version of the row traversal: chunks of THREADS entries of A, each flattened over the
 // whole workgroup.  Every thread of the (1-D) workgroup must call it.  seg(k, p0, len) gives the
 // segment of B's arrays that entry k expands to.  Ends with a barrier.
-template <int THREADS, bool HAS_VAL, typename V, typename SegFn, typename F>
+template <int THREADS, bool HAS_VAL, int WU = FLAT_U, typename V, typename SegFn, typename F>
 __device__ __forceinline__ void wg_traverse(const int32_t *__restrict__ a_col, const V *__restrict__ a_val,
                                             int64_t e0, int64_t e1, SegFn seg, const int32_t *__restrict__ b_col,
                                             const V *__restrict__ b_val, WgChunk<V, THREADS> &c, F f)
@@ -472,7 +473,7 @@ __device__ __forceinline__ void wg_traverse(const int32_t *__restrict__ a_col, c
             seg(k, p0, len);
         }
         const int64_t left = e1 - base;
-        wg_flat_chunk<THREADS, HAS_VAL>(c, left < THREADS ? (int)left : THREADS, p0, (uint32_t)len, a, b_col, b_val, f);
+        wg_flat_chunk<THREADS, HAS_VAL, WU>(c, left < THREADS ? (int)left : THREADS, p0, (uint32_t)len, a, b_col, b_val, f);
     }
 }
 
