@@ -242,11 +242,24 @@ k_hll_sketch(const int64_t *__restrict__ rp, const int32_t *__restrict__ col, in
         wave_sync();
         if (row < rows) {
             const int64_t p1 = rp[row + 1];
-            for (int64_t p = rp[row] + sub; p < p1; p += G) {
-                const uint32_t h = hll_hash(col[p]);
-                const uint32_t w = h >> P;
-                const uint32_t rank = w ? (uint32_t)(__clz((int)w) - P + 1) : (uint32_t)(32 - P + 1);
-                atomicMax(&my[h & (M - 1)], rank);
+            // four column ids per lane and turn (unconditional reads, index clamped): a long row is bound by
+            // the latency of one load after the other otherwise
+            for (int64_t p = rp[row] + sub; p < p1; p += 4 * (int64_t)G) {
+                int32_t c[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int64_t q = p + (int64_t)i * G;
+                    c[i] = col[q < p1 ? q : p1 - 1];
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (p + (int64_t)i * G < p1) {
+                        const uint32_t h = hll_hash(c[i]);
+                        const uint32_t w = h >> P;
+                        const uint32_t rank = w ? (uint32_t)(__clz((int)w) - P + 1) : (uint32_t)(32 - P + 1);
+                        atomicMax(&my[h & (M - 1)], rank);
+                    }
+                }
             }
         }
         wave_sync();
@@ -318,12 +331,26 @@ k_hll_merge(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col,
     if (t < n_rows) {
         row = rows ? rows[t] : t;
         const int64_t e1 = a_rp[row + 1];
-        for (int64_t e = a_rp[row] + part; e < e1; e += parts) {
-            const int64_t k = a_col[e];
-            acc = bytemax8(acc, sk[k * L + slice]);
+        // four entries per lane and turn (unconditional reads, index clamped; merging a sketch twice is
+        // harmless), so that the dependent loads entry -> sketch of four entries overlap
+        for (int64_t e = a_rp[row] + part; e < e1; e += 4 * (int64_t)parts) {
+            int64_t k[4];
+            uint64_t word[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int64_t q = e + (int64_t)i * parts;
+                k[i] = a_col[q < e1 ? q : e1 - 1];
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) word[i] = sk[k[i] * L + slice];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc = bytemax8(acc, word[i]);
             if (b_rp != nullptr && slice == 0) {
-                const long long len = b_rp[k + 1] - b_rp[k];
-                blen_max = len > blen_max ? len : blen_max;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const long long len = b_rp[k[i] + 1] - b_rp[k[i]];
+                    blen_max = len > blen_max ? len : blen_max;
+                }
             }
         }
     }
