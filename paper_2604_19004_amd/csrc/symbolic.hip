@@ -158,16 +158,29 @@ k_symbolic_bitmap(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ 
     __shared__ uint32_t s_bm[BM_WORDS];
     __shared__ WgChunk<NoVal, BM_THREADS> s_fc;
     __shared__ int s_count;
-    __shared__ long long s_row;
+    // Rows come from a shared counter.  The chain counter -> row id -> offsets of the row costs three memory
+    // round trips before the first entry of a row can be read, so it runs ahead of the work: the ticket of
+    // the row three turns ahead is drawn, the row id two turns ahead and the offsets one turn ahead are
+    // loaded while the current row is traversed (s_ticket: ring of four tickets; count >= 1).
+    __shared__ unsigned long long s_ticket[4];
     const int tid = threadIdx.x;
     for (int s = tid; s < BM_WORDS; s += BM_THREADS) s_bm[s] = 0u;
-    for (;;) {
-        if (tid == 0) { s_row = (long long)atomicAdd(queue, 1ull); s_count = 0; }
-        __syncthreads();
-        if (s_row >= count) break;   // uniform exit
-        const int64_t r = count - 1 - s_row;   // from the end of the list, where the rows with the largest bounds are
-        const int64_t row = rows[r];
-        const int64_t e0 = a_rp[row], e1 = a_rp[row + 1];
+    if (tid == 0) {
+        for (int j = 0; j < 3; ++j) s_ticket[j] = atomicAdd(queue, 1ull);
+        s_count = 0;
+    }
+    __syncthreads();
+    // a ticket beyond the list stands for no row; its loads use the list's first row instead
+    auto list_pos = [&](unsigned long long t) { return t < (unsigned long long)count ? count - 1 - (int64_t)t : (int64_t)0; };
+    int64_t row = rows[list_pos(s_ticket[0])];     // row of this turn (the rows with the largest bounds are at the end)
+    int64_t row1 = rows[list_pos(s_ticket[1])];    // row of the next turn
+    int64_t e0 = a_rp[row], e1 = a_rp[row + 1];
+    for (unsigned turn = 0;; ++turn) {
+        if (s_ticket[turn & 3u] >= (unsigned long long)count) break;   // uniform exit (tickets only grow)
+        unsigned long long drawn = 0;
+        if (tid == 0) drawn = atomicAdd(queue, 1ull);                  // ticket of turn + 3
+        const int64_t row2 = rows[list_pos(s_ticket[(turn + 2u) & 3u])];
+        const int64_t e0n = a_rp[row1], e1n = a_rp[row1 + 1];
         for (int64_t w0 = 0; w0 < n_cols; w0 += BM_WIN) {
             wg_traverse<BM_THREADS, false, BM_U>(a_col, (const NoVal *)nullptr, e0, e1,
                                            [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
@@ -191,7 +204,13 @@ k_symbolic_bitmap(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ 
             if (lane_id() == 0 && c) atomicAdd(&s_count, c);
             __syncthreads();
         }
-        if (tid == 0) nnz_out[row] = s_count;
+        if (tid == 0) {
+            nnz_out[row] = s_count;
+            s_count = 0;
+            s_ticket[(turn + 3u) & 3u] = drawn;   // (its slot held the ticket of the turn before this one)
+        }
+        row = row1; row1 = row2;
+        e0 = e0n; e1 = e1n;
         __syncthreads();
     }
 }
