@@ -42,11 +42,114 @@ k_compact(int64_t m, int g_log2, const int64_t *__restrict__ c_rp, const int32_t
     }
 }
 
+// The same copy dealt out by entries of C instead of rows: every workgroup takes a tile of
+// CF_TILE consecutive entries of C, so that the stores of the whole grid sweep C linearly and the
+// loads sweep the temporary output in the same order (rows lie there in row order too), whatever
+// the lengths of the rows.  This is what a power-law C needs: with a lane group per row its long
+// rows turn the copy into thousands of independent streams.  The first and last row of a tile are
+// found by a search over row_ptr in which all 256 threads probe at once.
+constexpr int CF_THREADS = 256;
+constexpr int CF_TILE = CF_THREADS * 64;
+
+// Largest r in [0, m) with c_rp[r] <= pos (pos < c_rp[m]; rows without entries are skipped).  Uniform.
+__device__ __forceinline__ int64_t row_of_entry(const int64_t *__restrict__ c_rp, int64_t m, int64_t pos)
+{
+    int64_t lo = 0, hi = m;   // the answer lies in [lo, hi)
+    while (hi - lo > 1) {
+        const int64_t step = (hi - lo + CF_THREADS - 1) / CF_THREADS;
+        const int64_t idx = lo + (int64_t)threadIdx.x * step;
+        const bool le = idx < hi && c_rp[idx] <= pos;
+        const int cnt = __syncthreads_count(le);   // >= 1, since c_rp[lo] <= pos
+        const int64_t nlo = lo + (int64_t)(cnt - 1) * step;
+        hi = nlo + step < hi ? nlo + step : hi;
+        lo = nlo;
+    }
+    return lo;
+}
+
+template <typename V>
+__global__ void __launch_bounds__(CF_THREADS)
+k_compact_flat(int64_t m, int64_t nnz, const int64_t *__restrict__ c_rp, const int32_t *__restrict__ nnz1,
+               const int64_t *__restrict__ ptr1, const int32_t *__restrict__ col1, const V *__restrict__ val1,
+               const int64_t *__restrict__ ptr2, const int32_t *__restrict__ col2, const V *__restrict__ val2,
+               int32_t *__restrict__ c_col, V *__restrict__ c_val)
+{
+    const int tid = threadIdx.x;
+    const int64_t base = (int64_t)blockIdx.x * CF_TILE;
+    if (base >= nnz) return;   // uniform
+    const int64_t end = base + CF_TILE < nnz ? base + CF_TILE : nnz;
+    const int64_t r_lo = row_of_entry(c_rp, m, base);
+    const int64_t r_hi = row_of_entry(c_rp, m, end - 1);
+    if (r_hi - r_lo < 64) {
+        // few rows in the tile: thread t copies entries base + t, base + t + 256, ...; the row of an entry
+        // only moves forward, so a thread advances over at most 64 rows in all
+        int64_t row = r_lo;
+        int64_t row_end = c_rp[row + 1];
+        bool first = nnz1[row] >= 0;
+        int64_t delta = (first ? ptr1[row] : ptr2[row]) - c_rp[row];   // position in the source minus position in C
+        for (int64_t e0 = base + tid; e0 < end; e0 += 8 * CF_THREADS) {
+            int32_t cc[8];
+            V vv[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int64_t e = e0 + (int64_t)i * CF_THREADS;
+                cc[i] = 0; vv[i] = V();
+                if (e < end) {
+                    while (e >= row_end) {   // (row < r_hi here: the tile ends inside row r_hi)
+                        ++row;
+                        row_end = c_rp[row + 1];
+                        if (e < row_end) {
+                            first = nnz1[row] >= 0;
+                            delta = (first ? ptr1[row] : ptr2[row]) - c_rp[row];
+                        }
+                    }
+                    const int64_t sp = e + delta;
+                    cc[i] = first ? col1[sp] : col2[sp];
+                    vv[i] = first ? val1[sp] : val2[sp];
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int64_t e = e0 + (int64_t)i * CF_THREADS;
+                if (e < end) { c_col[e] = cc[i]; c_val[e] = vv[i]; }
+            }
+        }
+    } else {
+        // many short rows: one wave per row, the rows of the tile dealt out to the four waves
+        const int lane = tid & (WAVE - 1);
+        for (int64_t row = r_lo + tid / WAVE; row <= r_hi; row += CF_THREADS / WAVE) {
+            const int64_t d0 = c_rp[row], d1 = c_rp[row + 1];
+            const int64_t from = d0 > base ? d0 : base, to = d1 < end ? d1 : end;
+            if (from >= to) continue;
+            const bool first = nnz1[row] >= 0;
+            const int64_t delta = (first ? ptr1[row] : ptr2[row]) - d0;
+            const int32_t *sc = first ? col1 : col2;
+            const V *sv = first ? val1 : val2;
+            for (int64_t e = from + lane; e < to; e += WAVE) {
+                c_col[e] = sc[e + delta];
+                c_val[e] = sv[e + delta];
+            }
+        }
+    }
+}
+
 hipError_t launch_compact(int64_t m, int dtype, const int64_t *c_rp, const int32_t *nnz1, const int64_t *ptr1,
                           const int32_t *col1, const void *val1, const int64_t *ptr2, const int32_t *col2,
-                          const void *val2, int32_t *c_col, void *c_val, int g_log2, hipStream_t s)
+                          const void *val2, int32_t *c_col, void *c_val, int g_log2, int64_t nnz_c, hipStream_t s)
 {
     if (m == 0) return hipSuccess;
+    if (nnz_c >= (int64_t)512 * m && nnz_c > 0) {   // long rows on average: deal the copy out by entries
+        const int64_t tiles = (nnz_c + CF_TILE - 1) / CF_TILE;
+        if (dtype == OCEAN_F64)
+            hipLaunchKernelGGL(k_compact_flat<double>, dim3((unsigned)tiles), dim3(CF_THREADS), 0, s, m, nnz_c, c_rp, nnz1,
+                               ptr1, col1, static_cast<const double *>(val1), ptr2, col2, static_cast<const double *>(val2),
+                               c_col, static_cast<double *>(c_val));
+        else
+            hipLaunchKernelGGL(k_compact_flat<float>, dim3((unsigned)tiles), dim3(CF_THREADS), 0, s, m, nnz_c, c_rp, nnz1,
+                               ptr1, col1, static_cast<const float *>(val1), ptr2, col2, static_cast<const float *>(val2),
+                               c_col, static_cast<float *>(c_val));
+        return hipGetLastError();
+    }
     const int64_t threads = m << g_log2;
     const int64_t blocks = (threads + 255) / 256;
     if (dtype == OCEAN_F64)

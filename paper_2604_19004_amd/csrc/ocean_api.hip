@@ -705,7 +705,7 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
     if (!c_col || !c_val) return fail(OCEAN_EALLOC, "output allocation failed");
     const int g_log2 = ilog2_ceil_d((double)nnz_c / (double)m, 2, 6);
     HIP_TRY(launch_compact(m, dtype, c_rp, w.row_nnz, out_ptr, t_col, t_val, w.tmp_ptr2, r_col, r_val, c_col, c_val,
-                           g_log2, c.s));
+                           g_log2, nnz_c, c.s));
     OC_TRY(mark(c, -1));
     HIP_TRY(hipStreamSynchronize(c.s));
     S->nnz_c = nnz_c;

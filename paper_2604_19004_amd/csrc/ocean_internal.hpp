@@ -253,6 +253,6 @@ hipError_t launch_numeric_bin(const Csr &A, const Csr &B, int dtype, const NumLa
 // compact.hip
 hipError_t launch_compact(int64_t m, int dtype, const int64_t *c_rp, const int32_t *nnz1, const int64_t *ptr1,
                           const int32_t *col1, const void *val1, const int64_t *ptr2, const int32_t *col2,
-                          const void *val2, int32_t *c_col, void *c_val, int g_log2, hipStream_t s);
+                          const void *val2, int32_t *c_col, void *c_val, int g_log2, int64_t nnz_c, hipStream_t s);
 
 }  // namespace ocean

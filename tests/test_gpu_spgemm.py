@@ -388,6 +388,32 @@ def test_skewed_row_lengths_of_b(ob):
     assert np.array_equal(nnz.cpu().numpy().astype(np.int64), np.diff(ref.row_ptr))
 
 
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_compaction_by_entries_long_and_short_rows_mixed(ob, dtype):
+    # C's rows average more than 512 entries, so the estimation workflows compact by tiles of 16384 entries of C:
+    # tiles inside one long row, tiles that straddle a few rows, tiles over hundreds of short rows, empty rows
+    # between them, a last partial tile.  Row i of A picks one row of B, so C is rows of B, scaled.
+    rng = np.random.default_rng(77)
+    n = 1 << 17
+    lens = np.concatenate([[40000, 0, 16384, 16384, 1, 0, 0, 70000, 90000, 120000], rng.integers(0, 24, 400),
+                           [33000, 5, 16383, 16385], rng.integers(0, 4, 200), [50000, 2, 0]])
+    k = lens.size
+    rp = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    ci = np.concatenate([np.sort(rng.choice(n, int(l), replace=False)) for l in lens]).astype(np.int32)
+    Bm = CSR(k, n, rp, ci, rng.uniform(-1, 1, ci.size).astype(dtype))
+    pick = np.concatenate([np.arange(k), rng.integers(0, k, 60)])         # every row of B, then some again
+    m = pick.size
+    A = CSR(m, k, np.arange(m + 1, dtype=np.int64), pick.astype(np.int32), rng.uniform(0.5, 2.0, m).astype(dtype))
+    ref = O.multiply_rows(A, Bm)
+    assert ref.col_idx.size >= 512 * m
+    for wf in ("upper_bound", "hll", "symbolic"):
+        for scale in ((1.0,) if wf != "hll" else (1.0, 0.3)):   # 0.3: overflow rows come from the retry's output
+            Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(Bm), workflow=wf_id(ob, wf), estimate_scale=scale)
+            check_result(Cd, ref, A, f"compaction by entries/{wf}/{scale}")
+            if scale < 1.0:
+                assert st["overflow_rows"] > 0
+
+
 def test_invalid_arguments_are_rejected(ob):
     A = _csr(2, 3, [0, 1, 2], [0, 5], [1., 1.])          # column id 5 outside 3 columns
     B = _csr(3, 2, [0, 1, 1, 2], [0, 1], [1., 1.])
