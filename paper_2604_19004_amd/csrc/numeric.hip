@@ -648,8 +648,8 @@ k_numeric_hybrid(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
 //     add + one LDS or per product; the bitmap's prefix popcount places each
 //     present column at its sorted position;
 //   * consecutive windows whose products fit the staging memory left beside
-//     their bitmap (a sparse stretch: up to 10240 products over 2 windows, 8192
-//     over 10, fewer over more) share one pass in the manner of an
+//     their bitmap (a sparse stretch: up to 8192 products over 10 windows,
+//     fewer over more) share one pass in the manner of an
 //     expand-sort-compress accumulator whose sort is a bitmap rank: every
 //     product is written to LDS at its own number (no atomics) and marks its
 //     column in a bitmap over the stretch; the prefix popcount of the bitmap is
