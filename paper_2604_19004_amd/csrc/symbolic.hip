@@ -175,33 +175,63 @@ k_symbolic_bitmap(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ 
     int64_t row = rows[list_pos(s_ticket[0])];     // row of this turn (the rows with the largest bounds are at the end)
     int64_t row1 = rows[list_pos(s_ticket[1])];    // row of the next turn
     int64_t e0 = a_rp[row], e1 = a_rp[row + 1];
+    // the segments of B that the first BM_THREADS entries of the row expand to are fetched a turn ahead as well
+    auto first_segment = [&](int64_t f0, int64_t f1, int64_t &p0, uint32_t &len) {
+        p0 = 0; len = 0u;
+        if (f0 + tid < f1) {
+            const int32_t k = a_col[f0 + tid];
+            p0 = b_rp[k];
+            len = (uint32_t)(b_rp[k + 1] - p0);
+        }
+    };
+    int64_t fp0;
+    uint32_t flen;
+    first_segment(e0, e1, fp0, flen);
+    auto mark = [&](const auto &cj, uint32_t w0) {
+        constexpr int U = sizeof(cj) / sizeof(cj[0]);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            // (32-bit arithmetic: a column before the window wraps to a large number)
+            const uint32_t d = (uint32_t)cj[u] - w0;
+            // Only the number of set bits matters, so neighbouring columns (the sorted entries of one row of
+            // B in neighbouring lanes) go to neighbouring words, i.e. different LDS banks, not to one word.
+            if (cj[u] >= 0 && (ONE_WINDOW || d < (uint32_t)BM_WIN))
+                atomicOr(&s_bm[d & (uint32_t)(BM_WORDS - 1)], 1u << (d / (uint32_t)BM_WORDS));
+        }
+    };
     for (unsigned turn = 0;; ++turn) {
         if (s_ticket[turn & 3u] >= (unsigned long long)count) break;   // uniform exit (tickets only grow)
         unsigned long long drawn = 0;
         if (tid == 0) drawn = atomicAdd(queue, 1ull);                  // ticket of turn + 3
         const int64_t row2 = rows[list_pos(s_ticket[(turn + 2u) & 3u])];
         const int64_t e0n = a_rp[row1], e1n = a_rp[row1 + 1];
+        int64_t fp0n = 0;
+        uint32_t flenn = 0u;
+        const int64_t ne = e1 - e0;
         for (int64_t w0 = 0; w0 < n_cols; w0 += BM_WIN) {
-            wg_traverse<BM_THREADS, false, BM_U>(a_col, (const NoVal *)nullptr, e0, e1,
-                                           [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
-                                           b_col, (const NoVal *)nullptr, s_fc, [&](const auto &cj, const auto &) {
-                                               constexpr int U = sizeof(cj) / sizeof(cj[0]);
-#pragma unroll
-                                               for (int u = 0; u < U; ++u) {
-                                                   // (32-bit arithmetic: a column before the window wraps to a large number)
-                                                   const uint32_t d = (uint32_t)cj[u] - (uint32_t)w0;
-                                                   // Only the number of set bits matters, so neighbouring columns (the
-                                                   // sorted entries of one row of B in neighbouring lanes) go to
-                                                   // neighbouring words, i.e. different LDS banks, not to one word.
-                                                   if (cj[u] >= 0 && (ONE_WINDOW || d < (uint32_t)BM_WIN))
-                                                       atomicOr(&s_bm[d & (uint32_t)(BM_WORDS - 1)], 1u << (d / (uint32_t)BM_WORDS));
-                                               }
-                                           });
+            auto f = [&](const auto &cj, const auto &) { mark(cj, (uint32_t)w0); };
+            if (ne > 0)
+                wg_flat_chunk<BM_THREADS, false, BM_U>(s_fc, ne < BM_THREADS ? (int)ne : BM_THREADS, fp0, flen, NoVal(), b_col,
+                                                       (const NoVal *)nullptr, f);
+            if (ne > BM_THREADS)
+                wg_traverse<BM_THREADS, false, BM_U>(a_col, (const NoVal *)nullptr, e0 + BM_THREADS, e1,
+                                                     [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
+                                                     b_col, (const NoVal *)nullptr, s_fc, f);
             __syncthreads();
+            // the entries of the next row's first chunk are loaded under the sweep of the bitmap, their
+            // segments of B under the rest of the turn
+            const bool last_window = w0 + BM_WIN >= n_cols;
+            const bool has_next = last_window && e0n + tid < e1n;
+            int32_t kn = 0;
+            if (has_next) kn = a_col[e0n + tid];
             int c = 0;
             for (int s = tid; s < BM_WORDS; s += BM_THREADS) { c += __popc(s_bm[s]); s_bm[s] = 0u; }
             c = group_reduce_sum(c, WAVE);
             if (lane_id() == 0 && c) atomicAdd(&s_count, c);
+            if (has_next) {
+                fp0n = b_rp[kn];
+                flenn = (uint32_t)(b_rp[kn + 1] - fp0n);
+            }
             __syncthreads();
         }
         if (tid == 0) {
@@ -211,6 +241,7 @@ k_symbolic_bitmap(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ 
         }
         row = row1; row1 = row2;
         e0 = e0n; e1 = e1n;
+        fp0 = fp0n; flen = flenn;
         __syncthreads();
     }
 }
