@@ -900,8 +900,8 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                 const long long room = cap - done;
                 const int n_out = (long long)htotal < room ? htotal : (room > 0 ? (int)room : 0);
                 for (int i = tid; i < n_out; i += HV_THREADS) {
-                    out_col[o + done + i] = s_scol[i];
-                    out_val[o + done + i] = s_sval[i];
+                    __builtin_nontemporal_store(s_scol[i], &out_col[o + done + i]);
+                    __builtin_nontemporal_store(s_sval[i], &out_val[o + done + i]);
                 }
                 done += htotal;
                 __syncthreads();
@@ -943,7 +943,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                             const long long rank = done + (long long)s_dpre[j >> 5] + __popc(wbits & ((1u << (j & 31)) - 1u));
                             const V val = s_vals[j];
                             s_vals[j] = (V)0;
-                            if (rank < cap) { out_col[o + rank] = col0 + j; out_val[o + rank] = val; }
+                            if (rank < cap) { __builtin_nontemporal_store((int32_t)(col0 + j), &out_col[o + rank]); __builtin_nontemporal_store(val, &out_val[o + rank]); }
                         }
                     }
                     __syncthreads();
@@ -995,8 +995,8 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                     const long long room = cap - done;
                     const int n_out = (long long)htotal < room ? htotal : (room > 0 ? (int)room : 0);
                     for (int i = tid; i < n_out; i += HV_THREADS) {
-                        out_col[o + done + i] = s_scol[i];
-                        out_val[o + done + i] = s_sval[i];
+                        __builtin_nontemporal_store(s_scol[i], &out_col[o + done + i]);
+                        __builtin_nontemporal_store(s_sval[i], &out_val[o + done + i]);
                     }
                     done += htotal;
                     __syncthreads();
