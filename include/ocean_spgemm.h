@@ -155,7 +155,9 @@ int ocean_csr_release(ocean_csr *C, const ocean_allocator *allocator);
  * Analysis (Section 3.2): prod[i] = sum over stored A_ik of nnz(B_k), the
  * number of intermediate products and an upper bound of nnz(C_i).  prod:
  * device int64[A->rows].  total / max_row: host outputs, may be NULL.
- * Blocks until done.  Column ids of A outside [0, B->rows) give OCEAN_EINVAL.
+ * Blocks until done.  Column ids of A outside [0, B->rows), and row offsets of
+ * A that are negative, descending or beyond A->nnz, give OCEAN_EINVAL: such
+ * offsets are never dereferenced.
  */
 int ocean_row_products(const ocean_csr *A, const ocean_csr *B, int64_t *prod, int64_t *total, int64_t *max_row,
                        ocean_stream_t stream);

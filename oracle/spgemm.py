@@ -95,11 +95,14 @@ class RowBlock:
     absval: np.ndarray    # float64, sum_k |A_ik*B_kj|
 
 
-def multiply_rows(A, B, r0: int = 0, r1: int | None = None) -> RowBlock:
-    """Rows [r0, r1) of C = A*B: structure, values and per-entry |.| sums, all in double."""
+def multiply_rows(A, B, r0: int = 0, r1: int | None = None, nnz: np.ndarray | None = None) -> RowBlock:
+    """Rows [r0, r1) of C = A*B: structure, values and per-entry |.| sums, all in double.
+    nnz: the result of count_rows(A, B, r0, r1) when the caller already holds it (saves the recount)."""
     _chk(A, B)
     r1 = A.rows if r1 is None else r1
-    nnz = count_rows(A, B, r0, r1)
+    if nnz is None:
+        nnz = count_rows(A, B, r0, r1)
+    assert len(nnz) == max(r1 - r0, 0)
     rp = np.zeros(len(nnz) + 1, dtype=np.int64)
     np.cumsum(nnz, out=rp[1:])
     tot = int(rp[-1])

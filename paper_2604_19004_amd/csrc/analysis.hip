@@ -80,7 +80,7 @@ __device__ __forceinline__ void block_totals(long long tsum, long long tmax, lon
 }
 
 __global__ void __launch_bounds__(TPB)
-k_row_products(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col, int64_t m,
+k_row_products(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col, int64_t m, int64_t a_nnz,
                const int64_t *__restrict__ b_rp, int64_t b_rows, int g_log2, int64_t *__restrict__ prod,
                int32_t *__restrict__ maxb, unsigned long long *totals, int32_t *flags,
                int32_t *__restrict__ long_rows, unsigned long long *long_count)
@@ -93,13 +93,16 @@ k_row_products(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_c
     const int sub = threadIdx.x & (G - 1);
     const int64_t long_len = (int64_t)G * 16;
     long long tsum = 0, tmax = 0;
-    bool bad = false;
+    bool bad = false, bad_rp = false;
     for (int64_t base = (int64_t)blockIdx.x * R; base < m; base += (int64_t)gridDim.x * R) {
         const int64_t row = base + rl;
         long long p = 0, mx = 0;
         bool mine = row < m;
         if (mine) {
-            const int64_t e0 = a_rp[row], e1 = a_rp[row + 1];
+            // offsets outside [0, nnz] or descending are reported and never used as they stand: this kernel
+            // runs before the host has seen the verdict of the input check
+            int64_t e0 = a_rp[row], e1 = a_rp[row + 1];
+            if (e0 < 0 || e1 < e0 || e1 > a_nnz) { bad_rp = true; e0 = 0; e1 = 0; }
             if (long_rows != nullptr && e1 - e0 > long_len) {   // uniform for the group
                 if (sub == 0) long_rows[atomicAdd(long_count, 1ull)] = (int32_t)row;
                 mine = false;
@@ -141,6 +144,7 @@ k_row_products(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_c
     }
     block_totals(tsum, tmax, s_sum, s_max, totals);
     if (__ballot(bad) != 0 && lane_id() == 0) atomicOr(flags, 4);
+    if (__ballot(bad_rp) != 0 && lane_id() == 0) atomicOr(flags, 1);
 }
 
 // The listed long rows: one workgroup per row at a time.
@@ -158,7 +162,7 @@ k_row_products_long(const int64_t *__restrict__ a_rp, const int32_t *__restrict_
     bool bad = false;
     for (int64_t i = blockIdx.x; i < n; i += gridDim.x) {
         const int64_t row = long_rows[i];
-        const int64_t e0 = a_rp[row], e1 = a_rp[row + 1];
+        const int64_t e0 = a_rp[row], e1 = a_rp[row + 1];   // (only rows with valid offsets are listed)
         long long p = 0, mx = 0;
         for (int64_t e = e0 + threadIdx.x; e < e1; e += 4 * TPB) {
             int32_t k[4];
@@ -212,8 +216,8 @@ hipError_t launch_row_products(const Csr &A, const int64_t *b_rp, int64_t b_rows
     int64_t blocks = (A.rows + R - 1) / R;
     if (blocks > 2048) blocks = 2048;
     if (long_count == nullptr) long_rows = nullptr;
-    hipLaunchKernelGGL(k_row_products, dim3((unsigned)blocks), dim3(TPB), 0, s, A.rp, A.col, A.rows, b_rp, b_rows,
-                       g_log2, prod, maxb, totals, flags, long_rows, long_count);
+    hipLaunchKernelGGL(k_row_products, dim3((unsigned)blocks), dim3(TPB), 0, s, A.rp, A.col, A.rows, A.nnz, b_rp,
+                       b_rows, g_log2, prod, maxb, totals, flags, long_rows, long_count);
     if (long_rows != nullptr)
         hipLaunchKernelGGL(k_row_products_long, dim3(2048), dim3(TPB), 0, s, A.rp, A.col, b_rp, b_rows, prod, maxb,
                            totals, flags, long_rows, long_count);

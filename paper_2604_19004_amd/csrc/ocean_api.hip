@@ -800,6 +800,7 @@ int ocean_row_products(const ocean_csr *A, const ocean_csr *B, int64_t *prod, in
         HIP_TRY(hipMemsetAsync(sc, 0, sizeof(Scalars), c.s));
         HIP_TRY(launch_row_products(view(A), B->row_ptr, B->rows, prod, maxb, sc->totals, &sc->flags, nullptr, nullptr, c.s));
         OC_TRY(fetch_scalars(c, sc));
+        if (c.h->flags & 1) return fail(OCEAN_EINVAL, "A is not a valid CSR matrix (row offsets out of range or descending)");
         if (c.h->flags & 4) return fail(OCEAN_EINVAL, "a column id of A is outside [0, rows(B))");
         if (total) *total = (int64_t)c.h->totals[0];
         if (max_row) *max_row = (int64_t)c.h->totals[1];
