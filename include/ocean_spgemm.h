@@ -163,6 +163,30 @@ int ocean_row_products(const ocean_csr *A, const ocean_csr *B, int64_t *prod, in
                        ocean_stream_t stream);
 
 /*
+ * ocean_row_products for callers that cannot allocate device memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same kernels as ocean_row_products; the per-row scratch they
+ * need (4 + 4 bytes per row of A, and the call's device scalars) lives in a
+ * fixed array inside the library's code object, 8 MiB + 256 B per GPU, held
+ * until the process ends.  Hence A->rows <= OCEAN_NOALLOC_MAX_ROWS; more rows
+ * give OCEAN_EINVAL and nothing is launched.  The call allocates and frees
+ * nothing, does not synchronise and reads nothing back: it enqueues its
+ * kernels on `stream` and returns.  prod: device int64[A->rows].  totals:
+ * device int64[3], written by the last kernel: {P, largest prod[i], flags};
+ * flags bit 0: a row offset of A was negative, descending or beyond A->nnz
+ * (such rows count as empty), bit 2: a column id of A was outside
+ * [0, B->rows) (such entries are skipped).  Every call on one GPU uses that
+ * GPU's one array: calls that overlap on the same GPU (two streams, two
+ * threads) race and must be serialised by the caller.  ocean_init resolves
+ * the array's device address for the current device ahead of time (otherwise
+ * the first call on a device does it); call it outside graph capture.
+ */
+#define OCEAN_NOALLOC_MAX_ROWS (1 << 20)
+int ocean_init(void);
+int ocean_row_products_noalloc(const ocean_csr *A, const ocean_csr *B, int64_t *prod, int64_t *totals /* device */,
+                               ocean_stream_t stream);
+
+/*
  * HLL construct (Sections 2.4, 3.1): one sketch of m one-byte registers per
  * row of B, sketches: device uint8[B->rows * m], m in {32, 64, 128}.
  * Register index = low log2(m) bits of the 32-bit hash, register value =

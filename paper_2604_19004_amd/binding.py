@@ -91,6 +91,8 @@ def load():
     lib.ocean_spgemm.argtypes = [P(ocean_csr), P(ocean_csr), P(ocean_csr), P(ocean_options), P(ocean_stats), vp]
     lib.ocean_csr_release.argtypes = [P(ocean_csr), P(ocean_allocator)]
     lib.ocean_row_products.argtypes = [P(ocean_csr), P(ocean_csr), vp, P(i64), P(i64), vp]
+    lib.ocean_row_products_noalloc.argtypes = [P(ocean_csr), P(ocean_csr), vp, vp, vp]
+    lib.ocean_init.argtypes = []
     lib.ocean_hll_sketch_rows.argtypes = [P(ocean_csr), i32, vp, vp]
     lib.ocean_hll_merge_estimate.argtypes = [P(ocean_csr), vp, i32, vp, i64, vp, vp, i64, vp, vp, vp]
     lib.ocean_symbolic.argtypes = [P(ocean_csr), P(ocean_csr), vp, P(ocean_options), P(ocean_stats), vp]
@@ -104,7 +106,8 @@ def load():
     lib.ocean_bin_layout.argtypes = [P(i32), P(i32), P(i32), P(i32)]
     lib.ocean_last_error.restype = C.c_char_p
     lib.ocean_version.restype = C.c_int
-    for name in ("ocean_spgemm", "ocean_csr_release", "ocean_row_products", "ocean_hll_sketch_rows",
+    for name in ("ocean_spgemm", "ocean_csr_release", "ocean_row_products", "ocean_row_products_noalloc", "ocean_init",
+                 "ocean_hll_sketch_rows",
                  "ocean_hll_merge_estimate", "ocean_symbolic", "ocean_sample_rows", "ocean_bin_layout"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -264,6 +267,25 @@ def row_products(A: DeviceCSR, B: DeviceCSR, stream=None):
         _check(load().ocean_row_products(C.byref(a), C.byref(b), prod.data_ptr(), C.byref(tot), C.byref(mx),
                                          _stream_ptr(stream)))
     return prod, tot.value, mx.value
+
+
+NOALLOC_MAX_ROWS = 1 << 20
+
+
+def init():
+    """Resolve the library's fixed scratch array on the current device ahead of the first no-alloc call."""
+    _torch()
+    _check(load().ocean_init())
+
+
+def row_products_noalloc(A: DeviceCSR, B: DeviceCSR, prod, totals, stream=None):
+    """ocean_row_products_noalloc: prod (int64 [rows]) and totals (int64 [3]: P, largest row, flags) are
+    device tensors of the caller; the call only enqueues work on the stream."""
+    torch = _torch()
+    a, b = A.c_struct(), B.c_struct()
+    with torch.cuda.device(A.row_ptr.device):
+        _check(load().ocean_row_products_noalloc(C.byref(a), C.byref(b), prod.data_ptr(), totals.data_ptr(),
+                                                 _stream_ptr(stream)))
 
 
 def hll_sketch_rows(B: DeviceCSR, m: int, stream=None):

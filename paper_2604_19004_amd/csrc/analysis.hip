@@ -224,6 +224,22 @@ hipError_t launch_row_products(const Csr &A, const int64_t *b_rp, int64_t b_rows
     return hipGetLastError();
 }
 
+// Totals of a finished row-products pass, handed to a caller-owned device array: {P, largest row, flags}.
+__global__ void k_publish_totals(const unsigned long long *totals, const int32_t *flags, int64_t *out)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        out[0] = (int64_t)totals[0];
+        out[1] = (int64_t)totals[1];
+        out[2] = (int64_t)*flags;
+    }
+}
+
+hipError_t launch_publish_totals(const unsigned long long *totals, const int32_t *flags, int64_t *out, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_publish_totals, dim3(1), dim3(WAVE), 0, s, totals, flags, out);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------- HLL sketch
 // Registers of the rows in flight sit in LDS as 32-bit words (LDS has a
 // 32-bit atomic max, Section 3.1 "parallel updates ... atomicMax"); they are

@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <utility>
 #include <vector>
@@ -719,6 +720,40 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
     return OCEAN_OK;
 }
 
+// ---- scratch of the entry point that allocates nothing ----------------------------------------------
+// Layout: the call's device scalars (one 256-byte aligned block), then the longest referenced row of B per
+// row of A, then the list of long rows.  The array lives in every GPU's copy of the code object; the name
+// below is only a host-side handle, the device address comes from hipGetSymbolAddress, once per device.
+constexpr size_t NOALLOC_SCALARS = (sizeof(Scalars) + ALIGN - 1) / ALIGN * ALIGN;
+constexpr size_t NOALLOC_BYTES = NOALLOC_SCALARS + 2 * (size_t)OCEAN_NOALLOC_MAX_ROWS * sizeof(int32_t);
+constexpr int NOALLOC_MAX_DEVICES = 64;
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[NOALLOC_BYTES];
+
+namespace {
+
+std::mutex g_scratch_mu;
+unsigned char *g_scratch_ptr[NOALLOC_MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device (resolved on the first call per device).
+int scratch_of_current_device(unsigned char **out)
+{
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= NOALLOC_MAX_DEVICES) return fail(OCEAN_EINVAL, "device ordinal beyond what the library tracks");
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(OCEAN_EHIP, "hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[dev] = static_cast<unsigned char *>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return OCEAN_OK;
+}
+
 }  // namespace
 
 // =====================================================================================================
@@ -809,6 +844,38 @@ int ocean_row_products(const ocean_csr *A, const ocean_csr *B, int64_t *prod, in
     (void)hipStreamSynchronize(c.s);
     c.release_all();
     return rc;
+}
+
+int ocean_init(void)
+{
+    g_err.clear();
+    unsigned char *p = nullptr;
+    return scratch_of_current_device(&p);
+}
+
+int ocean_row_products_noalloc(const ocean_csr *A, const ocean_csr *B, int64_t *prod, int64_t *totals,
+                               ocean_stream_t stream)
+{
+    g_err.clear();
+    OC_TRY(check_csr(A, "A"));
+    OC_TRY(check_csr(B, "B"));
+    if (A->cols != B->rows) return fail(OCEAN_EINVAL, "A.cols != B.rows");
+    if (!totals) return fail(OCEAN_EINVAL, "totals is null");
+    if (!prod && A->rows > 0) return fail(OCEAN_EINVAL, "prod is null");
+    if (A->rows > OCEAN_NOALLOC_MAX_ROWS)
+        return fail(OCEAN_EINVAL, "A has more than OCEAN_NOALLOC_MAX_ROWS rows: the fixed scratch array cannot hold its per-row data");
+    unsigned char *base = nullptr;
+    OC_TRY(scratch_of_current_device(&base));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Scalars *sc = reinterpret_cast<Scalars *>(base);
+    int32_t *maxb = reinterpret_cast<int32_t *>(base + NOALLOC_SCALARS);
+    int32_t *long_rows = maxb + OCEAN_NOALLOC_MAX_ROWS;
+    // the scalars keep the last call's sums: clear them (a fill kernel, so that the call can be captured
+    // into a graph); the per-row arrays are written before they are read
+    HIP_TRY(launch_fill_u64(reinterpret_cast<unsigned long long *>(sc), (int64_t)(NOALLOC_SCALARS / 8), 0ull, s));
+    HIP_TRY(launch_row_products(view(A), B->row_ptr, B->rows, prod, maxb, sc->totals, &sc->flags, long_rows, &sc->queue[3], s));
+    HIP_TRY(launch_publish_totals(sc->totals, &sc->flags, totals, s));
+    return OCEAN_OK;
 }
 
 int ocean_hll_sketch_rows(const ocean_csr *B, int32_t m, uint8_t *sketches, ocean_stream_t stream)

@@ -181,6 +181,7 @@ hipError_t launch_validate(const Csr &A, const Csr &B, int32_t *flags, hipStream
 hipError_t launch_row_products(const Csr &A, const int64_t *b_rp, int64_t b_rows, int64_t *prod, int32_t *maxb,
                                unsigned long long *totals, int32_t *flags, int32_t *long_rows,
                                unsigned long long *long_count, hipStream_t s);
+hipError_t launch_publish_totals(const unsigned long long *totals, const int32_t *flags, int64_t *out, hipStream_t s);
 hipError_t launch_hll_sketch(const Csr &B, int m, uint8_t *sketches, hipStream_t s);
 hipError_t launch_hll_merge(const Csr &A, const uint8_t *sketches, int m, const int64_t *rows, int64_t n_rows,
                             const int64_t *prod, const int32_t *maxb, const int64_t *b_rp, int64_t b_cols,
