@@ -84,6 +84,18 @@ typedef struct ocean_options {
     int32_t validate_inputs;         /* 1: check column ids and row offsets on the device first */
     int32_t force_hash_kernels;      /* 1: rows beyond the 8192-slot LDS table always use the hybrid (LDS keys, global
                                         values) and global-table hash kernels, as they do when B's rows are unsorted */
+    int32_t assisted_symbolic;       /* assisted symbolic binning (Section 4.1): the key tables of the exact symbolic pass
+                                        are sized from products / conservative CR instead of the products.  0: off;
+                                        1 (default): whenever the analysis sampled rows, i.e. under OCEAN_WF_AUTO;
+                                        2: also sample (sketch + 3 % merge) when the workflow is forced to symbolic.
+                                        Rows whose table fills up are recounted with product-sized tables */
+    double assist_sigmas;            /* conservative CR = max(1, mean - assist_sigmas * std) of the per-row ratio
+                                        products / estimate over the sampled rows (1.0) */
+    int32_t bitmap_query;            /* dense accumulators read a column's presence bit and set it only when it is
+                                        clear (Section 4.1): 0 never, 1 always, -1 (default) when a sampled CR is
+                                        known and >= bitmap_query_cr */
+    int32_t reserved0;
+    double bitmap_query_cr;          /* 2.0 (Section 4.3) */
     const ocean_allocator *allocator; /* host pointer, may be NULL */
 } ocean_options;
 
@@ -108,6 +120,8 @@ typedef struct ocean_stats {
     double er;                 /* P / nnz(A) */
     double avg_products;       /* P / rows(A) */
     double sampled_cr;         /* 0 when not computed */
+    double cr_mean, cr_std;    /* mean and standard deviation of products / estimate over the sampled rows */
+    double assist_cr;          /* the conservative CR the symbolic pass was binned with; 0: binned by products */
     int32_t workflow;          /* the one that ran */
     int32_t hll_registers;     /* 0 when no sketch was built */
     int32_t sampled_rows;
@@ -115,6 +129,7 @@ typedef struct ocean_stats {
     int64_t rows_per_bin[OCEAN_MAX_BINS];          /* numeric bins */
     int64_t symbolic_rows_per_bin[OCEAN_MAX_BINS]; /* symbolic bins (two-pass workflow) */
     int64_t overflow_rows;
+    int64_t symbolic_overflow_rows; /* rows whose assisted key table filled up and that were recounted */
     int64_t temp_slots;        /* output slots reserved before compaction (estimation workflows) */
     int64_t peak_bytes;        /* largest total obtained from the allocator at one time */
     float stage_ms[OCEAN_NUM_STAGES];

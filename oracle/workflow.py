@@ -61,6 +61,21 @@ def sampled_cr(prod_s: np.ndarray, est_s: np.ndarray) -> float:
     return float(np.sum(prod_s[keep])) / den if den > 0 else 1.0
 
 
+def conservative_cr(prod_s: np.ndarray, est_s: np.ndarray, sigmas: float = 1.0) -> tuple[float, float, float]:
+    """Section 4.1 (assisted symbolic step): mean and standard deviation of the compression ratio over the
+    sampled rows, and a conservative ratio for the whole matrix.  The paper does not print how the two are
+    combined; the reading taken: per-row ratios products / estimate (rows with no output skipped), their
+    arithmetic mean mu and population standard deviation sigma, conservative CR = max(1, mu - sigmas*sigma).
+    Returns (mu, sigma, conservative)."""
+    keep = est_s > 0
+    if not np.any(keep):
+        return 0.0, 0.0, 1.0
+    r = prod_s[keep].astype(np.float64) / est_s[keep].astype(np.float64)
+    mu = float(np.mean(r))
+    sigma = float(np.sqrt(np.mean((r - mu) ** 2)))
+    return mu, sigma, max(1.0, mu - sigmas * sigma)
+
+
 def select_workflow(avg_products: float, er: float, cr: float) -> int:
     """Table 1."""
     if avg_products < 64.0:

@@ -40,21 +40,25 @@ class ocean_options(C.Structure):
                 ("er_threshold", C.c_double), ("cr_threshold", C.c_double), ("expand_coef", C.c_double),
                 ("exact_load_coef", C.c_double), ("sample_ratio", C.c_double), ("sample_min", C.c_int32),
                 ("sample_max", C.c_int32), ("sample_seed", C.c_uint32), ("estimate_scale", C.c_double),
-                ("validate_inputs", C.c_int32), ("force_hash_kernels", C.c_int32), ("allocator", C.POINTER(ocean_allocator))]
+                ("validate_inputs", C.c_int32), ("force_hash_kernels", C.c_int32), ("assisted_symbolic", C.c_int32),
+                ("assist_sigmas", C.c_double), ("bitmap_query", C.c_int32), ("reserved0", C.c_int32),
+                ("bitmap_query_cr", C.c_double), ("allocator", C.POINTER(ocean_allocator))]
 
 
 class ocean_stats(C.Structure):
     _fields_ = [("products", C.c_int64), ("max_row_products", C.c_int64), ("nnz_c", C.c_int64), ("er", C.c_double),
-                ("avg_products", C.c_double), ("sampled_cr", C.c_double), ("workflow", C.c_int32),
+                ("avg_products", C.c_double), ("sampled_cr", C.c_double), ("cr_mean", C.c_double),
+                ("cr_std", C.c_double), ("assist_cr", C.c_double), ("workflow", C.c_int32),
                 ("hll_registers", C.c_int32), ("sampled_rows", C.c_int32), ("fell_back", C.c_int32),
                 ("rows_per_bin", C.c_int64 * MAX_BINS), ("symbolic_rows_per_bin", C.c_int64 * MAX_BINS),
-                ("overflow_rows", C.c_int64), ("temp_slots", C.c_int64), ("peak_bytes", C.c_int64),
+                ("overflow_rows", C.c_int64), ("symbolic_overflow_rows", C.c_int64), ("temp_slots", C.c_int64), ("peak_bytes", C.c_int64),
                 ("stage_ms", C.c_float * 8), ("total_ms", C.c_float), ("bin_ms", C.c_float * MAX_BINS),
                 ("bin_products", C.c_int64 * MAX_BINS), ("bin_nnz_a", C.c_int64 * MAX_BINS),
                 ("bin_nnz_c", C.c_int64 * MAX_BINS)]
 
     def as_dict(self) -> dict:
         d = {k: getattr(self, k) for k in ("products", "max_row_products", "nnz_c", "er", "avg_products", "sampled_cr",
+                                           "cr_mean", "cr_std", "assist_cr", "symbolic_overflow_rows",
                                            "hll_registers", "sampled_rows", "fell_back", "overflow_rows", "temp_slots",
                                            "peak_bytes", "total_ms")}
         d["workflow"] = WORKFLOW_NAMES.get(self.workflow, str(self.workflow))

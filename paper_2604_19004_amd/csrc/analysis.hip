@@ -432,28 +432,35 @@ hipError_t launch_hll_merge(const Csr &A, const uint8_t *sketches, int m, const 
 // --------------------------------------------------------- sample reduce
 // Sums over the sampled rows in a fixed order (one workgroup, strided partial
 // sums, tree reduction), so the sampled CR is the same on every run.
+// out[0] = sum of products, out[1] = sum of estimates (their ratio is the sampled CR, Section 3.2);
+// out[2], out[3] = sum and sum of squares of the per-row ratios products / estimate, out[4] = rows counted
+// (mean and standard deviation of the compression ratio over the sample, Section 4.1).
 __global__ void __launch_bounds__(TPB)
 k_sample_reduce(const int64_t *__restrict__ rows, int64_t n_rows, const int64_t *__restrict__ prod,
                 const double *__restrict__ est, double *out)
 {
-    __shared__ double s_p[TPB];
-    __shared__ double s_e[TPB];
-    double sp = 0.0, se = 0.0;
+    constexpr int NS = 5;
+    __shared__ double s_acc[NS][TPB];
+    double acc[NS] = {0.0, 0.0, 0.0, 0.0, 0.0};
     for (int64_t t = threadIdx.x; t < n_rows; t += TPB) {
         const double e = est[t];
-        if (e > 0.0) { se += e; sp += (double)prod[rows[t]]; }
+        if (e > 0.0) {
+            const double p = (double)prod[rows[t]];
+            const double r = p / e;
+            acc[0] += p; acc[1] += e; acc[2] += r; acc[3] += r * r; acc[4] += 1.0;
+        }
     }
-    s_p[threadIdx.x] = sp;
-    s_e[threadIdx.x] = se;
+#pragma unroll
+    for (int k = 0; k < NS; ++k) s_acc[k][threadIdx.x] = acc[k];
     __syncthreads();
     for (int off = TPB / 2; off > 0; off >>= 1) {
         if ((int)threadIdx.x < off) {
-            s_p[threadIdx.x] += s_p[threadIdx.x + off];
-            s_e[threadIdx.x] += s_e[threadIdx.x + off];
+#pragma unroll
+            for (int k = 0; k < NS; ++k) s_acc[k][threadIdx.x] += s_acc[k][threadIdx.x + off];
         }
         __syncthreads();
     }
-    if (threadIdx.x == 0) { out[0] = s_p[0]; out[1] = s_e[0]; }
+    if (threadIdx.x < NS) out[threadIdx.x] = s_acc[threadIdx.x][0];
 }
 
 hipError_t launch_sample_reduce(const int64_t *rows, int64_t n_rows, const int64_t *prod, const double *est,

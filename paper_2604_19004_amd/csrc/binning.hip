@@ -16,12 +16,14 @@ struct BinTable {
 //   mode 0  upper bound: both are ub = min(prod, n)               (Section 3.2, upper-bound workflow)
 //   mode 1  estimate:    ceil(coef * scale * est), limited to ub  (Section 5.3: estimate x coefficient)
 //   mode 2  exact:       cap = nnz, need = ceil(coef * nnz) limited to ub   (two-pass workflow)
-//   mode 3  symbolic:    need = ceil(1.25 * ub), no capacity
+//   mode 3  symbolic:    need = ceil(1.25 * e), no capacity; e = ub, or with assisted binning (coef > 1,
+//                        Section 4.1) ceil(prod / coef) kept inside [longest referenced row of B, ub]
 // max_cap receives the largest capacity among the rows of the last (global-memory) bin.
 __global__ void __launch_bounds__(TPB)
 k_classify(int64_t m, int mode, double coef, double scale, BinTable bt, int64_t n_cols,
            const int64_t *__restrict__ prod, const double *__restrict__ est, const int32_t *__restrict__ nnz_exact,
-           const int32_t *__restrict__ row_mask, uint8_t *__restrict__ bin_of_row, int32_t *__restrict__ cap,
+           const int32_t *__restrict__ row_mask, const int32_t *__restrict__ lower_bound,
+           uint8_t *__restrict__ bin_of_row, int32_t *__restrict__ cap,
            unsigned long long *bin_count, unsigned long long *max_cap)
 {
     __shared__ unsigned int s_cnt[OCEAN_MAX_BINS];
@@ -50,7 +52,15 @@ k_classify(int64_t m, int mode, double coef, double scale, BinTable bt, int64_t 
                 need = want >= (double)ub ? ub : (long long)want;
                 if (need < c) need = c;
             } else {
-                need = ub + (ub + 3) / 4;
+                long long e = ub;
+                if (coef > 1.0) {
+                    const double q = ceil((double)pr / coef);
+                    e = q >= (double)ub ? ub : (long long)q;
+                    if (lower_bound != nullptr && e < (long long)lower_bound[i]) e = lower_bound[i];
+                    if (e > ub) e = ub;
+                    if (e < 1) e = 1;
+                }
+                need = e + (e + 3) / 4;
             }
             bin = bt.n - 1;
             for (int b = 0; b < bt.n; ++b)
@@ -67,8 +77,9 @@ k_classify(int64_t m, int mode, double coef, double scale, BinTable bt, int64_t 
 }
 
 hipError_t launch_classify(int64_t m, const BinParams &p, double scale, const int64_t *prod, const double *est,
-                           const int32_t *nnz_exact, const int32_t *row_mask, uint8_t *bin_of_row, int32_t *cap,
-                           unsigned long long *bin_count, unsigned long long *max_cap, hipStream_t s)
+                           const int32_t *nnz_exact, const int32_t *row_mask, const int32_t *lower_bound,
+                           uint8_t *bin_of_row, int32_t *cap, unsigned long long *bin_count,
+                           unsigned long long *max_cap, hipStream_t s)
 {
     if (m == 0) return hipSuccess;
     BinTable bt;
@@ -77,7 +88,7 @@ hipError_t launch_classify(int64_t m, const BinParams &p, double scale, const in
     int64_t blocks = (m + TPB - 1) / TPB;
     if (blocks > 1024) blocks = 1024;   // one set of atomics per workgroup: keep the workgroups few
     hipLaunchKernelGGL(k_classify, dim3((unsigned)blocks), dim3(TPB), 0, s, m, p.mode, p.coef, scale, bt, p.n_cols,
-                       prod, est, nnz_exact, row_mask, bin_of_row, cap, bin_count, max_cap);
+                       prod, est, nnz_exact, row_mask, lower_bound, bin_of_row, cap, bin_count, max_cap);
     return hipGetLastError();
 }
 

@@ -45,7 +45,7 @@ struct Scalars {
     unsigned long long max_cap;
     unsigned long long ovf_count;
     unsigned long long queue[4];
-    double sample_sums[2];
+    double sample_sums[6];                        // products, estimates, per-row CR, its squares, rows counted
     int32_t flags;
     int32_t pad;
     unsigned long long bin_work[3 * OCEAN_MAX_BINS];   // products, entries of A, entries of C per numeric bin
@@ -293,43 +293,87 @@ int run_analysis(Ctx &c, Work &w, const Csr &A, const Csr &B, bool validate, oce
     return OCEAN_OK;
 }
 
+void sample_rows_of(int64_t rows, const ocean_options &o, int64_t *out);
+
 // ---- exact symbolic pass ---------------------------------------------------------------------------
-int run_symbolic(Ctx &c, Work &w, const Csr &A, const Csr &B, int gb_log2, int32_t *nnz_out, ocean_stats *st)
+// assist_cr > 1: assisted binning (Section 4.1) - key tables are sized from products / assist_cr, rows
+// whose table fills up report -1 and are recounted in a second round with tables sized from the products.
+int run_symbolic(Ctx &c, Work &w, const Csr &A, const Csr &B, int gb_log2, double assist_cr, int32_t *nnz_out,
+                 ocean_stats *st)
 {
-    BinParams bp{};
-    bp.mode = 3;
-    bp.coef = 1.0;
-    bp.n_bins = SB_COUNT;
-    for (int b = 0; b < SB_COUNT; ++b) bp.slots[b] = kSymbolicSlots[b];
-    bp.n_cols = B.cols;
-    OC_TRY(zero_bins(c, w));
     HIP_TRY(launch_fill_i32(nnz_out, A.rows, 0, c.s));
-    HIP_TRY(launch_classify(A.rows, bp, 1.0, w.prod, nullptr, nullptr, nullptr, w.bin, nullptr, w.sc->bin_count,
-                            nullptr, c.s));
-    HIP_TRY(launch_scatter(A.rows, SB_COUNT, w.bin, w.sc->bin_count, w.sc->bin_cursor, w.bin_rows, c.s));
-    OC_TRY(fetch_scalars(c, w.sc));
-    int64_t start[SB_COUNT + 1];
-    start[0] = 0;
-    for (int b = 0; b < SB_COUNT; ++b) {
-        start[b + 1] = start[b] + (int64_t)c.h->bin_count[b];
-        if (st) st->symbolic_rows_per_bin[b] = (int64_t)c.h->bin_count[b];
-    }
     // With at most 2^20 columns the bitmap kernel covers a row in one window, and one pass over such a
     // window costs less than building a key table of 16384 or 32768 slots: those two bins go with it
     // (the row lists of consecutive bins are adjacent).
     const bool wide_bitmap = B.cols <= (1 << 20);
-    for (int b = SB_COUNT - 1; b >= 0; --b) {
-        SymLaunch l{w.bin_rows + start[b], start[b + 1] - start[b], b};
-        if (wide_bitmap && (b == SB_S16K || b == SB_S32K)) continue;
-        if (wide_bitmap && b == SB_BITMAP) {
-            l.rows = w.bin_rows + start[SB_S16K];
-            l.count = start[SB_COUNT] - start[SB_S16K];
+    for (int round = 0; round < 2; ++round) {
+        const bool assisted = round == 0 && assist_cr > 1.0;
+        BinParams bp{};
+        bp.mode = 3;
+        bp.coef = assisted ? assist_cr : 1.0;
+        bp.n_bins = SB_COUNT;
+        for (int b = 0; b < SB_COUNT; ++b) bp.slots[b] = kSymbolicSlots[b];
+        bp.n_cols = B.cols;
+        OC_TRY(zero_bins(c, w));
+        HIP_TRY(launch_classify(A.rows, bp, 1.0, w.prod, nullptr, nullptr, round == 0 ? nullptr : nnz_out, w.maxb, w.bin,
+                                nullptr, w.sc->bin_count, nullptr, c.s));
+        HIP_TRY(launch_scatter(A.rows, SB_COUNT, w.bin, w.sc->bin_count, w.sc->bin_cursor, w.bin_rows, c.s));
+        OC_TRY(fetch_scalars(c, w.sc));
+        int64_t start[SB_COUNT + 1];
+        start[0] = 0;
+        for (int b = 0; b < SB_COUNT; ++b) {
+            start[b + 1] = start[b] + (int64_t)c.h->bin_count[b];
+            if (st && round == 0) st->symbolic_rows_per_bin[b] = (int64_t)c.h->bin_count[b];
         }
-        if (l.count == 0) continue;
-        const int n_wg = (int)(l.count < c.n_cu ? l.count : c.n_cu);
-        HIP_TRY(launch_symbolic_bin(A, B, l, gb_log2, nnz_out, n_wg, &w.sc->queue[0], c.s));
+        for (int b = SB_COUNT - 1; b >= 0; --b) {
+            SymLaunch l{w.bin_rows + start[b], start[b + 1] - start[b], b, assisted};
+            if (wide_bitmap && (b == SB_S16K || b == SB_S32K)) continue;
+            if (wide_bitmap && b == SB_BITMAP) {
+                l.rows = w.bin_rows + start[SB_S16K];
+                l.count = start[SB_COUNT] - start[SB_S16K];
+            }
+            if (l.count == 0) continue;
+            const int n_wg = (int)(l.count < c.n_cu ? l.count : c.n_cu);
+            HIP_TRY(launch_symbolic_bin(A, B, l, gb_log2, nnz_out, n_wg, &w.sc->queue[round], c.s));
+        }
+        if (!assisted) break;
+        HIP_TRY(launch_count_overflow(A.rows, nnz_out, &w.sc->ovf_count, c.s));
+        OC_TRY(fetch_scalars(c, w.sc));
+        if (st) st->symbolic_overflow_rows = (int64_t)c.h->ovf_count;
+        if (c.h->ovf_count == 0) break;
     }
     return OCEAN_OK;
+}
+
+// ---- sampled compression ratio (Section 3.2) and its spread over the sample (Section 4.1) ------------
+int run_sample(Ctx &c, Work &w, const Csr &A, int64_t n_cols, const uint8_t *sketches, int m_regs, int64_t n_sample,
+               const ocean_options &o, ocean_stats *S)
+{
+    std::vector<int64_t> rows_h((size_t)n_sample);
+    sample_rows_of(A.rows, o, rows_h.data());
+    HIP_TRY(hipMemcpyAsync(w.sample_rows, rows_h.data(), (size_t)n_sample * 8, hipMemcpyHostToDevice, c.s));
+    HIP_TRY(launch_hll_merge(A, sketches, m_regs, w.sample_rows, n_sample, w.prod, w.maxb, nullptr, n_cols, w.sample_est,
+                             nullptr, c.s));
+    HIP_TRY(launch_sample_reduce(w.sample_rows, n_sample, w.prod, w.sample_est, w.sc->sample_sums, c.s));
+    OC_TRY(fetch_scalars(c, w.sc));   // also keeps rows_h alive until the copy is done
+    const double *ss = c.h->sample_sums;
+    S->sampled_cr = ss[1] > 0.0 ? ss[0] / ss[1] : 1.0;
+    S->sampled_rows = (int32_t)n_sample;
+    if (ss[4] > 0.0) {
+        S->cr_mean = ss[2] / ss[4];
+        const double var = ss[3] / ss[4] - S->cr_mean * S->cr_mean;
+        S->cr_std = var > 0.0 ? std::sqrt(var) : 0.0;
+    }
+    return OCEAN_OK;
+}
+
+// The compression ratio the symbolic pass may count on (Section 4.1: "conservative estimate" from the mean
+// and standard deviation over the sample): assist_sigmas standard deviations below the mean, at least 1.
+double conservative_cr(const ocean_stats *S, const ocean_options &o)
+{
+    if (S->sampled_rows <= 0 || !(S->cr_mean > 0.0)) return 1.0;
+    const double v = S->cr_mean - o.assist_sigmas * S->cr_std;
+    return v > 1.0 ? v : 1.0;
 }
 
 // ---- numeric bins ------------------------------------------------------------------------------------
@@ -433,6 +477,10 @@ void fill_defaults(ocean_options *o)
     o->estimate_scale = 1.0;
     o->validate_inputs = 1;
     o->force_hash_kernels = 0;
+    o->assisted_symbolic = 1;
+    o->assist_sigmas = 1.0;
+    o->bitmap_query = -1;
+    o->bitmap_query_cr = 2.0;
     o->allocator = nullptr;
 }
 
@@ -541,18 +589,14 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
         } else {
             OC_TRY(build_sketches());
             OC_TRY(mark(c, OCEAN_ST_SAMPLE));
-            std::vector<int64_t> rows_h((size_t)n_sample);
-            sample_rows_of(m, o, rows_h.data());
-            HIP_TRY(hipMemcpyAsync(w.sample_rows, rows_h.data(), (size_t)n_sample * 8, hipMemcpyHostToDevice, c.s));
-            HIP_TRY(launch_hll_merge(A, sketches, m_regs, w.sample_rows, n_sample, w.prod, w.maxb, nullptr, n,
-                                     w.sample_est, nullptr, c.s));
-            HIP_TRY(launch_sample_reduce(w.sample_rows, n_sample, w.prod, w.sample_est, w.sc->sample_sums, c.s));
-            OC_TRY(fetch_scalars(c, w.sc));   // also keeps rows_h alive until the copy is done
-            const double den = c.h->sample_sums[1];
-            S->sampled_cr = den > 0.0 ? c.h->sample_sums[0] / den : 1.0;
-            S->sampled_rows = (int32_t)n_sample;
+            OC_TRY(run_sample(c, w, A, n, sketches, m_regs, n_sample, o, S));
             workflow = select_of(S->avg_products, S->er, S->sampled_cr, o);
         }
+    }
+    if (workflow == OCEAN_WF_SYMBOLIC && o.assisted_symbolic == 2 && S->sampled_rows == 0) {
+        OC_TRY(build_sketches());
+        OC_TRY(mark(c, OCEAN_ST_SAMPLE));
+        OC_TRY(run_sample(c, w, A, n, sketches, m_regs, n_sample, o, S));
     }
 
     int32_t *t_col = nullptr;   // output region of the first attempt (C itself on the two-pass path)
@@ -574,7 +618,9 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
             bp.mode = 1;
             bp.coef = o.expand_coef > 0.0 ? o.expand_coef : (m_regs == 32 ? 2.0 : 1.5);
         } else if (workflow == OCEAN_WF_SYMBOLIC) {
-            OC_TRY(run_symbolic(c, w, A, B, gb_log2, w.nnz_final, S));
+            S->assist_cr = o.assisted_symbolic ? conservative_cr(S, o) : 1.0;
+            if (!(S->assist_cr > 1.0)) S->assist_cr = 0.0;
+            OC_TRY(run_symbolic(c, w, A, B, gb_log2, S->assist_cr, w.nnz_final, S));
             bp.mode = 2;
             bp.coef = o.exact_load_coef;
             global_coef = o.exact_load_coef;
@@ -589,7 +635,7 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
         OC_TRY(mark(c, OCEAN_ST_BINNING));
         OC_TRY(zero_bins(c, w));
         int64_t *ptr = workflow == OCEAN_WF_SYMBOLIC ? c_rp : w.tmp_ptr;
-        HIP_TRY(launch_classify(m, bp, o.estimate_scale, w.prod, w.est, w.nnz_final, nullptr, w.bin, w.cap,
+        HIP_TRY(launch_classify(m, bp, o.estimate_scale, w.prod, w.est, w.nnz_final, nullptr, nullptr, w.bin, w.cap,
                                 w.sc->bin_count, &w.sc->max_cap, c.s));
         HIP_TRY(launch_scan_i32_to_i64(w.cap, m, ptr, w.scan_tmp, c.s));
         HIP_TRY(launch_scatter(m, NB_COUNT, w.bin, w.sc->bin_count, w.sc->bin_cursor, w.bin_rows, c.s));
@@ -674,7 +720,7 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
         for (int b = 0; b < NB_COUNT; ++b) bp.slots[b] = kNumericSlots[b];
         bp.n_cols = n;
         OC_TRY(zero_bins(c, w));
-        HIP_TRY(launch_classify(m, bp, 1.0, w.prod, nullptr, nullptr, w.row_nnz, w.bin, w.cap, w.sc->bin_count,
+        HIP_TRY(launch_classify(m, bp, 1.0, w.prod, nullptr, nullptr, w.row_nnz, nullptr, w.bin, w.cap, w.sc->bin_count,
                                 &w.sc->max_cap, c.s));
         HIP_TRY(launch_scan_i32_to_i64(w.cap, m, w.tmp_ptr2, w.scan_tmp, c.s));
         HIP_TRY(launch_scatter(m, NB_COUNT, w.bin, w.sc->bin_count, w.sc->bin_cursor, w.bin_rows, c.s));
@@ -922,11 +968,24 @@ int ocean_symbolic(const ocean_csr *A, const ocean_csr *B, int32_t *nnz_per_row,
     ocean_stats *S = stats ? stats : &local;
     int rc = [&]() -> int {
         Work w;
-        OC_TRY(work_alloc(c, w, A->rows, 0));
+        const int64_t n_sample = o.assisted_symbolic == 2 ? sample_size_of(A->rows, o) : 0;
+        OC_TRY(work_alloc(c, w, A->rows, n_sample));
         const Csr a = view(A), b = view(B);
         OC_TRY(run_analysis(c, w, a, b, o.validate_inputs != 0, S));
         const int gb_log2 = ilog2_ceil_d(S->er, 0, 6);
-        OC_TRY(run_symbolic(c, w, a, b, gb_log2, nnz_per_row, S));
+        double assist_cr = 0.0;
+        if (n_sample > 0 && S->products > 0) {
+            const int m_regs = registers_of(S->er, o);
+            uint8_t *sketches = static_cast<uint8_t *>(c.alloc((size_t)b.rows * m_regs));
+            if (!sketches) return fail(OCEAN_EALLOC, "sketch allocation failed");
+            HIP_TRY(launch_hll_sketch(b, m_regs, sketches, c.s));
+            OC_TRY(run_sample(c, w, a, b.cols, sketches, m_regs, n_sample, o, S));
+            S->hll_registers = m_regs;
+            assist_cr = conservative_cr(S, o);
+            if (!(assist_cr > 1.0)) assist_cr = 0.0;
+        }
+        S->assist_cr = assist_cr;
+        OC_TRY(run_symbolic(c, w, a, b, gb_log2, assist_cr, nnz_per_row, S));
         HIP_TRY(hipStreamSynchronize(c.s));
         return OCEAN_OK;
     }();

@@ -187,19 +187,21 @@ hipError_t launch_hll_merge(const Csr &A, const uint8_t *sketches, int m, const 
                             const int64_t *prod, const int32_t *maxb, const int64_t *b_rp, int64_t b_cols,
                             double *est, uint8_t *merged, hipStream_t s);
 hipError_t launch_sample_reduce(const int64_t *rows, int64_t n_rows, const int64_t *prod, const double *est,
-                                double *out /*[0]=sum prod,[1]=sum est*/, hipStream_t s);
+                                double *out /*[5]: sum prod, sum est, sum cr, sum cr^2, rows*/, hipStream_t s);
 
 // binning.hip
 struct BinParams {
     int mode;            // 0 upper bound, 1 estimate, 2 exact nnz, 3 symbolic pass (see k_classify)
-    double coef;         // table slots per predicted entry
+    double coef;         // table slots per predicted entry; mode 3: the compression ratio the product counts
+                         // are divided by (assisted symbolic binning, Section 4.1), 1.0 = plain product counts
     int n_bins;
     int32_t slots[OCEAN_MAX_BINS];
     int64_t n_cols;
 };
 hipError_t launch_classify(int64_t m, const BinParams &p, double scale, const int64_t *prod, const double *est,
-                           const int32_t *nnz_exact, const int32_t *row_mask, uint8_t *bin_of_row, int32_t *cap,
-                           unsigned long long *bin_count, unsigned long long *max_cap, hipStream_t s);
+                           const int32_t *nnz_exact, const int32_t *row_mask, const int32_t *lower_bound,
+                           uint8_t *bin_of_row, int32_t *cap, unsigned long long *bin_count,
+                           unsigned long long *max_cap, hipStream_t s);
 hipError_t launch_scatter(int64_t m, int n_bins, const uint8_t *bin_of_row, const unsigned long long *bin_count,
                           unsigned long long *bin_cursor, int32_t *bin_rows, hipStream_t s);
 hipError_t launch_scan_i32_to_i64(const int32_t *in, int64_t n, int64_t *out /*n+1*/, int64_t *block_tmp,
@@ -217,6 +219,8 @@ struct SymLaunch {
     const int32_t *rows;   // row ids of this bin
     int64_t count;
     int bin;
+    bool may_overflow;     // tables were sized from a guess (assisted binning): a row whose table fills up
+                           // reports -1 instead of a count and probing gives up early
 };
 hipError_t launch_symbolic_bin(const Csr &A, const Csr &B, const SymLaunch &l, int gb_log2, int32_t *nnz_out,
                                int n_wg, unsigned long long *queue, hipStream_t s);

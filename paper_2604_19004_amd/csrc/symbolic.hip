@@ -16,10 +16,18 @@ using NoVal = unsigned char;   // the symbolic pass carries no values
 // were new.  Double hashing, and every lane walks its own ids at its own pace
 // (one compare-and-swap per lane and round), so the wave-wide loop runs for the
 // largest per-lane sum of probes.  Valid ids come first in a batch.
-template <int BITS, int U>
-__device__ __forceinline__ int lds_count_new_batch(int32_t *keys, const int32_t (&cj)[U])
+// A table sized from the product count cannot fill up.  A table sized from a
+// guess (assisted binning, Section 4.1) can: then CAPPED gives up on an id after
+// PROBE_CAP probes - at the load such a table is meant for (0.8) a longer probe
+// sequence is a one-in-a-million event, in a table about to fill up it is the
+// rule and would cost thousands of probes per id - and sets ovf; the caller
+// redoes such a row with a table sized from its product count.
+constexpr uint32_t PROBE_CAP = 64;
+template <int BITS, bool CAPPED, int U>
+__device__ __forceinline__ int lds_count_new_batch(int32_t *keys, const int32_t (&cj)[U], bool &ovf)
 {
     constexpr uint32_t MASK = (1u << BITS) - 1u;
+    constexpr uint32_t LIMIT = CAPPED && PROBE_CAP < MASK ? PROBE_CAP : MASK;
     int idx = 0, fresh = 0;
     int32_t key = cj[0];
     uint32_t h = table_hash(key, BITS);
@@ -39,13 +47,14 @@ __device__ __forceinline__ int lds_count_new_batch(int32_t *keys, const int32_t 
             rounds = 0;
         } else {
             h = (h + step) & MASK;
-            if (++rounds > MASK) key = -1;   // cannot happen: tables are sized from the product count
+            if (++rounds > LIMIT) { ovf = true; key = -1; }
         }
     }
     return fresh;
 }
 
 // ---------------------------------------------------------- group kernel
+template <bool CAPPED>
 __global__ void __launch_bounds__(256)
 k_symbolic_group(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col,
                  const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_col,
@@ -66,9 +75,10 @@ k_symbolic_group(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
     for (int s = sub; s < SLOTS; s += G) keys[s] = EMPTY_KEY;
     wave_sync();
     int fresh = 0;
+    bool ovf = false;
     const int64_t e0 = live ? a_rp[row] : 0;
     const int64_t e1 = live ? a_rp[row + 1] : 0;
-    auto f = [&](const auto &cj, const auto &) { fresh += lds_count_new_batch<BITS>(keys, cj); };
+    auto f = [&](const auto &cj, const auto &) { if (!ovf) fresh += lds_count_new_batch<BITS, CAPPED>(keys, cj, ovf); };
     const int chunks = group_reduce_max((int)((e1 - e0 + G - 1) / G), WAVE);
     for (int ch = 0; ch < chunks; ++ch) {
         const int64_t e = e0 + (int64_t)ch * G + sub;
@@ -82,10 +92,12 @@ k_symbolic_group(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
         group_flat<G, false>(s_fc[rl], p0, len, NoVal(), b_col, (const NoVal *)nullptr, f);
     }
     fresh = group_reduce_sum(fresh, G);
-    if (live && sub == 0) nnz_out[row] = fresh;
+    const bool ovf_any = CAPPED && group_reduce_max((int)ovf, G) != 0;
+    if (live && sub == 0) nnz_out[row] = ovf_any ? -1 : fresh;
 }
 
 // ----------------------------------------------------------- wave kernel
+template <bool CAPPED>
 __global__ void __launch_bounds__(256)
 k_symbolic_wave(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col,
                 const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_col,
@@ -104,16 +116,18 @@ k_symbolic_wave(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     for (int s = sub; s < SLOTS; s += WAVE) keys[s] = EMPTY_KEY;
     wave_sync();
     int fresh = 0;
+    bool ovf = false;
     wave_traverse<false>(a_col, (const NoVal *)nullptr, a_rp[row], a_rp[row + 1],
                          [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
                          b_col, (const NoVal *)nullptr, s_fc[rl],
-                         [&](const auto &cj, const auto &) { fresh += lds_count_new_batch<BITS>(keys, cj); });
+                         [&](const auto &cj, const auto &) { if (!ovf) fresh += lds_count_new_batch<BITS, CAPPED>(keys, cj, ovf); });
     fresh = group_reduce_sum(fresh, WAVE);
-    if (sub == 0) nnz_out[row] = fresh;
+    const bool ovf_any = CAPPED && __ballot(ovf) != 0ull;
+    if (sub == 0) nnz_out[row] = ovf_any ? -1 : fresh;
 }
 
 // ------------------------------------------------------ workgroup kernel
-template <int BITS, int THREADS>
+template <int BITS, int THREADS, bool CAPPED>
 __global__ void __launch_bounds__(THREADS)
 k_symbolic_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col,
               const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_col,
@@ -122,23 +136,25 @@ k_symbolic_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_co
     constexpr int SLOTS = 1 << BITS;
     __shared__ int32_t s_keys[SLOTS];
     __shared__ WgChunk<NoVal, THREADS> s_fc;
-    __shared__ int s_count;
+    __shared__ int s_count, s_ovf;
     const int tid = threadIdx.x;
     const int64_t r = blockIdx.x;
     if (r >= count) return;
     const int64_t row = rows[r];
     for (int s = tid; s < SLOTS; s += THREADS) s_keys[s] = EMPTY_KEY;
-    if (tid == 0) s_count = 0;
+    if (tid == 0) { s_count = 0; s_ovf = 0; }
     __syncthreads();
     int fresh = 0;
+    bool ovf = false;
     wg_traverse<THREADS, false>(a_col, (const NoVal *)nullptr, a_rp[row], a_rp[row + 1],
                                 [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
                                 b_col, (const NoVal *)nullptr, s_fc,
-                                [&](const auto &cj, const auto &) { fresh += lds_count_new_batch<BITS>(s_keys, cj); });
+                                [&](const auto &cj, const auto &) { if (!ovf) fresh += lds_count_new_batch<BITS, CAPPED>(s_keys, cj, ovf); });
     fresh = group_reduce_sum(fresh, WAVE);
     if (lane_id() == 0 && fresh) atomicAdd(&s_count, fresh);
+    if (CAPPED && ovf) s_ovf = 1;
     __syncthreads();
-    if (tid == 0) nnz_out[row] = s_count;
+    if (tid == 0) nnz_out[row] = (CAPPED && s_ovf) ? -1 : s_count;
 }
 
 // --------------------------------------------------------- bitmap kernel
@@ -252,16 +268,30 @@ hipError_t launch_symbolic_bin(const Csr &A, const Csr &B, const SymLaunch &l, i
 {
     if (l.count <= 0) return hipSuccess;
 #define OCEAN_SYM_WG(BITS, THREADS)                                                                               \
-    hipLaunchKernelGGL((k_symbolic_wg<BITS, THREADS>), dim3((unsigned)l.count), dim3(THREADS), 0, s, A.rp, A.col,   \
-                       B.rp, B.col, l.rows, l.count, nnz_out)
+    do {                                                                                                          \
+        if (l.may_overflow)                                                                                       \
+            hipLaunchKernelGGL((k_symbolic_wg<BITS, THREADS, true>), dim3((unsigned)l.count), dim3(THREADS), 0, s,  \
+                               A.rp, A.col, B.rp, B.col, l.rows, l.count, nnz_out);                               \
+        else                                                                                                      \
+            hipLaunchKernelGGL((k_symbolic_wg<BITS, THREADS, false>), dim3((unsigned)l.count), dim3(THREADS), 0, s, \
+                               A.rp, A.col, B.rp, B.col, l.rows, l.count, nnz_out);                               \
+    } while (0)
     switch (l.bin) {
     case SB_G16:
-        hipLaunchKernelGGL(k_symbolic_group, dim3((unsigned)((l.count + 15) / 16)), dim3(256), 0, s, A.rp, A.col, B.rp, B.col,
-                           l.rows, l.count, nnz_out);
+        if (l.may_overflow)
+            hipLaunchKernelGGL(k_symbolic_group<true>, dim3((unsigned)((l.count + 15) / 16)), dim3(256), 0, s, A.rp, A.col,
+                               B.rp, B.col, l.rows, l.count, nnz_out);
+        else
+            hipLaunchKernelGGL(k_symbolic_group<false>, dim3((unsigned)((l.count + 15) / 16)), dim3(256), 0, s, A.rp, A.col,
+                               B.rp, B.col, l.rows, l.count, nnz_out);
         break;
     case SB_W64:
-        hipLaunchKernelGGL(k_symbolic_wave, dim3((unsigned)((l.count + 3) / 4)), dim3(256), 0, s, A.rp, A.col, B.rp, B.col,
-                           l.rows, l.count, nnz_out);
+        if (l.may_overflow)
+            hipLaunchKernelGGL(k_symbolic_wave<true>, dim3((unsigned)((l.count + 3) / 4)), dim3(256), 0, s, A.rp, A.col, B.rp,
+                               B.col, l.rows, l.count, nnz_out);
+        else
+            hipLaunchKernelGGL(k_symbolic_wave<false>, dim3((unsigned)((l.count + 3) / 4)), dim3(256), 0, s, A.rp, A.col, B.rp,
+                               B.col, l.rows, l.count, nnz_out);
         break;
     case SB_S1K: OCEAN_SYM_WG(10, 256); break;
     case SB_S4K: OCEAN_SYM_WG(12, 512); break;

@@ -89,6 +89,36 @@ def test_symbolic_exact(ob, name):
     assert st["products"] == int(prod.sum())
 
 
+@pytest.mark.parametrize("name", ["rmat", "rect", "clustered"])
+def test_assisted_symbolic_binning(ob, name):
+    """Section 4.1: key tables of the symbolic pass sized from products / conservative CR.  The counts stay
+    exact whatever the ratio: a ratio far above the truth (negative sigmas) makes tables fill up, and those
+    rows are recounted with product-sized tables."""
+    A, B, ref, prod = workload(name, True)
+    dA, dB = ob.to_device(A), ob.to_device(B)
+    want = np.diff(ref.row_ptr)
+    plain, st0 = ob.symbolic(dA, dB, opt=ob.default_options(assisted_symbolic=0))
+    assert st0["assist_cr"] == 0.0 and st0["symbolic_overflow_rows"] == 0
+    assert np.array_equal(plain.cpu().numpy().astype(np.int64), want)
+    nnz, st = ob.symbolic(dA, dB, opt=ob.default_options(assisted_symbolic=2))
+    assert np.array_equal(nnz.cpu().numpy().astype(np.int64), want)
+    m = owf.hll_registers(prod.sum() / A.nnz)
+    rows = owf.sample_rows(A.rows, 1)
+    mu, sigma, cons = owf.conservative_cr(prod[rows].astype(np.float64), ohll.estimate_rows(A, B, m, rows=rows))
+    assert st["cr_mean"] == pytest.approx(mu, rel=1e-9) and st["cr_std"] == pytest.approx(sigma, rel=1e-7, abs=1e-9)
+    assert st["assist_cr"] == pytest.approx(cons if cons > 1.0 else 0.0, rel=1e-7)
+    if cons > 1.05:   # smaller tables: rows move to smaller bins
+        assert sum(i * n for i, n in enumerate(st["symbolic_rows_per_bin"])) < sum(i * n for i, n in enumerate(st0["symbolic_rows_per_bin"]))
+    over, st2 = ob.symbolic(dA, dB, opt=ob.default_options(assisted_symbolic=2, assist_sigmas=-6.0))
+    assert np.array_equal(over.cpu().numpy().astype(np.int64), want)
+    if name != "rect":   # (rect: CR ~ 1 everywhere, no spread to exaggerate)
+        assert st2["symbolic_overflow_rows"] > 0
+    # the whole path with the forced two-pass workflow and assisted binning
+    Cd, st3 = ob.spgemm(dA, dB, workflow=ob.WF_SYMBOLIC, assisted_symbolic=2, assist_sigmas=-2.0)
+    check_result(Cd, ref, A, f"{name}/symbolic assisted")
+    assert st3["assist_cr"] > 0.0 or name == "rect"
+
+
 def test_host_helpers_match_oracle(ob):
     for rows in (1, 100, 4096, 200000, 1 << 20):
         assert ob.sample_size(rows) == owf.sample_size(rows)

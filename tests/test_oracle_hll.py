@@ -162,3 +162,18 @@ def test_sampled_cr_close_to_true_cr():
     cr_s = wf.sampled_cr(prod[rows].astype(np.float64), est)
     cr = prod.sum() / nnz.sum()
     assert abs(cr_s / cr - 1) < 0.1
+
+
+def test_conservative_cr_by_hand():
+    # Section 4.1 as read here: ratios 2, 4, 3 -> mean 3, population std sqrt(2/3); an empty row is skipped
+    prod = np.array([10, 20, 30, 0], np.float64)
+    est = np.array([5, 5, 10, 0], np.float64)
+    mu, sigma, cons = wf.conservative_cr(prod, est)
+    assert mu == pytest.approx(3.0) and sigma == pytest.approx(math.sqrt(2.0 / 3.0))
+    assert cons == pytest.approx(3.0 - math.sqrt(2.0 / 3.0))
+    assert wf.conservative_cr(prod, est, sigmas=2.0)[2] == pytest.approx(3.0 - 2.0 * math.sqrt(2.0 / 3.0))
+    assert wf.conservative_cr(prod, est, sigmas=10.0)[2] == 1.0                      # never below 1: nnz <= products
+    assert wf.conservative_cr(np.zeros(3), np.zeros(3)) == (0.0, 0.0, 1.0)
+    # identical rows: no spread, the conservative ratio is the ratio itself
+    assert wf.conservative_cr(np.full(7, 12.0), np.full(7, 4.0)) == (3.0, 0.0, 3.0)
+
