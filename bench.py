@@ -26,11 +26,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-BIN_NAMES = ["k_numeric_group<8> (8 lanes/row, 32 slots)", "k_numeric_group<16> (16 lanes/row, 64 slots)",
+BIN_NAMES = ["16 slots (k_numeric_esc<16> under the product bound, else k_numeric_group<8>)",
+             "32 slots (k_numeric_esc<32> under the product bound, else k_numeric_group<8>)", "k_numeric_group<16> (16 lanes/row, 64 slots)",
              "k_numeric_wave (256 slots)", "k_numeric_wg<9> (512 slots)", "k_numeric_wg<10> (1024 slots)",
              "k_numeric_wg<11> (2048 slots)", "k_numeric_wg<12> (4096 slots)", "k_numeric_wg<13> (8192 slots)",
              "rows up to 32768 entries", "k_numeric_heavy (column windows in LDS)"]
-LAST_BIN = 9   # the last bin of ocean_bin_layout
+LAST_BIN = 10   # the last bin of ocean_bin_layout
 
 
 def model_bytes(nnz_a, products, nnz_c, rows, v):
@@ -38,10 +39,14 @@ def model_bytes(nnz_a, products, nnz_c, rows, v):
     return nnz_a * (4 + v) + products * (4 + v) + nnz_c * (4 + v) + 8 * (rows + 1)
 
 
+_inputs = {}
+
+
 def run_workload(ob, W, torch, name, workflow, steps, warmup):
-    import numpy as np
-    A, B, desc = W.make(name)
-    dA, dB = ob.to_device(A), ob.to_device(B)
+    if name not in _inputs:   # generated once, resident in HBM from here on
+        A, B, desc = W.make(name)
+        _inputs[name] = (A, B, desc, ob.to_device(A), ob.to_device(B))
+    A, B, desc, dA, dB = _inputs[name]
     v = A.val.dtype.itemsize
     wf = {"auto": ob.WF_AUTO, "upper_bound": ob.WF_UPPER_BOUND, "hll": ob.WF_HLL, "symbolic": ob.WF_SYMBOLIC}[workflow]
     for _ in range(warmup):

@@ -38,6 +38,12 @@ enum {
 /* Workflows of Table 1 of the paper.  AUTO applies the table's rule. */
 enum { OCEAN_WF_AUTO = 0, OCEAN_WF_UPPER_BOUND = 1, OCEAN_WF_HLL = 2, OCEAN_WF_SYMBOLIC = 3 };
 
+/* How AUTO chooses: Table 1 as printed (thresholds from the options), or the same table with the CR
+ * threshold re-derived for MI355X from measured compaction and symbolic rates: it slides from
+ * tuned_cr_light (all products in rows that fit the LDS key tables) to tuned_cr_heavy (all in rows that
+ * outgrow them); problems with fewer than tuned_min_products products keep the printed rule. */
+enum { OCEAN_SEL_TABLE1 = 0, OCEAN_SEL_MI355X = 1 };
+
 /*
  * CSR matrix (Section 2.1): row_ptr has rows+1 ascending 0-based offsets,
  * col_idx / val hold the entries of each row contiguously.  Column ids are
@@ -94,8 +100,15 @@ typedef struct ocean_options {
     int32_t bitmap_query;            /* dense accumulators read a column's presence bit and set it only when it is
                                         clear (Section 4.1): 0 never, 1 always, -1 (default) when a sampled CR is
                                         known and >= bitmap_query_cr */
-    int32_t reserved0;
+    int32_t esc_short_rows;          /* 1 (default): rows with at most 16 / 32 intermediate products are accumulated by
+                                        expand-sort-compress, 4 / 2 rows per wave, wherever accumulators are sized from
+                                        the product bound (upper-bound workflow, retry; Section 3.3); 0: hash tables */
     double bitmap_query_cr;          /* 2.0 (Section 4.3) */
+    int32_t selector;                /* OCEAN_SEL_TABLE1 (default) or OCEAN_SEL_MI355X */
+    int32_t reserved1;
+    double tuned_cr_light;           /* 1.0 */
+    double tuned_cr_heavy;           /* 4.5 */
+    double tuned_min_products;       /* 4194304 */
     const ocean_allocator *allocator; /* host pointer, may be NULL */
 } ocean_options;
 
@@ -116,6 +129,7 @@ enum {
 typedef struct ocean_stats {
     int64_t products;          /* P: intermediate products */
     int64_t max_row_products;
+    int64_t heavy_products;    /* products of the rows whose product count exceeds the largest LDS hash table (4096) */
     int64_t nnz_c;
     double er;                 /* P / nnz(A) */
     double avg_products;       /* P / rows(A) */
@@ -233,6 +247,9 @@ int ocean_symbolic(const ocean_csr *A, const ocean_csr *B, int32_t *nnz_per_row,
 
 /* Host-only helpers of the analysis step (Section 4.3, Table 1). */
 int32_t ocean_select_workflow(double avg_products, double er, double cr, const ocean_options *opt);
+/* The choice under OCEAN_SEL_MI355X (see above); products / heavy_products as in ocean_stats. */
+int32_t ocean_select_workflow_tuned(double avg_products, double er, double cr, double products, double heavy_products,
+                                    const ocean_options *opt);
 int32_t ocean_hll_register_count(double er, const ocean_options *opt);
 int64_t ocean_sample_size(int64_t rows, const ocean_options *opt);
 /* rows_out: host int64[ocean_sample_size(rows)], ascending row ids of the stratified sample. */

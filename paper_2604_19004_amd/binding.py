@@ -17,6 +17,7 @@ from . import build as _build
 
 F64, F32 = 0, 1
 WF_AUTO, WF_UPPER_BOUND, WF_HLL, WF_SYMBOLIC = 0, 1, 2, 3
+SEL_TABLE1, SEL_MI355X = 0, 1
 WORKFLOW_NAMES = {WF_AUTO: "auto", WF_UPPER_BOUND: "upper_bound", WF_HLL: "hll", WF_SYMBOLIC: "symbolic"}
 MAX_BINS = 12
 STAGES = ("analysis", "sketch", "sample", "predict", "binning", "numeric", "retry", "compact")
@@ -41,12 +42,14 @@ class ocean_options(C.Structure):
                 ("exact_load_coef", C.c_double), ("sample_ratio", C.c_double), ("sample_min", C.c_int32),
                 ("sample_max", C.c_int32), ("sample_seed", C.c_uint32), ("estimate_scale", C.c_double),
                 ("validate_inputs", C.c_int32), ("force_hash_kernels", C.c_int32), ("assisted_symbolic", C.c_int32),
-                ("assist_sigmas", C.c_double), ("bitmap_query", C.c_int32), ("reserved0", C.c_int32),
-                ("bitmap_query_cr", C.c_double), ("allocator", C.POINTER(ocean_allocator))]
+                ("assist_sigmas", C.c_double), ("bitmap_query", C.c_int32), ("esc_short_rows", C.c_int32),
+                ("bitmap_query_cr", C.c_double), ("selector", C.c_int32), ("reserved1", C.c_int32),
+                ("tuned_cr_light", C.c_double), ("tuned_cr_heavy", C.c_double), ("tuned_min_products", C.c_double),
+                ("allocator", C.POINTER(ocean_allocator))]
 
 
 class ocean_stats(C.Structure):
-    _fields_ = [("products", C.c_int64), ("max_row_products", C.c_int64), ("nnz_c", C.c_int64), ("er", C.c_double),
+    _fields_ = [("products", C.c_int64), ("max_row_products", C.c_int64), ("heavy_products", C.c_int64), ("nnz_c", C.c_int64), ("er", C.c_double),
                 ("avg_products", C.c_double), ("sampled_cr", C.c_double), ("cr_mean", C.c_double),
                 ("cr_std", C.c_double), ("assist_cr", C.c_double), ("workflow", C.c_int32),
                 ("hll_registers", C.c_int32), ("sampled_rows", C.c_int32), ("fell_back", C.c_int32),
@@ -57,7 +60,7 @@ class ocean_stats(C.Structure):
                 ("bin_nnz_c", C.c_int64 * MAX_BINS)]
 
     def as_dict(self) -> dict:
-        d = {k: getattr(self, k) for k in ("products", "max_row_products", "nnz_c", "er", "avg_products", "sampled_cr",
+        d = {k: getattr(self, k) for k in ("products", "max_row_products", "heavy_products", "nnz_c", "er", "avg_products", "sampled_cr",
                                            "cr_mean", "cr_std", "assist_cr", "symbolic_overflow_rows",
                                            "hll_registers", "sampled_rows", "fell_back", "overflow_rows", "temp_slots",
                                            "peak_bytes", "total_ms")}
@@ -102,6 +105,8 @@ def load():
     lib.ocean_symbolic.argtypes = [P(ocean_csr), P(ocean_csr), vp, P(ocean_options), P(ocean_stats), vp]
     lib.ocean_select_workflow.argtypes = [dbl, dbl, dbl, P(ocean_options)]
     lib.ocean_select_workflow.restype = i32
+    lib.ocean_select_workflow_tuned.argtypes = [dbl, dbl, dbl, dbl, dbl, P(ocean_options)]
+    lib.ocean_select_workflow_tuned.restype = i32
     lib.ocean_hll_register_count.argtypes = [dbl, P(ocean_options)]
     lib.ocean_hll_register_count.restype = i32
     lib.ocean_sample_size.argtypes = [i64, P(ocean_options)]
@@ -136,6 +141,12 @@ def default_options(**kw) -> ocean_options:
 # ---------------------------------------------------------------- host-only helpers
 def select_workflow(avg_products: float, er: float, cr: float, opt: ocean_options | None = None) -> int:
     return int(load().ocean_select_workflow(avg_products, er, cr, C.byref(opt) if opt else None))
+
+
+def select_workflow_tuned(avg_products: float, er: float, cr: float, products: float, heavy_products: float,
+                          opt: ocean_options | None = None) -> int:
+    return int(load().ocean_select_workflow_tuned(avg_products, er, cr, products, heavy_products,
+                                                  C.byref(opt) if opt else None))
 
 
 def hll_register_count(er: float, opt: ocean_options | None = None) -> int:

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libocean_spgemm.so")
-SOURCES = ["analysis.hip", "binning.hip", "symbolic.hip", "numeric.hip", "compact.hip", "order.hip", "ocean_api.hip"]
+SOURCES = ["analysis.hip", "binning.hip", "symbolic.hip", "numeric.hip", "esc.hip", "compact.hip", "order.hip", "ocean_api.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",

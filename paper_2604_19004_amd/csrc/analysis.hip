@@ -63,19 +63,23 @@ hipError_t launch_validate(const Csr &A, const Csr &B, int32_t *flags, hipStream
 // and on power-law inputs such rows cluster (their indices share bit patterns,
 // so whole workgroups would get nothing else): they are put on a list and a
 // second kernel gives each of them a workgroup of its own.
-__device__ __forceinline__ void block_totals(long long tsum, long long tmax, long long *s_sum, long long *s_max,
-                                             unsigned long long *totals)
+// totals[0] += products, totals[1] = max(products of a row), totals[2] += products of the rows whose
+// product count exceeds heavy_from (the rows that outgrow the LDS hash tables).
+__device__ __forceinline__ void block_totals(long long tsum, long long tmax, long long theavy, long long *s_sum,
+                                             long long *s_max, long long *s_heavy, unsigned long long *totals)
 {
     const long long wsum = group_reduce_sum(tsum, WAVE);
     const long long wmax = group_reduce_max(tmax, WAVE);
+    const long long wheavy = group_reduce_sum(theavy, WAVE);
     const int w = threadIdx.x / WAVE;
-    if (lane_id() == 0) { s_sum[w] = wsum; s_max[w] = wmax; }
+    if (lane_id() == 0) { s_sum[w] = wsum; s_max[w] = wmax; s_heavy[w] = wheavy; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        long long bs = 0, bm = 0;
-        for (int i = 0; i < TPB / WAVE; ++i) { bs += s_sum[i]; bm = s_max[i] > bm ? s_max[i] : bm; }
+        long long bs = 0, bm = 0, bh = 0;
+        for (int i = 0; i < TPB / WAVE; ++i) { bs += s_sum[i]; bm = s_max[i] > bm ? s_max[i] : bm; bh += s_heavy[i]; }
         if (bs) atomicAdd(&totals[0], (unsigned long long)bs);
         if (bm) atomicMax(&totals[1], (unsigned long long)bm);
+        if (bh) atomicAdd(&totals[2], (unsigned long long)bh);
     }
 }
 
@@ -83,16 +87,17 @@ __global__ void __launch_bounds__(TPB)
 k_row_products(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col, int64_t m, int64_t a_nnz,
                const int64_t *__restrict__ b_rp, int64_t b_rows, int g_log2, int64_t *__restrict__ prod,
                int32_t *__restrict__ maxb, unsigned long long *totals, int32_t *flags,
-               int32_t *__restrict__ long_rows, unsigned long long *long_count)
+               int32_t *__restrict__ long_rows, unsigned long long *long_count, int64_t heavy_from)
 {
     __shared__ long long s_sum[TPB / WAVE];
     __shared__ long long s_max[TPB / WAVE];
+    __shared__ long long s_heavy[TPB / WAVE];
     const int G = 1 << g_log2;
     const int R = TPB >> g_log2;
     const int rl = threadIdx.x >> g_log2;
     const int sub = threadIdx.x & (G - 1);
     const int64_t long_len = (int64_t)G * 16;
-    long long tsum = 0, tmax = 0;
+    long long tsum = 0, tmax = 0, theavy = 0;
     bool bad = false, bad_rp = false;
     for (int64_t base = (int64_t)blockIdx.x * R; base < m; base += (int64_t)gridDim.x * R) {
         const int64_t row = base + rl;
@@ -140,9 +145,10 @@ k_row_products(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_c
             maxb[row] = (int32_t)(mx > 0x7fffffffLL ? 0x7fffffffLL : mx);
             tsum += p;
             tmax = p > tmax ? p : tmax;
+            theavy += p > heavy_from ? p : 0;
         }
     }
-    block_totals(tsum, tmax, s_sum, s_max, totals);
+    block_totals(tsum, tmax, theavy, s_sum, s_max, s_heavy, totals);
     if (__ballot(bad) != 0 && lane_id() == 0) atomicOr(flags, 4);
     if (__ballot(bad_rp) != 0 && lane_id() == 0) atomicOr(flags, 1);
 }
@@ -152,13 +158,14 @@ __global__ void __launch_bounds__(TPB)
 k_row_products_long(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col,
                     const int64_t *__restrict__ b_rp, int64_t b_rows, int64_t *__restrict__ prod,
                     int32_t *__restrict__ maxb, unsigned long long *totals, int32_t *flags,
-                    const int32_t *__restrict__ long_rows, const unsigned long long *long_count)
+                    const int32_t *__restrict__ long_rows, const unsigned long long *long_count, int64_t heavy_from)
 {
     __shared__ long long s_sum[TPB / WAVE];
     __shared__ long long s_max[TPB / WAVE];
+    __shared__ long long s_heavy[TPB / WAVE];
     const int64_t n = (int64_t)*long_count;
     const int w = threadIdx.x / WAVE;
-    long long tsum = 0, tmax = 0;
+    long long tsum = 0, tmax = 0, theavy = 0;
     bool bad = false;
     for (int64_t i = blockIdx.x; i < n; i += gridDim.x) {
         const int64_t row = long_rows[i];
@@ -196,10 +203,11 @@ k_row_products_long(const int64_t *__restrict__ a_rp, const int32_t *__restrict_
             maxb[row] = (int32_t)(rm > 0x7fffffffLL ? 0x7fffffffLL : rm);
             tsum += rp;
             tmax = rp > tmax ? rp : tmax;
+            theavy += rp > heavy_from ? rp : 0;
         }
         __syncthreads();
     }
-    block_totals(tsum, tmax, s_sum, s_max, totals);
+    block_totals(tsum, tmax, theavy, s_sum, s_max, s_heavy, totals);
     if (__ballot(bad) != 0 && lane_id() == 0) atomicOr(flags, 4);
 }
 
@@ -209,6 +217,7 @@ hipError_t launch_row_products(const Csr &A, const int64_t *b_rp, int64_t b_rows
                                unsigned long long *totals, int32_t *flags, int32_t *long_rows,
                                unsigned long long *long_count, hipStream_t s)
 {
+    const int64_t heavy_from = kNumericSlots[NB_S4K];   // beyond the largest LDS hash table that sorted inputs use
     if (A.rows == 0) return hipSuccess;
     const double avg = A.rows ? (double)A.nnz / (double)A.rows : 0.0;
     const int g_log2 = ilog2_ceil(avg, 1, 6);
@@ -217,10 +226,10 @@ hipError_t launch_row_products(const Csr &A, const int64_t *b_rp, int64_t b_rows
     if (blocks > 2048) blocks = 2048;
     if (long_count == nullptr) long_rows = nullptr;
     hipLaunchKernelGGL(k_row_products, dim3((unsigned)blocks), dim3(TPB), 0, s, A.rp, A.col, A.rows, A.nnz, b_rp,
-                       b_rows, g_log2, prod, maxb, totals, flags, long_rows, long_count);
+                       b_rows, g_log2, prod, maxb, totals, flags, long_rows, long_count, heavy_from);
     if (long_rows != nullptr)
         hipLaunchKernelGGL(k_row_products_long, dim3(2048), dim3(TPB), 0, s, A.rp, A.col, b_rp, b_rows, prod, maxb,
-                           totals, flags, long_rows, long_count);
+                           totals, flags, long_rows, long_count, heavy_from);
     return hipGetLastError();
 }
 

@@ -1224,6 +1224,7 @@ static hipError_t dispatch(const Csr &A, const Csr &B, const NumLaunch &l, int g
     hipLaunchKernelGGL((k_numeric_wg<V, BITS, THREADS>), dim3((unsigned)l.count), dim3(THREADS), 0, s, A.rp, A.col, \
                        av, B.rp, B.col, bv, l.rows, l.count, l.out_ptr, l.out_col, ov, l.row_nnz)
     switch (l.bin) {
+    case NB_E16:
     case NB_G8: {
         const int64_t blocks = (l.count + 31) / 32;
         hipLaunchKernelGGL((k_numeric_group<V, 8, 5>), dim3((unsigned)blocks), dim3(256), 0, s, A.rp, A.col, av, B.rp, B.col,

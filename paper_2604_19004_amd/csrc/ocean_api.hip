@@ -39,7 +39,7 @@ int fail(int code, const std::string &msg)
 
 // Device scalars of one call; zeroed at the start.
 struct Scalars {
-    unsigned long long totals[2];                 // P, largest row
+    unsigned long long totals[4];                 // P, largest row, P of the rows beyond the LDS hash tables, spare
     unsigned long long bin_count[OCEAN_MAX_BINS];
     unsigned long long bin_cursor[OCEAN_MAX_BINS];
     unsigned long long max_cap;
@@ -287,6 +287,7 @@ int run_analysis(Ctx &c, Work &w, const Csr &A, const Csr &B, bool validate, oce
     if (st) {
         st->products = (int64_t)c.h->totals[0];
         st->max_row_products = (int64_t)c.h->totals[1];
+        st->heavy_products = (int64_t)c.h->totals[2];
         st->er = A.nnz > 0 ? (double)st->products / (double)A.nnz : 0.0;
         st->avg_products = A.rows > 0 ? (double)st->products / (double)A.rows : 0.0;
     }
@@ -381,7 +382,7 @@ double conservative_cr(const ocean_stats *S, const ocean_options &o)
 // and global bins is obtained here and kept until the caller releases all.
 int run_numeric(Ctx &c, Work &w, const Csr &A, const Csr &B, int dtype, int gb_log2, const unsigned long long *count,
                 int64_t max_cap_global, double global_coef, const int64_t *out_ptr, int32_t *out_col, void *out_val,
-                int32_t *row_nnz, int queue_base, int stage, bool time_bins)
+                int32_t *row_nnz, int queue_base, int stage, bool time_bins, bool esc)
 {
     // With the window table, the column-window kernel takes every row beyond the 4096-slot table (measured:
     // a row of the 8192-slot bin costs less there than a hash table of its own; smaller rows do not).
@@ -454,6 +455,12 @@ int run_numeric(Ctx &c, Work &w, const Csr &A, const Csr &B, int dtype, int gb_l
             c.bin_ev.emplace_back(b, (int)c.ev.size());
             OC_TRY(mark(c, stage));
         }
+        if (esc && (b == NB_E16 || b == NB_G8)) {
+            // sizes come from the product bound: a row of these bins has at most 16 / 32 products (Section 3.3, ESC)
+            EscLaunch e{l.rows, l.count, b == NB_E16 ? 16 : 32, out_ptr, out_col, out_val, row_nnz};
+            HIP_TRY(launch_numeric_esc(A, B, dtype, e, c.s));
+            continue;
+        }
         HIP_TRY(launch_numeric_bin(A, B, dtype, l, gb_log2, c.s));
     }
     if (time_bins) OC_TRY(mark(c, stage));
@@ -480,6 +487,11 @@ void fill_defaults(ocean_options *o)
     o->assisted_symbolic = 1;
     o->assist_sigmas = 1.0;
     o->bitmap_query = -1;
+    o->esc_short_rows = 1;
+    o->selector = OCEAN_SEL_TABLE1;
+    o->tuned_cr_light = 1.0;
+    o->tuned_cr_heavy = 4.5;
+    o->tuned_min_products = 4194304.0;
     o->bitmap_query_cr = 2.0;
     o->allocator = nullptr;
 }
@@ -513,6 +525,25 @@ int select_of(double avg, double er, double cr, const ocean_options &o)
 {
     if (avg < o.upper_bound_avg_products) return OCEAN_WF_UPPER_BOUND;
     if (er >= o.er_threshold && cr >= o.cr_threshold) return OCEAN_WF_HLL;
+    return OCEAN_WF_SYMBOLIC;
+}
+
+// Table 1 with its CR threshold re-derived for this GPU (selector = OCEAN_SEL_MI355X).  The paper's 8 was
+// "chosen empirically to amortize the cost of output compaction" on an A100 (Section 4.3).  Here the
+// compaction copy runs at 4.3 - 5.8 TB/s, so what it has to beat is the symbolic pass it replaces:
+// estimation wins when products / r_sym > 2 (4 + v) products / (CR * bw), i.e. CR > 2 (4 + v) r_sym / bw.
+// Rows that fit the LDS key tables are counted at r_sym = 140 - 290 G products/s (break-even CR about 1),
+// rows that outgrow them go through the bitmap kernel at about 960 G products/s (break-even CR 4 - 5).
+// So the threshold slides between the two with the share of the products that heavy rows hold.  Small
+// problems keep the paper's rule: below tuned_min_products the extra launches of the estimation path cost
+// more than either pass.
+int select_tuned(double avg, double er, double cr, double products, double heavy_products, const ocean_options &o)
+{
+    if (avg < o.upper_bound_avg_products) return OCEAN_WF_UPPER_BOUND;
+    if (products < o.tuned_min_products) return select_of(avg, er, cr, o);
+    const double share = products > 0.0 ? heavy_products / products : 0.0;
+    const double thr = o.tuned_cr_light + (o.tuned_cr_heavy - o.tuned_cr_light) * share;
+    if (er >= o.er_threshold && cr >= thr) return OCEAN_WF_HLL;
     return OCEAN_WF_SYMBOLIC;
 }
 
@@ -590,7 +621,9 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
             OC_TRY(build_sketches());
             OC_TRY(mark(c, OCEAN_ST_SAMPLE));
             OC_TRY(run_sample(c, w, A, n, sketches, m_regs, n_sample, o, S));
-            workflow = select_of(S->avg_products, S->er, S->sampled_cr, o);
+            workflow = o.selector == OCEAN_SEL_MI355X
+                           ? select_tuned(S->avg_products, S->er, S->sampled_cr, (double)P, (double)S->heavy_products, o)
+                           : select_of(S->avg_products, S->er, S->sampled_cr, o);
         }
     }
     if (workflow == OCEAN_WF_SYMBOLIC && o.assisted_symbolic == 2 && S->sampled_rows == 0) {
@@ -668,8 +701,11 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
     // ---- numeric ----
     OC_TRY(mark(c, OCEAN_ST_NUMERIC));
     HIP_TRY(launch_fill_i32(w.row_nnz, m, 0, c.s));
+    // expand-sort-compress needs every row of its bins to have no more products than lanes (true when the bins come
+    // from the product bound and B has at least 32 columns) and column ids that leave room for the lane number
+    const bool esc_ok = o.esc_short_rows != 0 && n >= 32 && n <= ESC_MAX_COLS;
     OC_TRY(run_numeric(c, w, A, B, dtype, gb_log2, bin_count, max_cap, global_coef, out_ptr, t_col, t_val, w.row_nnz, 0,
-                       OCEAN_ST_NUMERIC, st != nullptr));
+                       OCEAN_ST_NUMERIC, st != nullptr, esc_ok && workflow == OCEAN_WF_UPPER_BOUND));
     if (st) {
         HIP_TRY(hipMemsetAsync(w.sc->bin_work, 0, sizeof(w.sc->bin_work), c.s));
         HIP_TRY(launch_bin_work(m, w.bin, w.prod, A.rp, w.row_nnz, w.sc->bin_work, c.s));
@@ -734,7 +770,7 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
         std::memcpy(bc2, c.h->bin_count, sizeof(bc2));
         HIP_TRY(launch_fill_i32(w.row_nnz2, m, 0, c.s));
         OC_TRY(run_numeric(c, w, A, B, dtype, gb_log2, bc2, (int64_t)c.h->max_cap, 1.25, w.tmp_ptr2, r_col, r_val,
-                           w.row_nnz2, 2, OCEAN_ST_RETRY, false));
+                           w.row_nnz2, 2, OCEAN_ST_RETRY, false, esc_ok));
         HIP_TRY(launch_final_nnz(m, w.row_nnz, w.row_nnz2, w.nnz_final, c.s));
         HIP_TRY(launch_scan_i32_to_i64(w.nnz_final, m, c_rp, w.scan_tmp, c.s));
         HIP_TRY(hipMemcpyAsync(&w.sc->totals[0], c_rp + m, 8, hipMemcpyDeviceToDevice, c.s));
@@ -826,6 +862,7 @@ int ocean_spgemm(const ocean_csr *A, const ocean_csr *B, ocean_csr *C, const oce
     if (opt) o = *opt;
     else fill_defaults(&o);
     if (o.workflow < OCEAN_WF_AUTO || o.workflow > OCEAN_WF_SYMBOLIC) return fail(OCEAN_EINVAL, "unknown workflow");
+    if (o.selector != OCEAN_SEL_TABLE1 && o.selector != OCEAN_SEL_MI355X) return fail(OCEAN_EINVAL, "unknown selector");
     if (o.hll_registers != 0 && o.hll_registers != 32 && o.hll_registers != 64 && o.hll_registers != 128)
         return fail(OCEAN_EINVAL, "hll_registers must be 0, 32, 64 or 128");
     if (!(o.estimate_scale > 0.0) || !(o.exact_load_coef >= 1.0) || o.expand_coef < 0.0 || !(o.sample_ratio >= 0.0) ||
@@ -1001,6 +1038,15 @@ int32_t ocean_select_workflow(double avg_products, double er, double cr, const o
     if (opt) o = *opt;
     else fill_defaults(&o);
     return select_of(avg_products, er, cr, o);
+}
+
+int32_t ocean_select_workflow_tuned(double avg_products, double er, double cr, double products, double heavy_products,
+                                    const ocean_options *opt)
+{
+    ocean_options o;
+    if (opt) o = *opt;
+    else fill_defaults(&o);
+    return select_tuned(avg_products, er, cr, products, heavy_products, o);
 }
 
 int32_t ocean_hll_register_count(double er, const ocean_options *opt)

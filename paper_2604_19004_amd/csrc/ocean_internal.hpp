@@ -18,7 +18,8 @@ constexpr int32_t SORT_PAD = 0x7fffffff;   // sorts after every valid column id
 // multi-short-row and a long-row one; the sizes here are re-derived for 160 KB
 // of LDS and 64-wide waves).  slots = hash-table entries of the bin.
 enum NumericBin {
-    NB_G8 = 0,    // 8 lanes per row, 8 rows per wave, 32 slots
+    NB_E16 = 0,   // 16 slots: with sizes from the product bound, expand-sort-compress, 16 lanes per row (else as NB_G8)
+    NB_G8,        // 8 lanes per row, 8 rows per wave, 32 slots (product bound: expand-sort-compress, 32 lanes per row)
     NB_G16,       // 16 lanes per row, 4 rows per wave, 64 slots
     NB_W64,       // one wave per row, 256 slots
     NB_S512,      // one workgroup per row from here on
@@ -30,7 +31,7 @@ enum NumericBin {
     NB_GLOBAL,    // whole table in global memory
     NB_COUNT
 };
-constexpr int32_t kNumericSlots[NB_COUNT] = {32, 64, 256, 512, 1024, 2048, 4096, 8192, 32768, 0x7fffffff};
+constexpr int32_t kNumericSlots[NB_COUNT] = {16, 32, 64, 256, 512, 1024, 2048, 4096, 8192, 32768, 0x7fffffff};
 
 enum SymbolicBin {
     SB_G16 = 0,   // 64 keys
@@ -254,6 +255,19 @@ hipError_t launch_window_table(const Csr &B, int dtype, uint32_t *bw, int *n_win
 int heavy_workgroups_per_cu();   // workgroups of the column-window kernel that one compute unit holds
 int dense_window_count(int64_t n_cols, int dtype);
 hipError_t launch_numeric_bin(const Csr &A, const Csr &B, int dtype, const NumLaunch &l, int gb_log2, hipStream_t s);
+
+// esc.hip
+struct EscLaunch {
+    const int32_t *rows;      // row ids, each with at most `lanes` intermediate products
+    int64_t count;
+    int lanes;                // 16 or 32 lanes (= products) per row
+    const int64_t *out_ptr;
+    int32_t *out_col;
+    void *out_val;
+    int32_t *row_nnz;
+};
+constexpr int64_t ESC_MAX_COLS = (1ll << 26) - 1;   // column id and lane number share one 32-bit sort key
+hipError_t launch_numeric_esc(const Csr &A, const Csr &B, int dtype, const EscLaunch &l, hipStream_t s);
 
 // compact.hip
 hipError_t launch_compact(int64_t m, int dtype, const int64_t *c_rp, const int32_t *nnz1, const int64_t *ptr1,

@@ -72,6 +72,20 @@ def test_host_helpers_agree_with_the_oracle(ob):
                 assert ob.select_workflow(avg, er, cr) == owf.select_workflow(avg, er, cr)
     for er in (0.0, 47.999, 48.0, 1e6):
         assert ob.hll_register_count(er) == owf.hll_registers(er)
+    # the re-tuned rule: hand-checked corners, then the grid against the oracle's reading
+    U, H, S = owf.UPPER_BOUND, owf.HLL, owf.SYMBOLIC
+    assert ob.select_workflow_tuned(10.0, 100.0, 100.0, 1e9, 0.0) == U
+    assert ob.select_workflow_tuned(100.0, 30.0, 3.2, 4e8, 0.0) == H           # light rows only: threshold 1.0
+    assert ob.select_workflow_tuned(100.0, 30.0, 3.2, 4e8, 4e8) == S           # heavy rows only: threshold 4.5
+    assert ob.select_workflow_tuned(100.0, 30.0, 2.75, 4e8, 2e8) == H          # half and half: threshold 2.75
+    assert ob.select_workflow_tuned(100.0, 30.0, 2.74, 4e8, 2e8) == S
+    assert ob.select_workflow_tuned(100.0, 7.9, 100.0, 4e8, 0.0) == S          # ER below 8
+    assert ob.select_workflow_tuned(100.0, 30.0, 3.2, 1e6, 0.0) == S           # small problem: Table 1 as printed
+    for avg in grid:
+        for er in grid:
+            for cr in (0.5, 1.0, 2.0, 2.75, 4.5, 8.0):
+                for p_, h_ in ((1e3, 0.0), (1e8, 0.0), (1e8, 5e7), (1e8, 1e8)):
+                    assert ob.select_workflow_tuned(avg, er, cr, p_, h_) == owf.select_workflow_tuned(avg, er, cr, p_, h_)
     num, sym = ob.bin_layout()
     assert num == sorted(num) and sym == sorted(sym) and num[-1] == sym[-1] == 2 ** 31 - 1
 

@@ -200,6 +200,11 @@ def test_full_size_rect_and_clustered(ob, name):
         check_result(Cd, ref, A, f"{name}/{wf}")
         assert st["products"] == int(prod.sum()) and st["nnz_c"] == ref.col_idx.size
         del Cd
+    # AUTO with the selector re-tuned for this GPU: no heavy rows here, so the estimation workflow is chosen
+    Cd, st = ob.spgemm(dA, dB, workflow=ob.WF_AUTO, selector=ob.SEL_MI355X)
+    assert st["workflow"] == "hll" and st["heavy_products"] == 0
+    check_result(Cd, ref, A, f"{name}/auto, tuned selector")
+    del Cd
     _cache.pop((name, False), None)   # the reference of a full-size product is large
 
 
@@ -414,6 +419,43 @@ def test_random_matrices(ob, seed):
         print(f"random case seed={seed} case={case} {A.rows}x{A.cols}x{B.cols} nnzA={A.nnz} nnzB={B.nnz} {wf}", flush=True)
         Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(B), workflow=wf_id(ob, wf), estimate_scale=scale)
         check_result(Cd, ref, A, f"random seed={seed} case={case} {wf}")
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_esc_short_rows(ob, seed, dtype):
+    """Expand-sort-compress accumulators (Section 3.3: short rows of the upper-bound workflow, 2 or 4 rows per
+    wave): rows with 0 .. 40 intermediate products, repeated output columns (runs of equal keys up to the
+    whole row), entries of A that point to empty rows of B (a row may have more entries than products, and
+    more than 32 of them), columns up to the largest id the packed sort key takes."""
+    rng = np.random.default_rng(500 + seed)
+    k = 600
+    n = [40, 5000, (1 << 26) - 1][seed]
+    blen = rng.integers(0, 7, k)
+    blen[rng.random(k) < 0.3] = 0
+    b_rp = np.concatenate([[0], np.cumsum(blen)]).astype(np.int64)
+    hot = np.array([0, 1, n // 2, n - 2, n - 1])                       # columns many rows of B share
+    b_ci = np.concatenate([np.sort(rng.choice(np.unique(np.concatenate([hot, rng.integers(0, n, 12)])), int(l), replace=False))
+                           for l in blen]).astype(np.int32) if b_rp[-1] else np.zeros(0, np.int32)
+    B = CSR(k, n, b_rp, b_ci, rng.uniform(-1, 1, b_ci.size).astype(dtype))
+    m = 3000
+    alen = rng.integers(0, 14, m)
+    alen[rng.random(m) < 0.05] = 45                                      # more entries than lanes of a group
+    a_rp = np.concatenate([[0], np.cumsum(alen)]).astype(np.int64)
+    a_ci = np.concatenate([rng.choice(k, int(l), replace=False) for l in alen]).astype(np.int32)
+    A = CSR(m, k, a_rp, a_ci, rng.uniform(-1, 1, a_ci.size).astype(dtype))
+    ref = O.multiply_rows(A, B)
+    prod = O.row_products(A, B)
+    assert (prod <= 16).sum() > 100 and ((prod > 16) & (prod <= 32)).sum() > 100 and (prod > 32).sum() > 20
+    dA, dB = ob.to_device(A), ob.to_device(B)
+    Cd, st = ob.spgemm(dA, dB, workflow=ob.WF_UPPER_BOUND)
+    check_result(Cd, ref, A, f"esc seed {seed}")
+    assert st["rows_per_bin"][0] > 0 and st["rows_per_bin"][1] > 0
+    Cd, st = ob.spgemm(dA, dB, workflow=ob.WF_UPPER_BOUND, esc_short_rows=0)          # the hash kernels on the same bins
+    check_result(Cd, ref, A, f"esc off seed {seed}")
+    Cd, st = ob.spgemm(dA, dB, workflow=ob.WF_HLL, estimate_scale=0.3)               # retry rows go through ESC too
+    check_result(Cd, ref, A, f"esc in the retry seed {seed}")
+    assert st["overflow_rows"] > 0
 
 
 def test_skewed_row_lengths_of_b(ob):
