@@ -100,12 +100,18 @@ typedef struct ocean_options {
     int32_t bitmap_query;            /* dense accumulators read a column's presence bit and set it only when it is
                                         clear (Section 4.1): 0 never, 1 always, -1 (default) when a sampled CR is
                                         known and >= bitmap_query_cr */
-    int32_t esc_short_rows;          /* 1 (default): rows with at most 16 / 32 intermediate products are accumulated by
+    int32_t esc_short_rows;          /* 1: rows with at most 16 / 32 intermediate products are accumulated by
                                         expand-sort-compress, 4 / 2 rows per wave, wherever accumulators are sized from
-                                        the product bound (upper-bound workflow, retry; Section 3.3); 0: hash tables */
+                                        the product bound (upper-bound workflow, retry; Section 3.3); 0 (default): by the
+                                        8-lanes-per-row hash kernel, which measured faster on this GPU (one product per
+                                        lane leaves the sort network's lanes a quarter as busy) */
     double bitmap_query_cr;          /* 2.0 (Section 4.3) */
     int32_t selector;                /* OCEAN_SEL_TABLE1 (default) or OCEAN_SEL_MI355X */
-    int32_t reserved1;
+    int32_t compact_in_place;        /* estimation workflows: rows are compacted inside the temporary output, which then
+                                        becomes C (col_idx / val stay as large as the reservation), instead of into a
+                                        second allocation (Section 5.2, memory overhead).  0 never, 1 whenever the rows
+                                        allow it, -1 (default) when both copies together would exceed 40 % of the
+                                        device's memory or the second allocation fails */
     double tuned_cr_light;           /* 1.0 */
     double tuned_cr_heavy;           /* 4.5 */
     double tuned_min_products;       /* 4194304 */
@@ -146,6 +152,8 @@ typedef struct ocean_stats {
     int64_t symbolic_overflow_rows; /* rows whose assisted key table filled up and that were recounted */
     int64_t temp_slots;        /* output slots reserved before compaction (estimation workflows) */
     int64_t peak_bytes;        /* largest total obtained from the allocator at one time */
+    int32_t compacted_in_place; /* 1: C's col_idx / val are the temporary output, compacted in place */
+    int32_t reserved;
     float stage_ms[OCEAN_NUM_STAGES];
     float total_ms;            /* host wall clock of the call */
     /* per numeric bin (first attempt only): kernel time from events on the call's stream, and the

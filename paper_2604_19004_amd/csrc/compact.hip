@@ -67,17 +67,25 @@ __device__ __forceinline__ int64_t row_of_entry(const int64_t *__restrict__ c_rp
     return lo;
 }
 
+// Entries [first, last) of C are copied; entry e goes to c_col / c_val [e - dst_off] (dst_off = 0: C itself;
+// dst_off = first: a staging buffer that starts at the range's first entry).  No __restrict__ on the
+// destination and the first attempt's arrays: the in-place compaction passes the same allocation for both,
+// with ranges chosen by the host so that what one launch writes lies below everything it or a later launch
+// still reads.
 template <typename V>
 __global__ void __launch_bounds__(CF_THREADS)
-k_compact_flat(int64_t m, int64_t nnz, const int64_t *__restrict__ c_rp, const int32_t *__restrict__ nnz1,
-               const int64_t *__restrict__ ptr1, const int32_t *__restrict__ col1, const V *__restrict__ val1,
+k_compact_flat(int64_t m, int64_t first_entry, int64_t last_entry, int64_t dst_off, const int64_t *__restrict__ c_rp,
+               const int32_t *__restrict__ nnz1, const int64_t *__restrict__ ptr1, const int32_t *col1, const V *val1,
                const int64_t *__restrict__ ptr2, const int32_t *__restrict__ col2, const V *__restrict__ val2,
-               int32_t *__restrict__ c_col, V *__restrict__ c_val)
+               int32_t *c_col, V *c_val)
 {
     const int tid = threadIdx.x;
-    const int64_t base = (int64_t)blockIdx.x * CF_TILE;
+    const int64_t nnz = last_entry;
+    const int64_t base = first_entry + (int64_t)blockIdx.x * CF_TILE;
     if (base >= nnz) return;   // uniform
     const int64_t end = base + CF_TILE < nnz ? base + CF_TILE : nnz;
+    c_col -= dst_off;
+    c_val -= dst_off;
     const int64_t r_lo = row_of_entry(c_rp, m, base);
     const int64_t r_hi = row_of_entry(c_rp, m, end - 1);
     if (r_hi - r_lo < 64) {
@@ -141,13 +149,13 @@ hipError_t launch_compact(int64_t m, int dtype, const int64_t *c_rp, const int32
     if (nnz_c >= (int64_t)512 * m && nnz_c > 0) {   // long rows on average: deal the copy out by entries
         const int64_t tiles = (nnz_c + CF_TILE - 1) / CF_TILE;
         if (dtype == OCEAN_F64)
-            hipLaunchKernelGGL(k_compact_flat<double>, dim3((unsigned)tiles), dim3(CF_THREADS), 0, s, m, nnz_c, c_rp, nnz1,
-                               ptr1, col1, static_cast<const double *>(val1), ptr2, col2, static_cast<const double *>(val2),
-                               c_col, static_cast<double *>(c_val));
+            hipLaunchKernelGGL(k_compact_flat<double>, dim3((unsigned)tiles), dim3(CF_THREADS), 0, s, m, (int64_t)0, nnz_c,
+                               (int64_t)0, c_rp, nnz1, ptr1, col1, static_cast<const double *>(val1), ptr2, col2,
+                               static_cast<const double *>(val2), c_col, static_cast<double *>(c_val));
         else
-            hipLaunchKernelGGL(k_compact_flat<float>, dim3((unsigned)tiles), dim3(CF_THREADS), 0, s, m, nnz_c, c_rp, nnz1,
-                               ptr1, col1, static_cast<const float *>(val1), ptr2, col2, static_cast<const float *>(val2),
-                               c_col, static_cast<float *>(c_val));
+            hipLaunchKernelGGL(k_compact_flat<float>, dim3((unsigned)tiles), dim3(CF_THREADS), 0, s, m, (int64_t)0, nnz_c,
+                               (int64_t)0, c_rp, nnz1, ptr1, col1, static_cast<const float *>(val1), ptr2, col2,
+                               static_cast<const float *>(val2), c_col, static_cast<float *>(c_val));
         return hipGetLastError();
     }
     const int64_t threads = m << g_log2;
@@ -160,6 +168,25 @@ hipError_t launch_compact(int64_t m, int dtype, const int64_t *c_rp, const int32
         hipLaunchKernelGGL(k_compact<float>, dim3((unsigned)blocks), dim3(256), 0, s, m, g_log2, c_rp, nnz1, ptr1, col1,
                            static_cast<const float *>(val1), ptr2, col2, static_cast<const float *>(val2), c_col,
                            static_cast<float *>(c_val));
+    return hipGetLastError();
+}
+
+// Entries [first, last) of C from their places in the two temporary outputs to dst[e - dst_off].
+hipError_t launch_compact_range(int64_t m, int dtype, const int64_t *c_rp, const int32_t *nnz1, const int64_t *ptr1,
+                                const int32_t *col1, const void *val1, const int64_t *ptr2, const int32_t *col2,
+                                const void *val2, int32_t *dst_col, void *dst_val, int64_t first, int64_t last,
+                                int64_t dst_off, hipStream_t s)
+{
+    if (last <= first) return hipSuccess;
+    const int64_t tiles = (last - first + CF_TILE - 1) / CF_TILE;
+    if (dtype == OCEAN_F64)
+        hipLaunchKernelGGL(k_compact_flat<double>, dim3((unsigned)tiles), dim3(CF_THREADS), 0, s, m, first, last, dst_off, c_rp,
+                           nnz1, ptr1, col1, static_cast<const double *>(val1), ptr2, col2, static_cast<const double *>(val2),
+                           dst_col, static_cast<double *>(dst_val));
+    else
+        hipLaunchKernelGGL(k_compact_flat<float>, dim3((unsigned)tiles), dim3(CF_THREADS), 0, s, m, first, last, dst_off, c_rp,
+                           nnz1, ptr1, col1, static_cast<const float *>(val1), ptr2, col2, static_cast<const float *>(val2),
+                           dst_col, static_cast<float *>(dst_val));
     return hipGetLastError();
 }
 

@@ -467,6 +467,63 @@ int run_numeric(Ctx &c, Work &w, const Csr &A, const Csr &B, int dtype, int gb_l
     return OCEAN_OK;
 }
 
+// ---- compaction inside the temporary output (Section 5.2: "a small auxiliary buffer can compact
+// non-consecutive outputs back into the original array") ------------------------------------------------
+// Rows lie in the slab in row order, row r from ptr1[r] on, and move down to c_rp[r] <= ptr1[r].  Entries
+// are moved in C's order, a range [x, x1) per launch, so that no launch writes where it or a later launch
+// still reads: the slab positions not yet consumed start at F(x) (the source of entry x, or for a row that
+// comes from the retry's output the start of the next row's region), and F(x) - x, the room gained so far,
+// only has to cover the range.  Ranges are copied directly while that room is large (it grows
+// geometrically with x when rows were reserved with slack); where it is small the range goes through a
+// staging buffer, which only needs the rows after it to stay where they are: that is the condition checked
+// first, and it fails only when overflow rows need more room than the rows before them left unused.
+// *done = false (nothing moved) when it fails; then the caller needs a separate output.
+int compact_in_place(Ctx &c, int64_t m, int dtype, const int64_t *c_rp, const int32_t *nnz1, const int64_t *ptr1,
+                     int32_t *t_col, void *t_val, const int64_t *ptr2, const int32_t *r_col, const void *r_val,
+                     int64_t nnz_c, bool *done)
+{
+    constexpr int64_t DIRECT_MIN = 1ll << 20, STAGE = 1ll << 24;
+    const size_t vbytes = dtype == OCEAN_F64 ? 8 : 4;
+    *done = false;
+    std::vector<int64_t> rp((size_t)m + 1), tp((size_t)m + 1);
+    std::vector<int32_t> n1((size_t)m);
+    HIP_TRY(hipMemcpyAsync(rp.data(), c_rp, (size_t)(m + 1) * 8, hipMemcpyDeviceToHost, c.s));
+    HIP_TRY(hipMemcpyAsync(tp.data(), ptr1, (size_t)(m + 1) * 8, hipMemcpyDeviceToHost, c.s));
+    HIP_TRY(hipMemcpyAsync(n1.data(), nnz1, (size_t)m * 4, hipMemcpyDeviceToHost, c.s));
+    HIP_TRY(hipStreamSynchronize(c.s));
+    for (int64_t r = 0; r < m; ++r)
+        if (rp[r + 1] > tp[r + 1]) return OCEAN_OK;   // C up to the end of row r would reach into row r+1's region
+    int32_t *s_col = nullptr;
+    char *s_val = nullptr;
+    int64_t x = 0, r = 0;
+    while (x < nnz_c) {
+        while (rp[r + 1] <= x) ++r;   // row of entry x
+        const bool first = n1[r] >= 0;
+        if (first && tp[r] == rp[r]) { x = rp[r + 1]; continue; }   // the row already is where it belongs
+        const int64_t unread = first ? tp[r] + (x - rp[r]) : tp[r + 1];
+        const int64_t room = unread - x;
+        if (room >= DIRECT_MIN || x + room >= nnz_c) {
+            const int64_t x1 = x + room < nnz_c ? x + room : nnz_c;
+            HIP_TRY(launch_compact_range(m, dtype, c_rp, nnz1, ptr1, t_col, t_val, ptr2, r_col, r_val, t_col, t_val, x, x1, 0, c.s));
+            x = x1;
+        } else {
+            if (!s_col) {
+                s_col = static_cast<int32_t *>(c.alloc((size_t)STAGE * 4));
+                s_val = s_col ? static_cast<char *>(c.alloc((size_t)STAGE * vbytes)) : nullptr;
+                if (!s_col || !s_val) return fail(OCEAN_EALLOC, "staging buffer of the in-place compaction could not be allocated");
+            }
+            const int64_t x1 = x + STAGE < nnz_c ? x + STAGE : nnz_c;
+            HIP_TRY(launch_compact_range(m, dtype, c_rp, nnz1, ptr1, t_col, t_val, ptr2, r_col, r_val, s_col, s_val, x, x1, x, c.s));
+            HIP_TRY(hipMemcpyAsync(t_col + x, s_col, (size_t)(x1 - x) * 4, hipMemcpyDeviceToDevice, c.s));
+            HIP_TRY(hipMemcpyAsync(static_cast<char *>(t_val) + (size_t)x * vbytes, s_val, (size_t)(x1 - x) * vbytes,
+                                   hipMemcpyDeviceToDevice, c.s));
+            x = x1;
+        }
+    }
+    *done = true;
+    return OCEAN_OK;
+}
+
 void fill_defaults(ocean_options *o)
 {
     std::memset(o, 0, sizeof(*o));
@@ -487,7 +544,8 @@ void fill_defaults(ocean_options *o)
     o->assisted_symbolic = 1;
     o->assist_sigmas = 1.0;
     o->bitmap_query = -1;
-    o->esc_short_rows = 1;
+    o->esc_short_rows = 0;
+    o->compact_in_place = -1;
     o->selector = OCEAN_SEL_TABLE1;
     o->tuned_cr_light = 1.0;
     o->tuned_cr_heavy = 4.5;
@@ -783,12 +841,38 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
 
     // ---- compaction ----
     OC_TRY(mark(c, OCEAN_ST_COMPACT));
-    int32_t *c_col = static_cast<int32_t *>(c.alloc((size_t)nnz_c * 4));
-    void *c_val = c_col ? c.alloc((size_t)nnz_c * vbytes) : nullptr;
-    if (!c_col || !c_val) return fail(OCEAN_EALLOC, "output allocation failed");
-    const int g_log2 = ilog2_ceil_d((double)nnz_c / (double)m, 2, 6);
-    HIP_TRY(launch_compact(m, dtype, c_rp, w.row_nnz, out_ptr, t_col, t_val, w.tmp_ptr2, r_col, r_val, c_col, c_val,
-                           g_log2, nnz_c, c.s));
+    int32_t *c_col = nullptr;
+    void *c_val = nullptr;
+    bool in_place = false;
+    const double both = (double)(total_slots + nnz_c) * (double)(4 + vbytes);
+    bool want_in_place = o.compact_in_place == 1;
+    if (o.compact_in_place < 0) {
+        // two copies of a large output side by side are what makes the estimation workflows run out of memory
+        // (Section 5.2): beyond 40 % of the device's memory the rows are compacted inside the slab
+        size_t mem_free = 0, mem_total = 0;
+        if (hipMemGetInfo(&mem_free, &mem_total) == hipSuccess && both > 0.4 * (double)mem_total) want_in_place = true;
+        else (void)hipGetLastError();
+    }
+    for (int attempt = 0; attempt < 2 && !c_col; ++attempt) {
+        if (want_in_place) {
+            OC_TRY(compact_in_place(c, m, dtype, c_rp, w.row_nnz, out_ptr, t_col, t_val, w.tmp_ptr2, r_col, r_val, nnz_c, &in_place));
+            if (in_place) { c_col = t_col; c_val = t_val; break; }
+        }
+        c_col = static_cast<int32_t *>(c.alloc((size_t)nnz_c * 4));
+        c_val = c_col ? c.alloc((size_t)nnz_c * vbytes) : nullptr;
+        if (c_col && c_val) break;
+        if (c_col) c.release(c_col);
+        c_col = nullptr;
+        if (want_in_place || o.compact_in_place == 0) return fail(OCEAN_EALLOC, "output allocation failed");
+        want_in_place = true;   // no room for a second copy: compact inside the slab if the rows allow it
+    }
+    if (!c_col) return fail(OCEAN_EALLOC, "output allocation failed");
+    if (!in_place) {
+        const int g_log2 = ilog2_ceil_d((double)nnz_c / (double)m, 2, 6);
+        HIP_TRY(launch_compact(m, dtype, c_rp, w.row_nnz, out_ptr, t_col, t_val, w.tmp_ptr2, r_col, r_val, c_col, c_val,
+                               g_log2, nnz_c, c.s));
+    }
+    S->compacted_in_place = in_place ? 1 : 0;
     OC_TRY(mark(c, -1));
     HIP_TRY(hipStreamSynchronize(c.s));
     S->nnz_c = nnz_c;

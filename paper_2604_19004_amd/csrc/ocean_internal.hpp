@@ -274,4 +274,9 @@ hipError_t launch_compact(int64_t m, int dtype, const int64_t *c_rp, const int32
                           const int32_t *col1, const void *val1, const int64_t *ptr2, const int32_t *col2,
                           const void *val2, int32_t *c_col, void *c_val, int g_log2, int64_t nnz_c, hipStream_t s);
 
+hipError_t launch_compact_range(int64_t m, int dtype, const int64_t *c_rp, const int32_t *nnz1, const int64_t *ptr1,
+                                const int32_t *col1, const void *val1, const int64_t *ptr2, const int32_t *col2,
+                                const void *val2, int32_t *dst_col, void *dst_val, int64_t first, int64_t last,
+                                int64_t dst_off, hipStream_t s);
+
 }  // namespace ocean

@@ -178,11 +178,13 @@ def test_forced_register_counts(ob, regs):
     assert st["hll_registers"] == regs
 
 
-@pytest.mark.parametrize("wf", ["upper_bound", "hll", "symbolic"])
+@pytest.mark.parametrize("wf", ["upper_bound", "upper_bound_esc", "hll", "symbolic"])
 def test_full_size_er_and_laplacian(ob, wf):
+    esc = int(wf.endswith("_esc"))
+    wf = wf.replace("_esc", "")
     for name in ("er", "laplacian"):
         A, B, ref, prod = workload(name, False)
-        Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(B), workflow=wf_id(ob, wf))
+        Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(B), workflow=wf_id(ob, wf), esc_short_rows=esc)
         check_result(Cd, ref, A, f"{name}/{wf}")
         if name == "laplacian":
             # all products are small integers: values are exact
@@ -286,9 +288,43 @@ def test_full_size_rmat_forced_hll_every_row(ob):
     assert st["workflow"] == "hll" and st["hll_registers"] == 64
     assert st["overflow_rows"] > 0 and st["temp_slots"] > 1 << 32
     assert st["nnz_c"] == int(counts.sum())
+    # slab and C side by side would be 2.3 x C: the rows were compacted inside the slab (Section 5.2)
+    assert st["compacted_in_place"] == 1 and st["peak_bytes"] <= 1.5 * 12 * st["nnz_c"]
     assert check_streamed(Cd, A, B, counts, "rmat/hll") == st["nnz_c"]
     del Cd
     torch.cuda.empty_cache()
+
+
+def test_full_size_rmat_forced_upper_bound_every_row(ob):
+    """The upper-bound workflow at full R-MAT size: 19.3 G reserved entries (215 GiB) leave no room for a
+    second copy of C, so the rows are compacted inside the reservation; every row of C against the oracle."""
+    import torch
+    A, B, prod, counts = rmat_full()
+    dA, dB = ob.to_device(A), ob.to_device(B)
+    torch.cuda.empty_cache()
+    print("full size rmat/upper_bound", flush=True)
+    Cd, st = ob.spgemm(dA, dB, workflow=ob.WF_UPPER_BOUND)
+    assert st["workflow"] == "upper_bound" and st["overflow_rows"] == 0 and st["compacted_in_place"] == 1
+    assert st["temp_slots"] == int(np.minimum(prod, B.cols).sum()) and st["nnz_c"] == int(counts.sum())
+    assert check_streamed(Cd, A, B, counts, "rmat/upper_bound") == st["nnz_c"]
+    del Cd
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("name", ["laplacian", "rmat", "rect", "clustered"])
+def test_compaction_in_place(ob, name):
+    """Rows compacted inside the temporary output (it becomes C): direct ranges, staged ranges (little room
+    gained, e.g. CR close to 1), rows already in place, and overflow rows that come from the retry's output;
+    when the overflow rows need more room than the rows before them left, a second allocation is used."""
+    A, B, ref, prod = workload(name, True)
+    dA, dB = ob.to_device(A), ob.to_device(B)
+    for wf, scale in (("upper_bound", 1.0), ("hll", 1.0), ("hll", 0.5), ("hll", 0.25)):
+        Cd, st = ob.spgemm(dA, dB, workflow=wf_id(ob, wf), estimate_scale=scale, compact_in_place=1)
+        check_result(Cd, ref, A, f"{name}/{wf}/{scale} in place")
+        if wf == "upper_bound":
+            assert st["compacted_in_place"] == 1 and Cd.col_idx.numel() == st["nnz_c"]
+        if scale <= 0.25 and name != "laplacian":
+            assert st["overflow_rows"] > 0
 
 
 def test_structure_is_identical_across_runs(ob):
@@ -448,12 +484,12 @@ def test_esc_short_rows(ob, seed, dtype):
     prod = O.row_products(A, B)
     assert (prod <= 16).sum() > 100 and ((prod > 16) & (prod <= 32)).sum() > 100 and (prod > 32).sum() > 20
     dA, dB = ob.to_device(A), ob.to_device(B)
-    Cd, st = ob.spgemm(dA, dB, workflow=ob.WF_UPPER_BOUND)
+    Cd, st = ob.spgemm(dA, dB, workflow=ob.WF_UPPER_BOUND, esc_short_rows=1)
     check_result(Cd, ref, A, f"esc seed {seed}")
     assert st["rows_per_bin"][0] > 0 and st["rows_per_bin"][1] > 0
     Cd, st = ob.spgemm(dA, dB, workflow=ob.WF_UPPER_BOUND, esc_short_rows=0)          # the hash kernels on the same bins
     check_result(Cd, ref, A, f"esc off seed {seed}")
-    Cd, st = ob.spgemm(dA, dB, workflow=ob.WF_HLL, estimate_scale=0.3)               # retry rows go through ESC too
+    Cd, st = ob.spgemm(dA, dB, workflow=ob.WF_HLL, estimate_scale=0.3, esc_short_rows=1)   # retry rows go through ESC too
     check_result(Cd, ref, A, f"esc in the retry seed {seed}")
     assert st["overflow_rows"] > 0
 
@@ -502,10 +538,14 @@ def test_compaction_by_entries_long_and_short_rows_mixed(ob, dtype):
     assert ref.col_idx.size >= 512 * m
     for wf in ("upper_bound", "hll", "symbolic"):
         for scale in ((1.0,) if wf != "hll" else (1.0, 0.3)):   # 0.3: overflow rows come from the retry's output
-            Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(Bm), workflow=wf_id(ob, wf), estimate_scale=scale)
-            check_result(Cd, ref, A, f"compaction by entries/{wf}/{scale}")
-            if scale < 1.0:
-                assert st["overflow_rows"] > 0
+            for in_place in (0, 1):                               # into a second allocation / inside the slab
+                Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(Bm), workflow=wf_id(ob, wf), estimate_scale=scale,
+                                   compact_in_place=in_place)
+                check_result(Cd, ref, A, f"compaction by entries/{wf}/{scale}/in place {in_place}")
+                if scale < 1.0:
+                    assert st["overflow_rows"] > 0
+                if wf == "upper_bound":   # reservations never fall short there: always possible in place
+                    assert st["compacted_in_place"] == in_place
 
 
 def test_invalid_arguments_are_rejected(ob):
