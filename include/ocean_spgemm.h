@@ -98,8 +98,9 @@ typedef struct ocean_options {
     double assist_sigmas;            /* conservative CR = max(1, mean - assist_sigmas * std) of the per-row ratio
                                         products / estimate over the sampled rows (1.0) */
     int32_t bitmap_query;            /* dense accumulators read a column's presence bit and set it only when it is
-                                        clear (Section 4.1): 0 never, 1 always, -1 (default) when a sampled CR is
-                                        known and >= bitmap_query_cr */
+                                        clear (Section 4.1): 0 never; 1 always in the numeric pass; 2 also in the
+                                        bitmap kernel of the symbolic pass (where it measured slower); -1 (default)
+                                        in the numeric pass when a sampled CR is known and >= bitmap_query_cr */
     int32_t esc_short_rows;          /* 1: rows with at most 16 / 32 intermediate products are accumulated by
                                         expand-sort-compress, 4 / 2 rows per wave, wherever accumulators are sized from
                                         the product bound (upper-bound workflow, retry; Section 3.3); 0 (default): by the
@@ -115,6 +116,11 @@ typedef struct ocean_options {
     double tuned_cr_light;           /* 1.0 */
     double tuned_cr_heavy;           /* 4.5 */
     double tuned_min_products;       /* 4194304 */
+    double sort_b_ratio;             /* detector for the throughput-bound case of the accumulators that keep values in
+                                        global memory (Section 5.4): when B's rows are unsorted and the rows that
+                                        outgrow the LDS hash tables hold at least sort_b_ratio * nnz(B) products, a copy
+                                        of B with sorted rows is made (rows of B up to 4096 entries) so that they run
+                                        through the column-window kernel instead.  8.0; 0 = never */
     const ocean_allocator *allocator; /* host pointer, may be NULL */
 } ocean_options;
 
@@ -153,7 +159,7 @@ typedef struct ocean_stats {
     int64_t temp_slots;        /* output slots reserved before compaction (estimation workflows) */
     int64_t peak_bytes;        /* largest total obtained from the allocator at one time */
     int32_t compacted_in_place; /* 1: C's col_idx / val are the temporary output, compacted in place */
-    int32_t reserved;
+    int32_t b_sorted_copy;      /* 1: the numeric pass read a copy of B with sorted rows (see sort_b_ratio) */
     float stage_ms[OCEAN_NUM_STAGES];
     float total_ms;            /* host wall clock of the call */
     /* per numeric bin (first attempt only): kernel time from events on the call's stream, and the

@@ -23,12 +23,15 @@ static inline int ilog2_ceil(double x, int lo, int hi)
 }
 
 // ---------------------------------------------------------------- validate
+// near_pairs (may be null): += the number of neighbouring entries whose column ids differ by 1 .. 4 - how
+// clustered the columns of the matrix are (pairs across a row boundary count too; they are few).
 __global__ void k_validate(const int64_t *rp, const int32_t *col, int64_t rows, int64_t cols, int64_t nnz,
-                           int32_t *flags, int bit)
+                           int32_t *flags, int bit, unsigned long long *near_pairs)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     bool bad = false;
+    unsigned int near = 0;
     for (int64_t i = t0; i < rows; i += stride) {
         int64_t a = rp[i], b = rp[i + 1];
         bad |= (b < a) | (a < 0) | (b > nnz);
@@ -37,21 +40,28 @@ __global__ void k_validate(const int64_t *rp, const int32_t *col, int64_t rows, 
     for (int64_t e = t0; e < nnz; e += stride) {
         int32_t c = col[e];
         bad |= ((uint32_t)c >= (uint64_t)cols);
+        if (near_pairs != nullptr && e + 1 < nnz) near += (uint32_t)(col[e + 1] - c - 1) < 4u;
     }
     if (__ballot(bad) != 0 && lane_id() == 0) atomicOr(flags, bit);
+    if (near_pairs != nullptr) {
+        const unsigned int wave_near = wave_sum_u32(near);
+        if (lane_id() == 0 && wave_near) atomicAdd(near_pairs, (unsigned long long)wave_near);
+    }
 }
 
-hipError_t launch_validate(const Csr &A, const Csr &B, int32_t *flags, hipStream_t s)
+// b_near_pairs: zeroed device counter that receives the clustering measure of B's columns (see k_validate).
+hipError_t launch_validate(const Csr &A, const Csr &B, int32_t *flags, unsigned long long *b_near_pairs, hipStream_t s)
 {
-    auto go = [&](const Csr &M, int bit) {
+    auto go = [&](const Csr &M, int bit, unsigned long long *near) {
         int64_t work = M.nnz > M.rows ? M.nnz : M.rows;
         int blocks = (int)((work + TPB * 4 - 1) / (TPB * 4));
         if (blocks < 1) blocks = 1;
-        if (blocks > 65536) blocks = 65536;
-        hipLaunchKernelGGL(k_validate, dim3(blocks), dim3(TPB), 0, s, M.rp, M.col, M.rows, M.cols, M.nnz, flags, bit);
+        if (blocks > 4096) blocks = 4096;   // (one wave-level atomic per wave at the end: keep the waves few)
+        hipLaunchKernelGGL(k_validate, dim3(blocks), dim3(TPB), 0, s, M.rp, M.col, M.rows, M.cols, M.nnz, flags, bit, near);
     };
-    go(A, 1);
-    if (B.rp != A.rp || B.col != A.col || B.rows != A.rows || B.cols != A.cols) go(B, 2);
+    const bool same = B.rp == A.rp && B.col == A.col && B.rows == A.rows && B.cols == A.cols;
+    go(A, 1, same ? b_near_pairs : nullptr);
+    if (!same) go(B, 2, b_near_pairs);
     return hipGetLastError();
 }
 

@@ -24,11 +24,12 @@ k_classify(int64_t m, int mode, double coef, double scale, BinTable bt, int64_t 
            const int64_t *__restrict__ prod, const double *__restrict__ est, const int32_t *__restrict__ nnz_exact,
            const int32_t *__restrict__ row_mask, const int32_t *__restrict__ lower_bound,
            uint8_t *__restrict__ bin_of_row, int32_t *__restrict__ cap,
-           unsigned long long *bin_count, unsigned long long *max_cap)
+           unsigned long long *bin_count, unsigned long long *bin_prod, unsigned long long *max_cap)
 {
     __shared__ unsigned int s_cnt[OCEAN_MAX_BINS];
+    __shared__ unsigned long long s_prod[OCEAN_MAX_BINS];
     __shared__ unsigned int s_maxcap;
-    if (threadIdx.x < OCEAN_MAX_BINS) s_cnt[threadIdx.x] = 0;
+    if (threadIdx.x < OCEAN_MAX_BINS) { s_cnt[threadIdx.x] = 0; s_prod[threadIdx.x] = 0ull; }
     if (threadIdx.x == 0) s_maxcap = 0;
     __syncthreads();
     for (int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x; i < m; i += (int64_t)gridDim.x * TPB) {
@@ -66,6 +67,7 @@ k_classify(int64_t m, int mode, double coef, double scale, BinTable bt, int64_t 
             for (int b = 0; b < bt.n; ++b)
                 if ((long long)bt.slots[b] >= need) { bin = b; break; }
             atomicAdd(&s_cnt[bin], 1u);
+            if (bin_prod != nullptr) atomicAdd(&s_prod[bin], (unsigned long long)pr);
             if (bin == bt.n - 1 && c > 0) atomicMax(&s_maxcap, (unsigned int)c);
         }
         bin_of_row[i] = (uint8_t)bin;
@@ -73,13 +75,14 @@ k_classify(int64_t m, int mode, double coef, double scale, BinTable bt, int64_t 
     }
     __syncthreads();
     if (threadIdx.x < bt.n && s_cnt[threadIdx.x]) atomicAdd(&bin_count[threadIdx.x], (unsigned long long)s_cnt[threadIdx.x]);
+    if (bin_prod != nullptr && threadIdx.x < bt.n && s_prod[threadIdx.x]) atomicAdd(&bin_prod[threadIdx.x], s_prod[threadIdx.x]);
     if (threadIdx.x == 0 && s_maxcap && max_cap != nullptr) atomicMax(max_cap, (unsigned long long)s_maxcap);
 }
 
 hipError_t launch_classify(int64_t m, const BinParams &p, double scale, const int64_t *prod, const double *est,
                            const int32_t *nnz_exact, const int32_t *row_mask, const int32_t *lower_bound,
                            uint8_t *bin_of_row, int32_t *cap, unsigned long long *bin_count,
-                           unsigned long long *max_cap, hipStream_t s)
+                           unsigned long long *bin_prod, unsigned long long *max_cap, hipStream_t s)
 {
     if (m == 0) return hipSuccess;
     BinTable bt;
@@ -88,7 +91,7 @@ hipError_t launch_classify(int64_t m, const BinParams &p, double scale, const in
     int64_t blocks = (m + TPB - 1) / TPB;
     if (blocks > 1024) blocks = 1024;   // one set of atomics per workgroup: keep the workgroups few
     hipLaunchKernelGGL(k_classify, dim3((unsigned)blocks), dim3(TPB), 0, s, m, p.mode, p.coef, scale, bt, p.n_cols,
-                       prod, est, nnz_exact, row_mask, lower_bound, bin_of_row, cap, bin_count, max_cap);
+                       prod, est, nnz_exact, row_mask, lower_bound, bin_of_row, cap, bin_count, bin_prod, max_cap);
     return hipGetLastError();
 }
 

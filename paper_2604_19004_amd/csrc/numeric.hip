@@ -197,78 +197,6 @@ k_numeric_group(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     }
 }
 
-// ========================================================= wave kernel ====
-// One wave per row, four rows per workgroup, 256-slot table; entries of the
-// row of A are classified by the length of the row of B they reference.
-template <typename V>
-__global__ void __launch_bounds__(256)
-k_numeric_wave(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col, const V *__restrict__ a_val,
-               const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_col, const V *__restrict__ b_val,
-               const int32_t *__restrict__ rows, int64_t count, const int64_t *__restrict__ out_ptr,
-               int32_t *__restrict__ out_col, V *__restrict__ out_val, int32_t *__restrict__ row_nnz)
-{
-    constexpr int BITS = 8;
-    constexpr int SLOTS = 1 << BITS;
-    constexpr int R = 4;
-    __shared__ int32_t s_keys[R * SLOTS];
-    __shared__ int32_t s_sort[R * SLOTS];
-    __shared__ V s_vals[R * SLOTS];
-    __shared__ FlatChunk<V, WAVE> s_fc[R];
-    const int rl = threadIdx.x / WAVE;
-    const int sub = lane_id();
-    int32_t *keys = s_keys + rl * SLOTS;
-    int32_t *sbuf = s_sort + rl * SLOTS;
-    V *vals = s_vals + rl * SLOTS;
-    const int64_t r = (int64_t)blockIdx.x * R + rl;
-    if (r >= count) return;   // whole wave leaves; no workgroup barrier is used below
-    const int64_t row = rows[r];
-    for (int s = sub; s < SLOTS; s += WAVE) { keys[s] = EMPTY_KEY; vals[s] = (V)0; }
-    wave_sync();
-    bool ovf = false;
-    wave_traverse<true>(a_col, a_val, a_rp[row], a_rp[row + 1],
-                        [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
-                        b_col, b_val, s_fc[rl], [&](const auto &cj, const auto &cv) {
-                            if (!lds_insert_batch<BITS>(keys, cj, cv, [&](int slot, V v, bool) { lds_add(&vals[slot], v); })) ovf = true;
-                        });
-    wave_sync();
-    int c = 0;
-#pragma unroll
-    for (int it = 0; it < SLOTS / WAVE; ++it) {
-        const int32_t key = keys[it * WAVE + sub];
-        const bool occ = key != EMPTY_KEY;
-        const unsigned long long m = __ballot(occ);
-        if (occ) sbuf[c + __popcll(m & ((1ull << sub) - 1ull))] = key;
-        c += __popcll(m);
-    }
-    const bool ovf_any = __ballot(ovf) != 0;
-    const int N = pow2_ceil_i32(c);
-    for (int s = c + sub; s < N; s += WAVE) sbuf[s] = SORT_PAD;
-    wave_sync();
-    for (int k = 2; k <= N; k <<= 1) {
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int i = sub; i < (N >> 1); i += WAVE) {
-                const int lo = ((i & ~(j - 1)) << 1) | (i & (j - 1));
-                const int hi = lo | j;
-                const int32_t x = sbuf[lo], y = sbuf[hi];
-                if ((x > y) == ((lo & k) == 0)) { sbuf[lo] = y; sbuf[hi] = x; }
-            }
-            wave_sync();
-        }
-    }
-    const int64_t o = out_ptr[row];
-    const int64_t cap = out_ptr[row + 1] - o;
-    if (ovf_any || (int64_t)c > cap) {
-        if (sub == 0) row_nnz[row] = -1;
-    } else {
-        for (int t = sub; t < c; t += WAVE) {
-            const int32_t key = sbuf[t];
-            out_col[o + t] = key;
-            out_val[o + t] = vals[lds_find<BITS>(keys, key)];
-        }
-        if (sub == 0) row_nnz[row] = c;
-    }
-}
-
 // =================================================== workgroup helpers ====
 // s_wave: one word per wave.  With TRAILING_BARRIER = false the caller keeps s_wave untouched until
 // a later barrier of its own.
@@ -286,6 +214,30 @@ __device__ __forceinline__ int block_exclusive_scan_i32(int v, int *s_wave, int 
     return wave_off + inc - v;
 }
 
+// Who works on one row: a whole workgroup of THREADS threads, or one wave (THREADS = 64) among several
+// in a workgroup that each have a row of their own.  The ordered write-out below is written once for both.
+struct WorkgroupScope {
+    static __device__ __forceinline__ int tid() { return (int)threadIdx.x; }
+    static __device__ __forceinline__ void sync() { __syncthreads(); }
+    template <int THREADS>
+    static __device__ __forceinline__ int exclusive_scan(int v, int *s_wave, int &total)
+    {
+        return block_exclusive_scan_i32<THREADS>(v, s_wave, total);
+    }
+};
+struct WaveScope {
+    static __device__ __forceinline__ int tid() { return lane_id(); }
+    static __device__ __forceinline__ void sync() { wave_sync(); }
+    template <int THREADS>
+    static __device__ __forceinline__ int exclusive_scan(int v, int *, int &total)
+    {
+        static_assert(THREADS == WAVE, "one wave");
+        const int inc = (int)wave_inclusive_scan_u32((uint32_t)v);
+        total = (int)wave_read_lane_u32((uint32_t)inc, WAVE - 1);
+        return inc - v;
+    }
+};
+
 // Write the keys of an LDS hash table to the output in increasing column order
 // without sorting them.  Every thread holds PER keys of the table in registers
 // (EMPTY_KEY = none; key[q] sits in slot q*THREADS + tid).  The keys are counted
@@ -301,22 +253,26 @@ __device__ __forceinline__ int block_exclusive_scan_i32(int v, int *s_wave, int 
 //     its range for that bitmap: the keys set their bits and a key's rank is the
 //     number of set bits below its own.
 // So clustered and scattered columns cost about the same, a few LDS accesses
-// per key.  hist: NB/2 + 1 words, zeroed, two 16-bit counts per word.  Returns
+// per key.  With BF > 1 there are BF buckets per table slot (NB = THREADS*PER*BF): a
+// cluster's bitmap then has fewer words below a key's own, and the threads of a wave
+// wait for the longest such count among them.  hist: NB/2 + 1 words, zeroed, two
+// 16-bit counts per word.  Returns
 // the number of keys; with CHECK, -1 (and nothing written) when some listed
 // bucket holds more than `limit` keys, for the caller to sort instead.
 // Barriers inside; ends without one.  The table's values are overwritten (the
 // keys and values are put in order inside LDS and copied out from there).
 // `grouped` may be the table's own key array, provided every thread has read
 // its keys before the call (barrier).
-template <int THREADS, int PER, bool CHECK, typename V>
+template <int THREADS, int PER, bool CHECK, typename Scope = WorkgroupScope, int BF = 1, typename V>
 __device__ __forceinline__ int bucket_emit(const int32_t (&key)[PER], V *s_vals, int32_t kmin, int shift,
                                            uint32_t *hist, int32_t *grouped, int *s_wave, int *s_flag, int limit,
                                            int64_t o, int64_t cap, long long done, int32_t *__restrict__ out_col,
                                            V *__restrict__ out_val)
 {
     static_assert(PER % 2 == 0, "two buckets per word");
-    constexpr int NB = THREADS * PER;
-    const int tid = threadIdx.x;
+    constexpr int NB = THREADS * PER * BF;   // BF buckets per table slot: narrower buckets, shorter bitmaps to rank in
+    constexpr int OWNW = PER * BF / 2;       // words of counts (two buckets each) that a thread owns
+    const int tid = Scope::tid();
     const int words = shift > 5 ? 1 << (shift - 5) : 1;   // bitmap words of one bucket
     const uint32_t wmask = (1u << shift) - 1u;
     int arrival[PER];
@@ -329,15 +285,15 @@ __device__ __forceinline__ int bucket_emit(const int32_t (&key)[PER], V *s_vals,
             arrival[q] = (int)((old >> ((b & 1u) * 16)) & 0xffffu);
         }
     }
-    __syncthreads();
+    Scope::sync();
 #pragma unroll
     for (int q = 0; q < PER; ++q) grouped[q * THREADS + tid] = 0;
-    // counts -> starts, in place; this thread owns buckets tid*PER .. tid*PER + PER - 1
-    uint32_t wv[PER / 2];
+    // counts -> starts, in place; this thread owns buckets 2*tid*OWNW .. 2*(tid+1)*OWNW - 1
+    uint32_t wv[OWNW];
     int sum = 0, kmax = 0;
 #pragma unroll
-    for (int j = 0; j < PER / 2; ++j) {
-        wv[j] = hist[tid * (PER / 2) + j];
+    for (int j = 0; j < OWNW; ++j) {
+        wv[j] = hist[tid * OWNW + j];
         const int c0 = (int)(wv[j] & 0xffffu), c1 = (int)(wv[j] >> 16);
         sum += c0 + c1;
         if (c0 < words) kmax = max(kmax, c0);
@@ -345,15 +301,15 @@ __device__ __forceinline__ int bucket_emit(const int32_t (&key)[PER], V *s_vals,
     }
     if (CHECK && kmax > limit) *s_flag = 1;
     int total;
-    int base = block_exclusive_scan_i32<THREADS>(sum, s_wave, total);
+    int base = Scope::template exclusive_scan<THREADS>(sum, s_wave, total);
 #pragma unroll
-    for (int j = 0; j < PER / 2; ++j) {
+    for (int j = 0; j < OWNW; ++j) {
         const int c0 = (int)(wv[j] & 0xffffu), c1 = (int)(wv[j] >> 16);
-        hist[tid * (PER / 2) + j] = (uint32_t)base | ((uint32_t)(base + c0) << 16);
+        hist[tid * OWNW + j] = (uint32_t)base | ((uint32_t)(base + c0) << 16);
         base += c0 + c1;
     }
     if (tid == THREADS - 1) hist[NB / 2] = (uint32_t)total;
-    __syncthreads();
+    Scope::sync();
     if (CHECK && *s_flag) return -1;   // uniform
     auto start_of = [&](uint32_t b) { return (int)((hist[b >> 1] >> ((b & 1u) * 16)) & 0xffffu); };
     int lo[PER];
@@ -370,7 +326,7 @@ __device__ __forceinline__ int bucket_emit(const int32_t (&key)[PER], V *s_vals,
             else grouped[lo[q] + arrival[q]] = key[q];
         }
     }
-    __syncthreads();
+    Scope::sync();
     int rank[PER];
     V val[PER];
 #pragma unroll
@@ -393,13 +349,13 @@ __device__ __forceinline__ int bucket_emit(const int32_t (&key)[PER], V *s_vals,
             val[q] = s_vals[q * THREADS + tid];
         }
     }
-    __syncthreads();
+    Scope::sync();
     // permute keys and values into place inside LDS (every thread holds its own in registers), so
     // that the row leaves with coalesced stores
 #pragma unroll
     for (int q = 0; q < PER; ++q)
         if (key[q] != EMPTY_KEY) { grouped[rank[q]] = key[q]; s_vals[rank[q]] = val[q]; }
-    __syncthreads();
+    Scope::sync();
     const long long room = cap - done;
     const int n_out = (long long)total < room ? total : (room > 0 ? (int)room : 0);
     for (int i = tid; i < n_out; i += THREADS) {
@@ -409,8 +365,78 @@ __device__ __forceinline__ int bucket_emit(const int32_t (&key)[PER], V *s_vals,
     return total;
 }
 
+// ========================================================= wave kernel ====
+// One wave per row, R rows per workgroup, a table of 2^BITS slots (256, 512 or 1024) per row.  No
+// workgroup barrier anywhere: traversal, insertion and the ordered write-out (column buckets, as in the
+// workgroup kernels) are all wave-synchronous, so a row costs one wave's instructions instead of a
+// workgroup's, and none of the waiting at barriers.  Rows of these sizes are bound by instruction issue,
+// not by memory.
+template <typename V, int BITS, int R>
+__global__ void __launch_bounds__(WAVE * R)
+k_numeric_wave(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col, const V *__restrict__ a_val,
+               const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_col, const V *__restrict__ b_val,
+               const int32_t *__restrict__ rows, int64_t count, const int64_t *__restrict__ out_ptr,
+               int32_t *__restrict__ out_col, V *__restrict__ out_val, int32_t *__restrict__ row_nnz)
+{
+    constexpr int SLOTS = 1 << BITS;
+    constexpr int PER = SLOTS / WAVE;
+    constexpr int BF = 1;
+    constexpr int NBK = SLOTS * BF;
+    // the traversal's chunk and, after it, the bucket counts of the ordered write-out share one buffer per row
+    constexpr size_t HIST_BYTES = (NBK / 2 + 1) * sizeof(uint32_t);
+    constexpr size_t SCRATCH = sizeof(FlatChunk<V, WAVE>) > HIST_BYTES ? sizeof(FlatChunk<V, WAVE>) : HIST_BYTES;
+    __shared__ int32_t s_keys[R * SLOTS];
+    __shared__ V s_vals[R * SLOTS];
+    __shared__ __align__(16) unsigned char s_scratch[R][(SCRATCH + 15) / 16 * 16];
+    __shared__ int s_flag[R];
+    const int rl = threadIdx.x / WAVE;
+    const int sub = lane_id();
+    int32_t *keys = s_keys + rl * SLOTS;
+    V *vals = s_vals + rl * SLOTS;
+    FlatChunk<V, WAVE> &fc = *reinterpret_cast<FlatChunk<V, WAVE> *>(s_scratch[rl]);
+    uint32_t *hist = reinterpret_cast<uint32_t *>(s_scratch[rl]);
+    const int64_t r = (int64_t)blockIdx.x * R + rl;
+    if (r >= count) return;   // whole wave leaves; no workgroup barrier is used below
+    const int64_t row = rows[r];
+    for (int s = sub; s < SLOTS; s += WAVE) { keys[s] = EMPTY_KEY; vals[s] = (V)0; }
+    wave_sync();
+    bool ovf = false;
+    wave_traverse<true>(a_col, a_val, a_rp[row], a_rp[row + 1],
+                        [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
+                        b_col, b_val, fc, [&](const auto &cj, const auto &cv) {
+                            if (!lds_insert_batch<BITS>(keys, cj, cv, [&](int slot, V v, bool) { lds_add(&vals[slot], v); })) ovf = true;
+                        });
+    wave_sync();
+    // ---- ordered write-out through column buckets
+    int32_t key[PER];
+    int lmin = 0x7fffffff, lmax = -1;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+        key[q] = keys[q * WAVE + sub];
+        if (key[q] != EMPTY_KEY) { lmin = min(lmin, key[q]); lmax = max(lmax, key[q]); }
+    }
+    for (int j = sub; j < NBK / 2 + 1; j += WAVE) hist[j] = 0u;
+    const int kmax = group_reduce_max(lmax, WAVE);
+    const int kmin = -group_reduce_max(-lmin, WAVE);
+    const bool ovf_any = __ballot(ovf) != 0;
+    if (kmax < 0) {   // uniform: the row has no entries
+        if (sub == 0) row_nnz[row] = 0;
+        return;
+    }
+    wave_sync();   // every lane holds its keys in registers (the key array becomes the buckets' memory), counts are zero
+    int shift = 0;
+    while ((((uint32_t)(kmax - kmin)) >> shift) >= (uint32_t)NBK) ++shift;
+    const int64_t o = out_ptr[row];
+    const int64_t cap = out_ptr[row + 1] - o;
+    const int c = bucket_emit<WAVE, PER, false, WaveScope, BF>(key, vals, kmin, shift, hist, keys, nullptr, &s_flag[rl], 0, o, cap, 0,
+                                                           out_col, out_val);
+    if (sub == 0) row_nnz[row] = (ovf_any || (int64_t)c > cap) ? -1 : c;
+}
+
 // ==================================================== workgroup kernel ====
-template <typename V, int BITS, int THREADS>
+// BF: column buckets per table slot of the ordered write-out (see bucket_emit): 1, or more for inputs with
+// clustered columns, up to 2048 buckets.
+template <typename V, int BITS, int THREADS, int BF>
 __global__ void __launch_bounds__(THREADS)
 k_numeric_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col, const V *__restrict__ a_val,
              const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_col, const V *__restrict__ b_val,
@@ -419,12 +445,14 @@ k_numeric_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col
 {
     constexpr int SLOTS = 1 << BITS;
     constexpr int PER = SLOTS / THREADS;
+    constexpr int NBK = SLOTS * BF;
     __shared__ int32_t s_keys[SLOTS];
     __shared__ int32_t s_sort[SLOTS];
     __shared__ V s_vals[SLOTS];
     // the traversal's chunk and, after it, the bucket counts of the ordered write-out share one buffer
-    __shared__ __align__(16) unsigned char s_scratch[sizeof(WgChunk<V, THREADS>)];
-    static_assert(sizeof(WgChunk<V, THREADS>) >= (SLOTS / 2 + 1) * sizeof(uint32_t), "bucket counts fit the chunk buffer");
+    constexpr size_t HIST_BYTES = (NBK / 2 + 1) * sizeof(uint32_t);
+    constexpr size_t SCRATCH = sizeof(WgChunk<V, THREADS>) > HIST_BYTES ? sizeof(WgChunk<V, THREADS>) : HIST_BYTES;
+    __shared__ __align__(16) unsigned char s_scratch[(SCRATCH + 15) / 16 * 16];
     __shared__ int s_wave[THREADS / WAVE];
     __shared__ int s_ovf, s_min, s_max, s_flag;
     WgChunk<V, THREADS> &s_fc = *reinterpret_cast<WgChunk<V, THREADS> *>(s_scratch);
@@ -456,7 +484,7 @@ k_numeric_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col
         key[q] = s_keys[q * THREADS + tid];
         if (key[q] != EMPTY_KEY) { lmin = min(lmin, key[q]); lmax = max(lmax, key[q]); }
     }
-    for (int j = tid; j < SLOTS / 2 + 1; j += THREADS) s_hist[j] = 0u;
+    for (int j = tid; j < NBK / 2 + 1; j += THREADS) s_hist[j] = 0u;
     lmax = group_reduce_max(lmax, WAVE);
     lmin = -group_reduce_max(-lmin, WAVE);
     if (lane_id() == 0 && lmax >= 0) { atomicMin(&s_min, lmin); atomicMax(&s_max, lmax); }
@@ -467,9 +495,9 @@ k_numeric_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col
         return;
     }
     int shift = 0;
-    while ((((uint32_t)(kmax - kmin)) >> shift) >= (uint32_t)SLOTS) ++shift;
+    while ((((uint32_t)(kmax - kmin)) >> shift) >= (uint32_t)NBK) ++shift;
     constexpr bool CHECK = SLOTS >= 4096;   // smaller tables: even one bucket with every key is cheap to rank
-    int c = bucket_emit<THREADS, PER, CHECK>(key, s_vals, kmin, shift, s_hist, s_sort, s_wave, &s_flag, 1024, o, cap, 0,
+    int c = bucket_emit<THREADS, PER, CHECK, WorkgroupScope, BF>(key, s_vals, kmin, shift, s_hist, s_sort, s_wave, &s_flag, 1024, o, cap, 0,
                                              out_col, out_val);
     if (c >= 0) {
         if (tid == 0) row_nnz[row] = (s_ovf || (int64_t)c > cap) ? -1 : c;
@@ -681,7 +709,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                 const uint32_t *__restrict__ bw, int n_win, const int32_t *__restrict__ b_col,
                 const V *__restrict__ b_val, const int32_t *__restrict__ rows, int64_t count,
                 unsigned long long *queue, const int64_t *__restrict__ out_ptr, int32_t *__restrict__ out_col,
-                V *__restrict__ out_val, int32_t *__restrict__ row_nnz)
+                V *__restrict__ out_val, int32_t *__restrict__ row_nnz, int query_bitmap)
 {
     constexpr int WIN = DenseCfg<V>::WIN;
     constexpr int WORDS = DenseCfg<V>::WORDS;
@@ -841,7 +869,10 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                         const unsigned d = (unsigned)(cj[u] - col0);
                         if (cj[u] >= 0 && d < (unsigned)WIN) {   // d is in range for a consistent window table
                             lds_add(&s_vals[d], cv[u]);
-                            atomicOr(&s_dbm[d >> 5], 1u << (d & 31));
+                            // Section 4.1: with many products per output entry most presence bits are set already;
+                            // reading the bit first then saves the write (a stale read only costs a redundant OR)
+                            const uint32_t bit = 1u << (d & 31);
+                            if (!query_bitmap || !(s_dbm[d >> 5] & bit)) atomicOr(&s_dbm[d >> 5], bit);
                         }
                     }
                 } else {
@@ -1220,9 +1251,10 @@ static hipError_t dispatch(const Csr &A, const Csr &B, const NumLaunch &l, int g
     const V *av = static_cast<const V *>(A.val);
     const V *bv = static_cast<const V *>(B.val);
     V *ov = static_cast<V *>(l.out_val);
-#define OCEAN_WG(BITS, THREADS)                                                                                   \
-    hipLaunchKernelGGL((k_numeric_wg<V, BITS, THREADS>), dim3((unsigned)l.count), dim3(THREADS), 0, s, A.rp, A.col, \
+#define OCEAN_WG_BF(BITS, THREADS, BF)                                                                              \
+    hipLaunchKernelGGL((k_numeric_wg<V, BITS, THREADS, BF>), dim3((unsigned)l.count), dim3(THREADS), 0, s, A.rp, A.col, \
                        av, B.rp, B.col, bv, l.rows, l.count, l.out_ptr, l.out_col, ov, l.row_nnz)
+#define OCEAN_WG(BITS, THREADS) OCEAN_WG_BF(BITS, THREADS, 1)
     switch (l.bin) {
     case NB_E16:
     case NB_G8: {
@@ -1237,14 +1269,20 @@ static hipError_t dispatch(const Csr &A, const Csr &B, const NumLaunch &l, int g
                            bv, l.rows, l.count, l.out_ptr, l.out_col, ov, l.row_nnz);
         break;
     }
-    case NB_W64: {
-        const int64_t blocks = (l.count + 3) / 4;
-        hipLaunchKernelGGL((k_numeric_wave<V>), dim3((unsigned)blocks), dim3(256), 0, s, A.rp, A.col, av, B.rp, B.col, bv,
-                           l.rows, l.count, l.out_ptr, l.out_col, ov, l.row_nnz);
+#define OCEAN_WAVE(BITS, R)                                                                                        \
+    hipLaunchKernelGGL((k_numeric_wave<V, BITS, R>), dim3((unsigned)((l.count + (R) - 1) / (R))), dim3(WAVE * (R)), 0, s, A.rp, \
+                       A.col, av, B.rp, B.col, bv, l.rows, l.count, l.out_ptr, l.out_col, ov, l.row_nnz)
+    case NB_W64: OCEAN_WAVE(8, 4); break;
+    // a wave per row while the rows of the bin are light; a workgroup per row when they hold many products each
+    // (a wave per row was measured for the 512- and 1024-slot bins too: 1.3 - 1.6 x slower than a workgroup per row)
+    case NB_S512:
+        if (l.fine_buckets) OCEAN_WG_BF(9, 128, 4);
+        else OCEAN_WG(9, 128);
         break;
-    }
-    case NB_S512: OCEAN_WG(9, 128); break;
-    case NB_S1K: OCEAN_WG(10, 256); break;
+    case NB_S1K:
+        if (l.fine_buckets) OCEAN_WG_BF(10, 256, 2);
+        else OCEAN_WG(10, 256);
+        break;
     case NB_S2K: OCEAN_WG(11, 512); break;
     case NB_S4K: OCEAN_WG(12, 512); break;
     case NB_S8K: OCEAN_WG(13, 1024); break;
@@ -1258,7 +1296,7 @@ static hipError_t dispatch(const Csr &A, const Csr &B, const NumLaunch &l, int g
     case NB_GLOBAL:
         if (l.bw != nullptr)
             hipLaunchKernelGGL((k_numeric_heavy<V>), dim3((unsigned)l.n_wg), dim3(HV_THREADS), 0, s, A.rp, A.col, av, l.bw,
-                               l.n_win, B.col, bv, l.rows, l.count, l.queue, l.out_ptr, l.out_col, ov, l.row_nnz);
+                               l.n_win, B.col, bv, l.rows, l.count, l.queue, l.out_ptr, l.out_col, ov, l.row_nnz, l.query_bitmap ? 1 : 0);
         else
             hipLaunchKernelGGL((k_numeric_global<V>), dim3((unsigned)l.n_wg), dim3(GL_THREADS), 0, s, A.rp, A.col, av,
                                B.rp, B.col, bv, l.rows, l.count, l.queue, l.gkeys, static_cast<V *>(l.gvals), l.gbits,
@@ -1267,6 +1305,8 @@ static hipError_t dispatch(const Csr &A, const Csr &B, const NumLaunch &l, int g
     default: return hipErrorInvalidValue;
     }
 #undef OCEAN_WG
+#undef OCEAN_WG_BF
+#undef OCEAN_WAVE
     return hipGetLastError();
 }
 

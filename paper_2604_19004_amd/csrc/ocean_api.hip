@@ -42,6 +42,7 @@ struct Scalars {
     unsigned long long totals[4];                 // P, largest row, P of the rows beyond the LDS hash tables, spare
     unsigned long long bin_count[OCEAN_MAX_BINS];
     unsigned long long bin_cursor[OCEAN_MAX_BINS];
+    unsigned long long bin_prod[OCEAN_MAX_BINS];  // intermediate products of the rows of each bin
     unsigned long long max_cap;
     unsigned long long ovf_count;
     unsigned long long queue[4];
@@ -49,6 +50,7 @@ struct Scalars {
     int32_t flags;
     int32_t pad;
     unsigned long long bin_work[3 * OCEAN_MAX_BINS];   // products, entries of A, entries of C per numeric bin
+    unsigned long long near_pairs;                // neighbouring entries of B whose columns differ by 1 .. 4
 };
 
 constexpr size_t ALIGN = 256;
@@ -68,6 +70,8 @@ struct Ctx {
     // column-window boundary table of B for the dense kernel (null: heavy rows use global hash tables)
     uint32_t *bw = nullptr;
     int n_win = 0;
+    bool query_bitmap = false;
+    bool fine_buckets = false;
 
     void *alloc(size_t bytes)
     {
@@ -267,14 +271,14 @@ int work_alloc(Ctx &c, Work &w, int64_t m, int64_t n_sample)
 int zero_bins(Ctx &c, Work &w)
 {
     HIP_TRY(hipMemsetAsync(w.sc->bin_count, 0,
-                           sizeof(unsigned long long) * (2 * OCEAN_MAX_BINS + 2 + 4), c.s));   // counts, cursors, max_cap, ovf, queues
+                           sizeof(unsigned long long) * (3 * OCEAN_MAX_BINS + 2 + 4), c.s));   // counts, cursors, products, max_cap, ovf, queues
     return OCEAN_OK;
 }
 
 // ---- analysis: validation + products per row ------------------------------------------------------
 int run_analysis(Ctx &c, Work &w, const Csr &A, const Csr &B, bool validate, ocean_stats *st)
 {
-    if (validate) HIP_TRY(launch_validate(A, B, &w.sc->flags, c.s));
+    if (validate) HIP_TRY(launch_validate(A, B, &w.sc->flags, &w.sc->near_pairs, c.s));
     // (the row list of the bins and the last row counter are free at this point: scratch of the long-row list)
     HIP_TRY(launch_row_products(A, B.rp, B.rows, w.prod, w.maxb, w.sc->totals, &w.sc->flags, w.bin_rows, &w.sc->queue[3],
                                 c.s));
@@ -284,6 +288,9 @@ int run_analysis(Ctx &c, Work &w, const Csr &A, const Csr &B, bool validate, oce
     if (c.h->flags & 4) return fail(OCEAN_EINVAL, "a column id of A is outside [0, rows(B))");
     if (c.h->totals[1] >= (1ull << 31))   // the kernels number the products of a row in 32 bits
         return fail(OCEAN_EINVAL, "a row of A*B has 2^31 or more intermediate products");
+    // clustered columns (a quarter or more of B's entries sit within 4 columns of their successor): the hash kernels
+    // then order their rows through narrower column buckets (known only when the inputs were checked)
+    c.fine_buckets = validate && (double)c.h->near_pairs * 4.0 >= (double)B.nnz;
     if (st) {
         st->products = (int64_t)c.h->totals[0];
         st->max_row_products = (int64_t)c.h->totals[1];
@@ -299,8 +306,8 @@ void sample_rows_of(int64_t rows, const ocean_options &o, int64_t *out);
 // ---- exact symbolic pass ---------------------------------------------------------------------------
 // assist_cr > 1: assisted binning (Section 4.1) - key tables are sized from products / assist_cr, rows
 // whose table fills up report -1 and are recounted in a second round with tables sized from the products.
-int run_symbolic(Ctx &c, Work &w, const Csr &A, const Csr &B, int gb_log2, double assist_cr, int32_t *nnz_out,
-                 ocean_stats *st)
+int run_symbolic(Ctx &c, Work &w, const Csr &A, const Csr &B, int gb_log2, double assist_cr, bool query_bitmap,
+                 int32_t *nnz_out, ocean_stats *st)
 {
     HIP_TRY(launch_fill_i32(nnz_out, A.rows, 0, c.s));
     // With at most 2^20 columns the bitmap kernel covers a row in one window, and one pass over such a
@@ -317,7 +324,7 @@ int run_symbolic(Ctx &c, Work &w, const Csr &A, const Csr &B, int gb_log2, doubl
         bp.n_cols = B.cols;
         OC_TRY(zero_bins(c, w));
         HIP_TRY(launch_classify(A.rows, bp, 1.0, w.prod, nullptr, nullptr, round == 0 ? nullptr : nnz_out, w.maxb, w.bin,
-                                nullptr, w.sc->bin_count, nullptr, c.s));
+                                nullptr, w.sc->bin_count, nullptr, nullptr, c.s));
         HIP_TRY(launch_scatter(A.rows, SB_COUNT, w.bin, w.sc->bin_count, w.sc->bin_cursor, w.bin_rows, c.s));
         OC_TRY(fetch_scalars(c, w.sc));
         int64_t start[SB_COUNT + 1];
@@ -327,7 +334,7 @@ int run_symbolic(Ctx &c, Work &w, const Csr &A, const Csr &B, int gb_log2, doubl
             if (st && round == 0) st->symbolic_rows_per_bin[b] = (int64_t)c.h->bin_count[b];
         }
         for (int b = SB_COUNT - 1; b >= 0; --b) {
-            SymLaunch l{w.bin_rows + start[b], start[b + 1] - start[b], b, assisted};
+            SymLaunch l{w.bin_rows + start[b], start[b + 1] - start[b], b, query_bitmap, assisted};
             if (wide_bitmap && (b == SB_S16K || b == SB_S32K)) continue;
             if (wide_bitmap && b == SB_BITMAP) {
                 l.rows = w.bin_rows + start[SB_S16K];
@@ -381,7 +388,7 @@ double conservative_cr(const ocean_stats *S, const ocean_options &o)
 // Launches every non-empty bin, largest tables first.  Scratch for the hybrid
 // and global bins is obtained here and kept until the caller releases all.
 int run_numeric(Ctx &c, Work &w, const Csr &A, const Csr &B, int dtype, int gb_log2, const unsigned long long *count,
-                int64_t max_cap_global, double global_coef, const int64_t *out_ptr, int32_t *out_col, void *out_val,
+                const unsigned long long *bin_prod, int64_t max_cap_global, double global_coef, const int64_t *out_ptr, int32_t *out_col, void *out_val,
                 int32_t *row_nnz, int queue_base, int stage, bool time_bins, bool esc)
 {
     // With the window table, the column-window kernel takes every row beyond the 4096-slot table (measured:
@@ -401,6 +408,7 @@ int run_numeric(Ctx &c, Work &w, const Csr &A, const Csr &B, int dtype, int gb_l
         l.out_val = out_val;
         l.row_nnz = row_nnz;
         l.coef = global_coef;
+        l.fine_buckets = c.fine_buckets;
         if (c.bw != nullptr && b >= HEAVY_FROM && b < NB_GLOBAL) continue;   // went with the last bin, see below
         if (c.bw != nullptr && b == NB_GLOBAL) {
             // the windowed kernel takes the rows of those bins in one launch (their row lists are adjacent)
@@ -424,6 +432,7 @@ int run_numeric(Ctx &c, Work &w, const Csr &A, const Csr &B, int dtype, int gb_l
         } else if (b == NB_GLOBAL && c.bw != nullptr) {
             l.bw = c.bw;
             l.n_win = c.n_win;
+            l.query_bitmap = c.query_bitmap;
             const int64_t resident = (int64_t)c.n_cu * heavy_workgroups_per_cu();
             l.n_wg = (int)(l.count < resident ? l.count : resident);
             l.queue = &w.sc->queue[queue_base + 1];
@@ -546,6 +555,7 @@ void fill_defaults(ocean_options *o)
     o->bitmap_query = -1;
     o->esc_short_rows = 0;
     o->compact_in_place = -1;
+    o->sort_b_ratio = 8.0;
     o->selector = OCEAN_SEL_TABLE1;
     o->tuned_cr_light = 1.0;
     o->tuned_cr_heavy = 4.5;
@@ -690,6 +700,13 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
         OC_TRY(run_sample(c, w, A, n, sketches, m_regs, n_sample, o, S));
     }
 
+    // Section 4.1 / 4.3: dense accumulators query the bitmap before writing when the (sampled) CR is at least 2
+    // (measured on R-MAT, sampled CR 2.5: the dense windows of the numeric pass gain 2.8 %, the symbolic bitmap kernel,
+    // whose only LDS operation per product is that OR, loses 14 %: it queries only when told to, bitmap_query = 2)
+    c.query_bitmap = o.bitmap_query >= 1 || (o.bitmap_query < 0 && S->sampled_rows > 0 && S->sampled_cr >= o.bitmap_query_cr);
+    const bool query_bitmap = o.bitmap_query == 2;
+    Csr Bnum = B;   // what the numeric kernels read: B, or a copy of it with sorted rows (see below)
+    bool tried_sorted_copy = false;
     int32_t *t_col = nullptr;   // output region of the first attempt (C itself on the two-pass path)
     void *t_val = nullptr;
     int64_t total_slots = 0;
@@ -711,7 +728,7 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
         } else if (workflow == OCEAN_WF_SYMBOLIC) {
             S->assist_cr = o.assisted_symbolic ? conservative_cr(S, o) : 1.0;
             if (!(S->assist_cr > 1.0)) S->assist_cr = 0.0;
-            OC_TRY(run_symbolic(c, w, A, B, gb_log2, S->assist_cr, w.nnz_final, S));
+            OC_TRY(run_symbolic(c, w, A, B, gb_log2, S->assist_cr, query_bitmap, w.nnz_final, S));
             bp.mode = 2;
             bp.coef = o.exact_load_coef;
             global_coef = o.exact_load_coef;
@@ -727,7 +744,7 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
         OC_TRY(zero_bins(c, w));
         int64_t *ptr = workflow == OCEAN_WF_SYMBOLIC ? c_rp : w.tmp_ptr;
         HIP_TRY(launch_classify(m, bp, o.estimate_scale, w.prod, w.est, w.nnz_final, nullptr, nullptr, w.bin, w.cap,
-                                w.sc->bin_count, &w.sc->max_cap, c.s));
+                                w.sc->bin_count, w.sc->bin_prod, &w.sc->max_cap, c.s));
         HIP_TRY(launch_scan_i32_to_i64(w.cap, m, ptr, w.scan_tmp, c.s));
         HIP_TRY(launch_scatter(m, NB_COUNT, w.bin, w.sc->bin_count, w.sc->bin_cursor, w.bin_rows, c.s));
         HIP_TRY(hipMemcpyAsync(&w.sc->totals[0], ptr + m, 8, hipMemcpyDeviceToDevice, c.s));   // total slots
@@ -735,6 +752,29 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
         total_slots = (int64_t)c.h->totals[0];
         for (int b = 0; b < NB_COUNT; ++b) S->rows_per_bin[b] = (int64_t)c.h->bin_count[b];
         c.bw = (bw_try != nullptr && !(c.h->flags & 8)) ? bw_try : nullptr;
+        if (bw_try != nullptr && (c.h->flags & 8) && !tried_sorted_copy && o.sort_b_ratio > 0.0 &&
+            (double)S->heavy_products >= o.sort_b_ratio * (double)B.nnz) {
+            // Throughput-bound case of the accumulators that keep values in global memory (Section 5.4): B's rows
+            // are unsorted, so heavy rows would go to those kernels, and they hold many times more products than B
+            // has entries.  Sorting a copy of B once (nnz(B) work) buys them the column-window kernel instead.
+            tried_sorted_copy = true;
+            int32_t *s_col = static_cast<int32_t *>(c.alloc((size_t)B.nnz * 4));
+            void *s_val = s_col ? c.alloc((size_t)B.nnz * vbytes) : nullptr;
+            if (s_col && s_val) {
+                HIP_TRY(hipMemsetAsync(&w.sc->flags, 0, sizeof(int32_t), c.s));
+                HIP_TRY(launch_sort_b_rows(B, dtype, s_col, s_val, &w.sc->flags, c.s));
+                Csr Bs = B;
+                Bs.col = s_col;
+                Bs.val = s_val;
+                HIP_TRY(launch_window_table(Bs, dtype, bw_try, &c.n_win, &w.sc->flags, c.s));
+                OC_TRY(fetch_scalars(c, w.sc));
+                if (!(c.h->flags & (8 | 16))) {
+                    Bnum = Bs;
+                    c.bw = bw_try;
+                    S->b_sorted_copy = 1;
+                }
+            }
+        }
         t_col = static_cast<int32_t *>(c.alloc((size_t)total_slots * 4));
         t_val = t_col ? c.alloc((size_t)total_slots * vbytes) : nullptr;
         if (!t_col || !t_val) {
@@ -751,8 +791,9 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
         out_ptr = ptr;
         break;
     }
-    unsigned long long bin_count[OCEAN_MAX_BINS];
+    unsigned long long bin_count[OCEAN_MAX_BINS], bin_prod[OCEAN_MAX_BINS];
     std::memcpy(bin_count, c.h->bin_count, sizeof(bin_count));
+    std::memcpy(bin_prod, c.h->bin_prod, sizeof(bin_prod));
     const int64_t max_cap = (int64_t)c.h->max_cap;
     double global_coef = workflow == OCEAN_WF_SYMBOLIC ? o.exact_load_coef : 1.25;
 
@@ -762,7 +803,7 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
     // expand-sort-compress needs every row of its bins to have no more products than lanes (true when the bins come
     // from the product bound and B has at least 32 columns) and column ids that leave room for the lane number
     const bool esc_ok = o.esc_short_rows != 0 && n >= 32 && n <= ESC_MAX_COLS;
-    OC_TRY(run_numeric(c, w, A, B, dtype, gb_log2, bin_count, max_cap, global_coef, out_ptr, t_col, t_val, w.row_nnz, 0,
+    OC_TRY(run_numeric(c, w, A, Bnum, dtype, gb_log2, bin_count, bin_prod, max_cap, global_coef, out_ptr, t_col, t_val, w.row_nnz, 0,
                        OCEAN_ST_NUMERIC, st != nullptr, esc_ok && workflow == OCEAN_WF_UPPER_BOUND));
     if (st) {
         HIP_TRY(hipMemsetAsync(w.sc->bin_work, 0, sizeof(w.sc->bin_work), c.s));
@@ -815,7 +856,7 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
         bp.n_cols = n;
         OC_TRY(zero_bins(c, w));
         HIP_TRY(launch_classify(m, bp, 1.0, w.prod, nullptr, nullptr, w.row_nnz, nullptr, w.bin, w.cap, w.sc->bin_count,
-                                &w.sc->max_cap, c.s));
+                                w.sc->bin_prod, &w.sc->max_cap, c.s));
         HIP_TRY(launch_scan_i32_to_i64(w.cap, m, w.tmp_ptr2, w.scan_tmp, c.s));
         HIP_TRY(launch_scatter(m, NB_COUNT, w.bin, w.sc->bin_count, w.sc->bin_cursor, w.bin_rows, c.s));
         HIP_TRY(hipMemcpyAsync(&w.sc->totals[0], w.tmp_ptr2 + m, 8, hipMemcpyDeviceToDevice, c.s));
@@ -824,10 +865,11 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
         r_col = static_cast<int32_t *>(c.alloc((size_t)slots2 * 4));
         r_val = r_col ? c.alloc((size_t)slots2 * vbytes) : nullptr;
         if (!r_col || !r_val) return fail(OCEAN_EALLOC, "retry output allocation failed");
-        unsigned long long bc2[OCEAN_MAX_BINS];
+        unsigned long long bc2[OCEAN_MAX_BINS], bp2[OCEAN_MAX_BINS];
         std::memcpy(bc2, c.h->bin_count, sizeof(bc2));
+        std::memcpy(bp2, c.h->bin_prod, sizeof(bp2));
         HIP_TRY(launch_fill_i32(w.row_nnz2, m, 0, c.s));
-        OC_TRY(run_numeric(c, w, A, B, dtype, gb_log2, bc2, (int64_t)c.h->max_cap, 1.25, w.tmp_ptr2, r_col, r_val,
+        OC_TRY(run_numeric(c, w, A, Bnum, dtype, gb_log2, bc2, bp2, (int64_t)c.h->max_cap, 1.25, w.tmp_ptr2, r_col, r_val,
                            w.row_nnz2, 2, OCEAN_ST_RETRY, false, esc_ok));
         HIP_TRY(launch_final_nnz(m, w.row_nnz, w.row_nnz2, w.nnz_final, c.s));
         HIP_TRY(launch_scan_i32_to_i64(w.nnz_final, m, c_rp, w.scan_tmp, c.s));
@@ -1106,7 +1148,7 @@ int ocean_symbolic(const ocean_csr *A, const ocean_csr *B, int32_t *nnz_per_row,
             if (!(assist_cr > 1.0)) assist_cr = 0.0;
         }
         S->assist_cr = assist_cr;
-        OC_TRY(run_symbolic(c, w, a, b, gb_log2, assist_cr, nnz_per_row, S));
+        OC_TRY(run_symbolic(c, w, a, b, gb_log2, assist_cr, o.bitmap_query == 2, nnz_per_row, S));
         HIP_TRY(hipStreamSynchronize(c.s));
         return OCEAN_OK;
     }();

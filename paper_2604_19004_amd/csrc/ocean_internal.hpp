@@ -178,7 +178,7 @@ __device__ __forceinline__ T group_reduce_max(T v, int width)
 
 // --------------------------------------------------- launcher prototypes ----
 // analysis.hip
-hipError_t launch_validate(const Csr &A, const Csr &B, int32_t *flags, hipStream_t s);
+hipError_t launch_validate(const Csr &A, const Csr &B, int32_t *flags, unsigned long long *b_near_pairs, hipStream_t s);
 hipError_t launch_row_products(const Csr &A, const int64_t *b_rp, int64_t b_rows, int64_t *prod, int32_t *maxb,
                                unsigned long long *totals, int32_t *flags, int32_t *long_rows,
                                unsigned long long *long_count, hipStream_t s);
@@ -202,7 +202,8 @@ struct BinParams {
 hipError_t launch_classify(int64_t m, const BinParams &p, double scale, const int64_t *prod, const double *est,
                            const int32_t *nnz_exact, const int32_t *row_mask, const int32_t *lower_bound,
                            uint8_t *bin_of_row, int32_t *cap, unsigned long long *bin_count,
-                           unsigned long long *max_cap, hipStream_t s);
+                           unsigned long long *bin_prod /*products per bin, may be null*/, unsigned long long *max_cap,
+                           hipStream_t s);
 hipError_t launch_scatter(int64_t m, int n_bins, const uint8_t *bin_of_row, const unsigned long long *bin_count,
                           unsigned long long *bin_cursor, int32_t *bin_rows, hipStream_t s);
 hipError_t launch_scan_i32_to_i64(const int32_t *in, int64_t n, int64_t *out /*n+1*/, int64_t *block_tmp,
@@ -220,6 +221,7 @@ struct SymLaunch {
     const int32_t *rows;   // row ids of this bin
     int64_t count;
     int bin;
+    bool query_bitmap;     // bitmap kernel: read a column's bit before setting it (Section 4.1)
     bool may_overflow;     // tables were sized from a guess (assisted binning): a row whose table fills up
                            // reports -1 instead of a count and probing gives up early
 };
@@ -228,6 +230,7 @@ hipError_t launch_symbolic_bin(const Csr &A, const Csr &B, const SymLaunch &l, i
 
 // order.hip
 size_t sort_rows_scratch_bytes(int64_t count);
+hipError_t launch_sort_b_rows(const Csr &B, int dtype, int32_t *col_out, void *val_out, int32_t *flags, hipStream_t s);
 hipError_t launch_sort_rows_by_products(const int64_t *prod, int32_t *rows, int64_t count, void *scratch, hipStream_t s);
 
 // numeric.hip
@@ -250,6 +253,8 @@ struct NumLaunch {
     double coef;              // global: table slots per reserved output entry
     const uint32_t *bw;       // dense kernel: window boundary table of B, or null to use the global-table kernel
     int n_win;
+    bool query_bitmap;        // dense windows: read a column's presence bit before setting it (Section 4.1)
+    bool fine_buckets;        // 512- and 1024-slot bins: order the row through 2048 column buckets (clustered columns)
 };
 hipError_t launch_window_table(const Csr &B, int dtype, uint32_t *bw, int *n_win_out, int32_t *flags, hipStream_t s);
 int heavy_workgroups_per_cu();   // workgroups of the column-window kernel that one compute unit holds

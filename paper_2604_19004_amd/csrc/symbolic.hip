@@ -169,7 +169,7 @@ __global__ void __launch_bounds__(BM_THREADS)
 k_symbolic_bitmap(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col,
                   const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_col,
                   const int32_t *__restrict__ rows, int64_t count, int64_t n_cols,
-                  unsigned long long *queue, int32_t *__restrict__ nnz_out)
+                  unsigned long long *queue, int32_t *__restrict__ nnz_out, int query_bitmap)
 {
     __shared__ uint32_t s_bm[BM_WORDS];
     __shared__ WgChunk<NoVal, BM_THREADS> s_fc;
@@ -211,8 +211,11 @@ k_symbolic_bitmap(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ 
             const uint32_t d = (uint32_t)cj[u] - w0;
             // Only the number of set bits matters, so neighbouring columns (the sorted entries of one row of
             // B in neighbouring lanes) go to neighbouring words, i.e. different LDS banks, not to one word.
-            if (cj[u] >= 0 && (ONE_WINDOW || d < (uint32_t)BM_WIN))
-                atomicOr(&s_bm[d & (uint32_t)(BM_WORDS - 1)], 1u << (d / (uint32_t)BM_WORDS));
+            if (cj[u] >= 0 && (ONE_WINDOW || d < (uint32_t)BM_WIN)) {
+                const uint32_t bit = 1u << (d / (uint32_t)BM_WORDS);
+                uint32_t *word = &s_bm[d & (uint32_t)(BM_WORDS - 1)];
+                if (!query_bitmap || !(*word & bit)) atomicOr(word, bit);   // (Section 4.1: query before write)
+            }
         }
     };
     for (unsigned turn = 0;; ++turn) {
@@ -300,10 +303,10 @@ hipError_t launch_symbolic_bin(const Csr &A, const Csr &B, const SymLaunch &l, i
     case SB_BITMAP:
         if (B.cols <= BM_WIN)
             hipLaunchKernelGGL(k_symbolic_bitmap<true>, dim3((unsigned)n_wg), dim3(BM_THREADS), 0, s, A.rp, A.col, B.rp,
-                               B.col, l.rows, l.count, B.cols, queue, nnz_out);
+                               B.col, l.rows, l.count, B.cols, queue, nnz_out, l.query_bitmap ? 1 : 0);
         else
             hipLaunchKernelGGL(k_symbolic_bitmap<false>, dim3((unsigned)n_wg), dim3(BM_THREADS), 0, s, A.rp, A.col, B.rp,
-                               B.col, l.rows, l.count, B.cols, queue, nnz_out);
+                               B.col, l.rows, l.count, B.cols, queue, nnz_out, l.query_bitmap ? 1 : 0);
         break;
     default: return hipErrorInvalidValue;
     }

@@ -397,6 +397,42 @@ def test_heavy_rows_reach_hybrid_and_last_bin(ob, variant):
     assert st["overflow_rows"] > 0
 
 
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_unsorted_b_with_much_heavy_work_is_sorted_once(ob, dtype):
+    """The throughput-bound case of the accumulators with values in global memory (Section 5.4): B's rows are
+    unsorted and the heavy rows hold many times more products than B has entries.  The library then sorts a
+    copy of B and runs those rows through the column-window kernel; with the detector off, or when a row of
+    B is too long for the sort, the global-memory kernels run.  The result is the same every way."""
+    rng = np.random.default_rng(31)
+    n = 1 << 17
+    Bm = W.erdos_renyi(2048, 64, seed=32, cols=n)
+    Bm.val = Bm.val.astype(dtype)
+    perm = rng.permuted(np.arange(Bm.nnz).reshape(2048, 64), axis=1).reshape(-1)
+    Bm = CSR(Bm.rows, Bm.cols, Bm.row_ptr, Bm.col_idx[perm].copy(), Bm.val[perm].copy())
+    rows_spec = [1500] * 40 + [700] * 40 + [90, 3, 0]                   # 80 heavy rows: 5.6 M products, nnz(B) = 131 072
+    rp = np.concatenate([[0], np.cumsum(rows_spec)]).astype(np.int64)
+    ci = np.concatenate([np.sort(rng.choice(2048, k, replace=False)) for k in rows_spec]).astype(np.int32)
+    A = CSR(len(rows_spec), 2048, rp, ci, rng.uniform(-1, 1, ci.size).astype(dtype))
+    ref = O.multiply_rows(A, Bm)
+    dA, dB = ob.to_device(A), ob.to_device(Bm)
+    for wf in ("symbolic", "hll", "upper_bound"):
+        Cd, st = ob.spgemm(dA, dB, workflow=wf_id(ob, wf))
+        check_result(Cd, ref, A, f"sorted copy of B {np.dtype(dtype).name}/{wf}")
+        assert st["b_sorted_copy"] == 1 and st["heavy_products"] >= 8 * Bm.nnz
+    Cd, st = ob.spgemm(dA, dB, workflow=ob.WF_SYMBOLIC, sort_b_ratio=0.0)
+    check_result(Cd, ref, A, "detector off")
+    assert st["b_sorted_copy"] == 0
+    # one row of B longer than the sort takes (and unsorted): B stays as it is
+    long_cols = rng.permutation(n)[:5000].astype(np.int32)
+    b_rp = np.concatenate([Bm.row_ptr, [Bm.nnz + 5000]]).astype(np.int64)
+    B2 = CSR(Bm.rows + 1, n, b_rp, np.concatenate([Bm.col_idx, long_cols]), np.concatenate([Bm.val, np.ones(5000, dtype)]))
+    A2 = CSR(A.rows, B2.rows, A.row_ptr, A.col_idx, A.val)
+    ref2 = O.multiply_rows(A2, B2)
+    Cd, st = ob.spgemm(ob.to_device(A2), ob.to_device(B2), workflow=ob.WF_SYMBOLIC)
+    check_result(Cd, ref2, A2, "row of B too long to sort")
+    assert st["b_sorted_copy"] == 0
+
+
 @pytest.mark.parametrize("n", [1 << 20, 3 << 20])
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
 def test_heavy_rows_spread_thin_over_many_windows(ob, dtype, n):
