@@ -107,7 +107,7 @@ typedef struct ocean_options {
                                         8-lanes-per-row hash kernel, which measured faster on this GPU (one product per
                                         lane leaves the sort network's lanes a quarter as busy) */
     double bitmap_query_cr;          /* 2.0 (Section 4.3) */
-    int32_t selector;                /* OCEAN_SEL_TABLE1 (default) or OCEAN_SEL_MI355X */
+    int32_t selector;                /* OCEAN_SEL_MI355X (default) or OCEAN_SEL_TABLE1 (the paper's thresholds as printed) */
     int32_t compact_in_place;        /* estimation workflows: rows are compacted inside the temporary output, which then
                                         becomes C (col_idx / val stay as large as the reservation), instead of into a
                                         second allocation (Section 5.2, memory overhead).  0 never, 1 whenever the rows
@@ -271,6 +271,13 @@ int ocean_sample_rows(int64_t rows, const ocean_options *opt, int64_t *rows_out)
 
 /* Number of numeric / symbolic bins and the table slots of each (host arrays of OCEAN_MAX_BINS). */
 int ocean_bin_layout(int32_t *numeric_slots, int32_t *n_numeric, int32_t *symbolic_slots, int32_t *n_symbolic);
+
+/*
+ * The calls that read totals back keep, per host thread, a small pinned host buffer and the events behind
+ * ocean_stats' timings from one call to the next.  ocean_finalize releases those of the calling thread (they
+ * are created again on the next call); call it before the thread ends or the library is unloaded.
+ */
+int ocean_finalize(void);
 
 const char *ocean_last_error(void);
 int ocean_version(void);

@@ -102,6 +102,8 @@ def load():
     lib.ocean_row_products.argtypes = [P(ocean_csr), P(ocean_csr), vp, P(i64), P(i64), vp]
     lib.ocean_row_products_noalloc.argtypes = [P(ocean_csr), P(ocean_csr), vp, vp, vp]
     lib.ocean_init.argtypes = []
+    lib.ocean_finalize.argtypes = []
+    lib.ocean_finalize.restype = C.c_int
     lib.ocean_hll_sketch_rows.argtypes = [P(ocean_csr), i32, vp, vp]
     lib.ocean_hll_merge_estimate.argtypes = [P(ocean_csr), vp, i32, vp, i64, vp, vp, i64, vp, vp, vp]
     lib.ocean_symbolic.argtypes = [P(ocean_csr), P(ocean_csr), vp, P(ocean_options), P(ocean_stats), vp]
@@ -293,6 +295,11 @@ def init():
     """Resolve the library's fixed scratch array on the current device ahead of the first no-alloc call."""
     _torch()
     _check(load().ocean_init())
+
+
+def finalize():
+    """Release the calling thread's pinned read-back buffer and timing events."""
+    _check(load().ocean_finalize())
 
 
 def row_products_noalloc(A: DeviceCSR, B: DeviceCSR, prod, totals, stream=None):

@@ -27,8 +27,8 @@ def build(verbose: bool = False) -> str:
     """Compile every translation unit and link the shared library.  Always rebuilds."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objdir = os.path.join(HERE, "_build")
-    flags = HIPCC_FLAGS + os.environ.get("OCEAN_EXTRA_HIPCC_FLAGS", "").split()   # development switches
-    lib = os.environ.get("OCEAN_LIB_OUT", LIB)
+    flags = HIPCC_FLAGS
+    lib = LIB
     os.makedirs(objdir, exist_ok=True)
 
     def compile_one(src: str) -> str:

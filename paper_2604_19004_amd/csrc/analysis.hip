@@ -23,15 +23,18 @@ static inline int ilog2_ceil(double x, int lo, int hi)
 }
 
 // ---------------------------------------------------------------- validate
-// near_pairs (may be null): += the number of neighbouring entries whose column ids differ by 1 .. 4 - how
-// clustered the columns of the matrix are (pairs across a row boundary count too; they are few).
+// near_pairs (may be null): a measure of how clustered the columns of the matrix are, taken on a sample - every
+// 16th workgroup adds the number of entries it looked at to near_pairs[0] and the number of those whose
+// successor's column id is 1 .. 4 larger to near_pairs[1] (pairs across a row boundary count too; they are few).
+// One pair of atomics per sampling workgroup: same-address atomics serialise at about 12 ns each.
 __global__ void k_validate(const int64_t *rp, const int32_t *col, int64_t rows, int64_t cols, int64_t nnz,
                            int32_t *flags, int bit, unsigned long long *near_pairs)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     bool bad = false;
-    unsigned int near = 0;
+    const bool sampling = near_pairs != nullptr && (blockIdx.x & 15u) == 0u;   // uniform
+    unsigned int near = 0, seen = 0;
     for (int64_t i = t0; i < rows; i += stride) {
         int64_t a = rp[i], b = rp[i + 1];
         bad |= (b < a) | (a < 0) | (b > nnz);
@@ -40,23 +43,31 @@ __global__ void k_validate(const int64_t *rp, const int32_t *col, int64_t rows, 
     for (int64_t e = t0; e < nnz; e += stride) {
         int32_t c = col[e];
         bad |= ((uint32_t)c >= (uint64_t)cols);
-        if (near_pairs != nullptr && e + 1 < nnz) near += (uint32_t)(col[e + 1] - c - 1) < 4u;
+        if (sampling && e + 1 < nnz) { near += (uint32_t)(col[e + 1] - c - 1) < 4u; ++seen; }
     }
     if (__ballot(bad) != 0 && lane_id() == 0) atomicOr(flags, bit);
-    if (near_pairs != nullptr) {
-        const unsigned int wave_near = wave_sum_u32(near);
-        if (lane_id() == 0 && wave_near) atomicAdd(near_pairs, (unsigned long long)wave_near);
+    if (sampling) {
+        __shared__ unsigned int s_near, s_seen;
+        if (threadIdx.x == 0) { s_near = 0u; s_seen = 0u; }
+        __syncthreads();
+        const unsigned int wave_near = wave_sum_u32(near), wave_seen = wave_sum_u32(seen);
+        if (lane_id() == 0) { atomicAdd(&s_near, wave_near); atomicAdd(&s_seen, wave_seen); }
+        __syncthreads();
+        if (threadIdx.x == 0 && s_seen) {
+            atomicAdd(&near_pairs[0], (unsigned long long)s_seen);
+            atomicAdd(&near_pairs[1], (unsigned long long)s_near);
+        }
     }
 }
 
-// b_near_pairs: zeroed device counter that receives the clustering measure of B's columns (see k_validate).
+// b_near_pairs: two zeroed device counters that receive the clustering measure of B's columns (see k_validate).
 hipError_t launch_validate(const Csr &A, const Csr &B, int32_t *flags, unsigned long long *b_near_pairs, hipStream_t s)
 {
     auto go = [&](const Csr &M, int bit, unsigned long long *near) {
         int64_t work = M.nnz > M.rows ? M.nnz : M.rows;
         int blocks = (int)((work + TPB * 4 - 1) / (TPB * 4));
         if (blocks < 1) blocks = 1;
-        if (blocks > 4096) blocks = 4096;   // (one wave-level atomic per wave at the end: keep the waves few)
+        if (blocks > 65536) blocks = 65536;
         hipLaunchKernelGGL(k_validate, dim3(blocks), dim3(TPB), 0, s, M.rp, M.col, M.rows, M.cols, M.nnz, flags, bit, near);
     };
     const bool same = B.rp == A.rp && B.col == A.col && B.rows == A.rows && B.cols == A.cols;
@@ -73,8 +84,11 @@ hipError_t launch_validate(const Csr &A, const Csr &B, int32_t *flags, unsigned 
 // and on power-law inputs such rows cluster (their indices share bit patterns,
 // so whole workgroups would get nothing else): they are put on a list and a
 // second kernel gives each of them a workgroup of its own.
-// totals[0] += products, totals[1] = max(products of a row), totals[2] += products of the rows whose
-// product count exceeds heavy_from (the rows that outgrow the LDS hash tables).
+// Totals of the row-products pass.  Same-address atomics from all over the chip serialise in the L2 at about 12
+// ns each, and there is one set per workgroup: they are spread over ROW_TOTAL_SLOTS slots of 128 bytes (one
+// cache line each) by workgroup index and added up by whoever reads them (sum_row_totals on the host).
+// slot[0] += products, slot[1] = max(products of a row), slot[2] += products of the rows whose product count
+// exceeds heavy_from (the rows that outgrow the LDS hash tables).
 __device__ __forceinline__ void block_totals(long long tsum, long long tmax, long long theavy, long long *s_sum,
                                              long long *s_max, long long *s_heavy, unsigned long long *totals)
 {
@@ -87,9 +101,10 @@ __device__ __forceinline__ void block_totals(long long tsum, long long tmax, lon
     if (threadIdx.x == 0) {
         long long bs = 0, bm = 0, bh = 0;
         for (int i = 0; i < TPB / WAVE; ++i) { bs += s_sum[i]; bm = s_max[i] > bm ? s_max[i] : bm; bh += s_heavy[i]; }
-        if (bs) atomicAdd(&totals[0], (unsigned long long)bs);
-        if (bm) atomicMax(&totals[1], (unsigned long long)bm);
-        if (bh) atomicAdd(&totals[2], (unsigned long long)bh);
+        unsigned long long *slot = totals + (size_t)(blockIdx.x % ROW_TOTAL_SLOTS) * ROW_TOTAL_STRIDE;
+        if (bs) atomicAdd(&slot[0], (unsigned long long)bs);
+        if (bm) atomicMax(&slot[1], (unsigned long long)bm);
+        if (bh) atomicAdd(&slot[2], (unsigned long long)bh);
     }
 }
 
@@ -247,8 +262,14 @@ hipError_t launch_row_products(const Csr &A, const int64_t *b_rp, int64_t b_rows
 __global__ void k_publish_totals(const unsigned long long *totals, const int32_t *flags, int64_t *out)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
-        out[0] = (int64_t)totals[0];
-        out[1] = (int64_t)totals[1];
+        unsigned long long sum = 0, mx = 0;
+        for (int i = 0; i < ROW_TOTAL_SLOTS; ++i) {
+            sum += totals[(size_t)i * ROW_TOTAL_STRIDE];
+            const unsigned long long v = totals[(size_t)i * ROW_TOTAL_STRIDE + 1];
+            mx = v > mx ? v : mx;
+        }
+        out[0] = (int64_t)sum;
+        out[1] = (int64_t)mx;
         out[2] = (int64_t)*flags;
     }
 }

@@ -703,13 +703,14 @@ struct DenseCfg {
     static constexpr int WORDS = WIN / 32;
 };
 
-template <typename V>
+// QUERY: dense windows read a column's presence bit and set it only when it is clear (Section 4.1).
+template <typename V, bool QUERY>
 __global__ void __launch_bounds__(HV_THREADS)
 k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col, const V *__restrict__ a_val,
                 const uint32_t *__restrict__ bw, int n_win, const int32_t *__restrict__ b_col,
                 const V *__restrict__ b_val, const int32_t *__restrict__ rows, int64_t count,
                 unsigned long long *queue, const int64_t *__restrict__ out_ptr, int32_t *__restrict__ out_col,
-                V *__restrict__ out_val, int32_t *__restrict__ row_nnz, int query_bitmap)
+                V *__restrict__ out_val, int32_t *__restrict__ row_nnz)
 {
     constexpr int WIN = DenseCfg<V>::WIN;
     constexpr int WORDS = DenseCfg<V>::WORDS;
@@ -872,7 +873,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                             // Section 4.1: with many products per output entry most presence bits are set already;
                             // reading the bit first then saves the write (a stale read only costs a redundant OR)
                             const uint32_t bit = 1u << (d & 31);
-                            if (!query_bitmap || !(s_dbm[d >> 5] & bit)) atomicOr(&s_dbm[d >> 5], bit);
+                            if (!QUERY || !(s_dbm[d >> 5] & bit)) atomicOr(&s_dbm[d >> 5], bit);
                         }
                     }
                 } else {
@@ -1294,9 +1295,12 @@ static hipError_t dispatch(const Csr &A, const Csr &B, const NumLaunch &l, int g
                                static_cast<uint2 *>(l.pairs), l.out_ptr, l.out_col, ov, l.row_nnz);
         break;
     case NB_GLOBAL:
-        if (l.bw != nullptr)
-            hipLaunchKernelGGL((k_numeric_heavy<V>), dim3((unsigned)l.n_wg), dim3(HV_THREADS), 0, s, A.rp, A.col, av, l.bw,
-                               l.n_win, B.col, bv, l.rows, l.count, l.queue, l.out_ptr, l.out_col, ov, l.row_nnz, l.query_bitmap ? 1 : 0);
+        if (l.bw != nullptr && l.query_bitmap)
+            hipLaunchKernelGGL((k_numeric_heavy<V, true>), dim3((unsigned)l.n_wg), dim3(HV_THREADS), 0, s, A.rp, A.col, av, l.bw,
+                               l.n_win, B.col, bv, l.rows, l.count, l.queue, l.out_ptr, l.out_col, ov, l.row_nnz);
+        else if (l.bw != nullptr)
+            hipLaunchKernelGGL((k_numeric_heavy<V, false>), dim3((unsigned)l.n_wg), dim3(HV_THREADS), 0, s, A.rp, A.col, av, l.bw,
+                               l.n_win, B.col, bv, l.rows, l.count, l.queue, l.out_ptr, l.out_col, ov, l.row_nnz);
         else
             hipLaunchKernelGGL((k_numeric_global<V>), dim3((unsigned)l.n_wg), dim3(GL_THREADS), 0, s, A.rp, A.col, av,
                                B.rp, B.col, bv, l.rows, l.count, l.queue, l.gkeys, static_cast<V *>(l.gvals), l.gbits,

@@ -39,7 +39,7 @@ int fail(int code, const std::string &msg)
 
 // Device scalars of one call; zeroed at the start.
 struct Scalars {
-    unsigned long long totals[4];                 // P, largest row, P of the rows beyond the LDS hash tables, spare
+    unsigned long long totals[4];                 // [0]: a total copied here to be read back (slots reserved, nnz(C))
     unsigned long long bin_count[OCEAN_MAX_BINS];
     unsigned long long bin_cursor[OCEAN_MAX_BINS];
     unsigned long long bin_prod[OCEAN_MAX_BINS];  // intermediate products of the rows of each bin
@@ -50,8 +50,21 @@ struct Scalars {
     int32_t flags;
     int32_t pad;
     unsigned long long bin_work[3 * OCEAN_MAX_BINS];   // products, entries of A, entries of C per numeric bin
-    unsigned long long near_pairs;                // neighbouring entries of B whose columns differ by 1 .. 4
+    unsigned long long near_pairs[2];             // sampled entries of B, and those whose successor's column is 1 .. 4 larger
+    unsigned long long row_totals[ROW_TOTAL_SLOTS * ROW_TOTAL_STRIDE];   // totals of the row-products pass, by slot
 };
+
+// P, largest row, products of the heavy rows from the slots of a fetched Scalars
+void sum_row_totals(const Scalars *h, unsigned long long (&out)[3])
+{
+    out[0] = out[1] = out[2] = 0;
+    for (int i = 0; i < ROW_TOTAL_SLOTS; ++i) {
+        const unsigned long long *slot = h->row_totals + (size_t)i * ROW_TOTAL_STRIDE;
+        out[0] += slot[0];
+        out[1] = slot[1] > out[1] ? slot[1] : out[1];
+        out[2] += slot[2];
+    }
+}
 
 constexpr size_t ALIGN = 256;
 inline size_t up(size_t b) { return (b + ALIGN - 1) / ALIGN * ALIGN; }
@@ -278,23 +291,25 @@ int zero_bins(Ctx &c, Work &w)
 // ---- analysis: validation + products per row ------------------------------------------------------
 int run_analysis(Ctx &c, Work &w, const Csr &A, const Csr &B, bool validate, ocean_stats *st)
 {
-    if (validate) HIP_TRY(launch_validate(A, B, &w.sc->flags, &w.sc->near_pairs, c.s));
+    if (validate) HIP_TRY(launch_validate(A, B, &w.sc->flags, w.sc->near_pairs, c.s));
     // (the row list of the bins and the last row counter are free at this point: scratch of the long-row list)
-    HIP_TRY(launch_row_products(A, B.rp, B.rows, w.prod, w.maxb, w.sc->totals, &w.sc->flags, w.bin_rows, &w.sc->queue[3],
-                                c.s));
+    HIP_TRY(launch_row_products(A, B.rp, B.rows, w.prod, w.maxb, w.sc->row_totals, &w.sc->flags, w.bin_rows,
+                                &w.sc->queue[3], c.s));
     OC_TRY(fetch_scalars(c, w.sc));
+    unsigned long long tot[3];
+    sum_row_totals(c.h, tot);
     if (c.h->flags & 1) return fail(OCEAN_EINVAL, "A is not a valid CSR matrix (row offsets or column ids out of range)");
     if (c.h->flags & 2) return fail(OCEAN_EINVAL, "B is not a valid CSR matrix (row offsets or column ids out of range)");
     if (c.h->flags & 4) return fail(OCEAN_EINVAL, "a column id of A is outside [0, rows(B))");
-    if (c.h->totals[1] >= (1ull << 31))   // the kernels number the products of a row in 32 bits
+    if (tot[1] >= (1ull << 31))   // the kernels number the products of a row in 32 bits
         return fail(OCEAN_EINVAL, "a row of A*B has 2^31 or more intermediate products");
     // clustered columns (a quarter or more of B's entries sit within 4 columns of their successor): the hash kernels
     // then order their rows through narrower column buckets (known only when the inputs were checked)
-    c.fine_buckets = validate && (double)c.h->near_pairs * 4.0 >= (double)B.nnz;
+    c.fine_buckets = validate && c.h->near_pairs[0] > 0 && (double)c.h->near_pairs[1] * 4.0 >= (double)c.h->near_pairs[0];
     if (st) {
-        st->products = (int64_t)c.h->totals[0];
-        st->max_row_products = (int64_t)c.h->totals[1];
-        st->heavy_products = (int64_t)c.h->totals[2];
+        st->products = (int64_t)tot[0];
+        st->max_row_products = (int64_t)tot[1];
+        st->heavy_products = (int64_t)tot[2];
         st->er = A.nnz > 0 ? (double)st->products / (double)A.nnz : 0.0;
         st->avg_products = A.rows > 0 ? (double)st->products / (double)A.rows : 0.0;
     }
@@ -410,6 +425,11 @@ int run_numeric(Ctx &c, Work &w, const Csr &A, const Csr &B, int dtype, int gb_l
         l.coef = global_coef;
         l.fine_buckets = c.fine_buckets;
         if (c.bw != nullptr && b >= HEAVY_FROM && b < NB_GLOBAL) continue;   // went with the last bin, see below
+        if (!esc && b == NB_E16) continue;   // same kernel as the 32-slot bin: one launch for both (adjacent row lists)
+        if (!esc && b == NB_G8) {
+            l.rows = w.bin_rows + start[NB_E16];
+            l.count = start[NB_G8 + 1] - start[NB_E16];
+        }
         if (c.bw != nullptr && b == NB_GLOBAL) {
             // the windowed kernel takes the rows of those bins in one launch (their row lists are adjacent)
             l.rows = w.bin_rows + start[HEAVY_FROM];
@@ -556,7 +576,7 @@ void fill_defaults(ocean_options *o)
     o->esc_short_rows = 0;
     o->compact_in_place = -1;
     o->sort_b_ratio = 8.0;
-    o->selector = OCEAN_SEL_TABLE1;
+    o->selector = OCEAN_SEL_MI355X;
     o->tuned_cr_light = 1.0;
     o->tuned_cr_heavy = 4.5;
     o->tuned_min_products = 4194304.0;
@@ -834,8 +854,9 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
 
     // ---- overflow rows: redo them with bound-sized tables (Section 3.2) ----
     S->temp_slots = total_slots;
-    OC_TRY(mark(c, OCEAN_ST_RETRY));
-    HIP_TRY(launch_count_overflow(m, w.row_nnz, &w.sc->ovf_count, c.s));
+    OC_TRY(mark(c, workflow == OCEAN_WF_UPPER_BOUND ? OCEAN_ST_COMPACT : OCEAN_ST_RETRY));
+    // (sizes from the product bound cannot fall short: nothing to count in the upper-bound workflow)
+    if (workflow != OCEAN_WF_UPPER_BOUND) HIP_TRY(launch_count_overflow(m, w.row_nnz, &w.sc->ovf_count, c.s));
     // optimistic: if nothing overflowed this scan already is the final row_ptr
     HIP_TRY(launch_scan_i32_to_i64(w.row_nnz, m, c_rp, w.scan_tmp, c.s));
     HIP_TRY(hipMemcpyAsync(&w.sc->totals[0], c_rp + m, 8, hipMemcpyDeviceToDevice, c.s));
@@ -1042,17 +1063,31 @@ int ocean_row_products(const ocean_csr *A, const ocean_csr *B, int64_t *prod, in
     int32_t *maxb = reinterpret_cast<int32_t *>(buf + up(sizeof(Scalars)));
     int rc = [&]() -> int {
         HIP_TRY(hipMemsetAsync(sc, 0, sizeof(Scalars), c.s));
-        HIP_TRY(launch_row_products(view(A), B->row_ptr, B->rows, prod, maxb, sc->totals, &sc->flags, nullptr, nullptr, c.s));
+        HIP_TRY(launch_row_products(view(A), B->row_ptr, B->rows, prod, maxb, sc->row_totals, &sc->flags, nullptr, nullptr, c.s));
         OC_TRY(fetch_scalars(c, sc));
+        unsigned long long tot[3];
+        sum_row_totals(c.h, tot);
         if (c.h->flags & 1) return fail(OCEAN_EINVAL, "A is not a valid CSR matrix (row offsets out of range or descending)");
         if (c.h->flags & 4) return fail(OCEAN_EINVAL, "a column id of A is outside [0, rows(B))");
-        if (total) *total = (int64_t)c.h->totals[0];
-        if (max_row) *max_row = (int64_t)c.h->totals[1];
+        if (total) *total = (int64_t)tot[0];
+        if (max_row) *max_row = (int64_t)tot[1];
         return OCEAN_OK;
     }();
     (void)hipStreamSynchronize(c.s);
     c.release_all();
     return rc;
+}
+
+int ocean_finalize(void)
+{
+    g_err.clear();
+    for (hipEvent_t e : g_pinned.events) (void)hipEventDestroy(e);
+    g_pinned.events.clear();
+    if (g_pinned.p) {
+        HIP_TRY(hipHostFree(g_pinned.p));
+        g_pinned.p = nullptr;
+    }
+    return OCEAN_OK;
 }
 
 int ocean_init(void)
@@ -1082,8 +1117,8 @@ int ocean_row_products_noalloc(const ocean_csr *A, const ocean_csr *B, int64_t *
     // the scalars keep the last call's sums: clear them (a fill kernel, so that the call can be captured
     // into a graph); the per-row arrays are written before they are read
     HIP_TRY(launch_fill_u64(reinterpret_cast<unsigned long long *>(sc), (int64_t)(NOALLOC_SCALARS / 8), 0ull, s));
-    HIP_TRY(launch_row_products(view(A), B->row_ptr, B->rows, prod, maxb, sc->totals, &sc->flags, long_rows, &sc->queue[3], s));
-    HIP_TRY(launch_publish_totals(sc->totals, &sc->flags, totals, s));
+    HIP_TRY(launch_row_products(view(A), B->row_ptr, B->rows, prod, maxb, sc->row_totals, &sc->flags, long_rows, &sc->queue[3], s));
+    HIP_TRY(launch_publish_totals(sc->row_totals, &sc->flags, totals, s));
     return OCEAN_OK;
 }
 

@@ -176,6 +176,11 @@ __device__ __forceinline__ T group_reduce_max(T v, int width)
 }
 #endif
 
+// Totals of the row-products pass are kept in ROW_TOTAL_SLOTS slots of ROW_TOTAL_STRIDE 64-bit words each (128
+// bytes apart): [0] sum of products, [1] largest row, [2] products of the heavy rows; see analysis.hip.
+constexpr int ROW_TOTAL_SLOTS = 32;
+constexpr int ROW_TOTAL_STRIDE = 16;
+
 // --------------------------------------------------- launcher prototypes ----
 // analysis.hip
 hipError_t launch_validate(const Csr &A, const Csr &B, int32_t *flags, unsigned long long *b_near_pairs, hipStream_t s);

@@ -47,7 +47,10 @@ __device__ __forceinline__ int lds_count_new_batch(int32_t *keys, const int32_t 
             rounds = 0;
         } else {
             h = (h + step) & MASK;
-            if (++rounds > LIMIT) { ovf = true; key = -1; }
+            if (++rounds > LIMIT) {   // (a table sized from the product count cannot fill up)
+                if (CAPPED) ovf = true;
+                key = -1;
+            }
         }
     }
     return fresh;
@@ -78,7 +81,7 @@ k_symbolic_group(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
     bool ovf = false;
     const int64_t e0 = live ? a_rp[row] : 0;
     const int64_t e1 = live ? a_rp[row + 1] : 0;
-    auto f = [&](const auto &cj, const auto &) { if (!ovf) fresh += lds_count_new_batch<BITS, CAPPED>(keys, cj, ovf); };
+    auto f = [&](const auto &cj, const auto &) { if (!CAPPED || !ovf) fresh += lds_count_new_batch<BITS, CAPPED>(keys, cj, ovf); };
     const int chunks = group_reduce_max((int)((e1 - e0 + G - 1) / G), WAVE);
     for (int ch = 0; ch < chunks; ++ch) {
         const int64_t e = e0 + (int64_t)ch * G + sub;
@@ -120,7 +123,7 @@ k_symbolic_wave(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     wave_traverse<false>(a_col, (const NoVal *)nullptr, a_rp[row], a_rp[row + 1],
                          [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
                          b_col, (const NoVal *)nullptr, s_fc[rl],
-                         [&](const auto &cj, const auto &) { if (!ovf) fresh += lds_count_new_batch<BITS, CAPPED>(keys, cj, ovf); });
+                         [&](const auto &cj, const auto &) { if (!CAPPED || !ovf) fresh += lds_count_new_batch<BITS, CAPPED>(keys, cj, ovf); });
     fresh = group_reduce_sum(fresh, WAVE);
     const bool ovf_any = CAPPED && __ballot(ovf) != 0ull;
     if (sub == 0) nnz_out[row] = ovf_any ? -1 : fresh;
@@ -149,7 +152,7 @@ k_symbolic_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_co
     wg_traverse<THREADS, false>(a_col, (const NoVal *)nullptr, a_rp[row], a_rp[row + 1],
                                 [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
                                 b_col, (const NoVal *)nullptr, s_fc,
-                                [&](const auto &cj, const auto &) { if (!ovf) fresh += lds_count_new_batch<BITS, CAPPED>(s_keys, cj, ovf); });
+                                [&](const auto &cj, const auto &) { if (!CAPPED || !ovf) fresh += lds_count_new_batch<BITS, CAPPED>(s_keys, cj, ovf); });
     fresh = group_reduce_sum(fresh, WAVE);
     if (lane_id() == 0 && fresh) atomicAdd(&s_count, fresh);
     if (CAPPED && ovf) s_ovf = 1;
@@ -164,12 +167,13 @@ constexpr int BM_WIN = 1 << 20;          // columns per window
 constexpr int BM_WORDS = BM_WIN / 32;    // 32768 words = 128 KB
 
 // ONE_WINDOW: B has at most BM_WIN columns, so every column id falls into the one window.
-template <bool ONE_WINDOW>
+// QUERY: a column's bit is read first and set only when it is clear (Section 4.1).
+template <bool ONE_WINDOW, bool QUERY>
 __global__ void __launch_bounds__(BM_THREADS)
 k_symbolic_bitmap(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col,
                   const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_col,
                   const int32_t *__restrict__ rows, int64_t count, int64_t n_cols,
-                  unsigned long long *queue, int32_t *__restrict__ nnz_out, int query_bitmap)
+                  unsigned long long *queue, int32_t *__restrict__ nnz_out)
 {
     __shared__ uint32_t s_bm[BM_WORDS];
     __shared__ WgChunk<NoVal, BM_THREADS> s_fc;
@@ -214,7 +218,7 @@ k_symbolic_bitmap(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ 
             if (cj[u] >= 0 && (ONE_WINDOW || d < (uint32_t)BM_WIN)) {
                 const uint32_t bit = 1u << (d / (uint32_t)BM_WORDS);
                 uint32_t *word = &s_bm[d & (uint32_t)(BM_WORDS - 1)];
-                if (!query_bitmap || !(*word & bit)) atomicOr(word, bit);   // (Section 4.1: query before write)
+                if (!QUERY || !(*word & bit)) atomicOr(word, bit);
             }
         }
     };
@@ -300,14 +304,18 @@ hipError_t launch_symbolic_bin(const Csr &A, const Csr &B, const SymLaunch &l, i
     case SB_S4K: OCEAN_SYM_WG(12, 512); break;
     case SB_S16K: OCEAN_SYM_WG(14, 1024); break;
     case SB_S32K: OCEAN_SYM_WG(15, 1024); break;
-    case SB_BITMAP:
-        if (B.cols <= BM_WIN)
-            hipLaunchKernelGGL(k_symbolic_bitmap<true>, dim3((unsigned)n_wg), dim3(BM_THREADS), 0, s, A.rp, A.col, B.rp,
-                               B.col, l.rows, l.count, B.cols, queue, nnz_out, l.query_bitmap ? 1 : 0);
-        else
-            hipLaunchKernelGGL(k_symbolic_bitmap<false>, dim3((unsigned)n_wg), dim3(BM_THREADS), 0, s, A.rp, A.col, B.rp,
-                               B.col, l.rows, l.count, B.cols, queue, nnz_out, l.query_bitmap ? 1 : 0);
+    case SB_BITMAP: {
+#define OCEAN_SYM_BM(ONE, QUERY)                                                                                  \
+    hipLaunchKernelGGL((k_symbolic_bitmap<ONE, QUERY>), dim3((unsigned)n_wg), dim3(BM_THREADS), 0, s, A.rp, A.col, B.rp,  \
+                       B.col, l.rows, l.count, B.cols, queue, nnz_out)
+        const bool one = B.cols <= BM_WIN;
+        if (one && l.query_bitmap) OCEAN_SYM_BM(true, true);
+        else if (one) OCEAN_SYM_BM(true, false);
+        else if (l.query_bitmap) OCEAN_SYM_BM(false, true);
+        else OCEAN_SYM_BM(false, false);
+#undef OCEAN_SYM_BM
         break;
+    }
     default: return hipErrorInvalidValue;
     }
 #undef OCEAN_SYM_WG

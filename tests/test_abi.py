@@ -58,6 +58,8 @@ def test_defaults_are_the_papers_parameters(ob):
     assert (o.upper_bound_avg_products, o.er_threshold, o.cr_threshold) == (64.0, 8.0, 8.0)      # Table 1
     assert (o.sample_ratio, o.sample_min, o.sample_max) == (0.03, 600, 10000)                      # Section 4.3
     assert o.workflow == ob.WF_AUTO and o.hll_registers == 0 and o.estimate_scale == 1.0
+    assert o.bitmap_query_cr == 2.0 and o.assist_sigmas == 1.0                                      # Section 4.3 / 4.1
+    assert o.selector == ob.SEL_MI355X     # Table 1 with its CR threshold re-derived for this GPU; SEL_TABLE1 = as printed
 
 
 def test_host_helpers_agree_with_the_oracle(ob):

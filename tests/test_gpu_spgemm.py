@@ -156,8 +156,15 @@ def test_spgemm_small(ob, name, wf):
             rows = owf.sample_rows(A.rows, 1)
             cr = owf.sampled_cr(prod[rows].astype(np.float64), ohll.estimate_rows(A, B, m, rows=rows))
             assert st["sampled_cr"] == pytest.approx(cr, rel=1e-9)
-            assert st["workflow"] == {owf.HLL: "hll", owf.SYMBOLIC: "symbolic"}[owf.select_workflow(avg, er, cr)]
+            heavy = int(prod[prod > 4096].sum())          # products of the rows beyond the largest LDS hash table
+            assert st["heavy_products"] == heavy
+            want = owf.select_workflow_tuned(avg, er, cr, float(prod.sum()), float(heavy))
+            assert st["workflow"] == {owf.HLL: "hll", owf.SYMBOLIC: "symbolic"}[want]
             assert st["hll_registers"] == m
+            # Table 1 as printed
+            Cd2, st2 = ob.spgemm(ob.to_device(A), ob.to_device(B), workflow=ob.WF_AUTO, selector=ob.SEL_TABLE1)
+            assert st2["workflow"] == {owf.HLL: "hll", owf.SYMBOLIC: "symbolic"}[owf.select_workflow(avg, er, cr)]
+            check_result(Cd2, ref, A, f"{name}/auto, Table 1 as printed")
 
 
 @pytest.mark.parametrize("scale", [0.25, 0.6])
@@ -202,10 +209,13 @@ def test_full_size_rect_and_clustered(ob, name):
         check_result(Cd, ref, A, f"{name}/{wf}")
         assert st["products"] == int(prod.sum()) and st["nnz_c"] == ref.col_idx.size
         del Cd
-    # AUTO with the selector re-tuned for this GPU: no heavy rows here, so the estimation workflow is chosen
-    Cd, st = ob.spgemm(dA, dB, workflow=ob.WF_AUTO, selector=ob.SEL_MI355X)
+    # AUTO with the selector re-tuned for this GPU (the default): no heavy rows here, so the estimation workflow is
+    # chosen; with Table 1 as printed (CR >= 8) the two-pass workflow
+    Cd, st = ob.spgemm(dA, dB, workflow=ob.WF_AUTO)
     assert st["workflow"] == "hll" and st["heavy_products"] == 0
-    check_result(Cd, ref, A, f"{name}/auto, tuned selector")
+    Cd, st = ob.spgemm(dA, dB, workflow=ob.WF_AUTO, selector=ob.SEL_TABLE1)
+    assert st["workflow"] == "symbolic"
+    check_result(Cd, ref, A, f"{name}/auto, Table 1 as printed")
     del Cd
     _cache.pop((name, False), None)   # the reference of a full-size product is large
 
@@ -582,6 +592,16 @@ def test_compaction_by_entries_long_and_short_rows_mixed(ob, dtype):
                     assert st["overflow_rows"] > 0
                 if wf == "upper_bound":   # reservations never fall short there: always possible in place
                     assert st["compacted_in_place"] == in_place
+
+
+def test_finalize_releases_and_the_library_keeps_working(ob):
+    A, B, ref, prod = workload("er", True)
+    dA, dB = ob.to_device(A), ob.to_device(B)
+    Cd, _ = ob.spgemm(dA, dB)
+    ob.finalize()
+    ob.finalize()                                   # nothing left: still fine
+    Cd, _ = ob.spgemm(dA, dB)                       # buffer and events come back on demand
+    check_result(Cd, ref, A, "after finalize")
 
 
 def test_invalid_arguments_are_rejected(ob):
