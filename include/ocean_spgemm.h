@@ -41,7 +41,10 @@ enum { OCEAN_WF_AUTO = 0, OCEAN_WF_UPPER_BOUND = 1, OCEAN_WF_HLL = 2, OCEAN_WF_S
 /* How AUTO chooses: Table 1 as printed (thresholds from the options), or the same table with the CR
  * threshold re-derived for MI355X from measured compaction and symbolic rates: it slides from
  * tuned_cr_light (all products in rows that fit the LDS key tables) to tuned_cr_heavy (all in rows that
- * outgrow them); problems with fewer than tuned_min_products products keep the printed rule. */
+ * outgrow them); problems with fewer than tuned_min_products products keep the printed rule.  Where that
+ * rule picks the estimation workflow although the sampled CR is below tuned_cr_bound, the upper-bound
+ * workflow runs instead: an estimate with 13 - 18 % error and its expansion factor reserves no less than
+ * the product bound then does, and the bound costs no estimation pass and cannot overflow. */
 enum { OCEAN_SEL_TABLE1 = 0, OCEAN_SEL_MI355X = 1 };
 
 /*
@@ -116,6 +119,7 @@ typedef struct ocean_options {
     double tuned_cr_light;           /* 1.0 */
     double tuned_cr_heavy;           /* 4.5 */
     double tuned_min_products;       /* 4194304 */
+    double tuned_cr_bound;           /* 1.5; 0 = the estimation workflow is never replaced by the upper bound */
     double sort_b_ratio;             /* detector for the throughput-bound case of the accumulators that keep values in
                                         global memory (Section 5.4): when B's rows are unsorted and the rows that
                                         outgrow the LDS hash tables hold at least sort_b_ratio * nnz(B) products, a copy

@@ -580,6 +580,7 @@ void fill_defaults(ocean_options *o)
     o->tuned_cr_light = 1.0;
     o->tuned_cr_heavy = 4.5;
     o->tuned_min_products = 4194304.0;
+    o->tuned_cr_bound = 1.5;
     o->bitmap_query_cr = 2.0;
     o->allocator = nullptr;
 }
@@ -631,7 +632,10 @@ int select_tuned(double avg, double er, double cr, double products, double heavy
     if (products < o.tuned_min_products) return select_of(avg, er, cr, o);
     const double share = products > 0.0 ? heavy_products / products : 0.0;
     const double thr = o.tuned_cr_light + (o.tuned_cr_heavy - o.tuned_cr_light) * share;
-    if (er >= o.er_threshold && cr >= thr) return OCEAN_WF_HLL;
+    // (an estimate is worth its pass, its expansion factor and its retries only if it undercuts the product
+    // bound by more than its own error: below tuned_cr_bound the bound itself is the reservation.  Measured on
+    // the rectangular input, CR 1.03: 2.61 ms against 2.84 ms; on the clustered one, CR 3.3: 5.34 against 5.10 ms)
+    if (er >= o.er_threshold && cr >= thr) return cr < o.tuned_cr_bound ? OCEAN_WF_UPPER_BOUND : OCEAN_WF_HLL;
     return OCEAN_WF_SYMBOLIC;
 }
 

@@ -83,9 +83,13 @@ def test_host_helpers_agree_with_the_oracle(ob):
     assert ob.select_workflow_tuned(100.0, 30.0, 2.74, 4e8, 2e8) == S
     assert ob.select_workflow_tuned(100.0, 7.9, 100.0, 4e8, 0.0) == S          # ER below 8
     assert ob.select_workflow_tuned(100.0, 30.0, 3.2, 1e6, 0.0) == S           # small problem: Table 1 as printed
+    assert ob.select_workflow_tuned(100.0, 30.0, 1.49, 4e8, 0.0) == U          # estimation chosen, CR below 1.5: the bound
+    assert ob.select_workflow_tuned(100.0, 30.0, 1.5, 4e8, 0.0) == H
+    assert ob.select_workflow_tuned(100.0, 30.0, 1.2, 4e8, 4e8) == S           # heavy rows: two passes, whatever the CR
+    assert ob.select_workflow_tuned(100.0, 30.0, 0.99, 4e8, 0.0) == S          # below the light threshold
     for avg in grid:
         for er in grid:
-            for cr in (0.5, 1.0, 2.0, 2.75, 4.5, 8.0):
+            for cr in (0.5, 1.0, 1.499, 1.5, 2.0, 2.75, 4.5, 8.0):
                 for p_, h_ in ((1e3, 0.0), (1e8, 0.0), (1e8, 5e7), (1e8, 1e8)):
                     assert ob.select_workflow_tuned(avg, er, cr, p_, h_) == owf.select_workflow_tuned(avg, er, cr, p_, h_)
     num, sym = ob.bin_layout()

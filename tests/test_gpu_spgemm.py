@@ -159,7 +159,7 @@ def test_spgemm_small(ob, name, wf):
             heavy = int(prod[prod > 4096].sum())          # products of the rows beyond the largest LDS hash table
             assert st["heavy_products"] == heavy
             want = owf.select_workflow_tuned(avg, er, cr, float(prod.sum()), float(heavy))
-            assert st["workflow"] == {owf.HLL: "hll", owf.SYMBOLIC: "symbolic"}[want]
+            assert st["workflow"] == {owf.HLL: "hll", owf.SYMBOLIC: "symbolic", owf.UPPER_BOUND: "upper_bound"}[want]
             assert st["hll_registers"] == m
             # Table 1 as printed
             Cd2, st2 = ob.spgemm(ob.to_device(A), ob.to_device(B), workflow=ob.WF_AUTO, selector=ob.SEL_TABLE1)
@@ -209,10 +209,14 @@ def test_full_size_rect_and_clustered(ob, name):
         check_result(Cd, ref, A, f"{name}/{wf}")
         assert st["products"] == int(prod.sum()) and st["nnz_c"] == ref.col_idx.size
         del Cd
-    # AUTO with the selector re-tuned for this GPU (the default): no heavy rows here, so the estimation workflow is
-    # chosen; with Table 1 as printed (CR >= 8) the two-pass workflow
+    # AUTO with the selector re-tuned for this GPU (the default): no heavy rows here, so the two-pass workflow is
+    # not chosen - estimation on the clustered input (CR 3.3), the product bound on the rectangular one (CR 1.03, where
+    # an estimate cannot undercut the bound); with Table 1 as printed (CR >= 8) the two-pass workflow
     Cd, st = ob.spgemm(dA, dB, workflow=ob.WF_AUTO)
-    assert st["workflow"] == "hll" and st["heavy_products"] == 0
+    assert st["workflow"] == {"clustered": "hll", "rect": "upper_bound"}[name] and st["heavy_products"] == 0
+    Cd, st = ob.spgemm(dA, dB, workflow=ob.WF_AUTO, tuned_cr_bound=0.0)
+    assert st["workflow"] == "hll"
+    check_result(Cd, ref, A, f"{name}/auto without the bound rule")
     Cd, st = ob.spgemm(dA, dB, workflow=ob.WF_AUTO, selector=ob.SEL_TABLE1)
     assert st["workflow"] == "symbolic"
     check_result(Cd, ref, A, f"{name}/auto, Table 1 as printed")
@@ -487,6 +491,26 @@ def _random_case(rng, dtype):
     A = CSR(m, k, a_rp, a_ci, rng.uniform(-1, 1, a_ci.size).astype(dtype))
     B = CSR(k, n, b_rp, b_ci, rng.uniform(-1, 1, b_ci.size).astype(dtype))
     return A, B
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_matrices_with_every_option_combined(ob, seed):
+    """The random cases again with this round's switches in random combinations: assisted symbolic binning with
+    an exaggerated ratio (tables fill up), compaction in place, ESC for short rows, bitmap query, either
+    selector, the throughput detector at ratio 0 / 1, forced hash kernels."""
+    rng = np.random.default_rng(7000 + seed)
+    for case in range(6):
+        dtype = np.float32 if (seed + case) % 2 == 0 else np.float64
+        A, B = _random_case(rng, dtype)
+        ref = O.multiply_rows(A, B)
+        kw = dict(workflow=int(rng.integers(0, 4)), assisted_symbolic=int(rng.integers(0, 3)),
+                  assist_sigmas=float(rng.choice([1.0, -3.0])), compact_in_place=int(rng.integers(-1, 2)),
+                  esc_short_rows=int(rng.integers(0, 2)), bitmap_query=int(rng.integers(-1, 3)),
+                  selector=int(rng.integers(0, 2)), sort_b_ratio=float(rng.choice([0.0, 1.0, 8.0])),
+                  force_hash_kernels=int(rng.integers(0, 2)), estimate_scale=float(rng.choice([1.0, 0.5])))
+        print(f"combined case seed={seed} case={case} {A.rows}x{A.cols}x{B.cols} nnzA={A.nnz} nnzB={B.nnz} {kw}", flush=True)
+        Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(B), **kw)
+        check_result(Cd, ref, A, f"combined seed={seed} case={case}")
 
 
 @pytest.mark.parametrize("seed", range(12))
