@@ -120,6 +120,9 @@ typedef struct ocean_options {
     double tuned_cr_heavy;           /* 4.5 */
     double tuned_min_products;       /* 4194304 */
     double tuned_cr_bound;           /* 1.5; 0 = the estimation workflow is never replaced by the upper bound */
+    double bound_load_coef;          /* upper-bound workflow: table slots per intermediate product of the row.  1.15:
+                                        a row whose products are all distinct would otherwise fill its table to the
+                                        last slot (64 products in 64 slots measured twice as slow as in 256) */
     double sort_b_ratio;             /* detector for the throughput-bound case of the accumulators that keep values in
                                         global memory (Section 5.4): when B's rows are unsorted and the rows that
                                         outgrow the LDS hash tables hold at least sort_b_ratio * nnz(B) products, a copy

@@ -245,7 +245,7 @@ hipError_t launch_row_products(const Csr &A, const int64_t *b_rp, int64_t b_rows
     const int64_t heavy_from = kNumericSlots[NB_S4K];   // beyond the largest LDS hash table that sorted inputs use
     if (A.rows == 0) return hipSuccess;
     const double avg = A.rows ? (double)A.nnz / (double)A.rows : 0.0;
-    const int g_log2 = ilog2_ceil(avg, 1, 6);
+    const int g_log2 = ilog2_ceil(avg / 4.0, 1, 6);   // (a lane keeps four entries in flight)
     const int R = TPB >> g_log2;
     int64_t blocks = (A.rows + R - 1) / R;
     if (blocks > 2048) blocks = 2048;
@@ -332,11 +332,14 @@ k_hll_sketch(const int64_t *__restrict__ rp, const int32_t *__restrict__ col, in
     }
 }
 
-hipError_t launch_hll_sketch(const Csr &B, int m, uint8_t *sketches, hipStream_t s)
+// lanes_div: 1, or 4 when the rows are known to be of similar lengths - a lane keeps four entries in flight, so a
+// quarter of the lanes per row puts four times the rows in flight (short rows are bound by the latency of their
+// chain of loads); with skewed lengths the long rows then keep their few lanes busy long after the others.
+hipError_t launch_hll_sketch(const Csr &B, int m, uint8_t *sketches, int lanes_div, hipStream_t s)
 {
     if (B.rows == 0) return hipSuccess;
     const double avg = (double)B.nnz / (double)B.rows;
-    const int g_log2 = ilog2_ceil(avg, 3, 6);
+    const int g_log2 = ilog2_ceil(avg / (double)lanes_div, 3, 6);
     const int R = TPB >> g_log2;
     int64_t blocks = (B.rows + R - 1) / R;
     if (blocks > 256 * 64) blocks = 256 * 64;
@@ -449,12 +452,12 @@ k_hll_merge(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col,
 
 hipError_t launch_hll_merge(const Csr &A, const uint8_t *sketches, int m, const int64_t *rows, int64_t n_rows,
                             const int64_t *prod, const int32_t *maxb, const int64_t *b_rp, int64_t b_cols,
-                            double *est, uint8_t *merged, hipStream_t s)
+                            double *est, uint8_t *merged, int lanes_div, hipStream_t s)
 {
     if (n_rows == 0) return hipSuccess;
     const int L = m / 8;
     const double avg = A.rows ? (double)A.nnz / (double)A.rows : 1.0;
-    int g_log2 = ilog2_ceil(avg * L, 0, 6);
+    int g_log2 = ilog2_ceil(avg * L / (double)lanes_div, 0, 6);   // (lanes_div: see launch_hll_sketch)
     while ((1 << g_log2) < L) ++g_log2;
     const int64_t threads = n_rows << g_log2;
     const int64_t blocks = (threads + TPB - 1) / TPB;
@@ -469,31 +472,67 @@ hipError_t launch_hll_merge(const Csr &A, const uint8_t *sketches, int m, const 
     return hipGetLastError();
 }
 
+// ----------------------------------------------------------- sample rows
+// The stratified sample of Section 3.2 (one row out of each of ns equal strata, chosen by a hash of the
+// stratum's number and the seed), written on the device: the same rows as the host helper behind
+// ocean_sample_rows gives.
+__global__ void __launch_bounds__(TPB)
+k_sample_rows(int64_t rows, int64_t ns, uint32_t seed, int64_t *__restrict__ out)
+{
+    const int64_t t = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (t >= ns) return;
+    const int64_t lo = (int64_t)((unsigned __int128)t * (unsigned __int128)rows / (unsigned __int128)ns);
+    const int64_t hi = (int64_t)((unsigned __int128)(t + 1) * (unsigned __int128)rows / (unsigned __int128)ns);
+    const uint32_t h = fmix32(seed + 0x9E3779B9u * (uint32_t)(t + 1));
+    out[t] = lo + (int64_t)(h % (uint64_t)(hi - lo));
+}
+
+hipError_t launch_sample_rows(int64_t rows, int64_t ns, uint32_t seed, int64_t *out, hipStream_t s)
+{
+    if (ns <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_sample_rows, dim3((unsigned)((ns + TPB - 1) / TPB)), dim3(TPB), 0, s, rows, ns, seed, out);
+    return hipGetLastError();
+}
+
 // --------------------------------------------------------- sample reduce
 // Sums over the sampled rows in a fixed order (one workgroup, strided partial
 // sums, tree reduction), so the sampled CR is the same on every run.
 // out[0] = sum of products, out[1] = sum of estimates (their ratio is the sampled CR, Section 3.2);
 // out[2], out[3] = sum and sum of squares of the per-row ratios products / estimate, out[4] = rows counted
 // (mean and standard deviation of the compression ratio over the sample, Section 4.1).
-__global__ void __launch_bounds__(TPB)
+constexpr int SR_THREADS = 1024;
+__global__ void __launch_bounds__(SR_THREADS)
 k_sample_reduce(const int64_t *__restrict__ rows, int64_t n_rows, const int64_t *__restrict__ prod,
                 const double *__restrict__ est, double *out)
 {
     constexpr int NS = 5;
-    __shared__ double s_acc[NS][TPB];
+    __shared__ double s_acc[NS][SR_THREADS];
     double acc[NS] = {0.0, 0.0, 0.0, 0.0, 0.0};
-    for (int64_t t = threadIdx.x; t < n_rows; t += TPB) {
-        const double e = est[t];
-        if (e > 0.0) {
-            const double p = (double)prod[rows[t]];
-            const double r = p / e;
-            acc[0] += p; acc[1] += e; acc[2] += r; acc[3] += r * r; acc[4] += 1.0;
+    // four sampled rows per thread and turn, their dependent loads (row id -> products) issued together
+    for (int64_t t0 = threadIdx.x; t0 < n_rows; t0 += 4 * SR_THREADS) {
+        double e[4];
+        int64_t r[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int64_t t = t0 + (int64_t)i * SR_THREADS;
+            e[i] = t < n_rows ? est[t] : 0.0;
+            r[i] = rows[t < n_rows ? t : t0];
+        }
+        double p[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) p[i] = (double)prod[r[i]];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (e[i] > 0.0) {
+                const double q = p[i] / e[i];
+                acc[0] += p[i]; acc[1] += e[i]; acc[2] += q; acc[3] += q * q; acc[4] += 1.0;
+            }
         }
     }
 #pragma unroll
     for (int k = 0; k < NS; ++k) s_acc[k][threadIdx.x] = acc[k];
     __syncthreads();
-    for (int off = TPB / 2; off > 0; off >>= 1) {
+    for (int off = SR_THREADS / 2; off > 0; off >>= 1) {
         if ((int)threadIdx.x < off) {
 #pragma unroll
             for (int k = 0; k < NS; ++k) s_acc[k][threadIdx.x] += s_acc[k][threadIdx.x + off];
@@ -506,7 +545,7 @@ k_sample_reduce(const int64_t *__restrict__ rows, int64_t n_rows, const int64_t 
 hipError_t launch_sample_reduce(const int64_t *rows, int64_t n_rows, const int64_t *prod, const double *est,
                                 double *out, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_sample_reduce, dim3(1), dim3(TPB), 0, s, rows, n_rows, prod, est, out);
+    hipLaunchKernelGGL(k_sample_reduce, dim3(1), dim3(SR_THREADS), 0, s, rows, n_rows, prod, est, out);
     return hipGetLastError();
 }
 

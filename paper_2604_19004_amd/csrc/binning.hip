@@ -13,7 +13,7 @@ struct BinTable {
 };
 
 // need = table slots the row asks for, cap = output entries reserved for it.
-//   mode 0  upper bound: both are ub = min(prod, n)               (Section 3.2, upper-bound workflow)
+//   mode 0  upper bound: cap = ub = min(prod, n), need = ceil(coef * ub)   (Section 3.2, upper-bound workflow)
 //   mode 1  estimate:    ceil(coef * scale * est), limited to ub  (Section 5.3: estimate x coefficient)
 //   mode 2  exact:       cap = nnz, need = ceil(coef * nnz) limited to ub   (two-pass workflow)
 //   mode 3  symbolic:    need = ceil(1.25 * e), no capacity; e = ub, or with assisted binning (coef > 1,
@@ -41,7 +41,8 @@ k_classify(int64_t m, int mode, double coef, double scale, BinTable bt, int64_t 
         if (active && ub > 0) {
             long long need;
             if (mode == 0) {
-                need = ub; c = ub;
+                c = ub;
+                need = coef > 1.0 ? (long long)ceil(coef * (double)ub) : ub;
             } else if (mode == 1) {
                 double want = ceil(coef * scale * est[i]);
                 need = want >= (double)ub ? ub : (long long)want;

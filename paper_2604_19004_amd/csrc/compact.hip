@@ -36,9 +36,22 @@ k_compact(int64_t m, int g_log2, const int64_t *__restrict__ c_rp, const int32_t
 #pragma unroll
         for (int i = 0; i < 8; ++i) { c_col[dst + t + (int64_t)i * G] = cc[i]; c_val[dst + t + (int64_t)i * G] = vv[i]; }
     }
-    for (; t < n; t += G) {
-        c_col[dst + t] = sc[src + t];
-        c_val[dst + t] = sv[src + t];
+    // the rest four at a time, loads before stores: a short row is all "rest", and one load per lane in flight
+    // left the copy of a matrix of short rows bound by latency
+    for (; t < n; t += 4 * (int64_t)G) {
+        int32_t cc[4];
+        V vv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int64_t u = t + (int64_t)i * G;
+            cc[i] = 0; vv[i] = V();
+            if (u < n) { cc[i] = sc[src + u]; vv[i] = sv[src + u]; }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int64_t u = t + (int64_t)i * G;
+            if (u < n) { c_col[dst + u] = cc[i]; c_val[dst + u] = vv[i]; }
+        }
     }
 }
 

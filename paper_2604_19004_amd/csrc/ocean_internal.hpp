@@ -188,10 +188,11 @@ hipError_t launch_row_products(const Csr &A, const int64_t *b_rp, int64_t b_rows
                                unsigned long long *totals, int32_t *flags, int32_t *long_rows,
                                unsigned long long *long_count, hipStream_t s);
 hipError_t launch_publish_totals(const unsigned long long *totals, const int32_t *flags, int64_t *out, hipStream_t s);
-hipError_t launch_hll_sketch(const Csr &B, int m, uint8_t *sketches, hipStream_t s);
+hipError_t launch_hll_sketch(const Csr &B, int m, uint8_t *sketches, int lanes_div, hipStream_t s);
 hipError_t launch_hll_merge(const Csr &A, const uint8_t *sketches, int m, const int64_t *rows, int64_t n_rows,
                             const int64_t *prod, const int32_t *maxb, const int64_t *b_rp, int64_t b_cols,
-                            double *est, uint8_t *merged, hipStream_t s);
+                            double *est, uint8_t *merged, int lanes_div, hipStream_t s);
+hipError_t launch_sample_rows(int64_t rows, int64_t ns, uint32_t seed, int64_t *out, hipStream_t s);
 hipError_t launch_sample_reduce(const int64_t *rows, int64_t n_rows, const int64_t *prod, const double *est,
                                 double *out /*[5]: sum prod, sum est, sum cr, sum cr^2, rows*/, hipStream_t s);
 
