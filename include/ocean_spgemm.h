@@ -41,7 +41,8 @@ enum { OCEAN_WF_AUTO = 0, OCEAN_WF_UPPER_BOUND = 1, OCEAN_WF_HLL = 2, OCEAN_WF_S
 /* How AUTO chooses: Table 1 as printed (thresholds from the options), or the same table with the CR
  * threshold re-derived for MI355X from measured compaction and symbolic rates: it slides from
  * tuned_cr_light (all products in rows that fit the LDS key tables) to tuned_cr_heavy (all in rows that
- * outgrow them); problems with fewer than tuned_min_products products keep the printed rule.  Where that
+ * outgrow them); problems with fewer than tuned_min_products products run the two-pass workflow without
+ * sketching or sampling (no sampled CR in the statistics then).  Where that
  * rule picks the estimation workflow although the sampled CR is below tuned_cr_bound, the upper-bound
  * workflow runs instead: an estimate with 13 - 18 % error and its expansion factor reserves no less than
  * the product bound then does, and the bound costs no estimation pass and cannot overflow. */

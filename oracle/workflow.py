@@ -90,13 +90,14 @@ def select_workflow_tuned(avg_products: float, er: float, cr: float, products: f
                           cr_bound: float = 1.5) -> int:
     """Table 1 with the CR threshold re-derived for one GPU (not in the paper; Section 4.3 says the 8 was chosen
     empirically to amortize compaction): the threshold slides linearly from cr_light to cr_heavy with the
-    share of the products held by rows that outgrow the on-chip hash tables; small problems keep Table 1.
+    share of the products held by rows that outgrow the on-chip hash tables; small problems take the two-pass
+    workflow whatever the ratios (no sample is taken for them).
     Where the estimation workflow would be chosen at a CR below cr_bound, the upper-bound workflow is: the
     product bound is then as tight a reservation as an estimate with its expansion factor."""
     if avg_products < 64.0:
         return UPPER_BOUND
     if products < min_products:
-        return select_workflow(avg_products, er, cr)
+        return SYMBOLIC
     share = heavy_products / products if products > 0 else 0.0
     thr = cr_light + (cr_heavy - cr_light) * share
     if er >= 8.0 and cr >= thr:

@@ -633,12 +633,12 @@ int select_of(double avg, double er, double cr, const ocean_options &o)
 // Rows that fit the LDS key tables are counted at r_sym = 140 - 290 G products/s (break-even CR about 1),
 // rows that outgrow them go through the bitmap kernel at about 960 G products/s (break-even CR 4 - 5).
 // So the threshold slides between the two with the share of the products that heavy rows hold.  Small
-// problems keep the paper's rule: below tuned_min_products the extra launches of the estimation path cost
-// more than either pass.
+// problems (below tuned_min_products) run the two-pass workflow unsampled: there the sketches and the sample
+// cost more than any choice between the workflows can gain (4096 rows of 8 entries: 0.29 ms sampled, 0.24 ms not).
 int select_tuned(double avg, double er, double cr, double products, double heavy_products, const ocean_options &o)
 {
     if (avg < o.upper_bound_avg_products) return OCEAN_WF_UPPER_BOUND;
-    if (products < o.tuned_min_products) return select_of(avg, er, cr, o);
+    if (products < o.tuned_min_products) return OCEAN_WF_SYMBOLIC;
     const double share = products > 0.0 ? heavy_products / products : 0.0;
     const double thr = o.tuned_cr_light + (o.tuned_cr_heavy - o.tuned_cr_light) * share;
     // (an estimate is worth its pass, its expansion factor and its retries only if it undercuts the product
@@ -719,6 +719,8 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
     if (workflow == OCEAN_WF_AUTO) {
         if (S->avg_products < o.upper_bound_avg_products) {
             workflow = OCEAN_WF_UPPER_BOUND;
+        } else if (o.selector == OCEAN_SEL_MI355X && (double)P < o.tuned_min_products) {
+            workflow = OCEAN_WF_SYMBOLIC;   // (no sample taken: see select_tuned)
         } else {
             OC_TRY(build_sketches());
             OC_TRY(mark(c, OCEAN_ST_SAMPLE));

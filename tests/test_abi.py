@@ -82,7 +82,8 @@ def test_host_helpers_agree_with_the_oracle(ob):
     assert ob.select_workflow_tuned(100.0, 30.0, 2.75, 4e8, 2e8) == H          # half and half: threshold 2.75
     assert ob.select_workflow_tuned(100.0, 30.0, 2.74, 4e8, 2e8) == S
     assert ob.select_workflow_tuned(100.0, 7.9, 100.0, 4e8, 0.0) == S          # ER below 8
-    assert ob.select_workflow_tuned(100.0, 30.0, 3.2, 1e6, 0.0) == S           # small problem: Table 1 as printed
+    assert ob.select_workflow_tuned(100.0, 30.0, 3.2, 1e6, 0.0) == S           # small problem: two passes, unsampled
+    assert ob.select_workflow_tuned(100.0, 30.0, 100.0, 1e6, 0.0) == S
     assert ob.select_workflow_tuned(100.0, 30.0, 1.49, 4e8, 0.0) == U          # estimation chosen, CR below 1.5: the bound
     assert ob.select_workflow_tuned(100.0, 30.0, 1.5, 4e8, 0.0) == H
     assert ob.select_workflow_tuned(100.0, 30.0, 1.2, 4e8, 4e8) == S           # heavy rows: two passes, whatever the CR

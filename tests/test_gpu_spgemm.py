@@ -155,14 +155,21 @@ def test_spgemm_small(ob, name, wf):
             m = owf.hll_registers(er)
             rows = owf.sample_rows(A.rows, 1)
             cr = owf.sampled_cr(prod[rows].astype(np.float64), ohll.estimate_rows(A, B, m, rows=rows))
-            assert st["sampled_cr"] == pytest.approx(cr, rel=1e-9)
             heavy = int(prod[prod > 4096].sum())          # products of the rows beyond the largest LDS hash table
             assert st["heavy_products"] == heavy
             want = owf.select_workflow_tuned(avg, er, cr, float(prod.sum()), float(heavy))
             assert st["workflow"] == {owf.HLL: "hll", owf.SYMBOLIC: "symbolic", owf.UPPER_BOUND: "upper_bound"}[want]
-            assert st["hll_registers"] == m
+            if prod.sum() < 4194304:      # small problem: the tuned selector takes no sample
+                assert st["sampled_rows"] == 0 and st["workflow"] == "symbolic"
+            # the same with the small-problem shortcut off: the sample must be the oracle's
+            Cd1, st1 = ob.spgemm(ob.to_device(A), ob.to_device(B), workflow=ob.WF_AUTO, tuned_min_products=0.0)
+            assert st1["sampled_cr"] == pytest.approx(cr, rel=1e-9) and st1["hll_registers"] == m
+            want1 = owf.select_workflow_tuned(avg, er, cr, float(prod.sum()), float(heavy), min_products=0.0)
+            assert st1["workflow"] == {owf.HLL: "hll", owf.SYMBOLIC: "symbolic", owf.UPPER_BOUND: "upper_bound"}[want1]
+            check_result(Cd1, ref, A, f"{name}/auto, sampled")
             # Table 1 as printed
             Cd2, st2 = ob.spgemm(ob.to_device(A), ob.to_device(B), workflow=ob.WF_AUTO, selector=ob.SEL_TABLE1)
+            assert st2["sampled_cr"] == pytest.approx(cr, rel=1e-9)
             assert st2["workflow"] == {owf.HLL: "hll", owf.SYMBOLIC: "symbolic"}[owf.select_workflow(avg, er, cr)]
             check_result(Cd2, ref, A, f"{name}/auto, Table 1 as printed")
 
