@@ -78,7 +78,8 @@ typedef struct ocean_allocator {
     void (*release)(void *ctx, void *ptr);
 } ocean_allocator;
 
-/* Parameters; ocean_default_options fills in the paper's values (Section 4.3, Table 1). */
+/* Parameters; ocean_default_options fills in the paper's values (Section 4.3, Table 1) and, for what the paper
+ * tuned empirically on its own GPU or leaves to the implementation, the values measured on MI355X. */
 typedef struct ocean_options {
     int32_t workflow;                /* OCEAN_WF_*; AUTO = Table 1 */
     int32_t hll_registers;           /* 0 = 32 if ER < 48 else 64 (Section 4.3); or 32 / 64 / 128 */
