@@ -535,6 +535,46 @@ def test_random_matrices(ob, seed):
 
 
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_column_ids_up_to_the_int32_limit(ob, dtype):
+    """B with 2^31 - 1 columns and entries from column 0 to column 2^31 - 2.  The oracle's dense accumulator cannot
+    hold such a row, so the expected result comes from a relabelling: the structure of A*B does not depend on what
+    the columns of B are called, only on their order - the oracle multiplies the same matrices with B's columns
+    numbered 0 .. 59999, and C must be that result with every column id mapped back through the (increasing) map."""
+    rng = np.random.default_rng(77)
+    m, k, ns, nbig = 300, 400, 60000, 2 ** 31 - 1
+    phi = np.sort(rng.choice(nbig - 2, ns - 2, replace=False).astype(np.int64) + 1)
+    phi = np.concatenate([[0], phi, [nbig - 1]])                      # strictly increasing, both ends used
+    blen = rng.geometric(0.02, k) - 1
+    blen[rng.integers(0, k, 6)] = rng.integers(20000, ns + 1, 6)      # a few rows of B that cover most columns
+    blen = np.minimum(blen, ns)
+    b_rp = np.concatenate([[0], np.cumsum(blen)]).astype(np.int64)
+    b_ci = np.concatenate([np.sort(rng.choice(ns, int(l), replace=False)) for l in blen]).astype(np.int32)
+    alen = rng.geometric(0.1, m) - 1
+    alen[:3] = [k, k // 2, 150]                                        # rows beyond every LDS hash table
+    alen = np.minimum(alen, k)
+    a_rp = np.concatenate([[0], np.cumsum(alen)]).astype(np.int64)
+    a_ci = np.concatenate([np.sort(rng.choice(k, int(l), replace=False)) for l in alen]).astype(np.int32)
+    A = CSR(m, k, a_rp, a_ci, rng.uniform(-1, 1, a_ci.size).astype(dtype))
+    vb = rng.uniform(-1, 1, b_ci.size).astype(dtype)
+    Bs = CSR(k, ns, b_rp, b_ci, vb)
+    Bb = CSR(k, nbig, b_rp, phi[b_ci].astype(np.int32), vb)
+    assert Bb.col_idx.min() == 0 and Bb.col_idx.max() == nbig - 1
+    ref = O.multiply_rows(A, Bs)
+    want_cols = phi[ref.col_idx].astype(np.int32)
+    tol = 1e-12 if dtype == np.float64 else 1e-5
+    for wf in ("auto", "symbolic", "hll", "upper_bound"):
+        print(f"wide columns {np.dtype(dtype).name}/{wf}", flush=True)
+        Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(Bb), workflow=wf_id(ob, wf))
+        assert Cd.cols == nbig
+        assert np.array_equal(Cd.row_ptr.cpu().numpy(), ref.row_ptr), wf
+        assert np.array_equal(Cd.col_idx.cpu().numpy()[:ref.col_idx.size], want_cols), wf
+        err = np.abs(Cd.val.cpu().numpy()[:ref.col_idx.size].astype(np.float64) - ref.val)
+        assert np.all(err <= tol * ref.absval), wf
+        nb = len(ob.bin_layout()[0])
+        assert st["rows_per_bin"][nb - 1] + st["rows_per_bin"][nb - 2] >= 2     # the global-memory kernels ran
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
 @pytest.mark.parametrize("seed", [0, 1, 2])
 def test_esc_short_rows(ob, seed, dtype):
     """Expand-sort-compress accumulators (Section 3.3: short rows of the upper-bound workflow, 2 or 4 rows per
