@@ -687,6 +687,25 @@ def test_invalid_arguments_are_rejected(ob):
         ob.spgemm(ob.to_device(B), ob.to_device(_csr(2, 2, [0, 1, 2], [0, 1], [1., 1.], np.float32)))   # dtype mix
 
 
+def test_a_row_with_2_to_the_31_products_is_rejected(ob):
+    """The documented limit: the products of one row are numbered in 32 bits.  One row of A with 70 000 entries, all
+    in the same column (duplicates are legal), times a row of B with 32 768 entries is 2.29e9 products; the same
+    with 65 000 entries (2.13e9 < 2^31) is computed, and is 65 000 times the row of B."""
+    nb = 32768
+    B = _csr(1, nb, [0, nb], list(range(nb)), np.ones(nb))
+    A = _csr(1, 1, [0, 70000], [0] * 70000, np.ones(70000))
+    with pytest.raises(ob.OceanError) as e:
+        ob.spgemm(ob.to_device(A), ob.to_device(B))
+    assert e.value.code == 1 and "2^31" in str(e.value)
+    A = _csr(1, 1, [0, 65000], [0] * 65000, np.ones(65000))
+    for wf in ("auto", "upper_bound"):
+        Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(B), workflow=wf_id(ob, wf))
+        assert st["products"] == 65000 * nb and st["nnz_c"] == nb
+        assert np.array_equal(Cd.row_ptr.cpu().numpy(), [0, nb])
+        assert np.array_equal(Cd.col_idx.cpu().numpy()[:nb], np.arange(nb))
+        assert np.array_equal(Cd.val.cpu().numpy()[:nb], np.full(nb, 65000.0))     # sums of ones: exact
+
+
 @pytest.mark.parametrize("bad_rp", [[0, 3, 2], [0, 1, 9], [0, -1, 2]])
 def test_malformed_row_offsets_are_rejected(ob, bad_rp):
     """Row offsets of A that descend, go negative or point beyond nnz: the kernels that run before the host
