@@ -125,6 +125,10 @@ typedef struct ocean_options {
     double bound_load_coef;          /* upper-bound workflow: table slots per intermediate product of the row.  1.15:
                                         a row whose products are all distinct would otherwise fill its table to the
                                         last slot (64 products in 64 slots measured twice as slow as in 256) */
+    double estimate_table_coef;      /* estimation workflow: accumulator slots per estimated entry where that is less
+                                        than the expansion factor (which still sizes the reserved output).  1.75: with
+                                        32 registers the factor 2.0 sends a quarter of the rows of a 234-entries-per-row
+                                        input to tables twice the size they need; 0 = the expansion factor itself */
     double sort_b_ratio;             /* detector for the throughput-bound case of the accumulators that keep values in
                                         global memory (Section 5.4): when B's rows are unsorted and the rows that
                                         outgrow the LDS hash tables hold at least sort_b_ratio * nnz(B) products, a copy

@@ -45,7 +45,7 @@ class ocean_options(C.Structure):
                 ("assist_sigmas", C.c_double), ("bitmap_query", C.c_int32), ("esc_short_rows", C.c_int32),
                 ("bitmap_query_cr", C.c_double), ("selector", C.c_int32), ("compact_in_place", C.c_int32),
                 ("tuned_cr_light", C.c_double), ("tuned_cr_heavy", C.c_double), ("tuned_min_products", C.c_double),
-                ("tuned_cr_bound", C.c_double), ("bound_load_coef", C.c_double), ("sort_b_ratio", C.c_double),
+                ("tuned_cr_bound", C.c_double), ("bound_load_coef", C.c_double), ("estimate_table_coef", C.c_double), ("sort_b_ratio", C.c_double),
                 ("allocator", C.POINTER(ocean_allocator))]
 
 

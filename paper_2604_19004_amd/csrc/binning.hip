@@ -14,13 +14,14 @@ struct BinTable {
 
 // need = table slots the row asks for, cap = output entries reserved for it.
 //   mode 0  upper bound: cap = ub = min(prod, n), need = ceil(coef * ub)   (Section 3.2, upper-bound workflow)
-//   mode 1  estimate:    ceil(coef * scale * est), limited to ub  (Section 5.3: estimate x coefficient)
+//   mode 1  estimate:    cap = ceil(coef * scale * est), need = ceil(table_coef * scale * est), both limited to ub
+//                        (Section 5.3: estimate x coefficient; table_coef <= coef)
 //   mode 2  exact:       cap = nnz, need = ceil(coef * nnz) limited to ub   (two-pass workflow)
 //   mode 3  symbolic:    need = ceil(1.25 * e), no capacity; e = ub, or with assisted binning (coef > 1,
 //                        Section 4.1) ceil(prod / coef) kept inside [longest referenced row of B, ub]
 // max_cap receives the largest capacity among the rows of the last (global-memory) bin.
 __global__ void __launch_bounds__(TPB)
-k_classify(int64_t m, int mode, double coef, double scale, BinTable bt, int64_t n_cols,
+k_classify(int64_t m, int mode, double coef, double table_coef, double scale, BinTable bt, int64_t n_cols,
            const int64_t *__restrict__ prod, const double *__restrict__ est, const int32_t *__restrict__ nnz_exact,
            const int32_t *__restrict__ row_mask, const int32_t *__restrict__ lower_bound,
            uint8_t *__restrict__ bin_of_row, int32_t *__restrict__ cap,
@@ -45,9 +46,11 @@ k_classify(int64_t m, int mode, double coef, double scale, BinTable bt, int64_t 
                 need = coef > 1.0 ? (long long)ceil(coef * (double)ub) : ub;
             } else if (mode == 1) {
                 double want = ceil(coef * scale * est[i]);
-                need = want >= (double)ub ? ub : (long long)want;
+                c = want >= (double)ub ? ub : (long long)want;
+                if (c < 1) c = 1;
+                double slots = ceil(table_coef * scale * est[i]);
+                need = slots >= (double)ub ? ub : (long long)slots;
                 if (need < 1) need = 1;
-                c = need;
             } else if (mode == 2) {
                 c = nnz_exact[i];
                 double want = ceil(coef * (double)c);
@@ -91,7 +94,7 @@ hipError_t launch_classify(int64_t m, const BinParams &p, double scale, const in
     for (int b = 0; b < OCEAN_MAX_BINS; ++b) bt.slots[b] = b < p.n_bins ? p.slots[b] : 0;
     int64_t blocks = (m + TPB - 1) / TPB;
     if (blocks > 1024) blocks = 1024;   // one set of atomics per workgroup: keep the workgroups few
-    hipLaunchKernelGGL(k_classify, dim3((unsigned)blocks), dim3(TPB), 0, s, m, p.mode, p.coef, scale, bt, p.n_cols,
+    hipLaunchKernelGGL(k_classify, dim3((unsigned)blocks), dim3(TPB), 0, s, m, p.mode, p.coef, (p.table_coef > 0.0 && p.table_coef < p.coef) ? p.table_coef : p.coef, scale, bt, p.n_cols,
                        prod, est, nnz_exact, row_mask, lower_bound, bin_of_row, cap, bin_count, bin_prod, max_cap);
     return hipGetLastError();
 }

@@ -581,6 +581,7 @@ void fill_defaults(ocean_options *o)
     o->tuned_min_products = 4194304.0;
     o->tuned_cr_bound = 1.5;
     o->bound_load_coef = 1.15;
+    o->estimate_table_coef = 1.75;
     o->bitmap_query_cr = 2.0;
     o->allocator = nullptr;
 }
@@ -761,6 +762,7 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
             HIP_TRY(launch_hll_merge(A, sketches, m_regs, nullptr, m, w.prod, w.maxb, nullptr, n, w.est, nullptr, c.lanes_div, c.s));
             bp.mode = 1;
             bp.coef = o.expand_coef > 0.0 ? o.expand_coef : (m_regs == 32 ? 2.0 : 1.5);
+            bp.table_coef = o.estimate_table_coef;
         } else if (workflow == OCEAN_WF_SYMBOLIC) {
             S->assist_cr = o.assisted_symbolic ? conservative_cr(S, o) : 1.0;
             if (!(S->assist_cr > 1.0)) S->assist_cr = 0.0;

@@ -201,6 +201,8 @@ struct BinParams {
     int mode;            // 0 upper bound, 1 estimate, 2 exact nnz, 3 symbolic pass (see k_classify)
     double coef;         // table slots per predicted entry; mode 3: the compression ratio the product counts
                          // are divided by (assisted symbolic binning, Section 4.1), 1.0 = plain product counts
+    double table_coef;   // mode 1: table slots per estimated entry when smaller than coef (0: coef itself); the
+                         // reserved output stays coef x estimate
     int n_bins;
     int32_t slots[OCEAN_MAX_BINS];
     int64_t n_cols;
