@@ -122,9 +122,10 @@ typedef struct ocean_options {
     double tuned_cr_heavy;           /* 4.5 */
     double tuned_min_products;       /* 4194304 */
     double tuned_cr_bound;           /* 1.5; 0 = the estimation workflow is never replaced by the upper bound */
-    double bound_load_coef;          /* upper-bound workflow: table slots per intermediate product of the row.  1.15:
-                                        a row whose products are all distinct would otherwise fill its table to the
-                                        last slot (64 products in 64 slots measured twice as slow as in 256) */
+    double bound_load_coef;          /* table slots per intermediate product of the row: what the upper-bound workflow asks
+                                        for, and the most any workflow asks for (more slots than products are of no
+                                        use).  1.15: with 1.0 a row whose products are all distinct fills its table to
+                                        the last slot (64 products in 64 slots measured twice as slow as in 256) */
     double estimate_table_coef;      /* estimation workflow: accumulator slots per estimated entry where that is less
                                         than the expansion factor (which still sizes the reserved output).  1.75: with
                                         32 registers the factor 2.0 sends a quarter of the rows of a 234-entries-per-row

@@ -13,7 +13,8 @@ struct BinTable {
 };
 
 // need = table slots the row asks for, cap = output entries reserved for it.
-//   mode 0  upper bound: cap = ub = min(prod, n), need = ceil(coef * ub)   (Section 3.2, upper-bound workflow)
+//   mode 0  upper bound: cap = ub = min(prod, n), need = ceil(bound_coef * ub)   (Section 3.2, upper-bound workflow)
+//   (in modes 1 and 2 the table is limited to ceil(bound_coef * ub) slots as well: more cannot be of use)
 //   mode 1  estimate:    cap = ceil(coef * scale * est), need = ceil(table_coef * scale * est), both limited to ub
 //                        (Section 5.3: estimate x coefficient; table_coef <= coef)
 //   mode 2  exact:       cap = nnz, need = ceil(coef * nnz) limited to ub   (two-pass workflow)
@@ -21,7 +22,7 @@ struct BinTable {
 //                        Section 4.1) ceil(prod / coef) kept inside [longest referenced row of B, ub]
 // max_cap receives the largest capacity among the rows of the last (global-memory) bin.
 __global__ void __launch_bounds__(TPB)
-k_classify(int64_t m, int mode, double coef, double table_coef, double scale, BinTable bt, int64_t n_cols,
+k_classify(int64_t m, int mode, double coef, double table_coef, double bound_coef, double scale, BinTable bt, int64_t n_cols,
            const int64_t *__restrict__ prod, const double *__restrict__ est, const int32_t *__restrict__ nnz_exact,
            const int32_t *__restrict__ row_mask, const int32_t *__restrict__ lower_bound,
            uint8_t *__restrict__ bin_of_row, int32_t *__restrict__ cap,
@@ -41,20 +42,22 @@ k_classify(int64_t m, int mode, double coef, double table_coef, double scale, Bi
         const long long ub = pr < n_cols ? pr : n_cols;
         if (active && ub > 0) {
             long long need;
+            // the most slots a row can make use of: its bound with the load factor of bound-sized tables
+            const long long ub_slots = bound_coef > 1.0 ? (long long)ceil(bound_coef * (double)ub) : ub;
             if (mode == 0) {
                 c = ub;
-                need = coef > 1.0 ? (long long)ceil(coef * (double)ub) : ub;
+                need = ub_slots;
             } else if (mode == 1) {
                 double want = ceil(coef * scale * est[i]);
                 c = want >= (double)ub ? ub : (long long)want;
                 if (c < 1) c = 1;
                 double slots = ceil(table_coef * scale * est[i]);
-                need = slots >= (double)ub ? ub : (long long)slots;
+                need = slots >= (double)ub_slots ? ub_slots : (long long)slots;
                 if (need < 1) need = 1;
             } else if (mode == 2) {
                 c = nnz_exact[i];
                 double want = ceil(coef * (double)c);
-                need = want >= (double)ub ? ub : (long long)want;
+                need = want >= (double)ub_slots ? ub_slots : (long long)want;
                 if (need < c) need = c;
             } else {
                 long long e = ub;
@@ -94,7 +97,7 @@ hipError_t launch_classify(int64_t m, const BinParams &p, double scale, const in
     for (int b = 0; b < OCEAN_MAX_BINS; ++b) bt.slots[b] = b < p.n_bins ? p.slots[b] : 0;
     int64_t blocks = (m + TPB - 1) / TPB;
     if (blocks > 1024) blocks = 1024;   // one set of atomics per workgroup: keep the workgroups few
-    hipLaunchKernelGGL(k_classify, dim3((unsigned)blocks), dim3(TPB), 0, s, m, p.mode, p.coef, (p.table_coef > 0.0 && p.table_coef < p.coef) ? p.table_coef : p.coef, scale, bt, p.n_cols,
+    hipLaunchKernelGGL(k_classify, dim3((unsigned)blocks), dim3(TPB), 0, s, m, p.mode, p.coef, (p.table_coef > 0.0 && p.table_coef < p.coef) ? p.table_coef : p.coef, p.bound_coef, scale, bt, p.n_cols,
                        prod, est, nnz_exact, row_mask, lower_bound, bin_of_row, cap, bin_count, bin_prod, max_cap);
     return hipGetLastError();
 }

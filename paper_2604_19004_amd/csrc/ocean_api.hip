@@ -772,8 +772,9 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
             global_coef = o.exact_load_coef;
         } else {
             bp.mode = 0;
-            bp.coef = o.bound_load_coef;
+            bp.coef = 1.0;
         }
+        bp.bound_coef = o.bound_load_coef;
         S->workflow = workflow;
         S->hll_registers = m_regs;
 

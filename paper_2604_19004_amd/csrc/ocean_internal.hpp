@@ -203,6 +203,8 @@ struct BinParams {
                          // are divided by (assisted symbolic binning, Section 4.1), 1.0 = plain product counts
     double table_coef;   // mode 1: table slots per estimated entry when smaller than coef (0: coef itself); the
                          // reserved output stays coef x estimate
+    double bound_coef;   // table slots per intermediate product beyond which a table is of no use (modes 0, 1, 2;
+                         // at most 1.0 = the product bound itself)
     int n_bins;
     int32_t slots[OCEAN_MAX_BINS];
     int64_t n_cols;
