@@ -891,6 +891,7 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
         BinParams bp{};
         bp.mode = 0;
         bp.coef = 1.0;
+        bp.bound_coef = o.bound_load_coef;
         bp.n_bins = NB_COUNT;
         for (int b = 0; b < NB_COUNT; ++b) bp.slots[b] = kNumericSlots[b];
         bp.n_cols = n;
