@@ -196,7 +196,7 @@ k_scan_block_sums(const int32_t *__restrict__ in, int64_t n, int64_t *__restrict
 }
 
 __global__ void __launch_bounds__(TPB)
-k_scan_of_sums(int64_t *block_sum, int64_t n_blocks)
+k_scan_of_sums(int64_t *block_sum, int64_t n_blocks, unsigned long long *total_out)
 {
     __shared__ long long s_wave[TPB / WAVE];
     long long carry = 0;
@@ -208,7 +208,42 @@ k_scan_of_sums(int64_t *block_sum, int64_t n_blocks)
         if (i < n_blocks) block_sum[i] = carry + ex;
         carry += total;
     }
-    if (threadIdx.x == 0) block_sum[n_blocks] = carry;
+    if (threadIdx.x == 0) {
+        block_sum[n_blocks] = carry;
+        if (total_out != nullptr) *total_out = (unsigned long long)carry;
+    }
+}
+
+// The whole scan by one workgroup, tile after tile with a running carry: for inputs so short that three
+// launches would cost more than the work (up to SCAN_SMALL_MAX elements).
+constexpr int64_t SCAN_SMALL_MAX = 65536;
+__global__ void __launch_bounds__(TPB)
+k_scan_small(const int32_t *__restrict__ in, int64_t n, int64_t *__restrict__ out, unsigned long long *total_out)
+{
+    __shared__ long long s_wave[TPB / WAVE];
+    long long carry = 0;
+    for (int64_t tile = 0; tile < n; tile += SCAN_TILE) {
+        const int64_t base = tile + (int64_t)threadIdx.x * SCAN_ITEMS;
+        long long item[SCAN_ITEMS];
+        long long v = 0;
+#pragma unroll
+        for (int k = 0; k < SCAN_ITEMS; ++k) {
+            item[k] = (base + k < n) ? in[base + k] : 0;
+            v += item[k];
+        }
+        long long total;
+        long long run = carry + block_exclusive_scan(v, s_wave, total);
+#pragma unroll
+        for (int k = 0; k < SCAN_ITEMS; ++k) {
+            if (base + k < n) out[base + k] = run;
+            run += item[k];
+        }
+        carry += total;
+    }
+    if (threadIdx.x == 0) {
+        out[n] = carry;
+        if (total_out != nullptr) *total_out = (unsigned long long)carry;
+    }
 }
 
 __global__ void __launch_bounds__(TPB)
@@ -234,14 +269,17 @@ k_scan_apply(const int32_t *__restrict__ in, int64_t n, const int64_t *__restric
     if (blockIdx.x == 0 && threadIdx.x == 0) out[n] = block_sum[n_blocks];
 }
 
-hipError_t launch_scan_i32_to_i64(const int32_t *in, int64_t n, int64_t *out, int64_t *block_tmp, hipStream_t s)
+// total_out (may be null): a device word that receives the sum of all elements as well.
+hipError_t launch_scan_i32_to_i64(const int32_t *in, int64_t n, int64_t *out, int64_t *block_tmp,
+                                  unsigned long long *total_out, hipStream_t s)
 {
     const int64_t n_blocks = (n + SCAN_TILE - 1) / SCAN_TILE;
-    if (n_blocks == 0) {
-        return hipMemsetAsync(out, 0, sizeof(int64_t), s);
+    if (n <= SCAN_SMALL_MAX) {   // (also n == 0: out[0] = 0)
+        hipLaunchKernelGGL(k_scan_small, dim3(1), dim3(TPB), 0, s, in, n, out, total_out);
+        return hipGetLastError();
     }
     hipLaunchKernelGGL(k_scan_block_sums, dim3((unsigned)n_blocks), dim3(TPB), 0, s, in, n, block_tmp);
-    hipLaunchKernelGGL(k_scan_of_sums, dim3(1), dim3(TPB), 0, s, block_tmp, n_blocks);
+    hipLaunchKernelGGL(k_scan_of_sums, dim3(1), dim3(TPB), 0, s, block_tmp, n_blocks, total_out);
     hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)n_blocks), dim3(TPB), 0, s, in, n, block_tmp, n_blocks, out);
     return hipGetLastError();
 }

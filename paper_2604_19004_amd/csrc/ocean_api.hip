@@ -133,25 +133,41 @@ struct PinnedHost {
 };
 thread_local PinnedHost g_pinned;
 
-int device_cu_count()
+// Compute units and memory of the current device, asked for once per device and host thread.
+struct DeviceFacts {
+    int cus = 0;
+    size_t total_mem = 0;
+};
+const DeviceFacts &device_facts()
 {
-    static thread_local int cached = 0;
-    if (cached == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-            cached = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-        else
-            cached = 256;
+    static thread_local DeviceFacts cached[64];
+    static thread_local DeviceFacts fallback;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        (void)hipGetLastError();
+        fallback.cus = 256;
+        fallback.total_mem = 0;
+        return fallback;
     }
-    return cached;
+    DeviceFacts &f = cached[dev];
+    if (f.cus == 0) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) == hipSuccess) {
+            f.cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+            f.total_mem = prop.totalGlobalMem;
+        } else {
+            (void)hipGetLastError();
+            f.cus = 256;
+        }
+    }
+    return f;
 }
 
 int ctx_init(Ctx &c, const ocean_options *opt, ocean_stream_t stream)
 {
     c.s = static_cast<hipStream_t>(stream);
     c.al = opt ? opt->allocator : nullptr;
-    c.n_cu = device_cu_count();
+    c.n_cu = device_facts().cus;
     if (!g_pinned.p) {
         void *p = nullptr;
         HIP_TRY(hipHostMalloc(&p, sizeof(Scalars) + 4096, hipHostMallocPortable));
@@ -232,6 +248,7 @@ uint32_t fmix32_host(uint32_t h)
 struct Work {
     void *base = nullptr;
     Scalars *sc = nullptr;
+    bool bins_clean = false;   // the bin counters are still zero from the clearing of all scalars
     int64_t *prod = nullptr;
     int32_t *maxb = nullptr;
     uint8_t *bin = nullptr;
@@ -279,11 +296,16 @@ int work_alloc(Ctx &c, Work &w, int64_t m, int64_t n_sample)
     w.sample_rows = reinterpret_cast<int64_t *>(b + o_sr);
     w.sample_est = reinterpret_cast<double *>(b + o_se);
     HIP_TRY(hipMemsetAsync(w.sc, 0, sizeof(Scalars), c.s));
+    w.bins_clean = true;
     return OCEAN_OK;
 }
 
 int zero_bins(Ctx &c, Work &w)
 {
+    if (w.bins_clean) {   // (the analysis step in between touches none of them but the last row counter, which only
+        w.bins_clean = false;   // the retry uses, after a clearing of its own)
+        return OCEAN_OK;
+    }
     HIP_TRY(hipMemsetAsync(w.sc->bin_count, 0,
                            sizeof(unsigned long long) * (3 * OCEAN_MAX_BINS + 2 + 4), c.s));   // counts, cursors, products, max_cap, ovf, queues
     return OCEAN_OK;
@@ -784,9 +806,8 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
         int64_t *ptr = workflow == OCEAN_WF_SYMBOLIC ? c_rp : w.tmp_ptr;
         HIP_TRY(launch_classify(m, bp, o.estimate_scale, w.prod, w.est, w.nnz_final, nullptr, nullptr, w.bin, w.cap,
                                 w.sc->bin_count, w.sc->bin_prod, &w.sc->max_cap, c.s));
-        HIP_TRY(launch_scan_i32_to_i64(w.cap, m, ptr, w.scan_tmp, c.s));
+        HIP_TRY(launch_scan_i32_to_i64(w.cap, m, ptr, w.scan_tmp, &w.sc->totals[0], c.s));   // totals[0]: total slots
         HIP_TRY(launch_scatter(m, NB_COUNT, w.bin, w.sc->bin_count, w.sc->bin_cursor, w.bin_rows, c.s));
-        HIP_TRY(hipMemcpyAsync(&w.sc->totals[0], ptr + m, 8, hipMemcpyDeviceToDevice, c.s));   // total slots
         OC_TRY(fetch_scalars(c, w.sc));
         total_slots = (int64_t)c.h->totals[0];
         for (int b = 0; b < NB_COUNT; ++b) S->rows_per_bin[b] = (int64_t)c.h->bin_count[b];
@@ -877,8 +898,7 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
     // (sizes from the product bound cannot fall short: nothing to count in the upper-bound workflow)
     if (workflow != OCEAN_WF_UPPER_BOUND) HIP_TRY(launch_count_overflow(m, w.row_nnz, &w.sc->ovf_count, c.s));
     // optimistic: if nothing overflowed this scan already is the final row_ptr
-    HIP_TRY(launch_scan_i32_to_i64(w.row_nnz, m, c_rp, w.scan_tmp, c.s));
-    HIP_TRY(hipMemcpyAsync(&w.sc->totals[0], c_rp + m, 8, hipMemcpyDeviceToDevice, c.s));
+    HIP_TRY(launch_scan_i32_to_i64(w.row_nnz, m, c_rp, w.scan_tmp, &w.sc->totals[0], c.s));
     OC_TRY(fetch_scalars(c, w.sc));
     copy_bin_work();
     const int64_t n_ovf = (int64_t)c.h->ovf_count;
@@ -898,9 +918,8 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
         OC_TRY(zero_bins(c, w));
         HIP_TRY(launch_classify(m, bp, 1.0, w.prod, nullptr, nullptr, w.row_nnz, nullptr, w.bin, w.cap, w.sc->bin_count,
                                 w.sc->bin_prod, &w.sc->max_cap, c.s));
-        HIP_TRY(launch_scan_i32_to_i64(w.cap, m, w.tmp_ptr2, w.scan_tmp, c.s));
+        HIP_TRY(launch_scan_i32_to_i64(w.cap, m, w.tmp_ptr2, w.scan_tmp, &w.sc->totals[0], c.s));
         HIP_TRY(launch_scatter(m, NB_COUNT, w.bin, w.sc->bin_count, w.sc->bin_cursor, w.bin_rows, c.s));
-        HIP_TRY(hipMemcpyAsync(&w.sc->totals[0], w.tmp_ptr2 + m, 8, hipMemcpyDeviceToDevice, c.s));
         OC_TRY(fetch_scalars(c, w.sc));
         const int64_t slots2 = (int64_t)c.h->totals[0];
         r_col = static_cast<int32_t *>(c.alloc((size_t)slots2 * 4));
@@ -913,8 +932,7 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
         OC_TRY(run_numeric(c, w, A, Bnum, dtype, gb_log2, bc2, bp2, (int64_t)c.h->max_cap, 1.25, w.tmp_ptr2, r_col, r_val,
                            w.row_nnz2, 2, OCEAN_ST_RETRY, false, esc_ok));
         HIP_TRY(launch_final_nnz(m, w.row_nnz, w.row_nnz2, w.nnz_final, c.s));
-        HIP_TRY(launch_scan_i32_to_i64(w.nnz_final, m, c_rp, w.scan_tmp, c.s));
-        HIP_TRY(hipMemcpyAsync(&w.sc->totals[0], c_rp + m, 8, hipMemcpyDeviceToDevice, c.s));
+        HIP_TRY(launch_scan_i32_to_i64(w.nnz_final, m, c_rp, w.scan_tmp, &w.sc->totals[0], c.s));
         OC_TRY(fetch_scalars(c, w.sc));
         nnz_c = (int64_t)c.h->totals[0];
         final_nnz = w.nnz_final;
@@ -932,9 +950,8 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
     if (o.compact_in_place < 0) {
         // two copies of a large output side by side are what makes the estimation workflows run out of memory
         // (Section 5.2): beyond 40 % of the device's memory the rows are compacted inside the slab
-        size_t mem_free = 0, mem_total = 0;
-        if (hipMemGetInfo(&mem_free, &mem_total) == hipSuccess && both > 0.4 * (double)mem_total) want_in_place = true;
-        else (void)hipGetLastError();
+        const size_t mem_total = device_facts().total_mem;
+        if (mem_total > 0 && both > 0.4 * (double)mem_total) want_in_place = true;
     }
     for (int attempt = 0; attempt < 2 && !c_col; ++attempt) {
         if (want_in_place) {

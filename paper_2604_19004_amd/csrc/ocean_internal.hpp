@@ -216,8 +216,8 @@ hipError_t launch_classify(int64_t m, const BinParams &p, double scale, const in
                            hipStream_t s);
 hipError_t launch_scatter(int64_t m, int n_bins, const uint8_t *bin_of_row, const unsigned long long *bin_count,
                           unsigned long long *bin_cursor, int32_t *bin_rows, hipStream_t s);
-hipError_t launch_scan_i32_to_i64(const int32_t *in, int64_t n, int64_t *out /*n+1*/, int64_t *block_tmp,
-                                  hipStream_t s);
+hipError_t launch_scan_i32_to_i64(const int32_t *in, int64_t n, int64_t *out, int64_t *block_tmp,
+                                  unsigned long long *total_out, hipStream_t s);
 int64_t scan_tmp_elems(int64_t n);
 hipError_t launch_fill_i32(int32_t *p, int64_t n, int32_t v, hipStream_t s);
 hipError_t launch_fill_u64(unsigned long long *p, int64_t n, unsigned long long v, hipStream_t s);

@@ -502,7 +502,7 @@ def _random_case(rng, dtype):
 
 @pytest.mark.parametrize("seed", range(6))
 def test_random_matrices_with_every_option_combined(ob, seed):
-    """The random cases again with this round's switches in random combinations: assisted symbolic binning with
+    """The random cases again with the optional paths switched in random combinations: assisted symbolic binning with
     an exaggerated ratio (tables fill up), compaction in place, ESC for short rows, bitmap query, either
     selector, the throughput detector at ratio 0 / 1, forced hash kernels."""
     rng = np.random.default_rng(7000 + seed)
