@@ -904,7 +904,6 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
     const int64_t n_ovf = (int64_t)c.h->ovf_count;
     S->overflow_rows = n_ovf;
     int64_t nnz_c = (int64_t)c.h->totals[0];
-    const int32_t *final_nnz = w.row_nnz;
     int32_t *r_col = nullptr;
     void *r_val = nullptr;
     if (n_ovf > 0) {
@@ -935,10 +934,7 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
         HIP_TRY(launch_scan_i32_to_i64(w.nnz_final, m, c_rp, w.scan_tmp, &w.sc->totals[0], c.s));
         OC_TRY(fetch_scalars(c, w.sc));
         nnz_c = (int64_t)c.h->totals[0];
-        final_nnz = w.nnz_final;
     }
-    (void)final_nnz;
-    (void)max_ub;
 
     // ---- compaction ----
     OC_TRY(mark(c, OCEAN_ST_COMPACT));
