@@ -348,6 +348,19 @@ def test_compaction_in_place(ob, name):
             assert st["overflow_rows"] > 0
 
 
+@pytest.mark.parametrize("name", ["er", "laplacian", "rmat", "clustered"])
+def test_one_device_matrix_as_both_operands(ob, name):
+    """C = A*A with the same device arrays passed as A and as B (what bench.py does): the inputs are read-only."""
+    A, B, ref, prod = workload(name, True)
+    assert B is A
+    dA = ob.to_device(A)
+    for wf in WORKFLOWS:
+        Cd, st = ob.spgemm(dA, dA, workflow=wf_id(ob, wf))
+        check_result(Cd, ref, A, f"{name}/{wf}, aliased operands")
+    a = dA.col_idx.cpu().numpy()
+    assert np.array_equal(a, A.col_idx) and np.array_equal(dA.val.cpu().numpy(), A.val)     # untouched
+
+
 def test_structure_is_identical_across_runs(ob):
     A, B, ref, prod = workload("rmat", True)
     dA, dB = ob.to_device(A), ob.to_device(B)
