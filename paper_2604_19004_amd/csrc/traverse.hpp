@@ -142,16 +142,18 @@ __device__ __forceinline__ void wave_traverse(const int32_t *__restrict__ a_col,
     }
 }
 
-// LDS scratch of a workgroup-wide flattened chunk of up to THREADS entries.
-template <typename V, int THREADS>
+// LDS scratch of a workgroup-wide flattened chunk of up to THREADS entries.  RPT: products per thread up to which
+// the entries of a chunk are found by rank (below); the mark bitmap grows with it.
+template <typename V, int THREADS, int RPT = 16>
 struct WgChunk {
-    static constexpr uint32_t RANK_CAP = 16u * THREADS;   // most products of a chunk whose entries are found by rank
+    static constexpr uint32_t RANK_CAP = (uint32_t)RPT * THREADS;   // most products of a chunk whose entries are found by rank
+    static constexpr int START_WORDS = THREADS * RPT / 32 + 32;
     uint32_t excl[THREADS];
     long long pbase[THREADS];
     V a[THREADS];
     union alignas(8) {
         uint16_t first[THREADS + 2];       // entry of the first product of every block of 2^bshift products
-        uint32_t start[THREADS / 2 + 32];  // bit q set: a segment starts at product q (RANK_CAP bits + padding for batches of up to 16 per lane)
+        uint32_t start[START_WORDS];       // bit q set: a segment starts at product q (RANK_CAP bits + padding for batches of up to 16 per lane)
     };
     uint32_t wsum[THREADS / WAVE];
     uint32_t wcnt[THREADS / WAVE];
@@ -163,7 +165,7 @@ struct WgChunk {
 // that point to long rows of B keeps every wave as busy as a row with a thousand short ones.
 // Every wave takes one contiguous span of the products, 256 at a time.  The entry a product
 // belongs to is found in one of two ways:
-//   * a chunk of at most 16 products per thread marks the first product of every non-empty
+//   * a chunk of at most RPT (16, or what the chunk type says) products per thread marks the first product of every non-empty
 //     segment in a bitmap; the entry of product q (counting non-empty entries only, which are
 //     stored compacted) is the number of marks at or before q, minus one: one broadcast read of
 //     the 64 marks of the wave's batch and a population count, on top of a running count that the
@@ -176,17 +178,17 @@ struct WgChunk {
 // than 2^31.
 // Every thread calls it; the chunk arrays must be free on entry (the call ends with a barrier).
 // Returns the number of products of the chunk.
-template <int THREADS, bool HAS_VAL, int WU = FLAT_U, typename V, typename F>
-__device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS> &c, int nent, int64_t p0, uint32_t len, V a,
+template <int THREADS, bool HAS_VAL, int WU = FLAT_U, typename V, typename F, int RPT>
+__device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS, RPT> &c, int nent, int64_t p0, uint32_t len, V a,
                                               const int32_t *__restrict__ b_col, const V *__restrict__ b_val, F &f)
 {
     constexpr int NW = THREADS / WAVE;
-    constexpr uint32_t RANK_CAP = WgChunk<V, THREADS>::RANK_CAP;
-    constexpr int START_WORDS = THREADS / 2 + 32;
-    static_assert(THREADS <= 1024 && START_WORDS <= THREADS, "entry ids are kept in 16 bits and one block table entry per thread");
+    constexpr uint32_t RANK_CAP = WgChunk<V, THREADS, RPT>::RANK_CAP;
+    constexpr int START_WORDS = WgChunk<V, THREADS, RPT>::START_WORDS;
+    static_assert(THREADS <= 1024, "entry ids are kept in 16 bits and one block table entry per thread");
     const int tid = threadIdx.x;
     const int lane = tid & (WAVE - 1), wave = tid / WAVE;
-    if (tid < START_WORDS) c.start[tid] = 0u;
+    for (int j = tid; j < START_WORDS; j += THREADS) c.start[j] = 0u;
     uint32_t incl = wave_inclusive_scan_u32(len);
     // non-empty segments are numbered on their own
     const unsigned long long live = __ballot(len > 0);
@@ -366,18 +368,18 @@ __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS> &c, int ne
 // has been called once per product.  Needs at most NB * FLAT_U products per thread
 // (total <= NB * FLAT_U * THREADS) and total <= WgChunk::RANK_CAP; otherwise nothing is fetched and
 // fits = false.  Every thread calls it; ends with a barrier; returns the number of products.
-template <int THREADS, int NB, typename V, typename M>
-__device__ __forceinline__ uint32_t wg_flat_chunk_keep(WgChunk<V, THREADS> &c, int nent, int64_t p0, uint32_t len, V a,
+template <int THREADS, int NB, typename V, typename M, int RPT>
+__device__ __forceinline__ uint32_t wg_flat_chunk_keep(WgChunk<V, THREADS, RPT> &c, int nent, int64_t p0, uint32_t len, V a,
                                                    const int32_t *__restrict__ b_col, const V *__restrict__ b_val,
                                                    int32_t (&kc)[NB * FLAT_U], V (&kv)[NB * FLAT_U], M &mark,
                                                    bool &fits)
 {
     constexpr int NW = THREADS / WAVE;
-    constexpr uint32_t RANK_CAP = WgChunk<V, THREADS>::RANK_CAP;
-    constexpr int START_WORDS = THREADS / 2 + 32;
+    constexpr uint32_t RANK_CAP = WgChunk<V, THREADS, RPT>::RANK_CAP;
+    constexpr int START_WORDS = WgChunk<V, THREADS, RPT>::START_WORDS;
     const int tid = threadIdx.x;
     const int lane = tid & (WAVE - 1), wave = tid / WAVE;
-    if (tid < START_WORDS) c.start[tid] = 0u;
+    for (int j = tid; j < START_WORDS; j += THREADS) c.start[j] = 0u;
     uint32_t incl = wave_inclusive_scan_u32(len);
     const unsigned long long live = __ballot(len > 0);
     if (lane == WAVE - 1) { c.wsum[wave] = incl; c.wcnt[wave] = (uint32_t)__popcll(live); }
@@ -457,10 +459,10 @@ __device__ __forceinline__ uint32_t wg_flat_chunk_keep(WgChunk<V, THREADS> &c, i
 // Workgroup version of the row traversal: chunks of THREADS entries of A, each flattened over the
 // whole workgroup.  Every thread of the (1-D) workgroup must call it.  seg(k, p0, len) gives the
 // segment of B's arrays that entry k expands to.  Ends with a barrier.
-template <int THREADS, bool HAS_VAL, int WU = FLAT_U, typename V, typename SegFn, typename F>
+template <int THREADS, bool HAS_VAL, int WU = FLAT_U, typename V, typename SegFn, typename F, int RPT>
 __device__ __forceinline__ void wg_traverse(const int32_t *__restrict__ a_col, const V *__restrict__ a_val,
                                             int64_t e0, int64_t e1, SegFn seg, const int32_t *__restrict__ b_col,
-                                            const V *__restrict__ b_val, WgChunk<V, THREADS> &c, F f)
+                                            const V *__restrict__ b_val, WgChunk<V, THREADS, RPT> &c, F f)
 {
     const int tid = threadIdx.x;
     for (int64_t base = e0; base < e1; base += THREADS) {
