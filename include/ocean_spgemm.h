@@ -130,6 +130,12 @@ typedef struct ocean_options {
                                         than the expansion factor (which still sizes the reserved output).  1.75: with
                                         32 registers the factor 2.0 sends a quarter of the rows of a 234-entries-per-row
                                         input to tables twice the size they need; 0 = the expansion factor itself */
+    int32_t dense_range;             /* accumulator selection of Section 3.3: a row whose column range (first to last
+                                        column of the rows of B it references) is at most 4096 columns and needs no
+                                        more LDS as values + presence bits than the hash table the row would get
+                                        (512 slots or more) is accumulated densely over that range.  0 never; 1
+                                        (default) when 2 % or more of the sampled rows are such rows (then the ranges
+                                        of all rows are computed, one more pass over A); 2 always compute the ranges */
     double sort_b_ratio;             /* detector for the throughput-bound case of the accumulators that keep values in
                                         global memory (Section 5.4): when B's rows are unsorted and the rows that
                                         outgrow the LDS hash tables hold at least sort_b_ratio * nnz(B) products, a copy
@@ -166,7 +172,8 @@ typedef struct ocean_stats {
     int32_t hll_registers;     /* 0 when no sketch was built */
     int32_t sampled_rows;
     int32_t fell_back;         /* 1: estimation workflow abandoned for the two-pass one (out of memory) */
-    int64_t rows_per_bin[OCEAN_MAX_BINS];          /* numeric bins */
+    int64_t rows_per_bin[OCEAN_MAX_BINS];          /* numeric bins: the hash bins of ocean_bin_layout, then (at index
+                                                      n_numeric) the rows of the dense accumulator over the row's range */
     int64_t symbolic_rows_per_bin[OCEAN_MAX_BINS]; /* symbolic bins (two-pass workflow) */
     int64_t overflow_rows;
     int64_t symbolic_overflow_rows; /* rows whose assisted key table filled up and that were recounted */
@@ -174,6 +181,8 @@ typedef struct ocean_stats {
     int64_t peak_bytes;        /* largest total obtained from the allocator at one time */
     int32_t compacted_in_place; /* 1: C's col_idx / val are the temporary output, compacted in place */
     int32_t b_sorted_copy;      /* 1: the numeric pass read a copy of B with sorted rows (see sort_b_ratio) */
+    int32_t dense_range_rows;   /* sampled rows for which the dense accumulator over the row's column range would be
+                                   chosen (with dense_range = 1 and a sample taken) */
     float stage_ms[OCEAN_NUM_STAGES];
     float total_ms;            /* host wall clock of the call */
     /* per numeric bin (first attempt only): kernel time from events on the call's stream, and the

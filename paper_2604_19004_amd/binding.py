@@ -45,7 +45,7 @@ class ocean_options(C.Structure):
                 ("assist_sigmas", C.c_double), ("bitmap_query", C.c_int32), ("esc_short_rows", C.c_int32),
                 ("bitmap_query_cr", C.c_double), ("selector", C.c_int32), ("compact_in_place", C.c_int32),
                 ("tuned_cr_light", C.c_double), ("tuned_cr_heavy", C.c_double), ("tuned_min_products", C.c_double),
-                ("tuned_cr_bound", C.c_double), ("bound_load_coef", C.c_double), ("estimate_table_coef", C.c_double), ("sort_b_ratio", C.c_double),
+                ("tuned_cr_bound", C.c_double), ("bound_load_coef", C.c_double), ("estimate_table_coef", C.c_double), ("dense_range", C.c_int32), ("sort_b_ratio", C.c_double),
                 ("allocator", C.POINTER(ocean_allocator))]
 
 
@@ -56,14 +56,14 @@ class ocean_stats(C.Structure):
                 ("hll_registers", C.c_int32), ("sampled_rows", C.c_int32), ("fell_back", C.c_int32),
                 ("rows_per_bin", C.c_int64 * MAX_BINS), ("symbolic_rows_per_bin", C.c_int64 * MAX_BINS),
                 ("overflow_rows", C.c_int64), ("symbolic_overflow_rows", C.c_int64), ("temp_slots", C.c_int64), ("peak_bytes", C.c_int64),
-                ("compacted_in_place", C.c_int32), ("b_sorted_copy", C.c_int32),
+                ("compacted_in_place", C.c_int32), ("b_sorted_copy", C.c_int32), ("dense_range_rows", C.c_int32),
                 ("stage_ms", C.c_float * 8), ("total_ms", C.c_float), ("bin_ms", C.c_float * MAX_BINS),
                 ("bin_products", C.c_int64 * MAX_BINS), ("bin_nnz_a", C.c_int64 * MAX_BINS),
                 ("bin_nnz_c", C.c_int64 * MAX_BINS)]
 
     def as_dict(self) -> dict:
         d = {k: getattr(self, k) for k in ("products", "max_row_products", "heavy_products", "nnz_c", "er", "avg_products", "sampled_cr",
-                                           "cr_mean", "cr_std", "assist_cr", "symbolic_overflow_rows", "compacted_in_place", "b_sorted_copy",
+                                           "cr_mean", "cr_std", "assist_cr", "symbolic_overflow_rows", "compacted_in_place", "b_sorted_copy", "dense_range_rows",
                                            "hll_registers", "sampled_rows", "fell_back", "overflow_rows", "temp_slots",
                                            "peak_bytes", "total_ms")}
         d["workflow"] = WORKFLOW_NAMES.get(self.workflow, str(self.workflow))

@@ -472,6 +472,74 @@ hipError_t launch_hll_merge(const Csr &A, const uint8_t *sketches, int m, const 
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------- row spans
+// Column range that a row of C can reach: from the first entry of the rows of B it references to their last
+// entry (B's rows in column order; where they are not, the range is only a guess, and the kernel that relies
+// on it checks every product against it).  Used to choose the dense accumulator for rows whose range fits it
+// (Section 3.3, accumulator selection).  One lane group per row as in k_row_products; rows of A with more than
+// 64 entries per lane of the group are left with the full range (they are heavy rows, which have a dense
+// accumulator of their own).  rows: list of row ids, or null for all rows 0 .. n-1; outputs indexed like rows.
+__global__ void __launch_bounds__(TPB)
+k_row_spans(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col, const int64_t *__restrict__ b_rp,
+            const int32_t *__restrict__ b_col, const int64_t *__restrict__ rows, int64_t n, int g_log2,
+            int32_t *__restrict__ cmin, int32_t *__restrict__ cmax)
+{
+    const int G = 1 << g_log2;
+    const int R = TPB >> g_log2;
+    const int rl = threadIdx.x >> g_log2;
+    const int sub = threadIdx.x & (G - 1);
+    for (int64_t base = (int64_t)blockIdx.x * R; base < n; base += (int64_t)gridDim.x * R) {
+        const int64_t t = base + rl;
+        int lo = 0x7fffffff, hi = -1;
+        bool whole = false;
+        if (t < n) {
+            const int64_t row = rows ? rows[t] : t;
+            const int64_t e0 = a_rp[row], e1 = a_rp[row + 1];
+            whole = e1 - e0 > (int64_t)G * 64;
+            if (!whole) {
+                for (int64_t e = e0 + sub; e < e1; e += 4 * G) {
+                    int64_t p0[4], p1[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int64_t idx = e + (int64_t)i * G;
+                        const int32_t k = a_col[idx < e1 ? idx : e];
+                        p0[i] = b_rp[k];
+                        p1[i] = b_rp[k + 1];
+                    }
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        if (e + (int64_t)i * G < e1 && p1[i] > p0[i]) {
+                            const int32_t first = b_col[p0[i]], last = b_col[p1[i] - 1];
+                            lo = first < lo ? first : lo;
+                            hi = last > hi ? last : hi;
+                        }
+                    }
+                }
+            }
+        }
+        lo = -group_reduce_max(-lo, G);
+        hi = group_reduce_max(hi, G);
+        if (t < n && sub == 0) {
+            cmin[t] = whole ? 0 : lo;
+            cmax[t] = whole ? 0x7fffffff : hi;   // (hi < lo: a row without products)
+        }
+    }
+}
+
+hipError_t launch_row_spans(const Csr &A, const Csr &B, const int64_t *rows, int64_t n, int32_t *cmin, int32_t *cmax,
+                            hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    const double avg = A.rows ? (double)A.nnz / (double)A.rows : 0.0;
+    const int g_log2 = ilog2_ceil(avg / 4.0, 1, 6);
+    const int R = TPB >> g_log2;
+    int64_t blocks = (n + R - 1) / R;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(k_row_spans, dim3((unsigned)blocks), dim3(TPB), 0, s, A.rp, A.col, B.rp, B.col, rows, n, g_log2,
+                       cmin, cmax);
+    return hipGetLastError();
+}
+
 // ----------------------------------------------------------- sample rows
 // The stratified sample of Section 3.2 (one row out of each of ns equal strata, chosen by a hash of the
 // stratum's number and the seed), written on the device: the same rows as the host helper behind
@@ -499,15 +567,17 @@ hipError_t launch_sample_rows(int64_t rows, int64_t ns, uint32_t seed, int64_t *
 // sums, tree reduction), so the sampled CR is the same on every run.
 // out[0] = sum of products, out[1] = sum of estimates (their ratio is the sampled CR, Section 3.2);
 // out[2], out[3] = sum and sum of squares of the per-row ratios products / estimate, out[4] = rows counted
-// (mean and standard deviation of the compression ratio over the sample, Section 4.1).
+// (mean and standard deviation of the compression ratio over the sample, Section 4.1); out[5] = sampled rows
+// whose column range is narrow enough for the dense accumulator to pay (cmin / cmax of the sampled rows given).
 constexpr int SR_THREADS = 1024;
 __global__ void __launch_bounds__(SR_THREADS)
 k_sample_reduce(const int64_t *__restrict__ rows, int64_t n_rows, const int64_t *__restrict__ prod,
-                const double *__restrict__ est, double *out)
+                const double *__restrict__ est, const int32_t *__restrict__ cmin, const int32_t *__restrict__ cmax,
+                int64_t n_cols, int vbytes, double bound_coef, double *out)
 {
-    constexpr int NS = 5;
+    constexpr int NS = 6;
     __shared__ double s_acc[NS][SR_THREADS];
-    double acc[NS] = {0.0, 0.0, 0.0, 0.0, 0.0};
+    double acc[NS] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
     // four sampled rows per thread and turn, their dependent loads (row id -> products) issued together
     for (int64_t t0 = threadIdx.x; t0 < n_rows; t0 += 4 * SR_THREADS) {
         double e[4];
@@ -526,6 +596,14 @@ k_sample_reduce(const int64_t *__restrict__ rows, int64_t n_rows, const int64_t 
             if (e[i] > 0.0) {
                 const double q = p[i] / e[i];
                 acc[0] += p[i]; acc[1] += e[i]; acc[2] += q; acc[3] += q * q; acc[4] += 1.0;
+                if (cmin != nullptr) {
+                    const int64_t t = t0 + (int64_t)i * SR_THREADS;
+                    const long long span = (long long)cmax[t] - (long long)cmin[t] + 1;
+                    const double ub = p[i] < (double)n_cols ? p[i] : (double)n_cols;
+                    long long slots = 16;
+                    while ((double)slots < bound_coef * ub && slots < (1ll << 40)) slots <<= 1;   // table from the bound
+                    if (dense_span_pays(span, slots, vbytes)) acc[5] += 1.0;
+                }
             }
         }
     }
@@ -543,9 +621,11 @@ k_sample_reduce(const int64_t *__restrict__ rows, int64_t n_rows, const int64_t 
 }
 
 hipError_t launch_sample_reduce(const int64_t *rows, int64_t n_rows, const int64_t *prod, const double *est,
+                                const int32_t *cmin, const int32_t *cmax, int64_t n_cols, int vbytes, double bound_coef,
                                 double *out, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_sample_reduce, dim3(1), dim3(SR_THREADS), 0, s, rows, n_rows, prod, est, out);
+    hipLaunchKernelGGL(k_sample_reduce, dim3(1), dim3(SR_THREADS), 0, s, rows, n_rows, prod, est, cmin, cmax, n_cols,
+                       vbytes, bound_coef, out);
     return hipGetLastError();
 }
 

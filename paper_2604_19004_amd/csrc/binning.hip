@@ -25,6 +25,7 @@ __global__ void __launch_bounds__(TPB)
 k_classify(int64_t m, int mode, double coef, double table_coef, double bound_coef, double scale, BinTable bt, int64_t n_cols,
            const int64_t *__restrict__ prod, const double *__restrict__ est, const int32_t *__restrict__ nnz_exact,
            const int32_t *__restrict__ row_mask, const int32_t *__restrict__ lower_bound,
+           const int32_t *__restrict__ cmin, const int32_t *__restrict__ cmax, int vbytes,
            uint8_t *__restrict__ bin_of_row, int32_t *__restrict__ cap,
            unsigned long long *bin_count, unsigned long long *bin_prod, unsigned long long *max_cap)
 {
@@ -73,6 +74,15 @@ k_classify(int64_t m, int mode, double coef, double table_coef, double bound_coe
             bin = bt.n - 1;
             for (int b = 0; b < bt.n; ++b)
                 if ((long long)bt.slots[b] >= need) { bin = b; break; }
+            if (cmin != nullptr) {
+                // Section 3.3, accumulator selection: the dense accumulator over the row's own column range where
+                // it needs no more memory than the hash table the row would get
+                const long long span = (long long)cmax[i] - (long long)cmin[i] + 1;
+                if (dense_span_pays(span, (long long)bt.slots[bin], vbytes)) {
+                    bin = NB_DSPAN;
+                    if (c > span) c = span;
+                }
+            }
             atomicAdd(&s_cnt[bin], 1u);
             if (bin_prod != nullptr) atomicAdd(&s_prod[bin], (unsigned long long)pr);
             if (bin == bt.n - 1 && c > 0) atomicMax(&s_maxcap, (unsigned int)c);
@@ -81,8 +91,8 @@ k_classify(int64_t m, int mode, double coef, double table_coef, double bound_coe
         if (cap != nullptr) cap[i] = (int32_t)c;
     }
     __syncthreads();
-    if (threadIdx.x < bt.n && s_cnt[threadIdx.x]) atomicAdd(&bin_count[threadIdx.x], (unsigned long long)s_cnt[threadIdx.x]);
-    if (bin_prod != nullptr && threadIdx.x < bt.n && s_prod[threadIdx.x]) atomicAdd(&bin_prod[threadIdx.x], s_prod[threadIdx.x]);
+    if (threadIdx.x < OCEAN_MAX_BINS && s_cnt[threadIdx.x]) atomicAdd(&bin_count[threadIdx.x], (unsigned long long)s_cnt[threadIdx.x]);
+    if (bin_prod != nullptr && threadIdx.x < OCEAN_MAX_BINS && s_prod[threadIdx.x]) atomicAdd(&bin_prod[threadIdx.x], s_prod[threadIdx.x]);
     if (threadIdx.x == 0 && s_maxcap && max_cap != nullptr) atomicMax(max_cap, (unsigned long long)s_maxcap);
 }
 
@@ -91,6 +101,7 @@ hipError_t launch_classify(int64_t m, const BinParams &p, double scale, const in
                            uint8_t *bin_of_row, int32_t *cap, unsigned long long *bin_count,
                            unsigned long long *bin_prod, unsigned long long *max_cap, hipStream_t s)
 {
+    static_assert(NB_ALL <= OCEAN_MAX_BINS, "the dense-range bin has a place in the per-bin arrays");
     if (m == 0) return hipSuccess;
     BinTable bt;
     bt.n = p.n_bins;
@@ -98,7 +109,8 @@ hipError_t launch_classify(int64_t m, const BinParams &p, double scale, const in
     int64_t blocks = (m + TPB - 1) / TPB;
     if (blocks > 1024) blocks = 1024;   // one set of atomics per workgroup: keep the workgroups few
     hipLaunchKernelGGL(k_classify, dim3((unsigned)blocks), dim3(TPB), 0, s, m, p.mode, p.coef, (p.table_coef > 0.0 && p.table_coef < p.coef) ? p.table_coef : p.coef, p.bound_coef, scale, bt, p.n_cols,
-                       prod, est, nnz_exact, row_mask, lower_bound, bin_of_row, cap, bin_count, bin_prod, max_cap);
+                       prod, est, nnz_exact, row_mask, lower_bound, p.mode != 3 ? p.cmin : nullptr, p.cmax, p.vbytes, bin_of_row,
+                       cap, bin_count, bin_prod, max_cap);
     return hipGetLastError();
 }
 

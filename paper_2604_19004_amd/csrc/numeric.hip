@@ -23,6 +23,14 @@
 
 namespace ocean {
 
+// The type values are accumulated in inside LDS.  fp32 products are added up in fp64: the LDS atomic ds_add_f32
+// measured about twenty times slower than ds_add_f64 on this GPU (a block-diagonal input, same structure in both
+// types: dense accumulation 4.27 ms against 2.40 ms; with plain stores in place of the atomics 1.42 against 2.27 ms),
+// so an fp32 row costs the LDS of an fp64 row and is faster for it - and closer to the exact sum.
+template <typename V> struct AccOf { using type = V; };
+template <> struct AccOf<float> { using type = double; };
+template <typename V> using acc_t = typename AccOf<V>::type;
+
 template <typename V>
 __device__ __forceinline__ void lds_add(V *p, V v)
 {
@@ -113,13 +121,14 @@ k_numeric_group(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     constexpr int R = 256 / G;
     __shared__ int32_t s_keys[R * SLOTS];
     __shared__ int32_t s_sort[R * SLOTS];
-    __shared__ V s_vals[R * SLOTS];
+    using AV = acc_t<V>;
+    __shared__ AV s_vals[R * SLOTS];
     __shared__ FlatChunk<V, G> s_fc[R];
     const int rl = threadIdx.x / G;
     const int sub = threadIdx.x % G;
     int32_t *keys = s_keys + rl * SLOTS;
     int32_t *sbuf = s_sort + rl * SLOTS;
-    V *vals = s_vals + rl * SLOTS;
+    AV *vals = s_vals + rl * SLOTS;
     const int group_shift = (lane_id() / G) * G;
     const unsigned long long group_mask = (1ull << G) - 1ull;
 
@@ -127,14 +136,14 @@ k_numeric_group(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     const bool live = r < count;
     const int64_t row = live ? rows[r] : 0;
 
-    for (int s = sub; s < SLOTS; s += G) { keys[s] = EMPTY_KEY; vals[s] = (V)0; }
+    for (int s = sub; s < SLOTS; s += G) { keys[s] = EMPTY_KEY; vals[s] = (AV)0; }
     wave_sync();
 
     bool ovf = false;
     const int64_t e0 = live ? a_rp[row] : 0;
     const int64_t e1 = live ? a_rp[row + 1] : 0;
     auto f = [&](const auto &cj, const auto &cv) {
-        if (!lds_insert_batch<BITS>(keys, cj, cv, [&](int slot, V v, bool) { lds_add(&vals[slot], v); })) ovf = true;
+        if (!lds_insert_batch<BITS>(keys, cj, cv, [&](int slot, V v, bool) { lds_add(&vals[slot], (AV)v); })) ovf = true;
     };
     // the rows of a wave advance together: same number of G-entry chunks for all of them
     const int chunks = group_reduce_max((int)((e1 - e0 + G - 1) / G), WAVE);
@@ -190,7 +199,7 @@ k_numeric_group(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
             for (int t = sub; t < c; t += G) {
                 const int32_t key = sbuf[t];
                 out_col[o + t] = key;
-                out_val[o + t] = vals[lds_find<BITS>(keys, key)];
+                out_val[o + t] = (V)vals[lds_find<BITS>(keys, key)];
             }
             if (sub == 0) row_nnz[row] = c;
         }
@@ -263,8 +272,8 @@ struct WaveScope {
 // keys and values are put in order inside LDS and copied out from there).
 // `grouped` may be the table's own key array, provided every thread has read
 // its keys before the call (barrier).
-template <int THREADS, int PER, bool CHECK, typename Scope = WorkgroupScope, int BF = 1, typename V>
-__device__ __forceinline__ int bucket_emit(const int32_t (&key)[PER], V *s_vals, int32_t kmin, int shift,
+template <int THREADS, int PER, bool CHECK, typename Scope = WorkgroupScope, int BF = 1, typename AV, typename V>
+__device__ __forceinline__ int bucket_emit(const int32_t (&key)[PER], AV *s_vals, int32_t kmin, int shift,
                                            uint32_t *hist, int32_t *grouped, int *s_wave, int *s_flag, int limit,
                                            int64_t o, int64_t cap, long long done, int32_t *__restrict__ out_col,
                                            V *__restrict__ out_val)
@@ -328,11 +337,11 @@ __device__ __forceinline__ int bucket_emit(const int32_t (&key)[PER], V *s_vals,
     }
     Scope::sync();
     int rank[PER];
-    V val[PER];
+    AV val[PER];
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
         rank[q] = 0;
-        val[q] = V();
+        val[q] = AV();
         if (key[q] != EMPTY_KEY) {
             const uint32_t x = (uint32_t)(key[q] - kmin);
             const uint32_t b = x >> shift, d = x & wmask;
@@ -360,7 +369,7 @@ __device__ __forceinline__ int bucket_emit(const int32_t (&key)[PER], V *s_vals,
     const int n_out = (long long)total < room ? total : (room > 0 ? (int)room : 0);
     for (int i = tid; i < n_out; i += THREADS) {
         out_col[o + done + i] = grouped[i];
-        out_val[o + done + i] = s_vals[i];
+        out_val[o + done + i] = (V)s_vals[i];
     }
     return total;
 }
@@ -385,26 +394,27 @@ k_numeric_wave(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_c
     // the traversal's chunk and, after it, the bucket counts of the ordered write-out share one buffer per row
     constexpr size_t HIST_BYTES = (NBK / 2 + 1) * sizeof(uint32_t);
     constexpr size_t SCRATCH = sizeof(FlatChunk<V, WAVE>) > HIST_BYTES ? sizeof(FlatChunk<V, WAVE>) : HIST_BYTES;
+    using AV = acc_t<V>;
     __shared__ int32_t s_keys[R * SLOTS];
-    __shared__ V s_vals[R * SLOTS];
+    __shared__ AV s_vals[R * SLOTS];
     __shared__ __align__(16) unsigned char s_scratch[R][(SCRATCH + 15) / 16 * 16];
     __shared__ int s_flag[R];
     const int rl = threadIdx.x / WAVE;
     const int sub = lane_id();
     int32_t *keys = s_keys + rl * SLOTS;
-    V *vals = s_vals + rl * SLOTS;
+    AV *vals = s_vals + rl * SLOTS;
     FlatChunk<V, WAVE> &fc = *reinterpret_cast<FlatChunk<V, WAVE> *>(s_scratch[rl]);
     uint32_t *hist = reinterpret_cast<uint32_t *>(s_scratch[rl]);
     const int64_t r = (int64_t)blockIdx.x * R + rl;
     if (r >= count) return;   // whole wave leaves; no workgroup barrier is used below
     const int64_t row = rows[r];
-    for (int s = sub; s < SLOTS; s += WAVE) { keys[s] = EMPTY_KEY; vals[s] = (V)0; }
+    for (int s = sub; s < SLOTS; s += WAVE) { keys[s] = EMPTY_KEY; vals[s] = (AV)0; }
     wave_sync();
     bool ovf = false;
     wave_traverse<true>(a_col, a_val, a_rp[row], a_rp[row + 1],
                         [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
                         b_col, b_val, fc, [&](const auto &cj, const auto &cv) {
-                            if (!lds_insert_batch<BITS>(keys, cj, cv, [&](int slot, V v, bool) { lds_add(&vals[slot], v); })) ovf = true;
+                            if (!lds_insert_batch<BITS>(keys, cj, cv, [&](int slot, V v, bool) { lds_add(&vals[slot], (AV)v); })) ovf = true;
                         });
     wave_sync();
     // ---- ordered write-out through column buckets
@@ -447,8 +457,9 @@ k_numeric_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col
     constexpr int PER = SLOTS / THREADS;
     constexpr int NBK = SLOTS * BF;
     __shared__ int32_t s_keys[SLOTS];
+    using AV = acc_t<V>;
     __shared__ int32_t s_sort[SLOTS];
-    __shared__ V s_vals[SLOTS];
+    __shared__ AV s_vals[SLOTS];
     // the traversal's chunk and, after it, the bucket counts of the ordered write-out share one buffer
     constexpr size_t HIST_BYTES = (NBK / 2 + 1) * sizeof(uint32_t);
     constexpr size_t SCRATCH = sizeof(WgChunk<V, THREADS>) > HIST_BYTES ? sizeof(WgChunk<V, THREADS>) : HIST_BYTES;
@@ -462,14 +473,14 @@ k_numeric_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col
     if (r >= count) return;
     const int64_t row = rows[r];
 
-    for (int s = tid; s < SLOTS; s += THREADS) { s_keys[s] = EMPTY_KEY; s_vals[s] = (V)0; }
+    for (int s = tid; s < SLOTS; s += THREADS) { s_keys[s] = EMPTY_KEY; s_vals[s] = (AV)0; }
     if (tid == 0) { s_ovf = 0; s_min = 0x7fffffff; s_max = -1; s_flag = 0; }
     __syncthreads();
 
     wg_traverse<THREADS, true>(a_col, a_val, a_rp[row], a_rp[row + 1],
                                [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
                                b_col, b_val, s_fc, [&](const auto &cj, const auto &cv) {
-                                   if (!lds_insert_batch<BITS>(s_keys, cj, cv, [&](int slot, V v, bool) { lds_add(&s_vals[slot], v); }))
+                                   if (!lds_insert_batch<BITS>(s_keys, cj, cv, [&](int slot, V v, bool) { lds_add(&s_vals[slot], (AV)v); }))
                                        s_ovf = 1;
                                });
     // wg_traverse ends with a barrier
@@ -535,10 +546,86 @@ k_numeric_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col
         for (int t = tid; t < c; t += THREADS) {
             const int32_t k2 = s_sort[t];
             out_col[o + t] = k2;
-            out_val[o + t] = s_vals[lds_find<BITS>(s_keys, k2)];
+            out_val[o + t] = (V)s_vals[lds_find<BITS>(s_keys, k2)];
         }
         if (tid == 0) row_nnz[row] = c;
     }
+}
+
+// ================================================== dense-range kernel ====
+// Dense accumulator (Section 2.2) over the row's own column range, for rows whose range [cmin, cmin + DS_MAX_COLS)
+// is no larger than the hash table they would get (Section 3.3, accumulator selection): one value and one presence
+// bit per column of the range in LDS, no keys, no probing, and the row leaves in column order by the bitmap's
+// prefix popcount.  QUERY: the presence bit is read first and set only when it is clear (Section 4.1).  A product
+// outside the range (B's rows not in column order: the range was a guess) makes the row report overflow, like a
+// row with more entries than were reserved for it; the caller redoes such rows with hash tables.
+constexpr int DS_THREADS = 256;
+constexpr int DS_WORDS = (int)DS_MAX_COLS / 32;
+template <typename V, bool QUERY>
+__global__ void __launch_bounds__(DS_THREADS)
+k_numeric_dspan(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col, const V *__restrict__ a_val,
+                const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_col, const V *__restrict__ b_val,
+                const int32_t *__restrict__ rows, int64_t count, const int32_t *__restrict__ cmin,
+                const int64_t *__restrict__ out_ptr, int32_t *__restrict__ out_col, V *__restrict__ out_val,
+                int32_t *__restrict__ row_nnz)
+{
+    static_assert(DS_WORDS <= DS_THREADS, "one bitmap word per thread in the prefix sum");
+    using AV = acc_t<V>;
+    __shared__ AV s_vals[DS_MAX_COLS];
+    __shared__ uint32_t s_bm[DS_WORDS];
+    __shared__ uint32_t s_pre[DS_WORDS];
+    __shared__ WgChunk<V, DS_THREADS> s_fc;
+    __shared__ int s_wave[DS_THREADS / WAVE];
+    __shared__ int s_bad;
+    const int tid = threadIdx.x;
+    const int64_t r = blockIdx.x;
+    if (r >= count) return;
+    const int64_t row = rows[r];
+    const int32_t c0 = cmin[row];
+    for (int j = tid; j < (int)DS_MAX_COLS; j += DS_THREADS) s_vals[j] = (AV)0;
+    if (tid < DS_WORDS) s_bm[tid] = 0u;
+    if (tid == 0) s_bad = 0;
+    __syncthreads();
+    wg_traverse<DS_THREADS, true>(a_col, a_val, a_rp[row], a_rp[row + 1],
+                                  [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
+                                  b_col, b_val, s_fc, [&](const auto &cj, const auto &cv) {
+                                      constexpr int U = sizeof(cj) / sizeof(cj[0]);
+#pragma unroll
+                                      for (int u = 0; u < U; ++u) {
+                                          if (cj[u] < 0) continue;
+                                          const uint32_t d = (uint32_t)(cj[u] - c0);   // (a column before c0 wraps to a large number)
+                                          if (d < (uint32_t)DS_MAX_COLS) {
+                                              lds_add(&s_vals[d], (AV)cv[u]);
+                                              const uint32_t bit = 1u << (d & 31u);
+                                              if (!QUERY || !(s_bm[d >> 5] & bit)) atomicOr(&s_bm[d >> 5], bit);
+                                          } else {
+                                              s_bad = 1;
+                                          }
+                                      }
+                                  });
+    // (wg_traverse ends with a barrier)
+    const uint32_t word = tid < DS_WORDS ? s_bm[tid] : 0u;
+    int total;
+    const int ex = block_exclusive_scan_i32<DS_THREADS>(__popc(word), s_wave, total);
+    if (tid < DS_WORDS) s_pre[tid] = (uint32_t)ex;
+    __syncthreads();
+    const int64_t o = out_ptr[row];
+    const int64_t cap = out_ptr[row + 1] - o;
+    if (s_bad || (int64_t)total > cap) {   // uniform
+        if (tid == 0) row_nnz[row] = -1;
+        return;
+    }
+    // thread t looks at columns t, t + 256, ...: the lanes of a wave read consecutive values and the present ones
+    // among them go to consecutive places of the output
+    for (int j = tid; j < (int)DS_MAX_COLS; j += DS_THREADS) {
+        const uint32_t wbits = s_bm[j >> 5];
+        if ((wbits >> (j & 31)) & 1u) {
+            const int rank = (int)s_pre[j >> 5] + __popc(wbits & ((1u << (j & 31)) - 1u));
+            out_col[o + rank] = c0 + j;
+            out_val[o + rank] = (V)s_vals[j];
+        }
+    }
+    if (tid == 0) row_nnz[row] = total;
 }
 
 // ======================================================= hybrid kernel ====
@@ -701,7 +788,7 @@ constexpr int ilog2_const(int x) { return x <= 1 ? 0 : 1 + ilog2_const(x >> 1); 
 
 template <typename V>
 struct DenseCfg {
-    static constexpr int WIN = HV_REGION / (int)sizeof(V);   // columns of a window: a region full of values
+    static constexpr int WIN = HV_REGION / (int)sizeof(acc_t<V>);   // columns of a window: a region full of accumulators
     static constexpr int WORDS = WIN / 32;
 };
 
@@ -726,22 +813,23 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     __shared__ long long s_row;
     static_assert(WORDS <= HV_THREADS, "the prefix counts of a dense window reuse the chunk's array of prefix sums");
     uint32_t *s_dpre = s_fc.excl;   // (free between the traversal of a pass and the next one)
-    V *s_vals = reinterpret_cast<V *>(s_u);                                        // dense: WIN values
+    using AV = acc_t<V>;
+    AV *s_vals = reinterpret_cast<AV *>(s_u);                                      // dense: WIN accumulators
     // sparse pass: staged products (column, value) by product number; once every thread holds its
     // products in registers the same memory takes the output (columns, accumulated values) by rank
     // Its memory is laid out per pass: the more windows a stretch spans, the more of the region goes to
     // the bitmap (WIN/8 bytes per window) and its prefix counts (WIN/16), the less to staged products
-    // (4 + sizeof(V) bytes each, in multiples of one product per thread).
+    // (4 + sizeof(AV) bytes each, in multiples of one product per thread).
     constexpr int OV = WIN / 8 + WIN / 16;
     auto sparse_cap = [](int run) {
-        const int c = (HV_REGION - run * OV) / (4 + (int)sizeof(V)) / HV_THREADS * HV_THREADS;
+        const int c = (HV_REGION - run * OV) / (4 + (int)sizeof(AV)) / HV_THREADS * HV_THREADS;
         return c > HV_HCAP ? HV_HCAP : (c < 0 ? 0 : c);
     };
     int32_t *s_scol = reinterpret_cast<int32_t *>(s_u);
     const int tid = threadIdx.x;
     const size_t stride = (size_t)n_win + 1;
 
-    for (int j = tid; j < WIN; j += HV_THREADS) s_vals[j] = (V)0;
+    for (int j = tid; j < WIN; j += HV_THREADS) s_vals[j] = (AV)0;
     for (int j = tid; j < WORDS; j += HV_THREADS) s_dbm[j] = 0u;
     bool dense_clean = true;   // the region is an all-zero dense window
 
@@ -846,14 +934,14 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
             const uint32_t n_hi = have0 ? t0[nx1] : 0u;
             // memory of a sparse pass (see above)
             const int scap = sparse_cap(w1 - w);
-            V *s_sval = reinterpret_cast<V *>(s_u + (size_t)scap * 4);
-            uint16_t *s_hpre = reinterpret_cast<uint16_t *>(s_u + (size_t)scap * (4 + sizeof(V)));
-            uint32_t *s_hbm = reinterpret_cast<uint32_t *>(s_u + (size_t)scap * (4 + sizeof(V)) + (size_t)(w1 - w) * (WIN / 16));
+            AV *s_sval = reinterpret_cast<AV *>(s_u + (size_t)scap * 4);
+            uint16_t *s_hpre = reinterpret_cast<uint16_t *>(s_u + (size_t)scap * (4 + sizeof(AV)));
+            uint32_t *s_hbm = reinterpret_cast<uint32_t *>(s_u + (size_t)scap * (4 + sizeof(AV)) + (size_t)(w1 - w) * (WIN / 16));
             const int hwords = (w1 - w) * (WIN / 32);
             // accumulator of this pass
             if (dense) {
                 if (!dense_clean) {
-                    for (int j = tid; j < WIN; j += HV_THREADS) s_vals[j] = (V)0;
+                    for (int j = tid; j < WIN; j += HV_THREADS) s_vals[j] = (AV)0;
                     dense_clean = true;
                 }
             } else {
@@ -871,7 +959,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                     for (int u = 0; u < U; ++u) {
                         const unsigned d = (unsigned)(cj[u] - col0);
                         if (cj[u] >= 0 && d < (unsigned)WIN) {   // d is in range for a consistent window table
-                            lds_add(&s_vals[d], cv[u]);
+                            lds_add(&s_vals[d], (AV)cv[u]);
                             // Section 4.1: with many products per output entry most presence bits are set already;
                             // reading the bit first then saves the write (a stale read only costs a redundant OR)
                             const uint32_t bit = 1u << (d & 31);
@@ -885,7 +973,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                         const uint32_t d = (uint32_t)(cj[u] - col0);
                         if (cj[u] >= 0 && at < (uint32_t)scap && d < (uint32_t)hwords * 32u) {   // both hold by construction
                             s_scol[at] = cj[u];
-                            s_sval[at] = cv[u];
+                            s_sval[at] = (AV)cv[u];
                             atomicOr(&s_hbm[d >> 5], 1u << (d & 31u));
                         }
                     }
@@ -919,7 +1007,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                     const int j = tid * wpt + q;
                     if (j < hwords) { s_hpre[j] = (uint16_t)run; run += __popc(s_hbm[j]); }
                 }
-                for (int i = tid; i < htotal; i += HV_THREADS) s_sval[i] = (V)0;   // (htotal <= products <= scap)
+                for (int i = tid; i < htotal; i += HV_THREADS) s_sval[i] = (AV)0;   // (htotal <= products <= scap)
                 __syncthreads();
 #pragma unroll
                 for (int i = 0; i < HV_PPT; ++i) {
@@ -927,7 +1015,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                     if (kc[i] >= 0 && d < (uint32_t)hwords * 32u) {
                         const int rank = (int)s_hpre[d >> 5] + __popc(s_hbm[d >> 5] & ((1u << (d & 31u)) - 1u));
                         s_scol[rank] = kc[i];           // products of one column all write the same id
-                        lds_add(&s_sval[rank], kv[i]);
+                        lds_add(&s_sval[rank], (AV)kv[i]);
                     }
                 }
                 __syncthreads();
@@ -935,7 +1023,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                 const int n_out = (long long)htotal < room ? htotal : (room > 0 ? (int)room : 0);
                 for (int i = tid; i < n_out; i += HV_THREADS) {
                     __builtin_nontemporal_store(s_scol[i], &out_col[o + done + i]);
-                    __builtin_nontemporal_store(s_sval[i], &out_val[o + done + i]);
+                    __builtin_nontemporal_store((V)s_sval[i], &out_val[o + done + i]);
                 }
                 done += htotal;
                 __syncthreads();
@@ -975,8 +1063,8 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                         const uint32_t wbits = s_dbm[j >> 5];
                         if ((wbits >> (j & 31)) & 1u) {
                             const long long rank = done + (long long)s_dpre[j >> 5] + __popc(wbits & ((1u << (j & 31)) - 1u));
-                            const V val = s_vals[j];
-                            s_vals[j] = (V)0;
+                            const V val = (V)s_vals[j];
+                            s_vals[j] = (AV)0;
                             if (rank < cap) { __builtin_nontemporal_store((int32_t)(col0 + j), &out_col[o + rank]); __builtin_nontemporal_store(val, &out_val[o + rank]); }
                         }
                     }
@@ -1002,16 +1090,16 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                     // every thread takes its share of the staged products into registers, with their ranks
                     if (staged > (uint32_t)scap) staged = scap;   // cannot happen: passes are planned from the counts
                     int32_t pc[HV_PPT];
-                    V pv[HV_PPT];
+                    AV pv[HV_PPT];
                     int pr[HV_PPT];
     #pragma unroll
                     for (int i = 0; i < HV_PPT; ++i) {
                         const uint32_t at = (uint32_t)i * HV_THREADS + tid;
-                        pc[i] = -1; pv[i] = V(); pr[i] = 0;
+                        pc[i] = -1; pv[i] = AV(); pr[i] = 0;
                         if (at < staged) {
                             pc[i] = s_scol[at];
                             pv[i] = s_sval[at];
-                            s_sval[at] = (V)0;   // (htotal <= staged: the values of the output start from zero)
+                            s_sval[at] = (AV)0;   // (htotal <= staged: the values of the output start from zero)
                             const uint32_t d = (uint32_t)(pc[i] - col0);
                             pr[i] = (int)s_hpre[d >> 5] + __popc(s_hbm[d >> 5] & ((1u << (d & 31u)) - 1u));
                         }
@@ -1030,7 +1118,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                     const int n_out = (long long)htotal < room ? htotal : (room > 0 ? (int)room : 0);
                     for (int i = tid; i < n_out; i += HV_THREADS) {
                         __builtin_nontemporal_store(s_scol[i], &out_col[o + done + i]);
-                        __builtin_nontemporal_store(s_sval[i], &out_val[o + done + i]);
+                        __builtin_nontemporal_store((V)s_sval[i], &out_val[o + done + i]);
                     }
                     done += htotal;
                     __syncthreads();
@@ -1093,7 +1181,8 @@ k_window_table(const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_c
 
 hipError_t launch_window_table(const Csr &B, int dtype, uint32_t *bw, int *n_win_out, int32_t *flags, hipStream_t s)
 {
-    const int win_log2 = dtype == OCEAN_F64 ? ilog2_const(HV_REGION / 8) : ilog2_const(HV_REGION / 4);
+    (void)dtype;
+    const int win_log2 = ilog2_const(HV_REGION / 8);   // (both value types accumulate in 8 bytes)
     const int n_win = (int)((B.cols + (1ll << win_log2) - 1) >> win_log2);
     *n_win_out = n_win;
     if (B.rows == 0) return hipSuccess;
@@ -1107,7 +1196,8 @@ int heavy_workgroups_per_cu() { return HV_WG_PER_CU; }
 
 int dense_window_count(int64_t n_cols, int dtype)
 {
-    const int win_log2 = dtype == OCEAN_F64 ? ilog2_const(HV_REGION / 8) : ilog2_const(HV_REGION / 4);
+    (void)dtype;
+    const int win_log2 = ilog2_const(HV_REGION / 8);   // (both value types accumulate in 8 bytes)
     return (int)((n_cols + (1ll << win_log2) - 1) >> win_log2);
 }
 
@@ -1289,6 +1379,15 @@ static hipError_t dispatch(const Csr &A, const Csr &B, const NumLaunch &l, int g
     case NB_S2K: OCEAN_WG(11, 512); break;
     case NB_S4K: OCEAN_WG(12, 512); break;
     case NB_S8K: OCEAN_WG(13, 1024); break;
+    case NB_DSPAN:
+        if (l.cmin == nullptr) return hipErrorInvalidValue;
+        if (l.query_bitmap)
+            hipLaunchKernelGGL((k_numeric_dspan<V, true>), dim3((unsigned)l.count), dim3(DS_THREADS), 0, s, A.rp, A.col, av, B.rp,
+                               B.col, bv, l.rows, l.count, l.cmin, l.out_ptr, l.out_col, ov, l.row_nnz);
+        else
+            hipLaunchKernelGGL((k_numeric_dspan<V, false>), dim3((unsigned)l.count), dim3(DS_THREADS), 0, s, A.rp, A.col, av, B.rp,
+                               B.col, bv, l.rows, l.count, l.cmin, l.out_ptr, l.out_col, ov, l.row_nnz);
+        break;
     case NB_HYBRID:
         if (l.bw != nullptr) return hipErrorInvalidValue;   // such rows go with the last bin
         else

@@ -251,6 +251,9 @@ struct Work {
     bool bins_clean = false;   // the bin counters are still zero from the clearing of all scalars
     int64_t *prod = nullptr;
     int32_t *maxb = nullptr;
+    int32_t *cmin = nullptr, *cmax = nullptr;            // column range a row can reach (k_row_spans)
+    int32_t *s_cmin = nullptr, *s_cmax = nullptr;        // the same of the sampled rows
+    bool spans = false;                                   // cmin / cmax hold the ranges of all rows
     uint8_t *bin = nullptr;
     int32_t *cap = nullptr;
     int32_t *row_nnz = nullptr;
@@ -277,6 +280,8 @@ int work_alloc(Ctx &c, Work &w, int64_t m, int64_t n_sample)
     const size_t o_scan = take((size_t)scan_tmp_elems(m) * 8 + 8);
     const size_t o_est = take(mm * 8);
     const size_t o_sr = take((size_t)(n_sample + 1) * 8), o_se = take((size_t)(n_sample + 1) * 8);
+    const size_t o_cmin = take(mm * 4), o_cmax = take(mm * 4);
+    const size_t o_scmin = take((size_t)(n_sample + 1) * 4), o_scmax = take((size_t)(n_sample + 1) * 4);
     char *b = static_cast<char *>(c.alloc(off));
     if (!b) return fail(OCEAN_EALLOC, "workspace allocation failed");
     w.base = b;
@@ -295,6 +300,10 @@ int work_alloc(Ctx &c, Work &w, int64_t m, int64_t n_sample)
     w.est = reinterpret_cast<double *>(b + o_est);
     w.sample_rows = reinterpret_cast<int64_t *>(b + o_sr);
     w.sample_est = reinterpret_cast<double *>(b + o_se);
+    w.cmin = reinterpret_cast<int32_t *>(b + o_cmin);
+    w.cmax = reinterpret_cast<int32_t *>(b + o_cmax);
+    w.s_cmin = reinterpret_cast<int32_t *>(b + o_scmin);
+    w.s_cmax = reinterpret_cast<int32_t *>(b + o_scmax);
     HIP_TRY(hipMemsetAsync(w.sc, 0, sizeof(Scalars), c.s));
     w.bins_clean = true;
     return OCEAN_OK;
@@ -392,15 +401,21 @@ int run_symbolic(Ctx &c, Work &w, const Csr &A, const Csr &B, int gb_log2, doubl
 }
 
 // ---- sampled compression ratio (Section 3.2) and its spread over the sample (Section 4.1) ------------
-int run_sample(Ctx &c, Work &w, const Csr &A, int64_t n_cols, const uint8_t *sketches, int m_regs, int64_t n_sample,
-               const ocean_options &o, ocean_stats *S)
+// With B given (dense_range = 1) the column ranges of the sampled rows are looked at too: S->dense_range_rows is
+// the number of sampled rows for which the dense accumulator over the row's range would be chosen.
+int run_sample(Ctx &c, Work &w, const Csr &A, const Csr *B, int vbytes, int64_t n_cols, const uint8_t *sketches, int m_regs,
+               int64_t n_sample, const ocean_options &o, ocean_stats *S)
 {
     HIP_TRY(launch_sample_rows(A.rows, n_sample, o.sample_seed, w.sample_rows, c.s));   // (= sample_rows_of on the host)
     HIP_TRY(launch_hll_merge(A, sketches, m_regs, w.sample_rows, n_sample, w.prod, w.maxb, nullptr, n_cols, w.sample_est,
                              nullptr, c.lanes_div, c.s));
-    HIP_TRY(launch_sample_reduce(w.sample_rows, n_sample, w.prod, w.sample_est, w.sc->sample_sums, c.s));
+    const bool ranges = B != nullptr && o.dense_range == 1;
+    if (ranges) HIP_TRY(launch_row_spans(A, *B, w.sample_rows, n_sample, w.s_cmin, w.s_cmax, c.s));
+    HIP_TRY(launch_sample_reduce(w.sample_rows, n_sample, w.prod, w.sample_est, ranges ? w.s_cmin : nullptr, w.s_cmax, n_cols,
+                                 vbytes, o.bound_load_coef, w.sc->sample_sums, c.s));
     OC_TRY(fetch_scalars(c, w.sc));
     const double *ss = c.h->sample_sums;
+    S->dense_range_rows = (int32_t)ss[5];
     S->sampled_cr = ss[1] > 0.0 ? ss[0] / ss[1] : 1.0;
     S->sampled_rows = (int32_t)n_sample;
     if (ss[4] > 0.0) {
@@ -430,11 +445,11 @@ int run_numeric(Ctx &c, Work &w, const Csr &A, const Csr &B, int dtype, int gb_l
     // With the window table, the column-window kernel takes every row beyond the 4096-slot table (measured:
     // a row of the 8192-slot bin costs less there than a hash table of its own; smaller rows do not).
     constexpr int HEAVY_FROM = NB_S8K;
-    int64_t start[NB_COUNT + 1];
+    int64_t start[NB_ALL + 1];
     start[0] = 0;
-    for (int b = 0; b < NB_COUNT; ++b) start[b + 1] = start[b] + (int64_t)count[b];
+    for (int b = 0; b < NB_ALL; ++b) start[b + 1] = start[b] + (int64_t)count[b];
     const size_t vbytes = dtype == OCEAN_F64 ? 8 : 4;
-    for (int b = NB_COUNT - 1; b >= 0; --b) {
+    for (int b = NB_ALL - 1; b >= 0; --b) {
         NumLaunch l{};
         l.rows = w.bin_rows + start[b];
         l.count = start[b + 1] - start[b];
@@ -445,6 +460,10 @@ int run_numeric(Ctx &c, Work &w, const Csr &A, const Csr &B, int dtype, int gb_l
         l.row_nnz = row_nnz;
         l.coef = global_coef;
         l.fine_buckets = c.fine_buckets;
+        if (b == NB_DSPAN) {   // rows whose column range got them the dense accumulator over that range
+            l.cmin = w.cmin;
+            l.query_bitmap = c.query_bitmap;
+        }
         if (c.bw != nullptr && b >= HEAVY_FROM && b < NB_GLOBAL) continue;   // went with the last bin, see below
         if (!esc && b == NB_E16) continue;   // same kernel as the 32-slot bin: one launch for both (adjacent row lists)
         if (!esc && b == NB_G8) {
@@ -604,6 +623,7 @@ void fill_defaults(ocean_options *o)
     o->tuned_cr_bound = 1.5;
     o->bound_load_coef = 1.15;
     o->estimate_table_coef = 1.75;
+    o->dense_range = 1;
     o->bitmap_query_cr = 2.0;
     o->allocator = nullptr;
 }
@@ -747,7 +767,7 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
         } else {
             OC_TRY(build_sketches());
             OC_TRY(mark(c, OCEAN_ST_SAMPLE));
-            OC_TRY(run_sample(c, w, A, n, sketches, m_regs, n_sample, o, S));
+            OC_TRY(run_sample(c, w, A, &B, (int)vbytes, n, sketches, m_regs, n_sample, o, S));
             workflow = o.selector == OCEAN_SEL_MI355X
                            ? select_tuned(S->avg_products, S->er, S->sampled_cr, (double)P, (double)S->heavy_products, o)
                            : select_of(S->avg_products, S->er, S->sampled_cr, o);
@@ -756,7 +776,7 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
     if (workflow == OCEAN_WF_SYMBOLIC && o.assisted_symbolic == 2 && S->sampled_rows == 0) {
         OC_TRY(build_sketches());
         OC_TRY(mark(c, OCEAN_ST_SAMPLE));
-        OC_TRY(run_sample(c, w, A, n, sketches, m_regs, n_sample, o, S));
+        OC_TRY(run_sample(c, w, A, &B, (int)vbytes, n, sketches, m_regs, n_sample, o, S));
     }
 
     // Section 4.1 / 4.3: dense accumulators query the bitmap before writing when the (sampled) CR is at least 2
@@ -766,6 +786,15 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
     const bool query_bitmap = o.bitmap_query == 2;
     Csr Bnum = B;   // what the numeric kernels read: B, or a copy of it with sorted rows (see below)
     bool tried_sorted_copy = false;
+    // Section 3.3, accumulator selection: rows whose column range is no larger than the hash table they would get
+    // use the dense accumulator over that range.  The ranges of all rows cost a pass over A; it is taken when the
+    // sample found such rows (2 % of it or more) or when told to (dense_range = 2), and not when B's rows are known
+    // to be out of column order (first and last entry of a row then say nothing about its range).
+    if ((o.dense_range == 2 || (o.dense_range == 1 && S->sampled_rows > 0 && (int64_t)S->dense_range_rows * 50 >= S->sampled_rows)) &&
+        !(c.h->flags & 8)) {
+        HIP_TRY(launch_row_spans(A, B, nullptr, m, w.cmin, w.cmax, c.s));
+        w.spans = true;
+    }
     int32_t *t_col = nullptr;   // output region of the first attempt (C itself on the two-pass path)
     void *t_val = nullptr;
     int64_t total_slots = 0;
@@ -778,6 +807,11 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
         for (int b = 0; b < NB_COUNT; ++b) bp.slots[b] = kNumericSlots[b];
         bp.n_cols = n;
         double global_coef = 1.25;
+        if (w.spans) {
+            bp.cmin = w.cmin;
+            bp.cmax = w.cmax;
+            bp.vbytes = (int)vbytes;
+        }
         if (workflow == OCEAN_WF_HLL) {
             OC_TRY(build_sketches());
             OC_TRY(mark(c, OCEAN_ST_PREDICT));
@@ -807,10 +841,10 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
         HIP_TRY(launch_classify(m, bp, o.estimate_scale, w.prod, w.est, w.nnz_final, nullptr, nullptr, w.bin, w.cap,
                                 w.sc->bin_count, w.sc->bin_prod, &w.sc->max_cap, c.s));
         HIP_TRY(launch_scan_i32_to_i64(w.cap, m, ptr, w.scan_tmp, &w.sc->totals[0], c.s));   // totals[0]: total slots
-        HIP_TRY(launch_scatter(m, NB_COUNT, w.bin, w.sc->bin_count, w.sc->bin_cursor, w.bin_rows, c.s));
+        HIP_TRY(launch_scatter(m, NB_ALL, w.bin, w.sc->bin_count, w.sc->bin_cursor, w.bin_rows, c.s));
         OC_TRY(fetch_scalars(c, w.sc));
         total_slots = (int64_t)c.h->totals[0];
-        for (int b = 0; b < NB_COUNT; ++b) S->rows_per_bin[b] = (int64_t)c.h->bin_count[b];
+        for (int b = 0; b < NB_ALL; ++b) S->rows_per_bin[b] = (int64_t)c.h->bin_count[b];
         c.bw = (bw_try != nullptr && !(c.h->flags & 8)) ? bw_try : nullptr;
         if (bw_try != nullptr && (c.h->flags & 8) && !tried_sorted_copy && o.sort_b_ratio > 0.0 &&
             (double)S->heavy_products >= o.sort_b_ratio * (double)B.nnz) {
@@ -895,8 +929,9 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
     // ---- overflow rows: redo them with bound-sized tables (Section 3.2) ----
     S->temp_slots = total_slots;
     OC_TRY(mark(c, workflow == OCEAN_WF_UPPER_BOUND ? OCEAN_ST_COMPACT : OCEAN_ST_RETRY));
-    // (sizes from the product bound cannot fall short: nothing to count in the upper-bound workflow)
-    if (workflow != OCEAN_WF_UPPER_BOUND) HIP_TRY(launch_count_overflow(m, w.row_nnz, &w.sc->ovf_count, c.s));
+    // (sizes from the product bound cannot fall short: nothing to count in the upper-bound workflow, unless rows ran
+    // with the dense accumulator over a guessed column range)
+    if (workflow != OCEAN_WF_UPPER_BOUND || w.spans) HIP_TRY(launch_count_overflow(m, w.row_nnz, &w.sc->ovf_count, c.s));
     // optimistic: if nothing overflowed this scan already is the final row_ptr
     HIP_TRY(launch_scan_i32_to_i64(w.row_nnz, m, c_rp, w.scan_tmp, &w.sc->totals[0], c.s));
     OC_TRY(fetch_scalars(c, w.sc));
@@ -1211,7 +1246,7 @@ int ocean_symbolic(const ocean_csr *A, const ocean_csr *B, int32_t *nnz_per_row,
             if (!sketches) return fail(OCEAN_EALLOC, "sketch allocation failed");
             c.lanes_div = lanes_div_of(S);
             HIP_TRY(launch_hll_sketch(b, m_regs, sketches, c.lanes_div, c.s));
-            OC_TRY(run_sample(c, w, a, b.cols, sketches, m_regs, n_sample, o, S));
+            OC_TRY(run_sample(c, w, a, nullptr, 8, b.cols, sketches, m_regs, n_sample, o, S));
             S->hll_registers = m_regs;
             assist_cr = conservative_cr(S, o);
             if (!(assist_cr > 1.0)) assist_cr = 0.0;

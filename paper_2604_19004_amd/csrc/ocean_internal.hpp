@@ -47,6 +47,18 @@ constexpr int32_t kSymbolicSlots[SB_COUNT] = {64, 256, 1024, 4096, 16384, 32768,
 
 constexpr int32_t BIN_NONE = 255;          // row takes no part in this launch set
 
+// Dense accumulator over a row's own column range (Section 3.3, accumulator selection: the kind that needs fewer
+// resources, dense when both need the same): values and one presence bit per column of the range against keys
+// and values of a hash table.  Rows of the 512-slot bin and beyond are candidates; the range must fit the
+// kernel's LDS window.
+constexpr int NB_DSPAN = NB_COUNT;          // index of that bin in the per-bin arrays (after the hash bins)
+constexpr int NB_ALL = NB_COUNT + 1;
+constexpr int64_t DS_MAX_COLS = 4096;
+__host__ __device__ inline bool dense_span_pays(long long span, long long slots, int vbytes)
+{
+    return span > 0 && span <= DS_MAX_COLS && slots >= 512 && span * (8 * vbytes + 1) <= slots * 8 * (4 + vbytes);
+}
+
 // ------------------------------------------------------------- CSR view ----
 struct Csr {
     const int64_t *rp;
@@ -193,8 +205,13 @@ hipError_t launch_hll_merge(const Csr &A, const uint8_t *sketches, int m, const 
                             const int64_t *prod, const int32_t *maxb, const int64_t *b_rp, int64_t b_cols,
                             double *est, uint8_t *merged, int lanes_div, hipStream_t s);
 hipError_t launch_sample_rows(int64_t rows, int64_t ns, uint32_t seed, int64_t *out, hipStream_t s);
+hipError_t launch_row_spans(const Csr &A, const Csr &B, const int64_t *rows, int64_t n, int32_t *cmin, int32_t *cmax,
+                            hipStream_t s);
 hipError_t launch_sample_reduce(const int64_t *rows, int64_t n_rows, const int64_t *prod, const double *est,
-                                double *out /*[5]: sum prod, sum est, sum cr, sum cr^2, rows*/, hipStream_t s);
+                                const int32_t *cmin, const int32_t *cmax /*of the sampled rows, may be null*/,
+                                int64_t n_cols, int vbytes, double bound_coef,
+                                double *out /*[6]: sum prod, sum est, sum cr, sum cr^2, rows, rows a dense range pays for*/,
+                                hipStream_t s);
 
 // binning.hip
 struct BinParams {
@@ -205,6 +222,9 @@ struct BinParams {
                          // reserved output stays coef x estimate
     double bound_coef;   // table slots per intermediate product beyond which a table is of no use (modes 0, 1, 2;
                          // at most 1.0 = the product bound itself)
+    const int32_t *cmin; // per row: first and last column the row can reach (k_row_spans), or null: rows whose range
+    const int32_t *cmax; // pays for it go to the dense-range bin NB_DSPAN (modes 0, 1, 2)
+    int vbytes;          // bytes of a value (with cmin)
     int n_bins;
     int32_t slots[OCEAN_MAX_BINS];
     int64_t n_cols;
@@ -265,6 +285,7 @@ struct NumLaunch {
     int n_win;
     bool query_bitmap;        // dense windows: read a column's presence bit before setting it (Section 4.1)
     bool fine_buckets;        // 512- and 1024-slot bins: order the row through 2048 column buckets (clustered columns)
+    const int32_t *cmin;      // dense-range bin: first column each row can reach
 };
 hipError_t launch_window_table(const Csr &B, int dtype, uint32_t *bw, int *n_win_out, int32_t *flags, hipStream_t s);
 int heavy_workgroups_per_cu();   // workgroups of the column-window kernel that one compute unit holds

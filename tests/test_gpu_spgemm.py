@@ -547,6 +547,76 @@ def test_random_matrices(ob, seed):
         check_result(Cd, ref, A, f"random seed={seed} case={case} {wf}")
 
 
+def _blocks_case(rng, dtype, communities=48, size=1024, density=0.05, linked=0.0, shuffle_b=False):
+    """Block-diagonal matrix: `communities` blocks of `size` nodes, every ordered pair inside a block kept with
+    probability `density`; a share `linked` of the rows also gets two entries anywhere.  Rows of A*A inside the
+    blocks reach only their block's columns."""
+    n = communities * size
+    rows, cols = [], []
+    for c in range(communities):
+        mask = rng.random((size, size)) < density
+        r, q = np.nonzero(mask)
+        rows.append(r + c * size); cols.append(q + c * size)
+    rows = np.concatenate(rows); cols = np.concatenate(cols)
+    far = np.nonzero(rng.random(n) < linked)[0]
+    rows = np.concatenate([rows, np.repeat(far, 2)]); cols = np.concatenate([cols, rng.integers(0, n, 2 * far.size)])
+    key = np.unique(rows.astype(np.int64) * n + cols)
+    r, q = key // n, (key % n).astype(np.int32)
+    rp = np.concatenate([[0], np.cumsum(np.bincount(r, minlength=n))]).astype(np.int64)
+    A = CSR(n, n, rp, q, rng.uniform(0.5, 1.5, q.size).astype(dtype))
+    if not shuffle_b:
+        return A, A
+    qb = q.copy()
+    for i in range(n):
+        rng.shuffle(qb[rp[i]:rp[i + 1]])
+    vb = rng.uniform(0.5, 1.5, q.size).astype(dtype)
+    return A, CSR(n, n, rp, qb, vb)
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_dense_accumulator_over_the_rows_column_range(ob, dtype):
+    """Accumulator selection (Section 3.3): rows whose column range is no larger than their hash table would be are
+    accumulated densely over that range.  Block-diagonal input: every row qualifies; with far links on 1 % of the
+    rows those rows and the rows that reach them (about 40 % of all) stay with the hash kernels: both kinds in one call."""
+    rng = np.random.default_rng(31)
+    nb = len(ob.bin_layout()[0])          # index of the dense-range bin in rows_per_bin
+    for linked in (0.0, 0.01):
+        A, B = _blocks_case(rng, dtype, linked=linked)
+        ref = O.multiply_rows(A, B)
+        dA = ob.to_device(A)
+        # AUTO: the sample finds the rows, the ranges of all rows are computed
+        Cd, st = ob.spgemm(dA, dA)
+        check_result(Cd, ref, A, f"blocks linked={linked} auto")
+        assert st["dense_range_rows"] > 0 and st["rows_per_bin"][nb] > 0, st
+        if linked:
+            assert 0 < st["rows_per_bin"][nb] < A.rows
+        else:
+            assert st["rows_per_bin"][nb] == A.rows
+        for wf in ("upper_bound", "hll", "symbolic"):
+            Cd, st = ob.spgemm(dA, dA, workflow=wf_id(ob, wf), dense_range=2)
+            check_result(Cd, ref, A, f"blocks linked={linked} {wf}")
+            assert st["rows_per_bin"][nb] > 0
+            Cd, st0 = ob.spgemm(dA, dA, workflow=wf_id(ob, wf), dense_range=0)
+            check_result(Cd, ref, A, f"blocks linked={linked} {wf}, hash only")
+            assert st0["rows_per_bin"][nb] == 0
+        # estimates too small: rows of the dense bin overflow their reservation and are redone
+        Cd, st = ob.spgemm(dA, dA, workflow=ob.WF_HLL, dense_range=2, estimate_scale=0.3)
+        check_result(Cd, ref, A, f"blocks linked={linked} hll, scaled estimates")
+        assert st["overflow_rows"] > 0
+
+
+def test_dense_range_with_rows_of_b_out_of_order(ob):
+    """The range comes from the first and last entry of the rows of B: with B's rows shuffled it is wrong, the kernel
+    notices the first product outside it, the row counts as overflowed and is redone with a hash table."""
+    rng = np.random.default_rng(32)
+    A, B = _blocks_case(rng, np.float64, communities=8, shuffle_b=True)
+    ref = O.multiply_rows(A, B)
+    Cd, st = ob.spgemm(ob.to_device(A), ob.to_device(B), workflow=ob.WF_UPPER_BOUND, dense_range=2)
+    check_result(Cd, ref, A, "blocks, B shuffled")
+    nb = len(ob.bin_layout()[0])
+    assert st["rows_per_bin"][nb] > 0 and st["overflow_rows"] > 0
+
+
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
 def test_column_ids_up_to_the_int32_limit(ob, dtype):
     """B with 2^31 - 1 columns and entries from column 0 to column 2^31 - 2.  The oracle's dense accumulator cannot
