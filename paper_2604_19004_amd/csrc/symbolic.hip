@@ -207,15 +207,16 @@ k_symbolic_bitmap(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ 
     int64_t fp0;
     uint32_t flen;
     first_segment(e0, e1, fp0, flen);
-    auto mark = [&](const auto &cj, uint32_t w0) {
+    auto mark = [&](const auto &cj, uint32_t w0, auto all_valid) {
         constexpr int U = sizeof(cj) / sizeof(cj[0]);
+        constexpr bool ALL = decltype(all_valid)::value;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             // (32-bit arithmetic: a column before the window wraps to a large number)
-            const uint32_t d = (uint32_t)cj[u] - w0;
+            const uint32_t d = ONE_WINDOW ? (uint32_t)cj[u] : (uint32_t)cj[u] - w0;
             // Only the number of set bits matters, so neighbouring columns (the sorted entries of one row of
             // B in neighbouring lanes) go to neighbouring words, i.e. different LDS banks, not to one word.
-            if (cj[u] >= 0 && (ONE_WINDOW || d < (uint32_t)BM_WIN)) {
+            if ((ALL || cj[u] >= 0) && (ONE_WINDOW || d < (uint32_t)BM_WIN)) {
                 const uint32_t bit = 1u << (d / (uint32_t)BM_WORDS);
                 uint32_t *word = &s_bm[d & (uint32_t)(BM_WORDS - 1)];
                 if (!QUERY || !(*word & bit)) atomicOr(word, bit);
@@ -232,7 +233,9 @@ k_symbolic_bitmap(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ 
         uint32_t flenn = 0u;
         const int64_t ne = e1 - e0;
         for (int64_t w0 = 0; w0 < n_cols; w0 += BM_WIN) {
-            auto f = [&](const auto &cj, const auto &) { mark(cj, (uint32_t)w0); };
+            auto f = [&](const auto &cj, const auto &, auto... tag) {
+                mark(cj, (uint32_t)w0, std::bool_constant<(std::is_same_v<decltype(tag), AllValid> || ...)>{});
+            };
             if (ne > 0)
                 wg_flat_chunk<BM_THREADS, false, BM_U>(s_fc, ne < BM_THREADS ? (int)ne : BM_THREADS, fp0, flen, NoVal(), b_col,
                                                        (const NoVal *)nullptr, f);

@@ -31,6 +31,11 @@ namespace ocean {
 constexpr int T_LONG = 128;
 constexpr int FLAT_U = 4;
 
+// Third argument of an accumulator's batch function when every column id of the batch is a real one.
+struct AllValid {};
+// 16 bytes of column ids at any 4-byte boundary (one load instruction).
+struct alignas(4) Int4U { int32_t v[4]; };
+
 // Products p0 + lane, p0 + lane + STRIDE, ... of one segment, UNROLL loads in flight per lane.
 template <int STRIDE, int UNROLL, bool HAS_VAL, typename V, typename F>
 __device__ __forceinline__ void exec_segment(const int32_t *__restrict__ b_col, const V *__restrict__ b_val,
@@ -148,7 +153,7 @@ template <typename V, int THREADS, int RPT = 16>
 struct WgChunk {
     static constexpr uint32_t RANK_CAP = (uint32_t)RPT * THREADS;   // most products of a chunk whose entries are found by rank
     static constexpr int START_WORDS = THREADS * RPT / 32 + 32;
-    uint32_t excl[THREADS];
+    uint32_t excl[THREADS + 1];
     long long pbase[THREADS];
     V a[THREADS];
     union alignas(8) {
@@ -157,6 +162,8 @@ struct WgChunk {
     };
     uint32_t wsum[THREADS / WAVE];
     uint32_t wcnt[THREADS / WAVE];
+    uint32_t wsumr[THREADS / WAVE];
+    uint32_t next;                         // first product of the next batch nobody has taken yet
 };
 
 // The whole workgroup flattens the `nent` (1..THREADS) segments held by its first nent threads
@@ -193,6 +200,14 @@ __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS, RPT> &c, i
     // non-empty segments are numbered on their own
     const unsigned long long live = __ballot(len > 0);
     if (lane == WAVE - 1) { c.wsum[wave] = incl; c.wcnt[wave] = (uint32_t)__popcll(live); }
+    // column ids only: the same sums over the lengths rounded up to whole runs of WU (see below)
+    constexpr bool RUNS = !HAS_VAL && WU % 4 == 0;
+    const uint32_t lenr = (len + (uint32_t)(WU - 1)) & ~(uint32_t)(WU - 1);
+    uint32_t inclr = 0;
+    if constexpr (RUNS) {
+        inclr = wave_inclusive_scan_u32(lenr);
+        if (lane == WAVE - 1) c.wsumr[wave] = inclr;
+    }
     __syncthreads();
     uint32_t total, ctotal;
     const uint32_t before = waves_before_u32<NW>(c.wsum, wave, total);
@@ -264,6 +279,102 @@ __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS, RPT> &c, i
                 }
                 if constexpr (std::is_invocable_v<F &, int32_t(&)[WU], V(&)[WU], uint32_t>) f(cj, cv, q0);
                 else f(cj, cv);
+            }
+        }
+        __syncthreads();
+        return total;
+    }
+    if constexpr (RUNS) {
+        // Column ids only (the symbolic pass: whole rows of B, mostly long ones, and a set of columns as the
+        // result, so that a column seen twice does no harm).  Every lane takes a run of WU consecutive entries
+        // of ONE segment with 16-byte loads: the segments are laid out with their lengths rounded up to whole
+        // runs, so no run straddles two segments; the last run of a segment is moved back to end with the
+        // segment (it repeats entries of the run before), and a lane past the end of the chunk repeats the last
+        // run.  Only a segment shorter than one run needs loads of single entries.  One search per lane and
+        // batch finds the segment; excl[e + 1] carries in its low bits by how much segment e was rounded up.
+        uint32_t totalr;
+        inclr += waves_before_u32<NW>(c.wsumr, wave, totalr);
+        if (tid < nent) {
+            c.excl[tid + 1] = inclr | (lenr - len);
+            c.pbase[tid] = (long long)p0 - (long long)(inclr - lenr);
+        }
+        if (tid == 0) {
+            c.excl[0] = 0u;
+            c.next = 0u;
+        }
+        __syncthreads();
+        constexpr uint32_t LOW = (uint32_t)(WU - 1);
+        int bshift = 8;
+        while (((totalr - 1) >> bshift) >= (uint32_t)(THREADS - 1)) ++bshift;
+        const int nblk = (int)((totalr - 1) >> bshift) + 1;
+        const int top = nent > 1 ? 1 << (31 - __clz(nent - 1)) : 0;
+        if (tid <= nblk) {
+            int pos = nent - 1;
+            if (tid < nblk) {
+                const uint32_t q = ((uint32_t)tid << bshift) | LOW;
+                pos = 0;
+                for (int step = top; step > 0; step >>= 1) {
+                    const int t = pos + step;
+                    const uint32_t ex = c.excl[t < nent ? t : nent - 1];
+                    pos = (t < nent && ex <= q) ? t : pos;   // last entry starting at or before q (skips empty ones)
+                }
+            }
+            c.first[tid] = (uint16_t)pos;
+        }
+        __syncthreads();
+        // Batches are handed out one at a time from a counter in LDS, the ticket of the next one being drawn
+        // before the current one is worked on: batches differ in cost (searches are longer where segments are
+        // short, and the short segments of a chunk sit together, the entries of a row of A being in column
+        // order), so equal shares of the products would not be equal shares of the time.
+        auto draw = [&]() {
+            uint32_t t = 0u;
+            if (lane == 0) t = atomicAdd(&c.next, (uint32_t)(WAVE * WU));
+            return t;
+        };
+        uint32_t ticket = draw();
+        for (;;) {
+            const uint32_t q0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)ticket);
+            if (q0 >= totalr) break;   // uniform
+            ticket = draw();
+            const uint32_t qlast = q0 + WAVE * WU - 1 < totalr - 1 ? q0 + WAVE * WU - 1 : totalr - 1;
+            const int lo = c.first[q0 >> bshift];
+            const int hi = c.first[(qlast >> bshift) + 1];   // the entry of a later run, or the last entry
+            const int width = __builtin_amdgcn_readfirstlane(hi - lo);
+            uint32_t q = q0 + (uint32_t)lane * WU;
+            q = q < totalr ? q : totalr - (uint32_t)WU;   // (q0 <= totalr - WU: both are multiples of WU)
+            const uint32_t key = q | LOW;
+            int fp = lo;
+            for (int step = width > 0 ? 1 << (31 - __clz(width)) : 0; step > 0; step >>= 1) {
+                const int t = fp + step;
+                const uint32_t ex = c.excl[t <= hi ? t : hi];
+                fp = (t <= hi && ex <= key) ? t : fp;
+            }
+            const uint32_t endw = c.excl[fp + 1];
+            const uint32_t begin = c.excl[fp] & ~LOW;
+            const long long pb = c.pbase[fp];
+            const uint32_t nvalid = (endw & ~LOW) - (endw & LOW) - q;   // entries of the segment from q on: >= 1
+            const bool tail = nvalid < (uint32_t)WU;
+            const bool tiny = tail && q == begin;   // the whole segment is shorter than a run
+            const uint32_t back = tail && !tiny ? (uint32_t)WU - nvalid : 0u;
+            const int32_t *src = b_col + (pb + (long long)q - (long long)back);
+            V cv[WU] = {};
+            if (__ballot(tiny) == 0ull) {   // uniform
+                const Int4U *src4 = reinterpret_cast<const Int4U *>(src);
+#pragma unroll
+                for (int g = 0; g < WU / 4; ++g) {
+                    const Int4U x = src4[g];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) cj[g * 4 + i] = x.v[i];
+                }
+                if constexpr (std::is_invocable_v<F &, int32_t(&)[WU], V(&)[WU], AllValid>) f(cj, cv, AllValid{});
+                else f(cj, cv);
+            } else {
+#pragma unroll
+                for (int u = 0; u < WU; ++u) {
+                    cj[u] = -1;
+                    if (!tiny || (uint32_t)u < nvalid) cj[u] = src[u];
+                }
+                f(cj, cv);
             }
         }
         __syncthreads();
