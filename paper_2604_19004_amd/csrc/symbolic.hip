@@ -162,7 +162,7 @@ k_symbolic_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_co
 
 // --------------------------------------------------------- bitmap kernel
 constexpr int BM_THREADS = 1024;
-constexpr int BM_U = 8;                  // column ids per lane and batch (long rows of B: measured 10 % faster than 4)
+constexpr int BM_U = 16;                 // column ids per lane and batch (R-MAT: 16.2 ms against 16.9 with 8, 20.9 with 4)
 constexpr int BM_WIN = 1 << 20;          // columns per window
 constexpr int BM_WORDS = BM_WIN / 32;    // 32768 words = 128 KB
 
@@ -175,38 +175,45 @@ k_symbolic_bitmap(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ 
                   const int32_t *__restrict__ rows, int64_t count, int64_t n_cols,
                   unsigned long long *queue, int32_t *__restrict__ nnz_out)
 {
-    __shared__ uint32_t s_bm[BM_WORDS];
+    __shared__ __align__(16) uint32_t s_bm[BM_WORDS];
     __shared__ WgChunk<NoVal, BM_THREADS> s_fc;
-    __shared__ int s_count;
-    // Rows come from a shared counter.  The chain counter -> row id -> offsets of the row costs three memory
-    // round trips before the first entry of a row can be read, so it runs ahead of the work: the ticket of
-    // the row three turns ahead is drawn, the row id two turns ahead and the offsets one turn ahead are
-    // loaded while the current row is traversed (s_ticket: ring of four tickets; count >= 1).
-    __shared__ unsigned long long s_ticket[4];
+    // Rows come from a shared counter.  The chain counter -> row id -> offsets of the row -> entries -> their
+    // segments of B is five memory round trips before the first column id of a row can be asked for, so it runs
+    // ahead of the work, one link per turn: at the start of a turn the ticket of the row six turns ahead is
+    // drawn and the row id (four ahead), the offsets (three), the first BM_THREADS entries (two) and their
+    // segments (one) are asked for, all of which arrive under the traversal of the current row.  s_ticket: ring
+    // of eight tickets (count >= 1); a ticket is first read two turns after it was stored, behind the barriers
+    // of the turn between, and the row counts alternate between two cells, so a turn ends without a barrier.
+    __shared__ unsigned long long s_ticket[8];
+    __shared__ int s_count[2];
     const int tid = threadIdx.x;
     for (int s = tid; s < BM_WORDS; s += BM_THREADS) s_bm[s] = 0u;
     if (tid == 0) {
-        for (int j = 0; j < 3; ++j) s_ticket[j] = atomicAdd(queue, 1ull);
-        s_count = 0;
+        for (int j = 0; j < 6; ++j) s_ticket[j] = atomicAdd(queue, 1ull);
+        s_count[0] = s_count[1] = 0;
     }
     __syncthreads();
     // a ticket beyond the list stands for no row; its loads use the list's first row instead
-    auto list_pos = [&](unsigned long long t) { return t < (unsigned long long)count ? count - 1 - (int64_t)t : (int64_t)0; };
-    int64_t row = rows[list_pos(s_ticket[0])];     // row of this turn (the rows with the largest bounds are at the end)
-    int64_t row1 = rows[list_pos(s_ticket[1])];    // row of the next turn
-    int64_t e0 = a_rp[row], e1 = a_rp[row + 1];
-    // the segments of B that the first BM_THREADS entries of the row expand to are fetched a turn ahead as well
-    auto first_segment = [&](int64_t f0, int64_t f1, int64_t &p0, uint32_t &len) {
+    auto row_of = [&](unsigned turn) {
+        const unsigned long long t = s_ticket[turn & 7u];
+        return (int64_t)rows[t < (unsigned long long)count ? count - 1 - (int64_t)t : (int64_t)0];   // (the largest bounds are at the end)
+    };
+    auto entry_of = [&](int64_t f0, int64_t f1) { return f0 + tid < f1 ? a_col[f0 + tid] : (int32_t)-1; };
+    auto segment_of = [&](int32_t k, int64_t &p0, uint32_t &len) {
         p0 = 0; len = 0u;
-        if (f0 + tid < f1) {
-            const int32_t k = a_col[f0 + tid];
+        if (k >= 0) {
             p0 = b_rp[k];
             len = (uint32_t)(b_rp[k + 1] - p0);
         }
     };
+    int64_t row = row_of(0), row1 = row_of(1), row2 = row_of(2), row3 = row_of(3);
+    int64_t e0 = a_rp[row], e1 = a_rp[row + 1];
+    int64_t e0_1 = a_rp[row1], e1_1 = a_rp[row1 + 1];
+    int64_t e0_2 = a_rp[row2], e1_2 = a_rp[row2 + 1];
+    int32_t k1 = entry_of(e0_1, e1_1);
     int64_t fp0;
     uint32_t flen;
-    first_segment(e0, e1, fp0, flen);
+    segment_of(entry_of(e0, e1), fp0, flen);
     auto mark = [&](const auto &cj, uint32_t w0, auto all_valid) {
         constexpr int U = sizeof(cj) / sizeof(cj[0]);
         constexpr bool ALL = decltype(all_valid)::value;
@@ -224,13 +231,15 @@ k_symbolic_bitmap(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ 
         }
     };
     for (unsigned turn = 0;; ++turn) {
-        if (s_ticket[turn & 3u] >= (unsigned long long)count) break;   // uniform exit (tickets only grow)
+        if (s_ticket[turn & 7u] >= (unsigned long long)count) break;   // uniform exit (tickets only grow)
         unsigned long long drawn = 0;
-        if (tid == 0) drawn = atomicAdd(queue, 1ull);                  // ticket of turn + 3
-        const int64_t row2 = rows[list_pos(s_ticket[(turn + 2u) & 3u])];
-        const int64_t e0n = a_rp[row1], e1n = a_rp[row1 + 1];
-        int64_t fp0n = 0;
-        uint32_t flenn = 0u;
+        if (tid == 0) drawn = atomicAdd(queue, 1ull);                  // ticket of turn + 6
+        const int64_t row4 = row_of(turn + 4u);
+        const int64_t e0_3 = a_rp[row3], e1_3 = a_rp[row3 + 1];
+        const int32_t k2 = entry_of(e0_2, e1_2);
+        int64_t fp0_1;
+        uint32_t flen_1;
+        segment_of(k1, fp0_1, flen_1);
         const int64_t ne = e1 - e0;
         for (int64_t w0 = 0; w0 < n_cols; w0 += BM_WIN) {
             auto f = [&](const auto &cj, const auto &, auto... tag) {
@@ -243,32 +252,30 @@ k_symbolic_bitmap(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ 
                 wg_traverse<BM_THREADS, false, BM_U>(a_col, (const NoVal *)nullptr, e0 + BM_THREADS, e1,
                                                      [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
                                                      b_col, (const NoVal *)nullptr, s_fc, f);
-            __syncthreads();
-            // the entries of the next row's first chunk are loaded under the sweep of the bitmap, their
-            // segments of B under the rest of the turn
-            const bool last_window = w0 + BM_WIN >= n_cols;
-            const bool has_next = last_window && e0n + tid < e1n;
-            int32_t kn = 0;
-            if (has_next) kn = a_col[e0n + tid];
+            // (both end with a barrier)  count and clear the window, 16 bytes per thread and step
             int c = 0;
-            for (int s = tid; s < BM_WORDS; s += BM_THREADS) { c += __popc(s_bm[s]); s_bm[s] = 0u; }
-            c = group_reduce_sum(c, WAVE);
-            if (lane_id() == 0 && c) atomicAdd(&s_count, c);
-            if (has_next) {
-                fp0n = b_rp[kn];
-                flenn = (uint32_t)(b_rp[kn + 1] - fp0n);
+            uint4 *bm4 = reinterpret_cast<uint4 *>(s_bm);
+#pragma unroll
+            for (int s = 0; s < BM_WORDS / 4 / BM_THREADS; ++s) {
+                const uint4 x = bm4[s * BM_THREADS + tid];
+                c += __popc(x.x) + __popc(x.y) + __popc(x.z) + __popc(x.w);
+                bm4[s * BM_THREADS + tid] = make_uint4(0u, 0u, 0u, 0u);
             }
+            c = group_reduce_sum(c, WAVE);
+            if (lane_id() == 0 && c) atomicAdd(&s_count[turn & 1u], c);
             __syncthreads();
         }
         if (tid == 0) {
-            nnz_out[row] = s_count;
-            s_count = 0;
-            s_ticket[(turn + 3u) & 3u] = drawn;   // (its slot held the ticket of the turn before this one)
+            nnz_out[row] = s_count[turn & 1u];
+            s_count[turn & 1u] = 0;               // (next used two turns from now)
+            s_ticket[(turn + 6u) & 7u] = drawn;   // (its slot held the ticket of two turns ago)
         }
-        row = row1; row1 = row2;
-        e0 = e0n; e1 = e1n;
-        fp0 = fp0n; flen = flenn;
-        __syncthreads();
+        row = row1; row1 = row2; row2 = row3; row3 = row4;
+        e0 = e0_1; e1 = e1_1;
+        e0_1 = e0_2; e1_1 = e1_2;
+        e0_2 = e0_3; e1_2 = e1_3;
+        k1 = k2;
+        fp0 = fp0_1; flen = flen_1;
     }
 }
 
