@@ -488,6 +488,40 @@ def test_heavy_rows_spread_thin_over_many_windows(ob, dtype, n):
         assert st["rows_per_bin"][nb - 1] + st["rows_per_bin"][nb - 2] >= 2
 
 
+@pytest.mark.parametrize("n", [150000, 3 << 20])
+def test_symbolic_runs_of_column_ids(ob, n):
+    """The symbolic traversal of large chunks takes runs of consecutive entries of one row of B per lane, the
+    segments padded to whole runs: rows of B of every length from 0 to 70 (all remainders of the run lengths 4
+    and 16, segments shorter than a run, empty rows in between) mixed with rows of thousands of entries, rows of
+    A of more than 1024 entries (several chunks) and rows that end with a partial run; with more than 2^20
+    columns the bitmap kernel takes several windows per row and the 16384- and 32768-slot key tables are used."""
+    rng = np.random.default_rng(31)
+    kb = 3000
+    lens = np.arange(kb) % 71
+    lens[rng.random(kb) < 0.05] = 0
+    longs = {5: 9000, 6: 4097, 7: 16384, 8: 12345, 1500: 20001, 2999: 4111}
+    for k, v in longs.items():
+        lens[k] = v
+    rp = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    ci = np.concatenate([np.sort(rng.choice(n, int(k), replace=False)) for k in lens]).astype(np.int32)
+    Bm = CSR(kb, n, rp, ci, rng.uniform(-1, 1, ci.size))
+    short = np.array([k for k in range(kb) if k not in longs])
+    rows = [np.sort(np.concatenate([rng.choice(short, 2500, replace=False), [5, 8]])),    # three chunks, two long rows among short ones
+            np.array([5, 6, 7]), np.array([7]), np.array([8, 1500, 2999]),               # long rows only
+            np.sort(np.concatenate([rng.choice(short, 700, replace=False), [6, 1500]])),
+            np.sort(rng.choice(short, 1024, replace=False)),                            # exactly one chunk of short rows
+            np.sort(rng.choice(short, 300, replace=False)), np.array([0, 1, 2, 3]), np.array([], dtype=np.int64)]
+    arp = np.concatenate([[0], np.cumsum([len(r) for r in rows])]).astype(np.int64)
+    aci = np.concatenate(rows).astype(np.int32)
+    A = CSR(len(rows), kb, arp, aci, rng.uniform(-1, 1, aci.size))
+    want = O.count_rows(A, Bm)
+    dA, dB = ob.to_device(A), ob.to_device(Bm)
+    for kw in (dict(), dict(bitmap_query=2), dict(assisted_symbolic=2)):
+        nnz, st = ob.symbolic(dA, dB, opt=ob.default_options(**kw))
+        assert np.array_equal(nnz.cpu().numpy(), want), f"{kw}"
+    assert sum(st["symbolic_rows_per_bin"][4:]) >= 5
+
+
 def _random_case(rng, dtype):
     """A random pair (A, B) with a random mix of row lengths: empty rows, a few very long rows, duplicates
     within rows of A, and rows of B from one entry to most of the columns."""
