@@ -310,8 +310,8 @@ hipError_t launch_symbolic_bin(const Csr &A, const Csr &B, const SymLaunch &l, i
             hipLaunchKernelGGL(k_symbolic_wave<false>, dim3((unsigned)((l.count + 3) / 4)), dim3(256), 0, s, A.rp, A.col, B.rp,
                                B.col, l.rows, l.count, nnz_out);
         break;
-    case SB_S1K: OCEAN_SYM_WG(10, 256); break;
-    case SB_S4K: OCEAN_SYM_WG(12, 512); break;
+    case SB_S1K: OCEAN_SYM_WG(10, 64); break;    // (rect: 64 threads 0.68 ms, 128 0.76, 256 1.08 for the whole stage)
+    case SB_S4K: OCEAN_SYM_WG(12, 256); break;   // (clustered: 256 threads 1.16 ms, 128 1.23, 512 1.40)
     case SB_S16K: OCEAN_SYM_WG(14, 1024); break;
     case SB_S32K: OCEAN_SYM_WG(15, 1024); break;
     case SB_BITMAP: {
