@@ -210,18 +210,22 @@ def test_full_size_rect_and_clustered(ob, name):
     """Full BASELINE sizes, every element against the oracle, in the workflows bench.py times."""
     A, B, ref, prod = workload(name, False)
     dA, dB = ob.to_device(A), ob.to_device(B)
-    for wf in ("auto", "hll", "upper_bound"):
+    for wf in ("auto", "hll", "upper_bound", "symbolic"):
         print(f"full size {name}/{wf}", flush=True)
         Cd, st = ob.spgemm(dA, dB, workflow=wf_id(ob, wf))
         check_result(Cd, ref, A, f"{name}/{wf}")
         assert st["products"] == int(prod.sum()) and st["nnz_c"] == ref.col_idx.size
         del Cd
-    # AUTO with the selector re-tuned for this GPU (the default): no heavy rows here, so the two-pass workflow is
-    # not chosen - estimation on the clustered input (CR 3.3), the product bound on the rectangular one (CR 1.03, where
-    # an estimate cannot undercut the bound); with Table 1 as printed (CR >= 8) the two-pass workflow
+    # AUTO with the selector re-tuned for this GPU (the default): no heavy rows here, so estimation from a sampled CR
+    # of 1.5 on - the clustered input (CR 3.3) - and two passes below it - the rectangular input (CR 1.03); with the
+    # threshold lowered to 1.0 the rectangular input takes the product bound (an estimate cannot undercut the bound
+    # there), without that rule the estimate; with Table 1 as printed (CR >= 8) the two-pass workflow
     Cd, st = ob.spgemm(dA, dB, workflow=ob.WF_AUTO)
-    assert st["workflow"] == {"clustered": "hll", "rect": "upper_bound"}[name] and st["heavy_products"] == 0
-    Cd, st = ob.spgemm(dA, dB, workflow=ob.WF_AUTO, tuned_cr_bound=0.0)
+    assert st["workflow"] == {"clustered": "hll", "rect": "symbolic"}[name] and st["heavy_products"] == 0
+    Cd, st = ob.spgemm(dA, dB, workflow=ob.WF_AUTO, tuned_cr_light=1.0)
+    assert st["workflow"] == {"clustered": "hll", "rect": "upper_bound"}[name]
+    check_result(Cd, ref, A, f"{name}/auto, estimation from CR 1.0 on")
+    Cd, st = ob.spgemm(dA, dB, workflow=ob.WF_AUTO, tuned_cr_light=1.0, tuned_cr_bound=0.0)
     assert st["workflow"] == "hll"
     check_result(Cd, ref, A, f"{name}/auto without the bound rule")
     Cd, st = ob.spgemm(dA, dB, workflow=ob.WF_AUTO, selector=ob.SEL_TABLE1)
