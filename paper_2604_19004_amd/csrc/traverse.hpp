@@ -162,8 +162,8 @@ struct WgChunk {
     };
     uint32_t wsum[THREADS / WAVE];
     uint32_t wcnt[THREADS / WAVE];
-    uint32_t wsumr[THREADS / WAVE];
-    uint32_t next;                         // first product of the next batch nobody has taken yet
+    uint32_t wsumr[THREADS / WAVE];        // (runs) per-wave sums of the lengths rounded up to whole runs
+    uint32_t next;                         // (runs) first product slot of the next batch nobody has taken yet
 };
 
 // The whole workgroup flattens the `nent` (1..THREADS) segments held by its first nent threads
@@ -180,7 +180,9 @@ struct WgChunk {
 //   * a larger chunk (long segments) uses a binary search over the prefix sums, narrowed
 //     beforehand to the few entries a batch of 256 can touch: a table built once per chunk gives
 //     the entry of the first product of every block of products.  The searches of a batch have
-//     the same, wave-uniform number of steps and run interleaved.
+//     the same, wave-uniform number of steps and run interleaved.  Without values (the symbolic
+//     pass) such a chunk is walked in runs of WU consecutive column ids per lane instead, its
+//     batches handed out from a counter rather than in equal spans (see there).
 // WU is the number of products per lane and batch.  The products of one chunk must number less
 // than 2^31.
 // Every thread calls it; the chunk arrays must be free on entry (the call ends with a barrier).
