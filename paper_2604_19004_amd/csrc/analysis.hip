@@ -284,27 +284,49 @@ hipError_t launch_publish_totals(const unsigned long long *totals, const int32_t
 // Registers of the rows in flight sit in LDS as 32-bit words (LDS has a
 // 32-bit atomic max, Section 3.1 "parallel updates ... atomicMax"); they are
 // packed to one byte per register (Section 4.3) when the sketch is stored.
+// A row of SK_LONG or more entries is left to the whole workgroup, which takes the long rows of a turn one
+// after the other once the lane groups are through with the short ones: on a power-law matrix the longest
+// row, walked by one group of 16 lanes, was most of the kernel's time (R-MAT: 0.77 ms).
+constexpr int SK_LONG = 1024;
 template <int M>
 __global__ void __launch_bounds__(TPB)
 k_hll_sketch(const int64_t *__restrict__ rp, const int32_t *__restrict__ col, int64_t rows, int g_log2,
              uint8_t *__restrict__ out)
 {
     extern __shared__ uint32_t s_regs[];  // [TPB >> g_log2][M]
+    __shared__ uint32_t s_big[M];
+    __shared__ long long s_long[TPB / 8];   // (at most TPB / 8 rows per turn: groups have 8 lanes or more)
+    __shared__ int s_nlong;
     constexpr int P = (M == 32) ? 5 : (M == 64) ? 6 : 7;
     const int G = 1 << g_log2;
     const int sub = threadIdx.x & (G - 1);
     const int rl = threadIdx.x >> g_log2;
     const int R = TPB >> g_log2;
     uint32_t *my = s_regs + rl * M;
-    for (int64_t base = (int64_t)blockIdx.x * R; base < rows; base += (int64_t)gridDim.x * R) {
+    auto add = [&](uint32_t *regs, int32_t c) {
+        const uint32_t h = hll_hash(c);
+        const uint32_t w = h >> P;
+        const uint32_t rank = w ? (uint32_t)(__clz((int)w) - P + 1) : (uint32_t)(32 - P + 1);
+        atomicMax(&regs[h & (M - 1)], rank);
+    };
+    auto store = [&](const uint32_t *regs, int64_t row, int first, int step) {
+        uint32_t *dst = reinterpret_cast<uint32_t *>(out + row * M);
+        for (int j = first; j < M / 4; j += step)
+            dst[j] = regs[4 * j] | (regs[4 * j + 1] << 8) | (regs[4 * j + 2] << 16) | (regs[4 * j + 3] << 24);
+    };
+    for (int64_t base = (int64_t)blockIdx.x * R; base < rows; base += (int64_t)gridDim.x * R) {   // uniform
         const int64_t row = base + rl;
+        if (threadIdx.x == 0) s_nlong = 0;
         for (int j = sub; j < M; j += G) my[j] = 0;
-        wave_sync();
+        __syncthreads();
+        bool mine = false;
         if (row < rows) {
-            const int64_t p1 = rp[row + 1];
+            const int64_t p0 = rp[row], p1 = rp[row + 1];
+            mine = p1 - p0 < SK_LONG;
+            if (!mine && sub == 0) s_long[atomicAdd(&s_nlong, 1)] = row;
             // four column ids per lane and turn (unconditional reads, index clamped): a long row is bound by
             // the latency of one load after the other otherwise
-            for (int64_t p = rp[row] + sub; p < p1; p += 4 * (int64_t)G) {
+            for (int64_t p = p0 + sub; mine && p < p1; p += 4 * (int64_t)G) {
                 int32_t c[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
@@ -312,23 +334,35 @@ k_hll_sketch(const int64_t *__restrict__ rp, const int32_t *__restrict__ col, in
                     c[i] = col[q < p1 ? q : p1 - 1];
                 }
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    if (p + (int64_t)i * G < p1) {
-                        const uint32_t h = hll_hash(c[i]);
-                        const uint32_t w = h >> P;
-                        const uint32_t rank = w ? (uint32_t)(__clz((int)w) - P + 1) : (uint32_t)(32 - P + 1);
-                        atomicMax(&my[h & (M - 1)], rank);
-                    }
-                }
+                for (int i = 0; i < 4; ++i)
+                    if (p + (int64_t)i * G < p1) add(my, c[i]);
             }
         }
         wave_sync();
-        if (row < rows) {
-            uint32_t *dst = reinterpret_cast<uint32_t *>(out + row * M);
-            for (int j = sub; j < M / 4; j += G)
-                dst[j] = my[4 * j] | (my[4 * j + 1] << 8) | (my[4 * j + 2] << 16) | (my[4 * j + 3] << 24);
+        if (mine) store(my, row, sub, G);
+        __syncthreads();
+        const int nlong = s_nlong;
+        for (int i = 0; i < nlong; ++i) {   // uniform
+            const int64_t lrow = s_long[i];
+            for (int j = threadIdx.x; j < M; j += TPB) s_big[j] = 0;
+            __syncthreads();
+            const int64_t p1 = rp[lrow + 1];
+            for (int64_t p = rp[lrow] + threadIdx.x; p < p1; p += 4 * (int64_t)TPB) {
+                int32_t c[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int64_t q = p + (int64_t)k * TPB;
+                    c[k] = col[q < p1 ? q : p1 - 1];
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    if (p + (int64_t)k * TPB < p1) add(s_big, c[k]);
+            }
+            __syncthreads();
+            store(s_big, lrow, (int)threadIdx.x, TPB);
+            __syncthreads();
         }
-        wave_sync();
+        __syncthreads();   // (everyone has read s_nlong before the next turn clears it)
     }
 }
 

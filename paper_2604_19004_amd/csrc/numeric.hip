@@ -832,6 +832,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     for (int j = tid; j < WIN; j += HV_THREADS) s_vals[j] = (AV)0;
     for (int j = tid; j < WORDS; j += HV_THREADS) s_dbm[j] = 0u;
     bool dense_clean = true;   // the region is an all-zero dense window
+    bool chunk_clean = false;  // the traversal's marks are as wg_flat_chunk_keep leaves them
 
     for (;;) {
         if (tid == 0) {
@@ -993,7 +994,8 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                 };
                 bool fits;
                 wg_flat_chunk_keep<HV_THREADS, NBATCH>(s_fc, (int)ne, (int64_t)c_lo, c_hi - c_lo, ea, b_col, b_val, kc, kv,
-                                                       mark, fits);
+                                                       mark, fits, chunk_clean);
+                chunk_clean = true;
                 if (!fits && tid == 0) s_ovf = 1;   // cannot happen: passes are planned from the counts
                 const int wpt = (hwords + HV_THREADS - 1) / HV_THREADS;   // bitmap words per thread (consecutive)
                 int mine = 0;
@@ -1045,6 +1047,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                     const int64_t left = ne - base;
                     staged += wg_flat_chunk<HV_THREADS, true>(s_fc, left < HV_THREADS ? (int)left : HV_THREADS, (int64_t)c0,
                                                               c1 - c0, a, b_col, b_val, f);
+                    chunk_clean = false;
                 }
                 if (dense) {
                     // ---- dense window -> output, in column order
@@ -1134,47 +1137,68 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
 
 // Positions of the column-window boundaries inside every row of B:
 // bw[k*(n_win+1)+w] = first position p in row k with col[p] >= w*win (row end if none).
-// One 16-lane group per row.  flags |= 8 when a row is not sorted ascending.
+// One 16-lane group per row; a row of WT_LONG or more entries is left to the whole workgroup (every entry is
+// looked at on its own, together with its predecessor), which takes the long rows of its 16 one after the other:
+// the longest row of a power-law matrix, walked by 16 lanes, was most of the kernel's time.
+// flags |= 8 when a row is not sorted ascending.
+constexpr int WT_LONG = 1024;
 __global__ void __launch_bounds__(256)
 k_window_table(const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_col, int64_t rows, int win_log2,
                int n_win, uint32_t *__restrict__ bw, int32_t *flags)
 {
+    __shared__ long long s_long[16];
+    __shared__ int s_nlong;
     const int64_t gt = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t k = gt >> 4;
     const int sub = (int)(gt & 15);
-    if (k >= rows) return;
-    const int64_t p0 = b_rp[k], p1 = b_rp[k + 1];
-    uint32_t *t = bw + (size_t)k * ((size_t)n_win + 1);
+    if (threadIdx.x == 0) s_nlong = 0;
+    __syncthreads();
     bool unsorted = false;
-    if (p0 == p1) {
-        for (int w = sub; w <= n_win; w += 16) t[w] = (uint32_t)p0;
-        return;
-    }
-    for (int64_t q = p0 + sub; q < p1; q += 64) {
-        // four entries per lane and turn (unconditional reads, index clamped), so that a long row is
-        // not bound by the latency of one load after the other
-        int32_t c[4], cp[4];
+    // entries first, first + step, ... of row r (positions p0 .. p1 - 1, p0 < p1), four per lane and turn
+    // (unconditional reads, index clamped), so that a long row is not bound by the latency of one load after the other
+    auto walk = [&](int64_t r, int64_t p0, int64_t p1, int first, int step) {
+        uint32_t *t = bw + (size_t)r * ((size_t)n_win + 1);
+        for (int64_t q = p0 + first; q < p1; q += 4 * (int64_t)step) {
+            int32_t c[4], cp[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int64_t p = q + 16 * i;
-            const int64_t pc = p < p1 ? p : p1 - 1;
-            c[i] = b_col[pc];
-            cp[i] = b_col[pc > p0 ? pc - 1 : p0];
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int64_t p = q + 16 * i;
-            if (p >= p1) break;
-            const int wc = c[i] >> win_log2;
-            int wprev = -1;
-            if (p > p0) {
-                unsorted |= cp[i] > c[i];
-                wprev = cp[i] >> win_log2;
+            for (int i = 0; i < 4; ++i) {
+                const int64_t p = q + (int64_t)step * i;
+                const int64_t pc = p < p1 ? p : p1 - 1;
+                c[i] = b_col[pc];
+                cp[i] = b_col[pc > p0 ? pc - 1 : p0];
             }
-            for (int w = wprev + 1; w <= wc; ++w) t[w] = (uint32_t)p;
-            if (p == p1 - 1)
-                for (int w = wc + 1; w <= n_win; ++w) t[w] = (uint32_t)p1;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int64_t p = q + (int64_t)step * i;
+                if (p >= p1) break;
+                const int wc = c[i] >> win_log2;
+                int wprev = -1;
+                if (p > p0) {
+                    unsorted |= cp[i] > c[i];
+                    wprev = cp[i] >> win_log2;
+                }
+                for (int w = wprev + 1; w <= wc; ++w) t[w] = (uint32_t)p;
+                if (p == p1 - 1)
+                    for (int w = wc + 1; w <= n_win; ++w) t[w] = (uint32_t)p1;
+            }
         }
+    };
+    if (k < rows) {
+        const int64_t p0 = b_rp[k], p1 = b_rp[k + 1];
+        if (p0 == p1) {
+            uint32_t *t = bw + (size_t)k * ((size_t)n_win + 1);
+            for (int w = sub; w <= n_win; w += 16) t[w] = (uint32_t)p0;
+        } else if (p1 - p0 >= WT_LONG) {
+            if (sub == 0) s_long[atomicAdd(&s_nlong, 1)] = k;
+        } else {
+            walk(k, p0, p1, sub, 16);
+        }
+    }
+    __syncthreads();
+    const int nlong = s_nlong;
+    for (int i = 0; i < nlong; ++i) {   // uniform
+        const int64_t r = s_long[i];
+        walk(r, b_rp[r], b_rp[r + 1], (int)threadIdx.x, 256);
     }
     if (unsorted) atomicOr(flags, 8);
 }

@@ -164,6 +164,7 @@ struct WgChunk {
     uint32_t wcnt[THREADS / WAVE];
     uint32_t wsumr[THREADS / WAVE];        // (runs) per-wave sums of the lengths rounded up to whole runs
     uint32_t next;                         // (runs) first product slot of the next batch nobody has taken yet
+    unsigned long long alloc;              // (wg_flat_chunk_keep) products (low word) and non-empty segments handed out so far
 };
 
 // The whole workgroup flattens the `nent` (1..THREADS) segments held by its first nent threads
@@ -480,36 +481,38 @@ __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS, RPT> &c, i
 // share of the products (column id, a*b) in registers, kc[i] < 0 where it has none, and mark(col)
 // has been called once per product.  Needs at most NB * FLAT_U products per thread
 // (total <= NB * FLAT_U * THREADS) and total <= WgChunk::RANK_CAP; otherwise nothing is fetched and
-// fits = false.  Every thread calls it; ends with a barrier; returns the number of products.
+// fits = false.  The segments are laid end to end wave by wave, in the order in which the waves draw their share
+// of the product numbers from a counter in LDS (the order of the products of a chunk means nothing), which spares
+// the barrier and the scan over the waves' sums that a fixed order would need.  clean: the marks and the counter
+// are as this function leaves them (all zero); after any other use of the chunk pass false and they are cleared
+// first.  Every thread calls it; ends with a barrier; returns the number of products.
 template <int THREADS, int NB, typename V, typename M, int RPT>
 __device__ __forceinline__ uint32_t wg_flat_chunk_keep(WgChunk<V, THREADS, RPT> &c, int nent, int64_t p0, uint32_t len, V a,
                                                    const int32_t *__restrict__ b_col, const V *__restrict__ b_val,
                                                    int32_t (&kc)[NB * FLAT_U], V (&kv)[NB * FLAT_U], M &mark,
-                                                   bool &fits)
+                                                   bool &fits, bool clean)
 {
     constexpr int NW = THREADS / WAVE;
     constexpr uint32_t RANK_CAP = WgChunk<V, THREADS, RPT>::RANK_CAP;
     constexpr int START_WORDS = WgChunk<V, THREADS, RPT>::START_WORDS;
     const int tid = threadIdx.x;
     const int lane = tid & (WAVE - 1), wave = tid / WAVE;
-    for (int j = tid; j < START_WORDS; j += THREADS) c.start[j] = 0u;
+    if (!clean) {   // uniform
+        for (int j = tid; j < START_WORDS; j += THREADS) c.start[j] = 0u;
+        if (tid == 0) c.alloc = 0ull;
+        __syncthreads();
+    }
     uint32_t incl = wave_inclusive_scan_u32(len);
     const unsigned long long live = __ballot(len > 0);
-    if (lane == WAVE - 1) { c.wsum[wave] = incl; c.wcnt[wave] = (uint32_t)__popcll(live); }
+    unsigned long long got = 0ull;
+    if (lane == WAVE - 1) got = atomicAdd(&c.alloc, (unsigned long long)incl | ((unsigned long long)__popcll(live) << 32));
 #pragma unroll
     for (int i = 0; i < NB * FLAT_U; ++i) { kc[i] = -1; kv[i] = V(); }
-    __syncthreads();
-    uint32_t total, ctotal;
-    const uint32_t before = waves_before_u32<NW>(c.wsum, wave, total);
-    const uint32_t cbefore = waves_before_u32<NW>(c.wcnt, wave, ctotal);
+    const uint32_t before = wave_read_lane_u32((uint32_t)got, WAVE - 1);
+    const uint32_t cbefore = wave_read_lane_u32((uint32_t)(got >> 32), WAVE - 1);
     incl += before;
-    fits = total <= RANK_CAP && total <= (uint32_t)(NB * FLAT_U * THREADS);
-    if (total == 0 || !fits) {   // uniform
-        __syncthreads();
-        return total;
-    }
     const uint32_t ex = incl - len;
-    if (len > 0) {
+    if (len > 0 && incl <= RANK_CAP) {   // (beyond the marks nothing is fetched anyway, see fits)
         const uint32_t ce = cbefore + __builtin_amdgcn_mbcnt_hi((uint32_t)(live >> 32),
                                                                 __builtin_amdgcn_mbcnt_lo((uint32_t)live, 0u));
         c.pbase[ce] = (long long)p0 - (long long)ex;
@@ -517,6 +520,14 @@ __device__ __forceinline__ uint32_t wg_flat_chunk_keep(WgChunk<V, THREADS, RPT> 
         atomicOr(&c.start[ex >> 5], 1u << (ex & 31u));
     }
     __syncthreads();
+    const uint32_t total = (uint32_t)c.alloc;
+    fits = total <= RANK_CAP && total <= (uint32_t)(NB * FLAT_U * THREADS);
+    if (total == 0 || !fits) {   // uniform
+        __syncthreads();
+        for (int j = tid; j < START_WORDS; j += THREADS) c.start[j] = 0u;
+        if (tid == 0) c.alloc = 0ull;
+        return total;
+    }
     const uint32_t span = ((total + NW - 1) / NW + (WAVE - 1)) & ~(uint32_t)(WAVE - 1);   // <= NB * FLAT_U * WAVE
     const uint32_t qs = (uint32_t)wave * span;
     const uint32_t qe = qs + span < total ? qs + span : total;
@@ -566,6 +577,9 @@ __device__ __forceinline__ uint32_t wg_flat_chunk_keep(WgChunk<V, THREADS, RPT> 
         }
     }
     __syncthreads();
+    // (left clean for the next call; whatever the caller does next has a barrier before the chunk is used again)
+    for (int j = tid; j < (int)((total >> 5) + 2u) && j < START_WORDS; j += THREADS) c.start[j] = 0u;
+    if (tid == 0) c.alloc = 0ull;
     return total;
 }
 
