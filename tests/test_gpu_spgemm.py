@@ -81,6 +81,31 @@ def test_hll_sketch_merge_estimate(ob, name, m):
     np.testing.assert_allclose(est2.cpu().numpy(), ohll.estimate_rows(A, B, m, rows=rows), rtol=1e-12, atol=0)
 
 
+@pytest.mark.parametrize("m", [32, 64, 128])
+def test_hll_sketch_and_merge_of_long_rows(ob, m):
+    """Rows of B of 1024 and more entries are sketched by a whole workgroup, the others by a group of lanes, and a
+    row of A of thousands of entries is merged by one group: lengths on both sides of the switch, byte for byte
+    against the oracle."""
+    rng = np.random.default_rng(41)
+    n = 200000
+    lens = np.array([0, 1, 7, 1023, 1024, 1025, 2048, 4097, 30000, 5, 1500, 0, 999, 12345] + [3] * 300 + [20000])
+    rp = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    ci = np.concatenate([np.sort(rng.choice(n, int(k), replace=False)) for k in lens]).astype(np.int32)
+    Bm = CSR(len(lens), n, rp, ci, rng.uniform(-1, 1, ci.size))
+    a_rows = [np.arange(len(lens)), np.array([3, 4, 5]), np.array([8]), np.array([], dtype=np.int64),
+              rng.integers(0, len(lens), 9000), np.array([0, 11])]           # (one row of A with 9000 entries, repeats among them)
+    arp = np.concatenate([[0], np.cumsum([len(r) for r in a_rows])]).astype(np.int64)
+    A = CSR(len(a_rows), len(lens), arp, np.concatenate(a_rows).astype(np.int32), rng.uniform(-1, 1, int(arp[-1])))
+    dA, dB = ob.to_device(A), ob.to_device(Bm)
+    S = ob.hll_sketch_rows(dB, m)
+    S_ref = ohll.sketch_rows(Bm, m)
+    assert np.array_equal(S.cpu().numpy(), S_ref)
+    est, merged = ob.hll_merge_estimate(dA, S, m, want_merged=True)
+    merged_ref = ohll.merge_rows(A, S_ref)
+    assert np.array_equal(merged.cpu().numpy(), merged_ref)
+    np.testing.assert_allclose(est.cpu().numpy(), ohll.estimate(merged_ref), rtol=1e-12, atol=0)
+
+
 @pytest.mark.parametrize("name", ["er", "laplacian", "rmat", "rect", "clustered"])
 def test_symbolic_exact(ob, name):
     A, B, ref, prod = workload(name, True)
