@@ -407,6 +407,10 @@ __device__ __forceinline__ double hll_alpha(int m)
 // One group of G lanes per selected row of A; L = M/8 lanes cover one sketch
 // (8 registers per lane in a 64-bit word) so G/L entries of the row are
 // merged at once.  Each 64-byte sketch of B is read as one coalesced line.
+// A row of MG_LONG or more entries is left to the whole workgroup (TPB / L entries at once), which takes the
+// long rows of its groups one after the other: on a power-law matrix a sampled row of tens of thousands of
+// entries, merged by one group, was most of the sampled merge's time.
+constexpr int MG_LONG = 2048;
 template <int M>
 __global__ void __launch_bounds__(TPB)
 k_hll_merge(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col,
@@ -415,27 +419,27 @@ k_hll_merge(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col,
             int64_t b_cols, double *__restrict__ est, uint64_t *__restrict__ merged)
 {
     constexpr int L = M / 8;
+    __shared__ long long s_long[TPB / L];   // (slot of the row, i.e. its position among the selected rows)
+    __shared__ int s_nlong;
+    __shared__ uint64_t s_acc[TPB];
+    __shared__ long long s_blen[TPB / L];
     const int G = 1 << g_log2;  // >= L
     const int64_t gt = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t t = gt >> g_log2;
     const int sub = (int)(gt & (G - 1));
-    const int slice = sub & (L - 1);
-    const int part = sub / L;
-    const int parts = G / L;
-    uint64_t acc = 0;
-    long long blen_max = 0;
-    int64_t row = -1;
-    if (t < n_rows) {
-        row = rows ? rows[t] : t;
+    if (threadIdx.x == 0) s_nlong = 0;
+    __syncthreads();
+    // entries first, first + step, ... of a row, for this lane's slice of the sketch: four per lane and turn
+    // (unconditional reads, index clamped; merging a sketch twice is harmless), so that the dependent loads
+    // entry -> sketch of four entries overlap
+    auto walk = [&](int64_t row, int slice, int first, int step, uint64_t &acc, long long &blen_max) {
         const int64_t e1 = a_rp[row + 1];
-        // four entries per lane and turn (unconditional reads, index clamped; merging a sketch twice is
-        // harmless), so that the dependent loads entry -> sketch of four entries overlap
-        for (int64_t e = a_rp[row] + part; e < e1; e += 4 * (int64_t)parts) {
+        for (int64_t e = a_rp[row] + first; e < e1; e += 4 * (int64_t)step) {
             int64_t k[4];
             uint64_t word[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int64_t q = e + (int64_t)i * parts;
+                const int64_t q = e + (int64_t)i * step;
                 k[i] = a_col[q < e1 ? q : e1 - 1];
             }
 #pragma unroll
@@ -450,37 +454,77 @@ k_hll_merge(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col,
                 }
             }
         }
+    };
+    // L consecutive lanes hold the merged sketch of slot t2 (row row2), 8 registers each: estimate and store
+    auto finish = [&](uint64_t acc, long long blen_max, int64_t t2, int64_t row2, int slice, bool first_part) {
+        double ssum = 0.0;
+        int zeros = 0;
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const unsigned r = (unsigned)(acc >> (8 * b)) & 0xFFu;
+            ssum += __longlong_as_double((long long)(1023 - (int)r) << 52);  // 2^-r, exact
+            zeros += (r == 0);
+        }
+        for (int off = L >> 1; off > 0; off >>= 1) {
+            ssum += __shfl_xor(ssum, off, WAVE);
+            zeros += __shfl_xor(zeros, off, WAVE);
+        }
+        if (t2 < n_rows && first_part) {
+            if (merged != nullptr) merged[t2 * L + slice] = acc;
+            if (slice == 0) {
+                const double dm = (double)M;
+                double e = hll_alpha(M) * dm * dm / ssum;
+                if (e <= 2.5 * dm && zeros > 0) e = dm * log(dm / (double)zeros);
+                if (prod != nullptr) {
+                    const long long pr = prod[row2];
+                    const double hi = (double)(pr < b_cols ? pr : b_cols);
+                    const double lo = (double)(maxb != nullptr ? (long long)maxb[row2] : blen_max);
+                    e = e < lo ? lo : e;
+                    e = e > hi ? hi : e;
+                }
+                est[t2] = e;
+            }
+        }
+    };
+    const int slice = sub & (L - 1);
+    const int part = sub / L;
+    const int parts = G / L;
+    uint64_t acc = 0;
+    long long blen_max = 0;
+    int64_t row = -1;
+    bool mine = false;
+    if (t < n_rows) {
+        row = rows ? rows[t] : t;
+        mine = a_rp[row + 1] - a_rp[row] < MG_LONG;
+        if (mine) walk(row, slice, part, parts, acc, blen_max);
+        else if (sub == 0) s_long[atomicAdd(&s_nlong, 1)] = t;
     }
     for (int off = L; off < G; off <<= 1) acc = bytemax8(acc, __shfl_xor((unsigned long long)acc, off, WAVE));
     if (b_rp != nullptr) blen_max = group_reduce_max(blen_max, G);
-    // harmonic sum and empty-register count of this lane's 8 registers
-    double ssum = 0.0;
-    int zeros = 0;
-#pragma unroll
-    for (int b = 0; b < 8; ++b) {
-        const unsigned r = (unsigned)(acc >> (8 * b)) & 0xFFu;
-        ssum += __longlong_as_double((long long)(1023 - (int)r) << 52);  // 2^-r, exact
-        zeros += (r == 0);
-    }
-    for (int off = L >> 1; off > 0; off >>= 1) {
-        ssum += __shfl_xor(ssum, off, WAVE);
-        zeros += __shfl_xor(zeros, off, WAVE);
-    }
-    if (t < n_rows) {
-        if (merged != nullptr && part == 0) merged[t * L + slice] = acc;
-        if (sub == 0) {
-            const double dm = (double)M;
-            double e = hll_alpha(M) * dm * dm / ssum;
-            if (e <= 2.5 * dm && zeros > 0) e = dm * log(dm / (double)zeros);
-            if (prod != nullptr) {
-                const long long pr = prod[row];
-                const double hi = (double)(pr < b_cols ? pr : b_cols);
-                const double lo = (double)(maxb != nullptr ? (long long)maxb[row] : blen_max);
-                e = e < lo ? lo : e;
-                e = e > hi ? hi : e;
+    finish(acc, blen_max, mine ? t : n_rows, row, slice, part == 0);
+    __syncthreads();
+    const int nlong = s_nlong;
+    for (int i = 0; i < nlong; ++i) {   // uniform
+        const int64_t t2 = s_long[i];
+        const int64_t row2 = rows ? rows[t2] : t2;
+        const int wslice = (int)threadIdx.x & (L - 1), wpart = (int)threadIdx.x / L;
+        uint64_t a2 = 0;
+        long long b2 = 0;
+        walk(row2, wslice, wpart, TPB / L, a2, b2);
+        s_acc[threadIdx.x] = a2;
+        if (wslice == 0) s_blen[wpart] = b2;
+        __syncthreads();
+        // the first L lanes fold the partial sketches of the TPB / L parts
+        uint64_t f = 0;
+        long long fb = 0;
+        if (threadIdx.x < L) {
+            for (int p = 0; p < TPB / L; ++p) {
+                f = bytemax8(f, s_acc[p * L + threadIdx.x]);
+                fb = s_blen[p] > fb ? s_blen[p] : fb;
             }
-            est[t] = e;
         }
+        if (threadIdx.x < WAVE) finish(f, fb, threadIdx.x < L ? t2 : n_rows, row2, (int)threadIdx.x & (L - 1), true);   // (whole first wave: lane swaps)
+        __syncthreads();
     }
 }
 

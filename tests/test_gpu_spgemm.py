@@ -104,6 +104,12 @@ def test_hll_sketch_and_merge_of_long_rows(ob, m):
     merged_ref = ohll.merge_rows(A, S_ref)
     assert np.array_equal(merged.cpu().numpy(), merged_ref)
     np.testing.assert_allclose(est.cpu().numpy(), ohll.estimate(merged_ref), rtol=1e-12, atol=0)
+    # the estimates limited by the row's product count and its longest row of B, on a subset of the rows
+    import torch
+    rows = np.array([0, 2, 4, 5], dtype=np.int64)
+    prod = O.row_products(A, Bm)
+    est2, _ = ob.hll_merge_estimate(dA, S, m, rows=torch.from_numpy(rows).cuda(), prod=torch.from_numpy(prod).cuda(), B=dB)
+    np.testing.assert_allclose(est2.cpu().numpy(), ohll.estimate_rows(A, Bm, m, rows=rows), rtol=1e-12, atol=0)
 
 
 @pytest.mark.parametrize("name", ["er", "laplacian", "rmat", "rect", "clustered"])
