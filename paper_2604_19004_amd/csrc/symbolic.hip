@@ -176,7 +176,7 @@ k_symbolic_bitmap(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ 
                   unsigned long long *queue, int32_t *__restrict__ nnz_out)
 {
     __shared__ __align__(16) uint32_t s_bm[BM_WORDS];
-    __shared__ WgChunk<NoVal, BM_THREADS, 4> s_fc;   // (every row of this kernel is walked in runs: marks up to 16 products per thread measured 1 % slower)
+    __shared__ WgChunk<NoVal, BM_THREADS> s_fc;
     // Rows come from a shared counter.  The chain counter -> row id -> offsets of the row -> entries -> their
     // segments of B is five memory round trips before the first column id of a row can be asked for, so it runs
     // ahead of the work, one link per turn: at the start of a turn the ticket of the row six turns ahead is

@@ -226,7 +226,21 @@ __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS, RPT> &c, i
     int32_t cj[WU];
     V cb[WU];   // values of B
     int cp[WU];
-    if (total <= RANK_CAP) {   // uniform
+    // Runs (column ids only, below) pay when the segments are at least a run long on average - shorter ones leave
+    // most of a run's slots empty (rows of B of 8 entries in runs of 16: 0.93 against 0.60 ms on a test input, rows
+    // of 24: 0.86 against 1.62 ms) - and long runs are worth more than the marks even for a small chunk (R-MAT,
+    // 16 ids per run: 15.7 against 15.9 ms), short ones are not (rect, 4 ids per run: 0.78 against 0.68 ms).
+    const bool use_runs = RUNS && (unsigned long long)total >= (unsigned long long)ctotal * (unsigned)WU &&
+                          (WU >= 8 || total > RANK_CAP);   // uniform
+    if constexpr (RUNS && WU > 4) {
+        // (a chunk of short segments: the same with four column ids per lane and batch - the marks, runs of four
+        // or the search, whichever applies - which also keeps the registers of those paths out of this one)
+        if (!use_runs) {   // uniform
+            __syncthreads();   // (everyone has read the waves' sums)
+            return wg_flat_chunk<THREADS, HAS_VAL, 4>(c, nent, p0, len, a, b_col, b_val, f);
+        }
+    }
+    if (!use_runs && total <= RANK_CAP) {   // uniform
         const uint32_t ex = incl - len;
         if (len > 0) {
             const uint32_t ce = cbefore + __builtin_amdgcn_mbcnt_hi((uint32_t)(live >> 32),
@@ -287,7 +301,7 @@ __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS, RPT> &c, i
         __syncthreads();
         return total;
     }
-    if constexpr (RUNS) {
+    if constexpr (RUNS) if (use_runs) {
         // Column ids only (the symbolic pass: whole rows of B, mostly long ones, and a set of columns as the
         // result, so that a column seen twice does no harm).  Every lane takes a run of WU consecutive entries
         // of ONE segment with 16-byte loads: the segments are laid out with their lengths rounded up to whole
