@@ -286,12 +286,14 @@ hipError_t launch_publish_totals(const unsigned long long *totals, const int32_t
 // packed to one byte per register (Section 4.3) when the sketch is stored.
 // A row of SK_LONG or more entries is left to the whole workgroup, which takes the long rows of a turn one
 // after the other once the lane groups are through with the short ones: on a power-law matrix the longest
-// row, walked by one group of 16 lanes, was most of the kernel's time (R-MAT: 0.77 ms).
+// row, walked by one group of 16 lanes, was most of the kernel's time (R-MAT: 0.77 ms).  "Long" is relative: a row
+// of long_from entries or more, which the launcher sets to 1024 or eight times the average row, whichever is more
+// (where every row is long, sixteen groups side by side are 6 - 12 % faster than the workgroup on one row at a time).
 constexpr int SK_LONG = 1024;
 template <int M>
 __global__ void __launch_bounds__(TPB)
 k_hll_sketch(const int64_t *__restrict__ rp, const int32_t *__restrict__ col, int64_t rows, int g_log2,
-             uint8_t *__restrict__ out)
+             int64_t long_from, uint8_t *__restrict__ out)
 {
     extern __shared__ uint32_t s_regs[];  // [TPB >> g_log2][M]
     __shared__ uint32_t s_big[M];
@@ -322,7 +324,7 @@ k_hll_sketch(const int64_t *__restrict__ rp, const int32_t *__restrict__ col, in
         bool mine = false;
         if (row < rows) {
             const int64_t p0 = rp[row], p1 = rp[row + 1];
-            mine = p1 - p0 < SK_LONG;
+            mine = p1 - p0 < long_from;
             if (!mine && sub == 0) s_long[atomicAdd(&s_nlong, 1)] = row;
             // four column ids per lane and turn (unconditional reads, index clamped): a long row is bound by
             // the latency of one load after the other otherwise
@@ -378,10 +380,11 @@ hipError_t launch_hll_sketch(const Csr &B, int m, uint8_t *sketches, int lanes_d
     int64_t blocks = (B.rows + R - 1) / R;
     if (blocks > 256 * 64) blocks = 256 * 64;
     const size_t lds = (size_t)R * m * sizeof(uint32_t);
+    const int64_t long_from = 8.0 * avg > (double)SK_LONG ? (int64_t)(8.0 * avg) : (int64_t)SK_LONG;
     switch (m) {
-    case 32: hipLaunchKernelGGL(k_hll_sketch<32>, dim3((unsigned)blocks), dim3(TPB), lds, s, B.rp, B.col, B.rows, g_log2, sketches); break;
-    case 64: hipLaunchKernelGGL(k_hll_sketch<64>, dim3((unsigned)blocks), dim3(TPB), lds, s, B.rp, B.col, B.rows, g_log2, sketches); break;
-    case 128: hipLaunchKernelGGL(k_hll_sketch<128>, dim3((unsigned)blocks), dim3(TPB), lds, s, B.rp, B.col, B.rows, g_log2, sketches); break;
+    case 32: hipLaunchKernelGGL(k_hll_sketch<32>, dim3((unsigned)blocks), dim3(TPB), lds, s, B.rp, B.col, B.rows, g_log2, long_from, sketches); break;
+    case 64: hipLaunchKernelGGL(k_hll_sketch<64>, dim3((unsigned)blocks), dim3(TPB), lds, s, B.rp, B.col, B.rows, g_log2, long_from, sketches); break;
+    case 128: hipLaunchKernelGGL(k_hll_sketch<128>, dim3((unsigned)blocks), dim3(TPB), lds, s, B.rp, B.col, B.rows, g_log2, long_from, sketches); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -409,13 +412,14 @@ __device__ __forceinline__ double hll_alpha(int m)
 // merged at once.  Each 64-byte sketch of B is read as one coalesced line.
 // A row of MG_LONG or more entries is left to the whole workgroup (TPB / L entries at once), which takes the
 // long rows of its groups one after the other: on a power-law matrix a sampled row of tens of thousands of
-// entries, merged by one group, was most of the sampled merge's time.
+// entries, merged by one group, was most of the sampled merge's time.  "Long" is long_from entries or more: 2048
+// or eight times the average row of A, whichever is more (see k_hll_sketch).
 constexpr int MG_LONG = 2048;
 template <int M>
 __global__ void __launch_bounds__(TPB)
 k_hll_merge(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col,
             const uint64_t *__restrict__ sk, const int64_t *__restrict__ rows, int64_t n_rows, int g_log2,
-            const int64_t *__restrict__ prod, const int32_t *__restrict__ maxb, const int64_t *__restrict__ b_rp,
+            int64_t long_from, const int64_t *__restrict__ prod, const int32_t *__restrict__ maxb, const int64_t *__restrict__ b_rp,
             int64_t b_cols, double *__restrict__ est, uint64_t *__restrict__ merged)
 {
     constexpr int L = M / 8;
@@ -495,7 +499,7 @@ k_hll_merge(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col,
     bool mine = false;
     if (t < n_rows) {
         row = rows ? rows[t] : t;
-        mine = a_rp[row + 1] - a_rp[row] < MG_LONG;
+        mine = a_rp[row + 1] - a_rp[row] < long_from;
         if (mine) walk(row, slice, part, parts, acc, blen_max);
         else if (sub == 0) s_long[atomicAdd(&s_nlong, 1)] = t;
     }
@@ -541,10 +545,11 @@ hipError_t launch_hll_merge(const Csr &A, const uint8_t *sketches, int m, const 
     const int64_t blocks = (threads + TPB - 1) / TPB;
     const uint64_t *sk = reinterpret_cast<const uint64_t *>(sketches);
     uint64_t *mg = reinterpret_cast<uint64_t *>(merged);
+    const int64_t long_from = 8.0 * avg > (double)MG_LONG ? (int64_t)(8.0 * avg) : (int64_t)MG_LONG;
     switch (m) {
-    case 32: hipLaunchKernelGGL(k_hll_merge<32>, dim3((unsigned)blocks), dim3(TPB), 0, s, A.rp, A.col, sk, rows, n_rows, g_log2, prod, maxb, b_rp, b_cols, est, mg); break;
-    case 64: hipLaunchKernelGGL(k_hll_merge<64>, dim3((unsigned)blocks), dim3(TPB), 0, s, A.rp, A.col, sk, rows, n_rows, g_log2, prod, maxb, b_rp, b_cols, est, mg); break;
-    case 128: hipLaunchKernelGGL(k_hll_merge<128>, dim3((unsigned)blocks), dim3(TPB), 0, s, A.rp, A.col, sk, rows, n_rows, g_log2, prod, maxb, b_rp, b_cols, est, mg); break;
+    case 32: hipLaunchKernelGGL(k_hll_merge<32>, dim3((unsigned)blocks), dim3(TPB), 0, s, A.rp, A.col, sk, rows, n_rows, g_log2, long_from, prod, maxb, b_rp, b_cols, est, mg); break;
+    case 64: hipLaunchKernelGGL(k_hll_merge<64>, dim3((unsigned)blocks), dim3(TPB), 0, s, A.rp, A.col, sk, rows, n_rows, g_log2, long_from, prod, maxb, b_rp, b_cols, est, mg); break;
+    case 128: hipLaunchKernelGGL(k_hll_merge<128>, dim3((unsigned)blocks), dim3(TPB), 0, s, A.rp, A.col, sk, rows, n_rows, g_log2, long_from, prod, maxb, b_rp, b_cols, est, mg); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

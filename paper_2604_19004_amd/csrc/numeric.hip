@@ -1144,7 +1144,7 @@ k_numeric_heavy(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
 constexpr int WT_LONG = 1024;
 __global__ void __launch_bounds__(256)
 k_window_table(const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_col, int64_t rows, int win_log2,
-               int n_win, uint32_t *__restrict__ bw, int32_t *flags)
+               int n_win, int64_t long_from, uint32_t *__restrict__ bw, int32_t *flags)
 {
     __shared__ long long s_long[16];
     __shared__ int s_nlong;
@@ -1188,7 +1188,7 @@ k_window_table(const int64_t *__restrict__ b_rp, const int32_t *__restrict__ b_c
         if (p0 == p1) {
             uint32_t *t = bw + (size_t)k * ((size_t)n_win + 1);
             for (int w = sub; w <= n_win; w += 16) t[w] = (uint32_t)p0;
-        } else if (p1 - p0 >= WT_LONG) {
+        } else if (p1 - p0 >= long_from) {
             if (sub == 0) s_long[atomicAdd(&s_nlong, 1)] = k;
         } else {
             walk(k, p0, p1, sub, 16);
@@ -1211,8 +1211,11 @@ hipError_t launch_window_table(const Csr &B, int dtype, uint32_t *bw, int *n_win
     *n_win_out = n_win;
     if (B.rows == 0) return hipSuccess;
     const int64_t threads = B.rows * 16;
+    // ("long" is relative: 1024 entries or eight times the average row, whichever is more)
+    const double avg = (double)B.nnz / (double)B.rows;
+    const int64_t long_from = 8.0 * avg > (double)WT_LONG ? (int64_t)(8.0 * avg) : (int64_t)WT_LONG;
     hipLaunchKernelGGL(k_window_table, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, B.rp, B.col, B.rows,
-                       win_log2, n_win, bw, flags);
+                       win_log2, n_win, long_from, bw, flags);
     return hipGetLastError();
 }
 

@@ -83,9 +83,9 @@ def test_hll_sketch_merge_estimate(ob, name, m):
 
 @pytest.mark.parametrize("m", [32, 64, 128])
 def test_hll_sketch_and_merge_of_long_rows(ob, m):
-    """Rows of B of 1024 and more entries are sketched by a whole workgroup, the others by a group of lanes, and a
-    row of A of thousands of entries is merged by one group: lengths on both sides of the switch, byte for byte
-    against the oracle."""
+    """Rows of B far longer than the average (and of 1024 entries or more) are sketched by a whole workgroup, the
+    others by a group of lanes, and a row of A of thousands of entries is merged by the workgroup: lengths on both
+    sides of the switch, byte for byte against the oracle."""
     rng = np.random.default_rng(41)
     n = 200000
     lens = np.array([0, 1, 7, 1023, 1024, 1025, 2048, 4097, 30000, 5, 1500, 0, 999, 12345] + [3] * 300 + [20000])
@@ -94,6 +94,7 @@ def test_hll_sketch_and_merge_of_long_rows(ob, m):
     Bm = CSR(len(lens), n, rp, ci, rng.uniform(-1, 1, ci.size))
     a_rows = [np.arange(len(lens)), np.array([3, 4, 5]), np.array([8]), np.array([], dtype=np.int64),
               rng.integers(0, len(lens), 9000), np.array([0, 11])]           # (one row of A with 9000 entries, repeats among them)
+    a_rows += [rng.integers(0, len(lens), 2) for _ in range(200)]            # ("long" is relative to the average row)
     arp = np.concatenate([[0], np.cumsum([len(r) for r in a_rows])]).astype(np.int64)
     A = CSR(len(a_rows), len(lens), arp, np.concatenate(a_rows).astype(np.int32), rng.uniform(-1, 1, int(arp[-1])))
     dA, dB = ob.to_device(A), ob.to_device(Bm)
