@@ -546,7 +546,10 @@ def test_symbolic_runs_of_column_ids(ob, n):
             np.array([5, 6, 7]), np.array([7]), np.array([8, 1500, 2999]),               # long rows only
             np.sort(np.concatenate([rng.choice(short, 700, replace=False), [6, 1500]])),
             np.sort(rng.choice(short, 1024, replace=False)),                            # exactly one chunk of short rows
-            np.sort(rng.choice(short, 300, replace=False)), np.array([0, 1, 2, 3]), np.array([], dtype=np.int64)]
+            np.sort(rng.choice(short, 300, replace=False)), np.array([0, 1, 2, 3]), np.array([], dtype=np.int64),
+            # segments shorter than a run on average (rows of B of 1 to 12 entries, repeated): such chunks are not walked in runs
+            np.sort(rng.choice(np.array([k for k in short if 0 < lens[k] <= 12]), 3000, replace=True)),
+            np.sort(rng.choice(np.array([k for k in short if 0 < lens[k] <= 3]), 5000, replace=True))]
     arp = np.concatenate([[0], np.cumsum([len(r) for r in rows])]).astype(np.int64)
     aci = np.concatenate(rows).astype(np.int32)
     A = CSR(len(rows), kb, arp, aci, rng.uniform(-1, 1, aci.size))
