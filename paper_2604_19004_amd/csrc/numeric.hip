@@ -128,6 +128,9 @@ k_numeric_group(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     const int sub = threadIdx.x % G;
     int32_t *keys = s_keys + rl * SLOTS;
     int32_t *sbuf = s_sort + rl * SLOTS;
+    // table slot of every gathered key: in the traversal's chunk, which is free by then
+    static_assert(sizeof(FlatChunk<V, G>) >= SLOTS, "one byte per slot");
+    uint8_t *slot_of = reinterpret_cast<uint8_t *>(&s_fc[rl]);
     AV *vals = s_vals + rl * SLOTS;
     const int group_shift = (lane_id() / G) * G;
     const unsigned long long group_mask = (1ull << G) - 1ull;
@@ -146,7 +149,7 @@ k_numeric_group(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
         if (!lds_insert_batch<BITS>(keys, cj, cv, [&](int slot, V v, bool) { lds_add(&vals[slot], (AV)v); })) ovf = true;
     };
     // the rows of a wave advance together: same number of G-entry chunks for all of them
-    const int chunks = group_reduce_max((int)((e1 - e0 + G - 1) / G), WAVE);
+    const int chunks = (int)wave_max_u32((uint32_t)((e1 - e0 + G - 1) / G));   // (uniform)
     for (int ch = 0; ch < chunks; ++ch) {
         const int64_t e = e0 + (int64_t)ch * G + sub;
         int64_t p0 = 0;
@@ -162,33 +165,50 @@ k_numeric_group(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     }
     wave_sync();
 
-    // gather the occupied keys of this row's table
+    // gather the occupied keys of this row's table, and where their values are
     int c = 0;
 #pragma unroll
     for (int it = 0; it < SLOTS / G; ++it) {
         const int32_t key = keys[it * G + sub];
         const bool occ = key != EMPTY_KEY;
         const unsigned long long m = (__ballot(occ) >> group_shift) & group_mask;
-        if (occ) sbuf[c + __popcll(m & ((1ull << sub) - 1ull))] = key;
+        if (occ) {
+            const int at = c + __popcll(m & ((1ull << sub) - 1ull));
+            sbuf[at] = key;
+            slot_of[at] = (uint8_t)(it * G + sub);
+        }
         c += __popcll(m);
     }
     const bool ovf_any = ((__ballot(ovf) >> group_shift) & group_mask) != 0;
-    const int N = pow2_ceil_i32(c);
-    for (int s = c + sub; s < N; s += G) sbuf[s] = SORT_PAD;
     wave_sync();
 
-    // bitonic sort of N keys by the G lanes of the row
-    for (int k = 2; k <= N; k <<= 1) {
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int i = sub; i < (N >> 1); i += G) {
-                const int lo = ((i & ~(j - 1)) << 1) | (i & (j - 1));
-                const int hi = lo | j;
-                const int32_t x = sbuf[lo], y = sbuf[hi];
-                if ((x > y) == ((lo & k) == 0)) { sbuf[lo] = y; sbuf[hi] = x; }
-            }
-            wave_sync();
-        }
+    // Column order without a sort (Section 4.2 sorts key-pointer pairs; a row this short is cheaper to rank):
+    // the place of a key is the number of smaller keys in the row.  Every lane ranks the keys t = sub, sub + G, ...
+    // of the gathered list against all c of them, one broadcast read per step; the rows of a wave go through
+    // the loop together, as many steps as the longest of them has keys.
+    constexpr int T = SLOTS / G;
+    const int cmax = (int)wave_max_u32((uint32_t)c);   // uniform for the wave
+    int32_t mk[T];
+    int rank[T];
+#pragma unroll
+    for (int i = 0; i < T; ++i) {
+        const int t = sub + i * G;
+        mk[i] = t < c ? sbuf[t] : SORT_PAD;
+        rank[i] = 0;
     }
+    // (TT: keys per lane that the longest row of the wave needs ranked)
+    auto count_smaller = [&](auto tt) {
+        constexpr int TT = decltype(tt)::value;
+        for (int j = 0; j < cmax; ++j) {
+            const int32_t kr = sbuf[j];                   // (j < SLOTS; beyond the row's keys whatever is there)
+            const int32_t kj = j < c ? kr : SORT_PAD;     // nothing is smaller than the pad
+#pragma unroll
+            for (int i = 0; i < TT; ++i) rank[i] += kj < mk[i];
+        }
+    };
+    if (cmax <= G) count_smaller(std::integral_constant<int, 1>{});
+    else if (cmax <= 2 * G) count_smaller(std::integral_constant<int, 2>{});
+    else count_smaller(std::integral_constant<int, T>{});
 
     if (live) {
         const int64_t o = out_ptr[row];
@@ -196,10 +216,13 @@ k_numeric_group(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
         if (ovf_any || (int64_t)c > cap) {
             if (sub == 0) row_nnz[row] = -1;
         } else {
-            for (int t = sub; t < c; t += G) {
-                const int32_t key = sbuf[t];
-                out_col[o + t] = key;
-                out_val[o + t] = (V)vals[lds_find<BITS>(keys, key)];
+#pragma unroll
+            for (int i = 0; i < T; ++i) {
+                const int t = sub + i * G;
+                if (t < c) {
+                    out_col[o + rank[i]] = mk[i];
+                    out_val[o + rank[i]] = (V)vals[slot_of[t]];
+                }
             }
             if (sub == 0) row_nnz[row] = c;
         }

@@ -158,6 +158,19 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v)
 {
     return wave_read_lane_u32(wave_inclusive_scan_u32(v), WAVE - 1);
 }
+// Largest value over the wave, as a wave-uniform number: the moves of the prefix sum with max in place of
+// add (a lane without a source keeps its own value), read from the last lane.  Every lane must be active.
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+    auto larger = [](uint32_t a, uint32_t b) { return a > b ? a : b; };
+    v = larger(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false));   // row_shr:1
+    v = larger(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false));   // row_shr:2
+    v = larger(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false));   // row_shr:4
+    v = larger(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false));   // row_shr:8
+    v = larger(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false));   // row_bcast:15, rows 1 and 3
+    v = larger(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false));   // row_bcast:31, rows 2 and 3
+    return wave_read_lane_u32(v, WAVE - 1);
+}
 // Workgroup level of a two-level prefix sum: part[w] holds the sum of wave w (NW <= 64 waves).
 // Returns the sum of the waves before `wave`; total = sum of all.  Every lane must be active.
 template <int NW>
