@@ -120,17 +120,24 @@ k_numeric_group(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
     constexpr int SLOTS = 1 << BITS;
     constexpr int R = 256 / G;
     __shared__ int32_t s_keys[R * SLOTS];
-    __shared__ int32_t s_sort[R * SLOTS];
     using AV = acc_t<V>;
     __shared__ AV s_vals[R * SLOTS];
-    __shared__ FlatChunk<V, G> s_fc[R];
+    // per row: the traversal's chunk and, when the traversal is done, the gathered keys of the row's table with
+    // the slot each came from, in the same memory
+    struct Gathered {
+        int32_t key[SLOTS];
+        uint8_t slot[SLOTS];
+    };
+    union RowScratch {
+        FlatChunk<V, G> fc;
+        Gathered g;
+    };
+    __shared__ RowScratch s_rs[R];
     const int rl = threadIdx.x / G;
     const int sub = threadIdx.x % G;
     int32_t *keys = s_keys + rl * SLOTS;
-    int32_t *sbuf = s_sort + rl * SLOTS;
-    // table slot of every gathered key: in the traversal's chunk, which is free by then
-    static_assert(sizeof(FlatChunk<V, G>) >= SLOTS, "one byte per slot");
-    uint8_t *slot_of = reinterpret_cast<uint8_t *>(&s_fc[rl]);
+    int32_t *sbuf = s_rs[rl].g.key;
+    uint8_t *slot_of = s_rs[rl].g.slot;
     AV *vals = s_vals + rl * SLOTS;
     const int group_shift = (lane_id() / G) * G;
     const unsigned long long group_mask = (1ull << G) - 1ull;
@@ -161,7 +168,7 @@ k_numeric_group(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
             p0 = b_rp[k];
             len = (uint32_t)(b_rp[k + 1] - p0);
         }
-        group_flat<G, true>(s_fc[rl], p0, len, a, b_col, b_val, f);
+        group_flat<G, true>(s_rs[rl].fc, p0, len, a, b_col, b_val, f);
     }
     wave_sync();
 
