@@ -118,7 +118,7 @@ k_numeric_esc(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_co
     int32_t col = -1;
     V val = V();
     uint32_t off = 0;   // products of the entries before this chunk
-    const int chunks = group_reduce_max((int)((e1 - e0 + L - 1) / L), WAVE);   // the rows of a wave advance together
+    const int chunks = (int)wave_max_u32((uint32_t)((e1 - e0 + L - 1) / L));   // the rows of a wave advance together
     for (int c = 0; c < chunks; ++c) {
         const int64_t e = e0 + (int64_t)c * L + sub;
         int64_t p0 = 0;

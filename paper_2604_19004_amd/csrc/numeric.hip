@@ -456,8 +456,9 @@ k_numeric_wave(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_c
         if (key[q] != EMPTY_KEY) { lmin = min(lmin, key[q]); lmax = max(lmax, key[q]); }
     }
     for (int j = sub; j < NBK / 2 + 1; j += WAVE) hist[j] = 0u;
-    const int kmax = group_reduce_max(lmax, WAVE);
-    const int kmin = -group_reduce_max(-lmin, WAVE);
+    // (column ids are not negative: both extremes as maxima of unsigned numbers)
+    const int kmax = (int)wave_max_u32((uint32_t)(lmax + 1)) - 1;
+    const int kmin = 0x7fffffff - (int)wave_max_u32((uint32_t)(0x7fffffff - lmin));
     const bool ovf_any = __ballot(ovf) != 0;
     if (kmax < 0) {   // uniform: the row has no entries
         if (sub == 0) row_nnz[row] = 0;
@@ -526,8 +527,9 @@ k_numeric_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col
         if (key[q] != EMPTY_KEY) { lmin = min(lmin, key[q]); lmax = max(lmax, key[q]); }
     }
     for (int j = tid; j < NBK / 2 + 1; j += THREADS) s_hist[j] = 0u;
-    lmax = group_reduce_max(lmax, WAVE);
-    lmin = -group_reduce_max(-lmin, WAVE);
+    // (column ids are not negative: both extremes as maxima of unsigned numbers)
+    lmax = (int)wave_max_u32((uint32_t)(lmax + 1)) - 1;
+    lmin = 0x7fffffff - (int)wave_max_u32((uint32_t)(0x7fffffff - lmin));
     if (lane_id() == 0 && lmax >= 0) { atomicMin(&s_min, lmin); atomicMax(&s_max, lmax); }
     __syncthreads();
     const int kmin = s_min, kmax = s_max;

@@ -82,7 +82,7 @@ k_symbolic_group(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
     const int64_t e0 = live ? a_rp[row] : 0;
     const int64_t e1 = live ? a_rp[row + 1] : 0;
     auto f = [&](const auto &cj, const auto &) { if (!CAPPED || !ovf) fresh += lds_count_new_batch<BITS, CAPPED>(keys, cj, ovf); };
-    const int chunks = group_reduce_max((int)((e1 - e0 + G - 1) / G), WAVE);
+    const int chunks = (int)wave_max_u32((uint32_t)((e1 - e0 + G - 1) / G));   // (uniform: the rows of a wave advance together)
     for (int ch = 0; ch < chunks; ++ch) {
         const int64_t e = e0 + (int64_t)ch * G + sub;
         int64_t p0 = 0;
@@ -94,8 +94,8 @@ k_symbolic_group(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
         }
         group_flat<G, false>(s_fc[rl], p0, len, NoVal(), b_col, (const NoVal *)nullptr, f);
     }
-    fresh = group_reduce_sum(fresh, G);
-    const bool ovf_any = CAPPED && group_reduce_max((int)ovf, G) != 0;
+    fresh = (int)group_sum_u32<G>((uint32_t)fresh);
+    const bool ovf_any = CAPPED && group_sum_u32<G>((uint32_t)ovf) != 0u;
     if (live && sub == 0) nnz_out[row] = ovf_any ? -1 : fresh;
 }
 
@@ -124,7 +124,7 @@ k_symbolic_wave(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_
                          [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
                          b_col, (const NoVal *)nullptr, s_fc[rl],
                          [&](const auto &cj, const auto &) { if (!CAPPED || !ovf) fresh += lds_count_new_batch<BITS, CAPPED>(keys, cj, ovf); });
-    fresh = group_reduce_sum(fresh, WAVE);
+    fresh = (int)wave_sum_u32((uint32_t)fresh);
     const bool ovf_any = CAPPED && __ballot(ovf) != 0ull;
     if (sub == 0) nnz_out[row] = ovf_any ? -1 : fresh;
 }
@@ -153,7 +153,7 @@ k_symbolic_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_co
                                 [&](int32_t k, int64_t &p0, int64_t &len) { p0 = b_rp[k]; len = b_rp[k + 1] - p0; },
                                 b_col, (const NoVal *)nullptr, s_fc,
                                 [&](const auto &cj, const auto &) { if (!CAPPED || !ovf) fresh += lds_count_new_batch<BITS, CAPPED>(s_keys, cj, ovf); });
-    fresh = group_reduce_sum(fresh, WAVE);
+    fresh = (int)wave_sum_u32((uint32_t)fresh);
     if (lane_id() == 0 && fresh) atomicAdd(&s_count, fresh);
     if (CAPPED && ovf) s_ovf = 1;
     __syncthreads();
@@ -261,7 +261,7 @@ k_symbolic_bitmap(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ 
                 c += __popc(x.x) + __popc(x.y) + __popc(x.z) + __popc(x.w);
                 bm4[s * BM_THREADS + tid] = make_uint4(0u, 0u, 0u, 0u);
             }
-            c = group_reduce_sum(c, WAVE);
+            c = (int)wave_sum_u32((uint32_t)c);
             if (lane_id() == 0 && c) atomicAdd(&s_count[turn & 1u], c);
             __syncthreads();
         }
