@@ -46,7 +46,7 @@ enum { OCEAN_WF_AUTO = 0, OCEAN_WF_UPPER_BOUND = 1, OCEAN_WF_HLL = 2, OCEAN_WF_S
  * rule picks the estimation workflow although the sampled CR is below tuned_cr_bound, the upper-bound
  * workflow runs instead: an estimate with 13 - 18 % error and its expansion factor reserves no less than
  * the product bound then does, and the bound costs no estimation pass and cannot overflow (with the default
- * thresholds, tuned_cr_light = tuned_cr_bound, this is never the case: it matters when tuned_cr_light is
+ * thresholds, tuned_cr_light above tuned_cr_bound, this is never the case: it matters when tuned_cr_light is
  * lowered). */
 enum { OCEAN_SEL_TABLE1 = 0, OCEAN_SEL_MI355X = 1 };
 
@@ -120,7 +120,7 @@ typedef struct ocean_options {
                                         second allocation (Section 5.2, memory overhead).  0 never, 1 whenever the rows
                                         allow it, -1 (default) when both copies together would exceed 40 % of the
                                         device's memory or the second allocation fails */
-    double tuned_cr_light;           /* 1.5 */
+    double tuned_cr_light;           /* 3.0 */
     double tuned_cr_heavy;           /* 4.5 */
     double tuned_min_products;       /* 4194304 */
     double tuned_cr_bound;           /* 1.5; 0 = the estimation workflow is never replaced by the upper bound */

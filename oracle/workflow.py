@@ -86,7 +86,7 @@ def select_workflow(avg_products: float, er: float, cr: float) -> int:
 
 
 def select_workflow_tuned(avg_products: float, er: float, cr: float, products: float, heavy_products: float,
-                          cr_light: float = 1.5, cr_heavy: float = 4.5, min_products: float = 4194304.0,
+                          cr_light: float = 3.0, cr_heavy: float = 4.5, min_products: float = 4194304.0,
                           cr_bound: float = 1.5) -> int:
     """Table 1 with the CR threshold re-derived for one GPU (not in the paper; Section 4.3 says the 8 was chosen
     empirically to amortize compaction): the threshold slides linearly from cr_light to cr_heavy with the

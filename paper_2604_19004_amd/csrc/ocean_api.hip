@@ -617,7 +617,7 @@ void fill_defaults(ocean_options *o)
     o->compact_in_place = -1;
     o->sort_b_ratio = 8.0;
     o->selector = OCEAN_SEL_MI355X;
-    o->tuned_cr_light = 1.5;
+    o->tuned_cr_light = 3.0;
     o->tuned_cr_heavy = 4.5;
     o->tuned_min_products = 4194304.0;
     o->tuned_cr_bound = 1.5;
@@ -673,8 +673,10 @@ int select_of(double avg, double er, double cr, const ocean_options &o)
 // "chosen empirically to amortize the cost of output compaction" on an A100 (Section 4.3).  Here the
 // compaction copy runs at 4.3 - 5.8 TB/s, so what it has to beat is the symbolic pass it replaces:
 // estimation wins when products / r_sym > 2 (4 + v) products / (CR * bw), i.e. CR > 2 (4 + v) r_sym / bw.
-// Rows that fit the LDS key tables are counted at r_sym = 140 - 290 G products/s (break-even CR about 1),
-// rows that outgrow them go through the bitmap kernel at about 960 G products/s (break-even CR 4 - 5).
+// Rows that fit the LDS key tables are counted at r_sym = 250 - 460 G products/s (break-even CR 1.2 - 1.5 by
+// the rates alone; with the estimate's own pass, its retries and the larger tables it gives the numeric pass
+// the two workflows measure the same at CR 3.3 and two passes win by 14 % at CR 1.03: threshold 3),
+// rows that outgrow them go through the bitmap kernel at about 1.4 T products/s (break-even CR above 4.5).
 // So the threshold slides between the two with the share of the products that heavy rows hold.  Small
 // problems (below tuned_min_products) run the two-pass workflow unsampled: there the sketches and the sample
 // cost more than any choice between the workflows can gain (4096 rows of 8 entries: 0.29 ms sampled, 0.24 ms not).
@@ -687,8 +689,8 @@ int select_tuned(double avg, double er, double cr, double products, double heavy
     // (an estimate is worth its pass, its expansion factor and its retries only if it undercuts the product
     // bound by more than its own error: below tuned_cr_bound the bound itself is the reservation.  Measured on
     // the rectangular input, CR 1.03: 2.43 ms against 2.61 ms; on the clustered one, CR 3.3: 4.44 against 3.51 ms.
-    // With the default thresholds the rule is not reached: below a CR of 1.5 two passes are faster than either,
-    // 2.32 ms on the rectangular input)
+    // With the default thresholds the rule is not reached: below a CR of 3 two passes are faster than either,
+    // 2.20 ms on the rectangular input)
     if (er >= o.er_threshold && cr >= thr) return cr < o.tuned_cr_bound ? OCEAN_WF_UPPER_BOUND : OCEAN_WF_HLL;
     return OCEAN_WF_SYMBOLIC;
 }

@@ -77,15 +77,15 @@ def test_host_helpers_agree_with_the_oracle(ob):
     # the re-tuned rule: hand-checked corners, then the grid against the oracle's reading
     U, H, S = owf.UPPER_BOUND, owf.HLL, owf.SYMBOLIC
     assert ob.select_workflow_tuned(10.0, 100.0, 100.0, 1e9, 0.0) == U
-    assert ob.select_workflow_tuned(100.0, 30.0, 3.2, 4e8, 0.0) == H           # light rows only: threshold 1.5
+    assert ob.select_workflow_tuned(100.0, 30.0, 3.2, 4e8, 0.0) == H           # light rows only: threshold 3.0
     assert ob.select_workflow_tuned(100.0, 30.0, 3.2, 4e8, 4e8) == S           # heavy rows only: threshold 4.5
-    assert ob.select_workflow_tuned(100.0, 30.0, 3.0, 4e8, 2e8) == H           # half and half: threshold 3.0
-    assert ob.select_workflow_tuned(100.0, 30.0, 2.99, 4e8, 2e8) == S
+    assert ob.select_workflow_tuned(100.0, 30.0, 3.75, 4e8, 2e8) == H          # half and half: threshold 3.75
+    assert ob.select_workflow_tuned(100.0, 30.0, 3.74, 4e8, 2e8) == S
     assert ob.select_workflow_tuned(100.0, 7.9, 100.0, 4e8, 0.0) == S          # ER below 8
     assert ob.select_workflow_tuned(100.0, 30.0, 3.2, 1e6, 0.0) == S           # small problem: two passes, unsampled
     assert ob.select_workflow_tuned(100.0, 30.0, 100.0, 1e6, 0.0) == S
-    assert ob.select_workflow_tuned(100.0, 30.0, 1.49, 4e8, 0.0) == S          # below the light threshold: two passes
-    assert ob.select_workflow_tuned(100.0, 30.0, 1.5, 4e8, 0.0) == H
+    assert ob.select_workflow_tuned(100.0, 30.0, 2.99, 4e8, 0.0) == S          # below the light threshold: two passes
+    assert ob.select_workflow_tuned(100.0, 30.0, 3.0, 4e8, 0.0) == H
     assert ob.select_workflow_tuned(100.0, 30.0, 1.2, 4e8, 4e8) == S           # heavy rows: two passes, whatever the CR
     assert ob.select_workflow_tuned(100.0, 30.0, 0.99, 4e8, 0.0) == S          # below the light threshold
     low = ob.default_options(tuned_cr_light=1.0)                                  # estimation from CR 1.0 on: below 1.5 the bound
@@ -94,7 +94,7 @@ def test_host_helpers_agree_with_the_oracle(ob):
     assert owf.select_workflow_tuned(100.0, 30.0, 1.2, 4e8, 0.0, cr_light=1.0) == U
     for avg in grid:
         for er in grid:
-            for cr in (0.5, 1.0, 1.499, 1.5, 2.0, 2.75, 4.5, 8.0):
+            for cr in (0.5, 1.0, 1.499, 1.5, 2.0, 2.75, 2.999, 3.0, 3.75, 4.5, 8.0):
                 for p_, h_ in ((1e3, 0.0), (1e8, 0.0), (1e8, 5e7), (1e8, 1e8)):
                     assert ob.select_workflow_tuned(avg, er, cr, p_, h_) == owf.select_workflow_tuned(avg, er, cr, p_, h_)
     num, sym = ob.bin_layout()
