@@ -27,6 +27,8 @@ namespace ocean {
 // measured about twenty times slower than ds_add_f64 on this GPU (a block-diagonal input, same structure in both
 // types: dense accumulation 4.27 ms against 2.40 ms; with plain stores in place of the atomics 1.42 against 2.27 ms),
 // so an fp32 row costs the LDS of an fp64 row and is faster for it - and closer to the exact sum.
+constexpr int ilog2_const(int x) { return x <= 1 ? 0 : 1 + ilog2_const(x >> 1); }
+
 template <typename V> struct AccOf { using type = V; };
 template <> struct AccOf<float> { using type = double; };
 template <typename V> using acc_t = typename AccOf<V>::type;
@@ -465,8 +467,10 @@ k_numeric_wave(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_c
         return;
     }
     wave_sync();   // every lane holds its keys in registers (the key array becomes the buckets' memory), counts are zero
-    int shift = 0;
-    while ((((uint32_t)(kmax - kmin)) >> shift) >= (uint32_t)NBK) ++shift;
+    // smallest shift with (kmax - kmin) >> shift < NBK: the bits of the range beyond those of the bucket count
+    static_assert((NBK & (NBK - 1)) == 0, "bucket count is a power of two");
+    const int range_bits = 32 - __clz((uint32_t)(kmax - kmin) | 1u);
+    const int shift = range_bits > ilog2_const(NBK) ? range_bits - ilog2_const(NBK) : 0;
     const int64_t o = out_ptr[row];
     const int64_t cap = out_ptr[row + 1] - o;
     const int c = bucket_emit<WAVE, PER, false, WaveScope, BF>(key, vals, kmin, shift, hist, keys, nullptr, &s_flag[rl], 0, o, cap, 0,
@@ -532,13 +536,15 @@ k_numeric_wg(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a_col
     lmin = 0x7fffffff - (int)wave_max_u32((uint32_t)(0x7fffffff - lmin));
     if (lane_id() == 0 && lmax >= 0) { atomicMin(&s_min, lmin); atomicMax(&s_max, lmax); }
     __syncthreads();
-    const int kmin = s_min, kmax = s_max;
+    const int kmin = __builtin_amdgcn_readfirstlane(s_min), kmax = __builtin_amdgcn_readfirstlane(s_max);   // (the same in every thread)
     if (kmax < 0) {   // uniform: the row has no entries
         if (tid == 0) row_nnz[row] = 0;
         return;
     }
-    int shift = 0;
-    while ((((uint32_t)(kmax - kmin)) >> shift) >= (uint32_t)NBK) ++shift;
+    // smallest shift with (kmax - kmin) >> shift < NBK: the bits of the range beyond those of the bucket count
+    static_assert((NBK & (NBK - 1)) == 0, "bucket count is a power of two");
+    const int range_bits = 32 - __clz((uint32_t)(kmax - kmin) | 1u);
+    const int shift = range_bits > ilog2_const(NBK) ? range_bits - ilog2_const(NBK) : 0;
     constexpr bool CHECK = SLOTS >= 4096;   // smaller tables: even one bucket with every key is cheap to rank
     int c = bucket_emit<THREADS, PER, CHECK, WorkgroupScope, BF>(key, s_vals, kmin, shift, s_hist, s_sort, s_wave, &s_flag, 1024, o, cap, 0,
                                              out_col, out_val);
@@ -816,7 +822,6 @@ constexpr int HV_HCAP = HV_PPT * HV_THREADS;       // products one sparse pass t
 constexpr int HV_MAXWIN = 512;                     // windows per row the kernel can plan for
 constexpr int HV_RPT = 48;                         // chunks of up to 48 products per thread find their entries by rank
                                                    // (most dense windows then do: 96.8 -> 94.9 ms; 4 KB more LDS)
-constexpr int ilog2_const(int x) { return x <= 1 ? 0 : 1 + ilog2_const(x >> 1); }
 
 template <typename V>
 struct DenseCfg {
