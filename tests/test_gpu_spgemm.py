@@ -767,6 +767,48 @@ def test_esc_short_rows(ob, seed, dtype):
     assert st["overflow_rows"] > 0
 
 
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_short_rows_with_every_number_of_keys(ob, dtype):
+    """Rows of the 32- and 64-slot tables (8 or 16 lanes per row, ordered by counting the smaller keys of the
+    row): every number of distinct output columns from 0 to 64, tables filled to the last slot
+    (bound_load_coef 1.0: as many slots as products), rows of very different lengths side by side in one wave,
+    columns at both ends of the id range and repeated columns (several products per key)."""
+    rng = np.random.default_rng(77)
+    n = 1 << 20
+    k = 65 * 3
+    # row 3 L + v of B holds L distinct columns (v = 0: random, v = 1: consecutive from 0, v = 2: the largest ids)
+    b_rows = []
+    for L in range(65):
+        b_rows.append(np.sort(rng.choice(n, L, replace=False)))
+        b_rows.append(np.arange(L))
+        b_rows.append(np.arange(n - L, n))
+    b_rp = np.concatenate([[0], np.cumsum([len(r) for r in b_rows])]).astype(np.int64)
+    b_ci = np.concatenate(b_rows).astype(np.int32)
+    B = CSR(k, n, b_rp, b_ci, rng.uniform(-1, 1, b_ci.size).astype(dtype))
+    # a row of A: one entry (as many keys as products), or the same row of B twice over two entries with a third,
+    # short one (repeated columns); the order of the rows is shuffled so that neighbours differ in length
+    a_rows = []
+    for r in range(k):
+        a_rows.append([r])
+        a_rows.append([r, (r + 3) % k] if len(b_rows[r]) + len(b_rows[(r + 3) % k]) <= 64 else [r])
+        a_rows.append([r, 1, 2, r] if 2 * len(b_rows[r]) + 2 <= 64 else [r])   # (row 1 and 2 of B: empty) duplicates in A
+    order = rng.permutation(len(a_rows))
+    a_rows = [a_rows[i] for i in order] * 4
+    a_rp = np.concatenate([[0], np.cumsum([len(r) for r in a_rows])]).astype(np.int64)
+    a_ci = np.concatenate(a_rows).astype(np.int32)
+    A = CSR(len(a_rows), k, a_rp, a_ci, rng.uniform(-1, 1, a_ci.size).astype(dtype))
+    ref = O.multiply_rows(A, B)
+    counts = np.diff(ref.row_ptr)
+    assert set(range(65)) <= set(counts.tolist())
+    dA, dB = ob.to_device(A), ob.to_device(B)
+    for kw in (dict(workflow=ob.WF_UPPER_BOUND, bound_load_coef=1.0), dict(workflow=ob.WF_UPPER_BOUND),
+               dict(workflow=ob.WF_SYMBOLIC, exact_load_coef=1.0), dict(workflow=ob.WF_SYMBOLIC),
+               dict(workflow=ob.WF_HLL), dict(workflow=ob.WF_AUTO)):
+        Cd, st = ob.spgemm(dA, dB, **kw)
+        check_result(Cd, ref, A, f"short rows {kw}")
+        assert st["rows_per_bin"][0] + st["rows_per_bin"][1] + st["rows_per_bin"][2] > 0
+
+
 def test_skewed_row_lengths_of_b(ob):
     # rows of B from 0 to 20000 entries referenced by the same rows of A: exercises the short / medium /
     # long / huge classes of the product traversal in every kernel size
