@@ -1402,7 +1402,7 @@ k_numeric_global(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ a
 
 // ============================================================ dispatch ====
 template <typename V>
-static hipError_t dispatch(const Csr &A, const Csr &B, const NumLaunch &l, int gb_log2, hipStream_t s)
+static hipError_t dispatch(const Csr &A, const Csr &B, const NumLaunch &l, int /*gb_log2*/, hipStream_t s)
 {
     if (l.count <= 0) return hipSuccess;
     const V *av = static_cast<const V *>(A.val);

@@ -439,7 +439,7 @@ double conservative_cr(const ocean_stats *S, const ocean_options &o)
 // Launches every non-empty bin, largest tables first.  Scratch for the hybrid
 // and global bins is obtained here and kept until the caller releases all.
 int run_numeric(Ctx &c, Work &w, const Csr &A, const Csr &B, int dtype, int gb_log2, const unsigned long long *count,
-                const unsigned long long *bin_prod, int64_t max_cap_global, double global_coef, const int64_t *out_ptr, int32_t *out_col, void *out_val,
+                const unsigned long long * /*bin_prod*/, int64_t max_cap_global, double global_coef, const int64_t *out_ptr, int32_t *out_col, void *out_val,
                 int32_t *row_nnz, int queue_base, int stage, bool time_bins, bool esc)
 {
     // With the window table, the column-window kernel takes every row beyond the 4096-slot table (measured:
@@ -810,7 +810,6 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
         bp.n_bins = NB_COUNT;
         for (int b = 0; b < NB_COUNT; ++b) bp.slots[b] = kNumericSlots[b];
         bp.n_cols = n;
-        double global_coef = 1.25;
         if (w.spans) {
             bp.cmin = w.cmin;
             bp.cmax = w.cmax;
@@ -829,7 +828,6 @@ int spgemm_impl(Ctx &c, const ocean_csr *Ain, const ocean_csr *Bin, ocean_csr *C
             OC_TRY(run_symbolic(c, w, A, B, gb_log2, S->assist_cr, query_bitmap, w.nnz_final, S));
             bp.mode = 2;
             bp.coef = o.exact_load_coef;
-            global_coef = o.exact_load_coef;
         } else {
             bp.mode = 0;
             bp.coef = 1.0;

@@ -280,7 +280,7 @@ k_symbolic_bitmap(const int64_t *__restrict__ a_rp, const int32_t *__restrict__ 
 }
 
 // -------------------------------------------------------------- dispatch
-hipError_t launch_symbolic_bin(const Csr &A, const Csr &B, const SymLaunch &l, int gb_log2, int32_t *nnz_out,
+hipError_t launch_symbolic_bin(const Csr &A, const Csr &B, const SymLaunch &l, int /*gb_log2*/, int32_t *nnz_out,
                                int n_wg, unsigned long long *queue, hipStream_t s)
 {
     if (l.count <= 0) return hipSuccess;

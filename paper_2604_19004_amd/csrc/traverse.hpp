@@ -501,7 +501,7 @@ __device__ __forceinline__ uint32_t wg_flat_chunk(WgChunk<V, THREADS, RPT> &c, i
 // are as this function leaves them (all zero); after any other use of the chunk pass false and they are cleared
 // first.  Every thread calls it; ends with a barrier; returns the number of products.
 template <int THREADS, int NB, typename V, typename M, int RPT>
-__device__ __forceinline__ uint32_t wg_flat_chunk_keep(WgChunk<V, THREADS, RPT> &c, int nent, int64_t p0, uint32_t len, V a,
+__device__ __forceinline__ uint32_t wg_flat_chunk_keep(WgChunk<V, THREADS, RPT> &c, int /*nent*/, int64_t p0, uint32_t len, V a,
                                                    const int32_t *__restrict__ b_col, const V *__restrict__ b_val,
                                                    int32_t (&kc)[NB * FLAT_U], V (&kv)[NB * FLAT_U], M &mark,
                                                    bool &fits, bool clean)
